@@ -1,0 +1,256 @@
+"""CPU oracle for bottom-up pose post-processing: TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over `hp_oracle.c` (the plain C statement of the
+post-processing operator of the paper's Section 2.2.1) plus the loops that
+chain its steps over images, parts and limbs.  Only tests, the smoke check and
+the benchmark's `cpu_baseline` leg may import this package; it shares no code
+with the HIP library.
+
+Parity pins: see the header of `hp_oracle.c` (assembly is pinned by planted
+skeleton recovery and invariants only; parity with the paper's own engine is
+unpinned).
+"""
+import ctypes
+import os
+import subprocess
+import threading
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hp_oracle.c")
+
+
+def _cpu_has_fma():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("flags"):
+                    return " fma " in line + " "
+    except OSError:
+        pass
+    return False
+
+
+def build(force=False):
+    """Compile the oracle twice: with hardware FMA and without (libm fmaf)."""
+    out = []
+    for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
+        so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
+        if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(_SRC):
+            cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, "-o", so, "-lm"]
+            subprocess.check_call(cmd)
+        out.append(so)
+    return out
+
+
+_lib = None
+_lock = threading.Lock()
+
+
+def lib():
+    global _lib
+    if _lib is not None:
+        return _lib
+    with _lock:
+        if _lib is not None:
+            return _lib
+        fma_so, gen_so = build()
+        L = ctypes.CDLL(fma_so if _cpu_has_fma() else gen_so)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        ci = ctypes.c_int
+        cf = ctypes.c_float
+        L.hpo_up.restype = cf
+        L.hpo_up.argtypes = [f32p, ci, ci, ci, ci, ci]
+        L.hpo_resize.restype = None
+        L.hpo_resize.argtypes = [f32p, ci, ci, ci, ci, f32p]
+        L.hpo_find_peaks.restype = ci
+        L.hpo_find_peaks.argtypes = [f32p, ci, ci, cf, ci, i32p, i32p, f32p]
+        L.hpo_need.restype = ci
+        L.hpo_need.argtypes = [cf, ci]
+        L.hpo_score_limb.restype = ci
+        L.hpo_score_limb.argtypes = [f32p, f32p, ci, ci, ci, ci, i32p, i32p, ci, i32p, i32p,
+                                     ci, cf, ci, ci, i32p, i32p, f32p]
+        L.hpo_match_limb.restype = ci
+        L.hpo_match_limb.argtypes = [ci, i32p, i32p, f32p, ci, ci, i32p, i32p, f32p]
+        L.hpo_assemble.restype = ci
+        L.hpo_assemble.argtypes = [ci, ci, i32p, i32p, f32p, ci, i32p, i32p, i32p, f32p,
+                                   ci, ci, ci, i32p, i32p, f32p]
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _i32(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _as_f32(a):
+    """Exact widening of fp16/fp32 storage to contiguous fp32."""
+    return np.ascontiguousarray(np.asarray(a).astype(np.float32))
+
+
+def up(lo_plane, s, Y, X):
+    lo_plane = _as_f32(lo_plane)
+    h, w = lo_plane.shape
+    return float(lib().hpo_up(_f32(lo_plane), h, w, s, int(Y), int(X)))
+
+
+def resize(lo, s=8):
+    """[..., h, w] -> fp32 [..., s*h, s*w]."""
+    lo = _as_f32(lo)
+    h, w = lo.shape[-2:]
+    planes = int(np.prod(lo.shape[:-2], dtype=np.int64))
+    hi = np.empty(lo.shape[:-2] + (s * h, s * w), dtype=np.float32)
+    lib().hpo_resize(_f32(lo), planes, h, w, s, _f32(hi))
+    return hi
+
+
+def find_peaks(plane_hi, thr):
+    """Peaks of one fp32 hi-res plane: (x int32[], y int32[], score fp32[]) in raster order."""
+    u = np.ascontiguousarray(plane_hi, dtype=np.float32)
+    H, W = u.shape
+    cap = 256
+    while True:
+        px = np.empty(cap, np.int32)
+        py = np.empty(cap, np.int32)
+        ps = np.empty(cap, np.float32)
+        n = lib().hpo_find_peaks(_f32(u), H, W, float(thr), cap, _i32(px), _i32(py), _f32(ps))
+        if n <= cap:
+            return px[:n].copy(), py[:n].copy(), ps[:n].copy()
+        cap = n
+
+
+def need(min_valid_ratio, S):
+    return int(lib().hpo_need(float(min_valid_ratio), int(S)))
+
+
+def score_limb(pafx_lo, pafy_lo, s, xA, yA, xB, yB, n_samples, paf_thr, min_valid_ratio):
+    """Accepted candidates (i int32[], j int32[], score fp32[]) of one limb, (i, j) order."""
+    pafx_lo = _as_f32(pafx_lo)
+    pafy_lo = _as_f32(pafy_lo)
+    h, w = pafx_lo.shape
+    xA = np.ascontiguousarray(xA, np.int32)
+    yA = np.ascontiguousarray(yA, np.int32)
+    xB = np.ascontiguousarray(xB, np.int32)
+    yB = np.ascontiguousarray(yB, np.int32)
+    nd = need(min_valid_ratio, n_samples)
+    ccap = max(1024, 4 * max(len(xA), len(xB)))
+    while True:
+        ci = np.empty(ccap, np.int32)
+        cj = np.empty(ccap, np.int32)
+        cs = np.empty(ccap, np.float32)
+        n = lib().hpo_score_limb(_f32(pafx_lo), _f32(pafy_lo), h, w, s,
+                                 len(xA), _i32(xA), _i32(yA), len(xB), _i32(xB), _i32(yB),
+                                 int(n_samples), float(paf_thr), nd, ccap, _i32(ci), _i32(cj), _f32(cs))
+        if n <= ccap:
+            return ci[:n].copy(), cj[:n].copy(), cs[:n].copy()
+        ccap = n
+
+
+def match_limb(ci, cj, cs, nA, nB):
+    """Greedy matching: connections (i, j, score) in acceptance order."""
+    ci = np.ascontiguousarray(ci, np.int32)
+    cj = np.ascontiguousarray(cj, np.int32)
+    cs = np.ascontiguousarray(cs, np.float32)
+    m = max(min(nA, nB), 1)
+    mi = np.empty(m, np.int32)
+    mj = np.empty(m, np.int32)
+    ms = np.empty(m, np.float32)
+    n = lib().hpo_match_limb(len(ci), _i32(ci), _i32(cj), _f32(cs), int(nA), int(nB),
+                             _i32(mi), _i32(mj), _f32(ms))
+    return mi[:n].copy(), mj[:n].copy(), ms[:n].copy()
+
+
+def assemble(limb_a, limb_b, K, peak_scores, conns, min_parts):
+    """Persons of one image.
+
+    peak_scores: list over parts of fp32 arrays; conns: list over limbs of
+    (mi, mj, ms).  Returns (slots int32 [P, K], nparts int32 [P], score fp32 [P]).
+    """
+    limb_a = np.ascontiguousarray(limb_a, np.int32)
+    limb_b = np.ascontiguousarray(limb_b, np.int32)
+    L = len(limb_a)
+    pcount = np.array([len(p) for p in peak_scores], np.int32)
+    pstride = max(int(pcount.max()) if K else 0, 1)
+    pscore = np.zeros((K, pstride), np.float32)
+    for c in range(K):
+        pscore[c, :pcount[c]] = peak_scores[c]
+    mcount = np.array([len(c[0]) for c in conns], np.int32)
+    mstride = max(int(mcount.max()) if L else 0, 1)
+    mi = np.zeros((L, mstride), np.int32)
+    mj = np.zeros((L, mstride), np.int32)
+    ms = np.zeros((L, mstride), np.float32)
+    for l in range(L):
+        mi[l, :mcount[l]], mj[l, :mcount[l]], ms[l, :mcount[l]] = conns[l]
+    pcap = int(mcount.sum()) + 1
+    slots = np.empty((pcap, K), np.int32)
+    nparts = np.empty(pcap, np.int32)
+    score = np.empty(pcap, np.float32)
+    n = lib().hpo_assemble(K, L, _i32(limb_a), _i32(limb_b), _f32(pscore), pstride,
+                           _i32(mcount), _i32(mi), _i32(mj), _f32(ms), mstride,
+                           int(min_parts), pcap, _i32(slots), _i32(nparts), _f32(score))
+    assert n <= pcap
+    return slots[:n].copy(), nparts[:n].copy(), score[:n].copy()
+
+
+def postprocess(cm_lo, paf_lo, limb_a, limb_b, params, threads=1, stages="all"):
+    """The whole operator on a batch.
+
+    cm_lo [N, K+1, h, w], paf_lo [N, 2L, h, w] (fp16 or fp32).  The last CM
+    channel is background and is not searched.  Returns a dict of ragged
+    results:
+      peaks[n][c]  = (x, y, score)      candidates[n][l] = (i, j, score)
+      conns[n][l]  = (i, j, score)      poses[n] = (slots, nparts, score)
+    `threads` farms the independent (image, part) and (image, limb) calls over
+    a thread pool (the C calls release the GIL); results do not depend on it.
+    """
+    cm_lo = _as_f32(cm_lo)
+    paf_lo = _as_f32(paf_lo)
+    N, C_cm, h, w = cm_lo.shape
+    K = C_cm - 1
+    L = len(limb_a)
+    s = params.scale
+    assert paf_lo.shape == (N, 2 * L, h, w)
+
+    def run(fn, items):
+        if threads <= 1:
+            return [fn(it) for it in items]
+        with ThreadPoolExecutor(threads) as ex:
+            return list(ex.map(fn, items))
+
+    def peaks_of(nc):
+        n, c = nc
+        return find_peaks(resize(cm_lo[n, c], s), params.peak_thr)
+
+    flat = run(peaks_of, [(n, c) for n in range(N) for c in range(K)])
+    peaks = [[flat[n * K + c] for c in range(K)] for n in range(N)]
+    out = {"peaks": peaks}
+    if stages == "peaks":
+        return out
+
+    def limb_of(nl):
+        n, l = nl
+        a, b = int(limb_a[l]), int(limb_b[l])
+        xA, yA, _ = peaks[n][a]
+        xB, yB, _ = peaks[n][b]
+        cand = score_limb(paf_lo[n, 2 * l], paf_lo[n, 2 * l + 1], s, xA, yA, xB, yB,
+                          params.n_samples, params.paf_thr, params.min_valid_ratio)
+        conn = match_limb(*cand, len(xA), len(xB))
+        return cand, conn
+
+    flat = run(limb_of, [(n, l) for n in range(N) for l in range(L)])
+    out["candidates"] = [[flat[n * L + l][0] for l in range(L)] for n in range(N)]
+    out["conns"] = [[flat[n * L + l][1] for l in range(L)] for n in range(N)]
+
+    def person_of(n):
+        return assemble(limb_a, limb_b, K, [p[2] for p in peaks[n]], out["conns"][n], params.min_parts)
+
+    out["poses"] = run(person_of, list(range(N)))
+    return out
