@@ -1,0 +1,201 @@
+/*
+ * hp: bottom-up (CM + PAF) pose post-processing on one AMD MI355X (gfx950).
+ *
+ * C boundary of the library.  It implements the post-processing operator of the
+ * paper's inference engine (Section 2.2.1, operator 4: the network's activation
+ * maps go in, the human pose topology comes out) for the PAF / OpenPose family
+ * (Section 2.3).  The paper runs this operator on CPU threads and names it as
+ * its example of a CPU-side bottleneck (Section 2.2.2); here every step runs in
+ * HIP kernels.  The paper states the operator's job but not its arithmetic; the
+ * rules each call follows are written at its declaration.
+ *
+ * Conventions common to all calls
+ *   - Tensors are dense, row-major, NCHW.  "lo" tensors are the network outputs
+ *     [N][C][h][w] (fp32 or fp16); "hi" tensors are fp32 [N][C][s*h][s*w], s = 8.
+ *   - Every pointer named *device* must be device memory valid on the current
+ *     HIP device; hp_skeleton / hp_params / the hp_* descriptor structs are read
+ *     on the host before the call returns, the arrays inside descriptors are
+ *     device memory.  The caller owns every buffer.  The library allocates and
+ *     frees nothing and never synchronises: all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Return value: HP_OK or a negative hp_error, decided on the host before
+ *     anything is enqueued (invalid calls enqueue nothing).
+ *   - Conditions only the device can see (a list longer than its capacity) are
+ *     reported through `status`, one device int32 that the call overwrites:
+ *     0 or an OR of hp_status_bit.  `count` arrays always receive the number of
+ *     entries REQUIRED; when it exceeds the capacity the stored list is an
+ *     unspecified subset of `cap` entries in canonical order and every result
+ *     derived from it is invalid.
+ *   - Canonical orders: peaks of one (image, part) in raster order (y, then x);
+ *     candidates of one (image, limb) by (i, j) ascending; connections in
+ *     acceptance order of the greedy matching; persons in creation order.
+ *   - A peak is referred to by its rank in its (image, part) list.
+ */
+#ifndef HP_H
+#define HP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { HP_F32 = 0, HP_F16 = 1 } hp_dtype;
+
+typedef enum {
+    HP_OK = 0,
+    HP_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, inconsistent sizes */
+    HP_ERR_DTYPE = -2,         /* unknown hp_dtype */
+    HP_ERR_WORKSPACE = -3,     /* workspace smaller than hp_workspace_bytes() or misaligned */
+    HP_ERR_HIP = -4,           /* a launch failed (hipGetLastError) */
+    HP_ERR_UNSUPPORTED = -5    /* a size beyond the built limits (see HP_MAX_*) */
+} hp_error;
+
+typedef enum {
+    HP_STATUS_PEAK_OVERFLOW = 1,   /* some (image, part) has more peaks than hp_peaks.cap */
+    HP_STATUS_CAND_OVERFLOW = 2,   /* some (image, limb) has more candidates than its cap */
+    HP_STATUS_POSE_OVERFLOW = 4    /* some image has more persons than hp_poses.cap */
+} hp_status_bit;
+
+enum {
+    HP_SCALE = 8,          /* the only upsampling factor built */
+    HP_MAX_PARTS = 32,
+    HP_MAX_LIMBS = 64,
+    HP_MAX_CAP = 16384,    /* largest hp_peaks.cap */
+    HP_MAX_CCAP = 1 << 20, /* largest candidate capacity */
+    HP_MAX_SAMPLES = 64
+};
+
+/* Skeleton: limb l joins part limb_a[l] to part limb_b[l] and owns PAF channels
+ * (2l, 2l+1) = (x, y) components.  Host arrays of n_limbs entries. */
+typedef struct {
+    int32_t n_parts;
+    int32_t n_limbs;
+    const int32_t *limb_a;
+    const int32_t *limb_b;
+} hp_skeleton;
+
+typedef struct {
+    float peak_thr;         /* a peak must exceed this (strictly) */
+    float paf_thr;          /* a sample is valid when its projection exceeds this */
+    int32_t n_samples;      /* S >= 2 samples per candidate, end points included */
+    float min_valid_ratio;  /* a candidate needs ceil(ratio * S) valid samples (fp32 product) */
+    int32_t min_parts;      /* persons with fewer parts are dropped */
+    int32_t scale;          /* must be HP_SCALE */
+} hp_params;
+
+/* Peaks: x, y, score are device [N][K][cap]; count is device [N][K]. */
+typedef struct {
+    int32_t *x;
+    int32_t *y;
+    float *score;
+    int32_t *count;
+    int32_t cap;
+} hp_peaks;
+
+/* Limb candidates or connections: i, j, score are device [N][L][cap];
+ * count is device [N][L].  i / j are peak ranks of parts limb_a[l] / limb_b[l]. */
+typedef struct {
+    int32_t *i;
+    int32_t *j;
+    float *score;
+    int32_t *count;
+    int32_t cap;
+} hp_pairs;
+
+/* Persons: slots device [N][cap][K] (peak rank or -1), nparts and score device
+ * [N][cap], count device [N]. */
+typedef struct {
+    int32_t *slots;
+    int32_t *nparts;
+    float *score;
+    int32_t *count;
+    int32_t cap;
+} hp_poses;
+
+/* Bytes of device workspace that hp_find_peaks, hp_score_limbs, hp_assemble and
+ * hp_postprocess need for these sizes (cap = peaks per (image, part), ccap =
+ * candidates per (image, limb), pcap = persons per image).  0 if a size is
+ * invalid.  The workspace must be 256-byte aligned; its contents need not be
+ * preserved between calls and two calls running concurrently must not share it. */
+size_t hp_workspace_bytes(int N, int K, int L, int h, int w, int scale, int cap, int ccap, int pcap);
+
+/* Upsampling ("resizing", Section 2.2; imaging operations, Section 2.3).
+ * dst_hi[n][c][Y][X] = bilinear sample of src_lo[n][c] at ((Y+1/2)/s - 1/2,
+ * (X+1/2)/s - 1/2) with edge clamping, computed in fp32 as a horizontal pass
+ * r = fma(f, v[x1], (1-f)*v[x0]) on the two source rows followed by the same
+ * form vertically; fp16 sources are widened exactly first.
+ * src_lo: device [N][C][h][w] of `dt`; dst_hi: device fp32 [N][C][s*h][s*w]. */
+int hp_resize(const void *src_lo, hp_dtype dt, int N, int C, int h, int w, int scale,
+              float *dst_hi, void *stream);
+
+/* Peak extraction from materialised hi-res confidence maps (first half of
+ * "parsing human pose topology", Section 2.2.1).  Channels 0..K-1 of the C_cm
+ * = K+1 channels are searched (the last one is background).  A pixel is a peak
+ * when its value exceeds thr and, among its in-bounds 8 neighbours, is greater
+ * than those earlier in raster order and not less than those later.
+ * cm_hi: device fp32 [N][C_cm][H][W]. */
+int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
+                  const hp_peaks *peaks, void *workspace, size_t ws_bytes,
+                  int32_t *status, void *stream);
+
+/* Limb scoring on materialised hi-res PAFs (Section 2.3, PAF family).  For
+ * limb l = (a, b) and every pair (i in peaks[a], j in peaks[b]) with distinct
+ * pixels: unit direction u = (B - A)/|B - A|; S samples at
+ * round_half_up(A + k/(S-1) * (B - A)), k = 0..S-1; d_k = fma(paf_y, u_y, paf_x*u_x);
+ * score = (d_0 + ... + d_{S-1}) / S summed in k order.  The pair is a candidate
+ * when at least ceil(min_valid_ratio * S) samples have d_k > paf_thr and
+ * score > 0.  paf_hi: device fp32 [N][2L][H][W]; peaks: as written by
+ * hp_find_peaks (counts above cap are clamped). */
+int hp_score_limbs(const float *paf_hi, int N, int H, int W,
+                   const hp_skeleton *skel, const hp_params *prm,
+                   const hp_peaks *peaks, const hp_pairs *cands,
+                   void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
+/* Matching and assembly (second half of "parsing human pose topology").
+ * Per (image, limb): candidates are taken in the strict order (score
+ * descending, i ascending, j ascending) and accepted when neither peak is
+ * taken yet; `conns` receives them in acceptance order (conns->cap must be at
+ * least peaks->cap).  Per image, limbs are folded in table order, connection
+ * (i, j, s) of limb (a, b), pa / pb = owners of the two peaks:
+ *   none owned   -> new person {a: i, b: j}, score = ps(a,i) + ps(b,j) + s
+ *   one owned    -> fill the owner's empty slot, score += peak score, += s
+ *                   (skipped when that slot is already filled)
+ *   same owner   -> score += s
+ *   two owners   -> when they share no part, the later-created is merged into
+ *                   the earlier-created, score = earlier + later, += s
+ *                   (skipped otherwise)
+ * Persons alive at the end with >= min_parts parts are written in creation order. */
+int hp_assemble(const hp_skeleton *skel, const hp_params *prm, int N,
+                const hp_peaks *peaks, const hp_pairs *cands,
+                const hp_pairs *conns, const hp_poses *poses,
+                void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
+/* The whole operator in one call: cm_lo / paf_lo in, peaks, candidates,
+ * connections and persons out, identical to hp_resize -> hp_find_peaks ->
+ * hp_score_limbs -> hp_assemble.  cm_lo: device [N][K+1][h][w], paf_lo: device
+ * [N][2L][h][w], both of `dt`.  cm_hi / paf_hi are optional outputs (device
+ * fp32 [N][K+1][8h][8w] and [N][2L][8h][8w]): when both are NULL the
+ * upsampled maps are never written to memory (peaks are found on values kept
+ * in registers, PAF samples are recomputed from the lo-res tensors with the
+ * same arithmetic); when both are given they are materialised as hp_resize
+ * would.  Giving only one of them is an error. */
+int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                   const hp_skeleton *skel, const hp_params *prm,
+                   float *cm_hi, float *paf_hi,
+                   const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns,
+                   const hp_poses *poses,
+                   void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
+/* Static string for an hp_error value. */
+const char *hp_strerror(int code);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int hp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* HP_H */

@@ -1,0 +1,251 @@
+"""ctypes binding of libhp.so: argument marshalling only, every step runs in the library.
+
+The functions carry the names of the C entry points (include/hp.h).  Tensors are torch
+tensors on the GPU; the current torch stream is passed as the HIP stream.  There is no
+fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_float, c_int, c_int32, c_size_t, c_void_p
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+
+HP_F32, HP_F16 = 0, 1
+STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
+
+EXPORTS = ("hp_workspace_bytes", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
+           "hp_postprocess", "hp_strerror", "hp_version")
+
+
+class HPError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {hp_strerror(code)} ({code})")
+
+
+class _Skeleton(Structure):
+    _fields_ = [("n_parts", c_int32), ("n_limbs", c_int32),
+                ("limb_a", POINTER(c_int32)), ("limb_b", POINTER(c_int32))]
+
+
+class _Params(Structure):
+    _fields_ = [("peak_thr", c_float), ("paf_thr", c_float), ("n_samples", c_int32),
+                ("min_valid_ratio", c_float), ("min_parts", c_int32), ("scale", c_int32)]
+
+
+class _Peaks(Structure):
+    _fields_ = [("x", c_void_p), ("y", c_void_p), ("score", c_void_p), ("count", c_void_p), ("cap", c_int32)]
+
+
+class _Pairs(Structure):
+    _fields_ = [("i", c_void_p), ("j", c_void_p), ("score", c_void_p), ("count", c_void_p), ("cap", c_int32)]
+
+
+class _Poses(Structure):
+    _fields_ = [("slots", c_void_p), ("nparts", c_void_p), ("score", c_void_p), ("count", c_void_p),
+                ("cap", c_int32)]
+
+
+def lib_path():
+    return os.path.join(_PKG, "libhp.so")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2108_11826_amd.build)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: build it with `python -m paper_2108_11826_amd.build`")
+        L = ctypes.CDLL(path)
+        L.hp_workspace_bytes.restype = c_size_t
+        L.hp_workspace_bytes.argtypes = [c_int] * 9
+        L.hp_resize.restype = c_int
+        L.hp_resize.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+        L.hp_find_peaks.restype = c_int
+        L.hp_find_peaks.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, POINTER(_Peaks),
+                                    c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_score_limbs.restype = c_int
+        L.hp_score_limbs.argtypes = [c_void_p, c_int, c_int, c_int, POINTER(_Skeleton), POINTER(_Params),
+                                     POINTER(_Peaks), POINTER(_Pairs), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_assemble.restype = c_int
+        L.hp_assemble.argtypes = [POINTER(_Skeleton), POINTER(_Params), c_int, POINTER(_Peaks), POINTER(_Pairs),
+                                  POINTER(_Pairs), POINTER(_Poses), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_postprocess.restype = c_int
+        L.hp_postprocess.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
+                                     POINTER(_Params), c_void_p, c_void_p, POINTER(_Peaks), POINTER(_Pairs),
+                                     POINTER(_Pairs), POINTER(_Poses), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_strerror.restype = ctypes.c_char_p
+        L.hp_strerror.argtypes = [c_int]
+        L.hp_version.restype = c_int
+        L.hp_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def hp_strerror(code):
+    return lib().hp_strerror(int(code)).decode()
+
+
+def hp_version():
+    return int(lib().hp_version())
+
+
+def hp_workspace_bytes(N, K, L, h, w, scale, cap, ccap, pcap):
+    return int(lib().hp_workspace_bytes(N, K, L, h, w, scale, cap, ccap, pcap))
+
+
+class Skeleton:
+    """Host-side skeleton descriptor (keeps the limb arrays alive)."""
+
+    def __init__(self, n_parts, limb_a, limb_b):
+        self.limb_a = np.ascontiguousarray(limb_a, np.int32)
+        self.limb_b = np.ascontiguousarray(limb_b, np.int32)
+        self.n_parts = int(n_parts)
+        self.n_limbs = len(self.limb_a)
+        self.c = _Skeleton(self.n_parts, self.n_limbs,
+                           self.limb_a.ctypes.data_as(POINTER(c_int32)),
+                           self.limb_b.ctypes.data_as(POINTER(c_int32)))
+
+
+class Params:
+    def __init__(self, peak_thr=0.05, paf_thr=0.05, n_samples=10, min_valid_ratio=0.8, min_parts=3, scale=8):
+        self.c = _Params(peak_thr, paf_thr, n_samples, min_valid_ratio, min_parts, scale)
+        self.peak_thr, self.scale = float(peak_thr), int(scale)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return HP_F32
+    if t.dtype == torch.float16:
+        return HP_F16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t, dtype=None):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError("expected a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return c_void_p(t.data_ptr())
+
+
+def _stream():
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Buffers:
+    """Caller-owned output buffers and workspace for a given problem size, allocated once."""
+
+    def __init__(self, N, K, L, h, w, cap, ccap, pcap, device="cuda:0", scale=8):
+        self.N, self.K, self.L, self.h, self.w = N, K, L, h, w
+        self.cap, self.ccap, self.pcap = cap, ccap, pcap
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.px, self.py = torch.empty((N, K, cap), **i32), torch.empty((N, K, cap), **i32)
+        self.ps, self.pcount = torch.empty((N, K, cap), **f32), torch.empty((N, K), **i32)
+        self.ci, self.cj = torch.empty((N, L, ccap), **i32), torch.empty((N, L, ccap), **i32)
+        self.cs, self.ccount = torch.empty((N, L, ccap), **f32), torch.empty((N, L), **i32)
+        self.mi, self.mj = torch.empty((N, L, cap), **i32), torch.empty((N, L, cap), **i32)
+        self.ms, self.mcount = torch.empty((N, L, cap), **f32), torch.empty((N, L), **i32)
+        self.slots = torch.empty((N, pcap, K), **i32)
+        self.nparts, self.pscore = torch.empty((N, pcap), **i32), torch.empty((N, pcap), **f32)
+        self.pose_count = torch.empty((N,), **i32)
+        self.status = torch.zeros((1,), **i32)
+        self.ws_bytes = hp_workspace_bytes(N, K, L, h, w, scale, cap, ccap, pcap)
+        if self.ws_bytes == 0:
+            raise HPError(-1, "hp_workspace_bytes")
+        self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=device)
+        self.peaks = _Peaks(self.px.data_ptr(), self.py.data_ptr(), self.ps.data_ptr(), self.pcount.data_ptr(), cap)
+        self.cands = _Pairs(self.ci.data_ptr(), self.cj.data_ptr(), self.cs.data_ptr(), self.ccount.data_ptr(), ccap)
+        self.conns = _Pairs(self.mi.data_ptr(), self.mj.data_ptr(), self.ms.data_ptr(), self.mcount.data_ptr(), cap)
+        self.poses = _Poses(self.slots.data_ptr(), self.nparts.data_ptr(), self.pscore.data_ptr(),
+                            self.pose_count.data_ptr(), pcap)
+
+    def ws(self):
+        return c_void_p(self.workspace.data_ptr()), c_size_t(self.ws_bytes)
+
+    # ---- host copies as ragged lists (for tests and reports) ---------------
+    def host_status(self):
+        return int(self.status.cpu()[0])
+
+    def host_peaks(self):
+        cnt = self.pcount.cpu().numpy()
+        x, y, s = self.px.cpu().numpy(), self.py.cpu().numpy(), self.ps.cpu().numpy()
+        return [[(x[n, c, :min(cnt[n, c], self.cap)].copy(), y[n, c, :min(cnt[n, c], self.cap)].copy(),
+                  s[n, c, :min(cnt[n, c], self.cap)].copy()) for c in range(self.K)] for n in range(self.N)], cnt
+
+    def _host_pairs(self, i, j, s, count, cap):
+        cnt = count.cpu().numpy()
+        i, j, s = i.cpu().numpy(), j.cpu().numpy(), s.cpu().numpy()
+        return [[(i[n, l, :min(cnt[n, l], cap)].copy(), j[n, l, :min(cnt[n, l], cap)].copy(),
+                  s[n, l, :min(cnt[n, l], cap)].copy()) for l in range(self.L)] for n in range(self.N)], cnt
+
+    def host_cands(self):
+        return self._host_pairs(self.ci, self.cj, self.cs, self.ccount, self.ccap)
+
+    def host_conns(self):
+        return self._host_pairs(self.mi, self.mj, self.ms, self.mcount, self.cap)
+
+    def host_poses(self):
+        cnt = self.pose_count.cpu().numpy()
+        sl, npt, sc = self.slots.cpu().numpy(), self.nparts.cpu().numpy(), self.pscore.cpu().numpy()
+        return [(sl[n, :min(cnt[n], self.pcap)].copy(), npt[n, :min(cnt[n], self.pcap)].copy(),
+                 sc[n, :min(cnt[n], self.pcap)].copy()) for n in range(self.N)], cnt
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise HPError(rc, where)
+
+
+def hp_resize(src_lo, dst_hi=None, scale=8):
+    """src_lo [N, C, h, w] fp32/fp16 on the GPU -> dst_hi fp32 [N, C, 8h, 8w]."""
+    N, C, h, w = src_lo.shape
+    if dst_hi is None:
+        dst_hi = torch.empty((N, C, scale * h, scale * w), dtype=torch.float32, device=src_lo.device)
+    _check(lib().hp_resize(_dev(src_lo), _dtype_code(src_lo), N, C, h, w, scale, _dev(dst_hi, torch.float32),
+                           _stream()), "hp_resize")
+    return dst_hi
+
+
+def hp_find_peaks(cm_hi, K, thr, buf):
+    N, C_cm, H, W = cm_hi.shape
+    wsp, wsb = buf.ws()
+    _check(lib().hp_find_peaks(_dev(cm_hi, torch.float32), N, C_cm, K, H, W, thr, ctypes.byref(buf.peaks),
+                               wsp, wsb, _dev(buf.status), _stream()), "hp_find_peaks")
+
+
+def hp_score_limbs(paf_hi, skel, prm, buf):
+    N, C, H, W = paf_hi.shape
+    wsp, wsb = buf.ws()
+    _check(lib().hp_score_limbs(_dev(paf_hi, torch.float32), N, H, W, ctypes.byref(skel.c), ctypes.byref(prm.c),
+                                ctypes.byref(buf.peaks), ctypes.byref(buf.cands), wsp, wsb, _dev(buf.status),
+                                _stream()), "hp_score_limbs")
+
+
+def hp_assemble(skel, prm, buf):
+    wsp, wsb = buf.ws()
+    _check(lib().hp_assemble(ctypes.byref(skel.c), ctypes.byref(prm.c), buf.N, ctypes.byref(buf.peaks),
+                             ctypes.byref(buf.cands), ctypes.byref(buf.conns), ctypes.byref(buf.poses),
+                             wsp, wsb, _dev(buf.status), _stream()), "hp_assemble")
+
+
+def hp_postprocess(cm_lo, paf_lo, skel, prm, buf, cm_hi=None, paf_hi=None):
+    N, C_cm, h, w = cm_lo.shape
+    if cm_lo.dtype != paf_lo.dtype:
+        raise TypeError("cm_lo and paf_lo must share a dtype")
+    wsp, wsb = buf.ws()
+    _check(lib().hp_postprocess(_dev(cm_lo), _dev(paf_lo), _dtype_code(cm_lo), N, h, w,
+                                ctypes.byref(skel.c), ctypes.byref(prm.c),
+                                _dev(cm_hi, torch.float32) if cm_hi is not None else None,
+                                _dev(paf_hi, torch.float32) if paf_hi is not None else None,
+                                ctypes.byref(buf.peaks), ctypes.byref(buf.cands), ctypes.byref(buf.conns),
+                                ctypes.byref(buf.poses), wsp, wsb, _dev(buf.status), _stream()),
+           "hp_postprocess")

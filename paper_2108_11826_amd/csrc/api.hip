@@ -1,0 +1,268 @@
+// C boundary of the library: argument checks, workspace layout and the order in which
+// the kernels are enqueued.  Declarations and contracts are in include/hp.h.
+#include <math.h>
+#include <string.h>
+
+#include "hp_dev.h"
+
+namespace hp {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Lays the workspace out from `base` (may be null when only the size is wanted).
+static bool layout(void *base, int N, int K, int L, int cap, int ccap, Workspace &ws)
+{
+    if (N <= 0 || K <= 0 || L <= 0 || cap <= 0 || ccap <= 0) return false;
+    if (K > HP_MAX_PARTS || L > HP_MAX_LIMBS || cap > HP_MAX_CAP || ccap > HP_MAX_CCAP) return false;
+    ws.cap2 = next_pow2(cap);
+    ws.ccap2 = next_pow2(ccap);
+    ws.wcap = (int)(((long long)K * cap) / 2 + 1);
+    size_t off = 0;
+    char *b = (char *)base;
+    auto take = [&](size_t bytes) {
+        char *p = b ? b + off : nullptr;
+        off = align_up(off + bytes, 256);
+        return p;
+    };
+    ws.peak_stage = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * K * ws.cap2);
+    ws.cand_stage = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * L * ws.ccap2);
+    ws.owner = (int32_t *)take(sizeof(int32_t) * (size_t)N * K * cap);
+    ws.wslots = (int32_t *)take(sizeof(int32_t) * (size_t)N * ws.wcap * K);
+    ws.wnparts = (int32_t *)take(sizeof(int32_t) * (size_t)N * ws.wcap);
+    ws.wscore = (float *)take(sizeof(float) * (size_t)N * ws.wcap);
+    ws.bytes = off;
+    return true;
+}
+
+static int check_skeleton(const hp_skeleton *sk, LimbTable &tab)
+{
+    if (!sk || !sk->limb_a || !sk->limb_b) return HP_ERR_INVALID_ARG;
+    if (sk->n_parts <= 0 || sk->n_limbs <= 0) return HP_ERR_INVALID_ARG;
+    if (sk->n_parts > HP_MAX_PARTS || sk->n_limbs > HP_MAX_LIMBS) return HP_ERR_UNSUPPORTED;
+    memset(&tab, 0, sizeof(tab));
+    for (int l = 0; l < sk->n_limbs; ++l) {
+        int a = sk->limb_a[l], b = sk->limb_b[l];
+        if (a < 0 || a >= sk->n_parts || b < 0 || b >= sk->n_parts || a == b) return HP_ERR_INVALID_ARG;
+        tab.a[l] = (int8_t)a;
+        tab.b[l] = (int8_t)b;
+    }
+    return HP_OK;
+}
+
+static int check_params(const hp_params *p, int &need)
+{
+    if (!p) return HP_ERR_INVALID_ARG;
+    if (p->scale != HP_SCALE) return HP_ERR_UNSUPPORTED;
+    if (p->n_samples < 2 || p->min_parts < 0) return HP_ERR_INVALID_ARG;
+    if (p->n_samples > HP_MAX_SAMPLES) return HP_ERR_UNSUPPORTED;
+    if (!(p->min_valid_ratio >= 0.0f && p->min_valid_ratio <= 1.0f)) return HP_ERR_INVALID_ARG;
+    if (!(p->peak_thr == p->peak_thr) || !(p->paf_thr == p->paf_thr)) return HP_ERR_INVALID_ARG;
+    need = (int)ceilf(p->min_valid_ratio * (float)p->n_samples);
+    return HP_OK;
+}
+
+static int check_peaks(const hp_peaks *p)
+{
+    if (!p || !p->x || !p->y || !p->score || !p->count) return HP_ERR_INVALID_ARG;
+    if (p->cap <= 0) return HP_ERR_INVALID_ARG;
+    if (p->cap > HP_MAX_CAP) return HP_ERR_UNSUPPORTED;
+    return HP_OK;
+}
+
+static int check_pairs(const hp_pairs *p, int max_cap)
+{
+    if (!p || !p->i || !p->j || !p->score || !p->count) return HP_ERR_INVALID_ARG;
+    if (p->cap <= 0) return HP_ERR_INVALID_ARG;
+    if (p->cap > max_cap) return HP_ERR_UNSUPPORTED;
+    return HP_OK;
+}
+
+static int check_poses(const hp_poses *p)
+{
+    if (!p || !p->slots || !p->nparts || !p->score || !p->count) return HP_ERR_INVALID_ARG;
+    if (p->cap <= 0) return HP_ERR_INVALID_ARG;
+    return HP_OK;
+}
+
+static int check_dims(int N, int C, int h, int w)
+{
+    if (N <= 0 || C <= 0 || h <= 0 || w <= 0) return HP_ERR_INVALID_ARG;
+    // hi-res plane keys (Y * W + X) and thread indices must fit 31 bits
+    if ((long long)h * w * 64 >= (1LL << 31)) return HP_ERR_UNSUPPORTED;
+    if (2LL * N * C * h * w >= (1LL << 31) - 4096) return HP_ERR_UNSUPPORTED;
+    return HP_OK;
+}
+
+static int check_ws(void *workspace, size_t ws_bytes, int N, int K, int L, int cap, int ccap, Workspace &ws)
+{
+    if (!layout(workspace, N, K, L, cap, ccap, ws)) return HP_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes < ws.bytes) return HP_ERR_WORKSPACE;
+    return HP_OK;
+}
+
+#define HP_TRY(expr)                      \
+    do {                                  \
+        int rc_ = (expr);                 \
+        if (rc_ != HP_OK) return rc_;     \
+    } while (0)
+
+#define HP_LAUNCH(expr)                              \
+    do {                                             \
+        if ((expr) != hipSuccess) return HP_ERR_HIP; \
+    } while (0)
+
+}  // namespace hp
+
+using namespace hp;
+
+extern "C" {
+
+size_t hp_workspace_bytes(int N, int K, int L, int h, int w, int scale, int cap, int ccap, int pcap)
+{
+    Workspace ws;
+    if (h <= 0 || w <= 0 || scale != HP_SCALE || pcap <= 0) return 0;
+    if (!layout(nullptr, N, K, L, cap, ccap, ws)) return 0;
+    return ws.bytes;
+}
+
+int hp_resize(const void *src_lo, hp_dtype dt, int N, int C, int h, int w, int scale, float *dst_hi, void *stream)
+{
+    if (!src_lo || !dst_hi) return HP_ERR_INVALID_ARG;
+    if (dt != HP_F32 && dt != HP_F16) return HP_ERR_DTYPE;
+    if (scale != HP_SCALE) return HP_ERR_UNSUPPORTED;
+    HP_TRY(check_dims(N, C, h, w));
+    if (((uintptr_t)dst_hi & 15) != 0) return HP_ERR_INVALID_ARG;
+    HP_LAUNCH(launch_resize_nms(src_lo, nullptr, dt, dst_hi, nullptr, N, C, C, 0, 0, h, w, 0.0f, nullptr, nullptr,
+                                0, 0, (hipStream_t)stream));
+    return HP_OK;
+}
+
+int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
+                  const hp_peaks *peaks, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!cm_hi || !status) return HP_ERR_INVALID_ARG;
+    if (N <= 0 || H <= 0 || W <= 0 || K <= 0 || C_cm < K) return HP_ERR_INVALID_ARG;
+    if (K > HP_MAX_PARTS) return HP_ERR_UNSUPPORTED;
+    if ((long long)H * W >= (1LL << 31) || (long long)N * K * ((H + 7) / 8) * ((W + 3) / 4) >= (1LL << 31) - 4096)
+        return HP_ERR_UNSUPPORTED;
+    if (!(thr == thr)) return HP_ERR_INVALID_ARG;
+    HP_TRY(check_peaks(peaks));
+    Workspace ws;
+    // only the peak staging area is used; it is the first region of the common layout
+    ws.cap2 = next_pow2(peaks->cap);
+    size_t need = sizeof(uint64_t) * (size_t)N * K * ws.cap2;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes < need) return HP_ERR_WORKSPACE;
+    ws.peak_stage = (uint64_t *)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(launch_init(peaks->count, N * K, nullptr, 0, status, s));
+    HP_LAUNCH(launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
+    HP_LAUNCH(launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, W, *peaks, status, s));
+    return HP_OK;
+}
+
+int hp_score_limbs(const float *paf_hi, int N, int H, int W, const hp_skeleton *skel, const hp_params *prm,
+                   const hp_peaks *peaks, const hp_pairs *cands, void *workspace, size_t ws_bytes,
+                   int32_t *status, void *stream)
+{
+    if (!paf_hi || !status) return HP_ERR_INVALID_ARG;
+    LimbTable tab;
+    int need;
+    HP_TRY(check_skeleton(skel, tab));
+    HP_TRY(check_params(prm, need));
+    if (N <= 0 || H <= 0 || W <= 0 || (H % HP_SCALE) != 0 || (W % HP_SCALE) != 0) return HP_ERR_INVALID_ARG;
+    HP_TRY(check_dims(N, 2 * skel->n_limbs, H / HP_SCALE, W / HP_SCALE));
+    HP_TRY(check_peaks(peaks));
+    HP_TRY(check_pairs(cands, HP_MAX_CCAP));
+    Workspace ws;
+    HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
+    hipStream_t s = (hipStream_t)stream;
+    const int K = skel->n_parts, L = skel->n_limbs;
+    HP_LAUNCH(launch_init(cands->count, N * L, nullptr, 0, status, s));
+    HP_LAUNCH(launch_score(paf_hi, nullptr, HP_F32, N, H / HP_SCALE, W / HP_SCALE, tab, K, L, *prm, need, *peaks,
+                           cands->count, ws.cand_stage, cands->cap, ws.ccap2, s));
+    HP_LAUNCH(launch_match(0, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *cands, status, s));
+    return HP_OK;
+}
+
+int hp_assemble(const hp_skeleton *skel, const hp_params *prm, int N, const hp_peaks *peaks,
+                const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
+                void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!status || N <= 0) return HP_ERR_INVALID_ARG;
+    LimbTable tab;
+    int need;
+    HP_TRY(check_skeleton(skel, tab));
+    HP_TRY(check_params(prm, need));
+    HP_TRY(check_peaks(peaks));
+    HP_TRY(check_pairs(cands, HP_MAX_CCAP));
+    HP_TRY(check_pairs(conns, HP_MAX_CAP));
+    HP_TRY(check_poses(poses));
+    if (conns->cap < peaks->cap) return HP_ERR_INVALID_ARG;
+    Workspace ws;
+    HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
+    hipStream_t s = (hipStream_t)stream;
+    const int K = skel->n_parts, L = skel->n_limbs;
+    HP_LAUNCH(launch_init(nullptr, 0, nullptr, 0, status, s));
+    HP_LAUNCH(launch_match(2, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
+    HP_LAUNCH(launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
+    return HP_OK;
+}
+
+int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                   const hp_skeleton *skel, const hp_params *prm, float *cm_hi, float *paf_hi,
+                   const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
+                   void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!cm_lo || !paf_lo || !status) return HP_ERR_INVALID_ARG;
+    if (dt != HP_F32 && dt != HP_F16) return HP_ERR_DTYPE;
+    if ((cm_hi == nullptr) != (paf_hi == nullptr)) return HP_ERR_INVALID_ARG;
+    LimbTable tab;
+    int need;
+    HP_TRY(check_skeleton(skel, tab));
+    HP_TRY(check_params(prm, need));
+    const int K = skel->n_parts, L = skel->n_limbs;
+    HP_TRY(check_dims(N, K + 1 + 2 * L, h, w));
+    HP_TRY(check_peaks(peaks));
+    HP_TRY(check_pairs(cands, HP_MAX_CCAP));
+    HP_TRY(check_pairs(conns, HP_MAX_CAP));
+    HP_TRY(check_poses(poses));
+    if (conns->cap < peaks->cap) return HP_ERR_INVALID_ARG;
+    if (cm_hi && ((((uintptr_t)cm_hi) | ((uintptr_t)paf_hi)) & 15) != 0) return HP_ERR_INVALID_ARG;
+    Workspace ws;
+    HP_TRY(check_ws(workspace, ws_bytes, N, K, L, peaks->cap, cands->cap, ws));
+    hipStream_t s = (hipStream_t)stream;
+
+    HP_LAUNCH(launch_init(peaks->count, N * K, cands->count, N * L, status, s));
+    if (cm_hi) {
+        // materialising form: every CM and PAF channel is written once, in one launch; peaks come
+        // from the values while they are still in registers
+        HP_LAUNCH(launch_resize_nms(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, K, h, w, prm->peak_thr,
+                                    peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
+    } else {
+        HP_LAUNCH(launch_resize_nms(cm_lo, nullptr, dt, nullptr, nullptr, N, K, K + 1, 0, K, h, w, prm->peak_thr,
+                                    peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
+    }
+    HP_LAUNCH(launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
+    HP_LAUNCH(launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, cands->count,
+                           ws.cand_stage, cands->cap, ws.ccap2, s));
+    HP_LAUNCH(launch_match(1, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
+    HP_LAUNCH(launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
+    return HP_OK;
+}
+
+const char *hp_strerror(int code)
+{
+    switch (code) {
+    case HP_OK: return "ok";
+    case HP_ERR_INVALID_ARG: return "invalid argument";
+    case HP_ERR_DTYPE: return "unknown dtype";
+    case HP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case HP_ERR_HIP: return "kernel launch failed";
+    case HP_ERR_UNSUPPORTED: return "size beyond the built limits";
+    default: return "unknown error";
+    }
+}
+
+int hp_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,150 @@
+// Device-side helpers and launcher declarations shared by the kernel files.
+// Internal to the library; the public boundary is include/hp.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "hp.h"
+
+namespace hp {
+
+constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
+constexpr int kWave = 64;
+constexpr int kLdsSort = 4096;    // 64-bit keys a workgroup sorts in LDS; longer lists sort in global memory
+
+// Limb table passed to kernels by value.
+struct LimbTable {
+    int8_t a[HP_MAX_LIMBS];
+    int8_t b[HP_MAX_LIMBS];
+};
+
+// Where the pieces of the caller's workspace live (element offsets resolved on the host).
+struct Workspace {
+    uint64_t *peak_stage;   // [N*K][cap2]   unordered (key << 32 | score bits)
+    uint64_t *cand_stage;   // [N*L][ccap2]  unordered ((i << 16 | j) << 32 | score bits)
+    int32_t *owner;         // [N][K][cap]   person owning each peak
+    int32_t *wslots;        // [N][wcap][K]  working person table
+    int32_t *wnparts;       // [N][wcap]     (-1 = merged away)
+    float *wscore;          // [N][wcap]
+    int cap2, ccap2, wcap;
+    size_t bytes;
+};
+
+inline int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+template <typename T> __device__ __forceinline__ float ld(const T *p);
+template <> __device__ __forceinline__ float ld<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ld<__half>(const __half *p) { return __half2float(*p); }
+
+// One axis of the x8 half-pixel bilinear map: output index X reads nodes i0, i1 with weight f on i1.
+__device__ __forceinline__ void axis8(int X, int n, int &i0, int &i1, float &f)
+{
+    int num = 2 * X - 7;                       // 16 * source coordinate
+    if (num < 0) {
+        i0 = 0;
+        f = 0.0f;
+    } else {
+        i0 = num >> 4;
+        f = (float)(num & 15) * 0.0625f;
+    }
+    i1 = min(i0 + 1, n - 1);
+}
+
+// Upsampled value of one lo-res plane at hi-res pixel (Y, X): horizontal pass on the two
+// source rows, then the vertical pass, each a rounded product followed by one fma.
+template <typename T>
+__device__ __forceinline__ float up_lo(const T *lo, int h, int w, int Y, int X)
+{
+    int x0, x1, y0, y1;
+    float f, g;
+    axis8(X, w, x0, x1, f);
+    axis8(Y, h, y0, y1, g);
+    const T *r0p = lo + (size_t)y0 * w, *r1p = lo + (size_t)y1 * w;
+    float r0 = __fmaf_rn(f, ld(r0p + x1), (1.0f - f) * ld(r0p + x0));
+    float r1 = __fmaf_rn(f, ld(r1p + x1), (1.0f - f) * ld(r1p + x0));
+    return __fmaf_rn(g, r1, (1.0f - g) * r0);
+}
+
+// Ascending bitonic sort of n2 (a power of two) 64-bit keys by the whole workgroup.
+// `a` may be LDS or global memory; ends with a barrier.
+__device__ __forceinline__ void block_bitonic_sort(uint64_t *a, int n2)
+{
+    for (int k = 2; k <= n2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (n2 >> 1); t += blockDim.x) {
+                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                int p = i | j;
+                uint64_t x = a[i], y = a[p];
+                bool up = (i & k) == 0;
+                if ((x > y) == up) {
+                    a[i] = y;
+                    a[p] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Exclusive prefix of a per-thread flag over the workgroup (thread order) and the total.
+// `scratch` holds at least blockDim.x / 64 + 1 ints of LDS.  Contains two barriers.
+__device__ __forceinline__ int block_flag_scan(bool flag, int *scratch, int &total)
+{
+    unsigned long long m = __ballot(flag);
+    int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+    int within = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0) scratch[wv] = __popcll(m);
+    __syncthreads();
+    int nw = (blockDim.x + kWave - 1) >> 6;
+    int before = 0, tot = 0;
+    for (int q = 0; q < nw; ++q) {
+        int c = scratch[q];
+        if (q < wv) before += c;
+        tot += c;
+    }
+    __syncthreads();
+    total = tot;
+    return before + within;
+}
+
+// ---- launchers (each enqueues on `s` and returns the launch error) ----------
+
+hipError_t launch_init(int32_t *a, int na, int32_t *b, int nb, int32_t *status, hipStream_t s);
+
+// Upsampling with optional materialisation (hi_a != nullptr) and optional fused peak detection.
+// One launch covers channels [0, Ca) of tensor a (Ca_mem channels per image in memory) and all
+// Cb channels of tensor b (Cb may be 0); the first Knms channels of tensor a are searched.
+hipError_t launch_resize_nms(const void *lo_a, const void *lo_b, hp_dtype dt, float *hi_a, float *hi_b, int N,
+                             int Ca, int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
+                             uint64_t *stage, int cap, int cap2, hipStream_t s);
+
+hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
+                         int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);
+
+hipError_t launch_sort_peaks(uint64_t *stage, int cap, int cap2, int planes, int W, const hp_peaks &pk,
+                             int32_t *status, hipStream_t s);
+
+// PAF sampled either from hi-res fp32 maps (paf_hi != nullptr) or recomputed from lo-res.
+hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                        const LimbTable &T, int K, int L, const hp_params &prm, int need,
+                        const hp_peaks &pk, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
+                        hipStream_t s);
+
+// mode 0: staged candidates -> ordered candidate lists; 1: the same, then matching;
+// 2: ordered candidate lists in -> matching.
+hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
+                        uint64_t *cstage, int ccap2, const hp_pairs &cands, const hp_pairs &conns,
+                        int32_t *status, hipStream_t s);
+
+hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,
+                           const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
+                           int32_t *status, hipStream_t s);
+
+}  // namespace hp

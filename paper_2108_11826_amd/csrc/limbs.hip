@@ -1,0 +1,212 @@
+// Limb scoring (PAF line integral over every candidate pair) and per-limb greedy
+// matching: the PAF-family part (Section 2.3) of the post-processing operator of the
+// paper's inference engine (Section 2.2.1, operator 4).  Arithmetic as stated at
+// hp_score_limbs / hp_assemble in hp.h.
+#include "hp_dev.h"
+
+namespace hp {
+
+// grid = (chunks, N*L).  Each thread owns candidate pairs p = i * nB + j of its (image, limb),
+// strided by the whole row of workgroups; a score is never reduced across lanes, so the
+// summation order is the sample order.  Accepted pairs are appended unordered, tagged with
+// (i << 16 | j); the matching kernel orders them.
+template <typename T, bool FROM_HI>
+__global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
+                                                  int h, int w, LimbTable tab, int K, int L, int S,
+                                                  float paf_thr, int need,
+                                                  const int32_t *__restrict__ pcounts,
+                                                  const int32_t *__restrict__ px, const int32_t *__restrict__ py,
+                                                  int cap, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2)
+{
+    const int nl = blockIdx.y;
+    const int n = nl / L, l = nl - n * L;
+    const int a = tab.a[l], b = tab.b[l];
+    const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
+    const int P = nA * nB;
+    const int stride = gridDim.x * kBlock;
+    int p = blockIdx.x * kBlock + threadIdx.x;
+    if (p - (int)threadIdx.x >= P) return;
+
+    const int32_t *xa = px + (size_t)(n * K + a) * cap, *ya = py + (size_t)(n * K + a) * cap;
+    const int32_t *xb = px + (size_t)(n * K + b) * cap, *yb = py + (size_t)(n * K + b) * cap;
+    const int H = 8 * h, W = 8 * w;
+    const float *hx = FROM_HI ? paf_hi + ((size_t)n * 2 * L + 2 * l) * (size_t)H * W : nullptr;
+    const float *hy = FROM_HI ? hx + (size_t)H * W : nullptr;
+    const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
+    const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
+    const float fS1 = (float)(S - 1), fS = (float)S;
+    const int max_bad = S - need;
+
+    for (; p < P; p += stride) {
+        const int i = p / nB, j = p - i * nB;
+        const int x0 = xa[i], y0 = ya[i];
+        const int dx = xb[j] - x0, dy = yb[j] - y0;
+        if (dx == 0 && dy == 0) continue;
+        const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)x0, fy0 = (float)y0;
+        const float norm = sqrtf((float)(dx * dx + dy * dy));
+        const float ux = fdx / norm, uy = fdy / norm;
+        float acc = 0.0f;
+        int bad = 0;
+        for (int k = 0; k < S; ++k) {
+            const float t = (float)k / fS1;
+            // samples of a segment between two in-map pixels are in the map; the clamp only
+            // guards against peak lists that were not produced by this library
+            const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
+            const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
+            float vx, vy;
+            if (FROM_HI) {
+                const size_t o = (size_t)sy * W + sx;
+                vx = hx[o];
+                vy = hy[o];
+            } else {
+                vx = up_lo(lx, h, w, sy, sx);
+                vy = up_lo(ly, h, w, sy, sx);
+            }
+            const float d = __fmaf_rn(vy, uy, vx * ux);
+            if (!(d > paf_thr)) {
+                if (++bad > max_bad) break;     // cannot reach `need` valid samples any more
+            }
+            acc = acc + d;
+        }
+        if (bad > max_bad) continue;
+        const float score = acc / fS;
+        if (score > 0.0f) {
+            const int slot = atomicAdd(&ccounts[nl], 1);
+            if (slot < ccap)
+                cstage[(size_t)nl * ccap2 + slot] =
+                    ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+        }
+    }
+}
+
+hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                        const LimbTable &T, int K, int L, const hp_params &prm, int need,
+                        const hp_peaks &pk, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
+                        hipStream_t s)
+{
+    // enough workgroups per (image, limb) to spread cap^2 pairs, few enough that idle ones are cheap
+    long long pairs = (long long)pk.cap * pk.cap;
+    int chunks = (int)((pairs + kBlock * 16 - 1) / (kBlock * 16));
+    if (chunks < 4) chunks = 4;
+    if (chunks > 128) chunks = 128;
+    dim3 grid(chunks, N * L), block(kBlock);
+    if (paf_hi)
+        hipLaunchKernelGGL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, K, L,
+                           prm.n_samples, prm.paf_thr, need, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap,
+                           ccap2);
+    else if (dt == HP_F16)
+        hipLaunchKernelGGL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
+                           (const __half *)paf_lo, h, w, T, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
+                           pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
+    else
+        hipLaunchKernelGGL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
+                           (const float *)paf_lo, h, w, T, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
+                           pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
+    return hipGetLastError();
+}
+
+// One workgroup per (image, limb).
+//   MODE 0: staged candidates -> sorted by (i, j) -> candidate lists.
+//   MODE 1: the same, then sorted by (score desc, i, j) -> greedy matching -> connections.
+//   MODE 2: candidate lists in -> matching -> connections.
+// Scores are positive, so their bit patterns order like the values; the matching key is
+// (~score bits) << 32 | (i << 16 | j), ascending.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
+                                                  const int32_t *__restrict__ pcounts, int cap,
+                                                  uint64_t *cstage, int ccap2,
+                                                  int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap,
+                                                  int32_t *mcounts, int32_t *mi, int32_t *mj, float *ms, int mcap,
+                                                  int32_t *status)
+{
+    __shared__ uint64_t sk[kLdsSort];
+    __shared__ uint32_t usedA[HP_MAX_CAP / 32], usedB[HP_MAX_CAP / 32];
+    const int nl = blockIdx.x;
+    const int n = nl / L, l = nl - n * L;
+    const int cnt = ccounts[nl];
+    const int c = max(min(cnt, ccap), 0);
+    if (cnt > ccap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
+    int n2 = 1;
+    while (n2 < c) n2 <<= 1;
+    uint64_t *g = cstage + (size_t)nl * ccap2;
+    const bool in_lds = n2 <= kLdsSort;
+    uint64_t *keys = in_lds ? sk : g;
+    const size_t co = (size_t)nl * ccap;
+
+    if (MODE != 2) {
+        if (in_lds) {
+            for (int t = threadIdx.x; t < n2; t += kBlock) sk[t] = t < c ? g[t] : ~0ull;
+        } else {
+            for (int t = c + threadIdx.x; t < n2; t += kBlock) g[t] = ~0ull;
+        }
+        __syncthreads();
+        block_bitonic_sort(keys, n2);
+        for (int t = threadIdx.x; t < c; t += kBlock) {
+            uint64_t e = keys[t];
+            uint32_t ij = (uint32_t)(e >> 32);
+            ci[co + t] = (int32_t)(ij >> 16);
+            cj[co + t] = (int32_t)(ij & 0xffffu);
+            cs[co + t] = __uint_as_float((uint32_t)e);
+            keys[t] = ((uint64_t)(~(uint32_t)e) << 32) | ij;
+        }
+        if (MODE == 0) return;
+    } else {
+        for (int t = threadIdx.x; t < n2; t += kBlock) {
+            uint64_t e = ~0ull;
+            if (t < c) {
+                uint32_t ij = ((uint32_t)ci[co + t] << 16) | (uint32_t)cj[co + t];
+                e = ((uint64_t)(~__float_as_uint(cs[co + t])) << 32) | ij;
+            }
+            keys[t] = e;
+        }
+    }
+    const int a = tab.a[l], b = tab.b[l];
+    const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
+    for (int t = threadIdx.x; t < (nA + 31) / 32; t += kBlock) usedA[t] = 0;
+    for (int t = threadIdx.x; t < (nB + 31) / 32; t += kBlock) usedB[t] = 0;
+    __syncthreads();
+    block_bitonic_sort(keys, n2);
+
+    if (threadIdx.x == 0) {
+        const int limit = min(min(nA, nB), mcap);
+        const size_t mo = (size_t)nl * mcap;
+        int m = 0;
+        for (int t = 0; t < c && m < limit; ++t) {
+            uint64_t e = keys[t];
+            uint32_t ij = (uint32_t)e;
+            uint32_t i = ij >> 16, j = ij & 0xffffu;
+            if (i >= (uint32_t)nA || j >= (uint32_t)nB) continue;   // only possible for foreign candidate lists
+            if ((usedA[i >> 5] >> (i & 31)) & 1u) continue;
+            if ((usedB[j >> 5] >> (j & 31)) & 1u) continue;
+            usedA[i >> 5] |= 1u << (i & 31);
+            usedB[j >> 5] |= 1u << (j & 31);
+            mi[mo + m] = (int32_t)i;
+            mj[mo + m] = (int32_t)j;
+            ms[mo + m] = __uint_as_float(~(uint32_t)(e >> 32));
+            ++m;
+        }
+        mcounts[nl] = m;
+    }
+}
+
+hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
+                        uint64_t *cstage, int ccap2, const hp_pairs &cands, const hp_pairs &conns,
+                        int32_t *status, hipStream_t s)
+{
+    dim3 grid(N * L), block(kBlock);
+    if (mode == 0)
+        hipLaunchKernelGGL((k_match<0>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cstage, ccap2, cands.count,
+                           cands.i, cands.j, cands.score, cands.cap, (int32_t *)nullptr, (int32_t *)nullptr,
+                           (int32_t *)nullptr, (float *)nullptr, 0, status);
+    else if (mode == 1)
+        hipLaunchKernelGGL((k_match<1>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cstage, ccap2, cands.count,
+                           cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j, conns.score,
+                           conns.cap, status);
+    else
+        hipLaunchKernelGGL((k_match<2>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cstage, ccap2, cands.count,
+                           cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j, conns.score,
+                           conns.cap, status);
+    return hipGetLastError();
+}
+
+}  // namespace hp

@@ -1,0 +1,304 @@
+// Upsampling (x8 half-pixel bilinear) with optional materialisation and fused peak
+// detection, peak detection on materialised maps, and the ordering of peak lists.
+//
+// These are the "resizing" and the first half of the post-processing operator of the
+// paper's inference engine (Section 2.2, Section 2.2.1 operator 4).  The arithmetic is
+// the one stated at hp_resize / hp_find_peaks in hp.h.
+#include "hp_dev.h"
+
+namespace hp {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__global__ void k_init(int32_t *a, int na, int32_t *b, int nb, int32_t *status)
+{
+    int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g < na) a[g] = 0;
+    if (g < nb) b[g] = 0;
+    if (g == 0 && status) *status = 0;
+}
+
+hipError_t launch_init(int32_t *a, int na, int32_t *b, int nb, int32_t *status, hipStream_t s)
+{
+    int n = na > nb ? na : nb;
+    if (n < 1) n = 1;
+    hipLaunchKernelGGL(k_init, dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, a, na, b, nb, status);
+    return hipGetLastError();
+}
+
+__device__ __forceinline__ void emit_peak(int32_t *counts, uint64_t *stage, int plane, int cap, int cap2,
+                                          int key, float u)
+{
+    int slot = atomicAdd(&counts[plane], 1);
+    if (slot < cap)
+        stage[(size_t)plane * cap2 + slot] = ((uint64_t)(uint32_t)key << 32) | (uint64_t)__float_as_uint(u);
+}
+
+// One thread owns the 8-row x 4-column hi-res tile rows [8j, 8j+8), columns [8m+4hf, 8m+4hf+4)
+// of one plane: everything it needs (the tile plus a one-pixel halo) is a function of the
+// 3x3 lo-res neighbourhood of node (j, m).  Consecutive threads own consecutive 16-byte
+// column groups, so every row store of a wavefront is one contiguous 1 KiB run.
+//
+// Column X = 8m + t (t = -1..8) reads nodes (m-1, m) with weight (2t+9)/16 for t <= 3 and
+// nodes (m, m+1) with weight (2t-7)/16 for t >= 4; left of node 0 the weight is 0 and right
+// of node w-1 the upper node is clamped.  Rows alike.
+template <typename T, bool WRITE, bool NMS>
+__global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
+                                                       float *__restrict__ hi_a, float *__restrict__ hi_b,
+                                                       int total, int Ca, int Ca_mem, int Cb, int Knms,
+                                                       int h, int w, float thr, int32_t *counts, uint64_t *stage,
+                                                       int cap, int cap2)
+{
+    int g = blockIdx.x * kBlock + threadIdx.x;
+    if (g >= total) return;
+    int hf = g & 1;
+    int q = g >> 1;
+    int m = q % w; q /= w;
+    int j = q % h; q /= h;
+    const int Cg = Ca + Cb;
+    int c = q % Cg;
+    int n = q / Cg;
+
+    // channels [0, Ca) come from tensor a (Ca_mem channels per image), the rest from tensor b
+    const bool in_a = c < Ca;
+    const size_t plane_mem = in_a ? (size_t)n * Ca_mem + c : (size_t)n * Cb + (c - Ca);
+    const T *pl = (in_a ? lo_a : lo_b) + plane_mem * (size_t)h * w;
+    int jr[3] = {max(j - 1, 0), j, min(j + 1, h - 1)};
+    int mc[3] = {max(m - 1, 0), m, min(m + 1, w - 1)};
+
+    // column weights for the 6 columns t = 4hf-1 .. 4hf+4
+    float fx[6];
+    bool lft[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        int t = 4 * hf - 1 + k;
+        lft[k] = t <= 3;
+        fx[k] = lft[k] ? (m == 0 ? 0.0f : (float)(2 * t + 9) * 0.0625f) : (float)(2 * t - 7) * 0.0625f;
+    }
+
+    // horizontal pass on the three source rows
+    float hr[3][6];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const T *row = pl + (size_t)jr[r] * w;
+        float vl = ld(row + mc[0]), vc = ld(row + mc[1]), vr = ld(row + mc[2]);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            float a = lft[k] ? vl : vc;
+            float b = lft[k] ? vc : vr;
+            hr[r][k] = __fmaf_rn(fx[k], b, (1.0f - fx[k]) * a);
+        }
+    }
+
+    const int W = 8 * w, H = 8 * h;
+    const int X0 = 8 * m + 4 * hf, Y0 = 8 * j;
+    const bool do_nms = NMS && c < Knms;      // Knms <= Ca: searched channels lead tensor a
+    const float ninf = -__builtin_huge_valf();
+    const bool xlo_out = X0 == 0, xhi_out = X0 + 4 >= W;
+
+    // vertical pass, rows r = -1..8, rolling three rows for the 3x3 test
+    float v[10][6];
+#pragma unroll
+    for (int r = -1; r <= 8; ++r) {
+        const bool top = r <= 3;
+        const float gconst = top ? (float)(2 * r + 9) * 0.0625f : (float)(2 * r - 7) * 0.0625f;
+        const float gy = (top && j == 0) ? 0.0f : gconst;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            float a = top ? hr[0][k] : hr[1][k];
+            float b = top ? hr[1][k] : hr[2][k];
+            v[r + 1][k] = __fmaf_rn(gy, b, (1.0f - gy) * a);
+        }
+    }
+
+    if (WRITE) {
+        float *dst = (in_a ? hi_a : hi_b) + (plane_mem * H + Y0) * (size_t)W + X0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            v4f o = {v[r + 1][1], v[r + 1][2], v[r + 1][3], v[r + 1][4]};
+            __builtin_nontemporal_store(o, (v4f *)(dst + (size_t)r * W));
+        }
+    }
+
+    if (do_nms) {
+        // neighbours outside the map do not take part
+        if (xlo_out) {
+#pragma unroll
+            for (int r = 0; r < 10; ++r) v[r][0] = ninf;
+        }
+        if (xhi_out) {
+#pragma unroll
+            for (int r = 0; r < 10; ++r) v[r][5] = ninf;
+        }
+        if (j == 0) {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) v[0][k] = ninf;
+        }
+        if (j == h - 1) {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) v[9][k] = ninf;
+        }
+        const int plane = n * Knms + c;
+#pragma unroll
+        for (int r = 1; r <= 8; ++r) {
+#pragma unroll
+            for (int k = 1; k <= 4; ++k) {
+                float u = v[r][k];
+                float early = fmaxf(fmaxf(v[r - 1][k - 1], v[r - 1][k]), fmaxf(v[r - 1][k + 1], v[r][k - 1]));
+                float late = fmaxf(fmaxf(v[r + 1][k - 1], v[r + 1][k]), fmaxf(v[r + 1][k + 1], v[r][k + 1]));
+                if (u > thr && u > early && u >= late)
+                    emit_peak(counts, stage, plane, cap, cap2, (Y0 + r - 1) * W + X0 + k - 1, u);
+            }
+        }
+    }
+}
+
+template <typename T>
+static hipError_t launch_resize_nms_t(const T *lo_a, const T *lo_b, float *hi_a, float *hi_b, int N, int Ca,
+                                      int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
+                                      uint64_t *stage, int cap, int cap2, hipStream_t s)
+{
+    long long total64 = 2LL * N * (Ca + Cb) * h * w;
+    if (total64 <= 0 || total64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
+    int total = (int)total64;
+    dim3 grid((total + kBlock - 1) / kBlock), block(kBlock);
+    const bool write = hi_a != nullptr, nms = Knms > 0;
+    if (write && nms)
+        hipLaunchKernelGGL((k_resize_nms<T, true, true>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem,
+                           Cb, Knms, h, w, thr, counts, stage, cap, cap2);
+    else if (write)
+        hipLaunchKernelGGL((k_resize_nms<T, true, false>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem,
+                           Cb, Knms, h, w, thr, counts, stage, cap, cap2);
+    else if (nms)
+        hipLaunchKernelGGL((k_resize_nms<T, false, true>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem,
+                           Cb, Knms, h, w, thr, counts, stage, cap, cap2);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_resize_nms(const void *lo_a, const void *lo_b, hp_dtype dt, float *hi_a, float *hi_b, int N,
+                             int Ca, int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
+                             uint64_t *stage, int cap, int cap2, hipStream_t s)
+{
+    if (dt == HP_F16)
+        return launch_resize_nms_t((const __half *)lo_a, (const __half *)lo_b, hi_a, hi_b, N, Ca, Ca_mem, Cb, Knms, h,
+                                   w, thr, counts, stage, cap, cap2, s);
+    return launch_resize_nms_t((const float *)lo_a, (const float *)lo_b, hi_a, hi_b, N, Ca, Ca_mem, Cb, Knms, h, w,
+                               thr, counts, stage, cap, cap2, s);
+}
+
+// Peak detection on a materialised map.  One thread owns an 8-row x 4-column tile and reads
+// it with a one-pixel halo; pixels outside the map read as -inf.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_nms_hi(const float *__restrict__ cm, int total, int C_cm, int K,
+                                                   int H, int W, int tiles_x, int tiles_y, float thr,
+                                                   int32_t *counts, uint64_t *stage, int cap, int cap2)
+{
+    int g = blockIdx.x * kBlock + threadIdx.x;
+    if (g >= total) return;
+    int q = g;
+    int tx = q % tiles_x; q /= tiles_x;
+    int ty = q % tiles_y; q /= tiles_y;
+    int c = q % K;
+    int n = q / K;
+    const float *pl = cm + ((size_t)n * C_cm + c) * (size_t)H * W;
+    const float ninf = -__builtin_huge_valf();
+    const int X0 = 4 * tx, Y0 = 8 * ty;
+
+    float v[10][6];
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        int Y = Y0 + r - 1;
+        bool yin = Y >= 0 && Y < H;
+        const float *row = pl + (size_t)(yin ? Y : 0) * W;
+        if (VEC) {
+            // W % 4 == 0: the four centre columns are in bounds and 16-byte aligned
+            v4f cvec = yin ? *(const v4f *)(row + X0) : (v4f){ninf, ninf, ninf, ninf};
+            v[r][1] = cvec.x; v[r][2] = cvec.y; v[r][3] = cvec.z; v[r][4] = cvec.w;
+            v[r][0] = (yin && X0 > 0) ? row[X0 - 1] : ninf;
+            v[r][5] = (yin && X0 + 4 < W) ? row[X0 + 4] : ninf;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 6; ++k) {
+                int X = X0 + k - 1;
+                v[r][k] = (yin && X >= 0 && X < W) ? row[X] : ninf;
+            }
+        }
+    }
+    const int plane = n * K + c;
+#pragma unroll
+    for (int r = 1; r <= 8; ++r) {
+#pragma unroll
+        for (int k = 1; k <= 4; ++k) {
+            float u = v[r][k];
+            float early = fmaxf(fmaxf(v[r - 1][k - 1], v[r - 1][k]), fmaxf(v[r - 1][k + 1], v[r][k - 1]));
+            float late = fmaxf(fmaxf(v[r + 1][k - 1], v[r + 1][k]), fmaxf(v[r + 1][k + 1], v[r][k + 1]));
+            // a pixel outside the map holds -inf and never exceeds thr
+            if (u > thr && u > early && u >= late)
+                emit_peak(counts, stage, plane, cap, cap2, (Y0 + r - 1) * W + X0 + k - 1, u);
+        }
+    }
+}
+
+hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
+                         int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s)
+{
+    int tiles_x = (W + 3) / 4, tiles_y = (H + 7) / 8;
+    long long total64 = (long long)N * K * tiles_x * tiles_y;
+    if (total64 <= 0 || total64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
+    int total = (int)total64;
+    dim3 grid((total + kBlock - 1) / kBlock), block(kBlock);
+    if (W % 4 == 0 && ((uintptr_t)cm_hi % 16) == 0)
+        hipLaunchKernelGGL((k_nms_hi<true>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
+                           counts, stage, cap, cap2);
+    else
+        hipLaunchKernelGGL((k_nms_hi<false>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
+                           counts, stage, cap, cap2);
+    return hipGetLastError();
+}
+
+// One workgroup per (image, part): sorts the unordered staged peaks by raster key and
+// writes the ordered list.
+__global__ __launch_bounds__(kBlock) void k_sort_peaks(uint64_t *stage, int cap, int cap2, int W,
+                                                       const int32_t *counts, int32_t *px, int32_t *py,
+                                                       float *ps, int32_t *status)
+{
+    __shared__ uint64_t sk[kLdsSort];
+    const int plane = blockIdx.x;
+    const int cnt = counts[plane];
+    const int n = max(min(cnt, cap), 0);
+    if (cnt > cap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
+    if (n == 0) return;
+    int n2 = 1;
+    while (n2 < n) n2 <<= 1;
+    uint64_t *g = stage + (size_t)plane * cap2;
+    uint64_t *keys;
+    if (n2 <= kLdsSort) {
+        for (int t = threadIdx.x; t < n2; t += kBlock) sk[t] = t < n ? g[t] : ~0ull;
+        keys = sk;
+    } else {
+        for (int t = n + threadIdx.x; t < n2; t += kBlock) g[t] = ~0ull;
+        keys = g;
+    }
+    __syncthreads();
+    block_bitonic_sort(keys, n2);
+    for (int t = threadIdx.x; t < n; t += kBlock) {
+        uint64_t e = keys[t];
+        int key = (int)(e >> 32);
+        size_t o = (size_t)plane * cap + t;
+        px[o] = key % W;
+        py[o] = key / W;
+        ps[o] = __uint_as_float((uint32_t)e);
+    }
+}
+
+hipError_t launch_sort_peaks(uint64_t *stage, int cap, int cap2, int planes, int W, const hp_peaks &pk,
+                             int32_t *status, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_sort_peaks, dim3(planes), dim3(kBlock), 0, s, stage, cap, cap2, W, pk.count, pk.x, pk.y,
+                       pk.score, status);
+    return hipGetLastError();
+}
+
+}  // namespace hp

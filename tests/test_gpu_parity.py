@@ -1,0 +1,201 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import CONFIGS, COCO18, BODY25, SynthConfig, generate, DEFAULT_PARAMS
+from parity import assert_lists_equal, assert_poses_equal, run_oracle, caps_for, close
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def hp():
+    import paper_2108_11826_amd as m
+    return m
+
+
+def prm_of(p=DEFAULT_PARAMS):
+    return hp().Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, p.scale)
+
+
+def skel_of(sk):
+    return hp().Skeleton(sk.n_parts, sk.limb_a, sk.limb_b)
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+SMALL = [
+    SynthConfig(10, COCO18, 2, 5, 7, 1, scale_lo=20, scale_hi=40, noise_sd=0.05),
+    SynthConfig(11, COCO18, 1, 1, 9, 1, scale_lo=20, scale_hi=40, noise_sd=0.05),
+    SynthConfig(12, COCO18, 1, 9, 1, 1, scale_lo=20, scale_hi=40, noise_sd=0.05),
+    SynthConfig(13, COCO18, 3, 33, 47, 6, noise_sd=0.02, dropout=0.1, n_spurious=10),
+    SynthConfig(14, BODY25, 2, 31, 65, 5, noise_sd=0.02, dtype="float16"),
+    SynthConfig(15, COCO18, 1, 2, 2, 1, scale_lo=10, scale_hi=12, noise_sd=0.05),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"syn{c.index}")
+def test_resize_bit_exact(cfg):
+    b = generate(cfg)
+    for lo in (b.cm, b.paf):
+        got = hp().hp_resize(to_dev(lo)).cpu().numpy()
+        want = oracle.resize(lo, 8)
+        assert got.shape == want.shape
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def run_staged(b, ora, caps=None):
+    """hp_resize -> hp_find_peaks -> hp_score_limbs -> hp_assemble."""
+    m = hp()
+    cfg = b.config
+    sk = cfg.skeleton
+    cap, ccap, pcap = caps or caps_for(ora)
+    N = b.cm.shape[0]
+    buf = m.Buffers(N, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, cap, ccap, pcap, DEV)
+    skel, prm = skel_of(sk), prm_of()
+    cm_hi = m.hp_resize(to_dev(b.cm))
+    paf_hi = m.hp_resize(to_dev(b.paf))
+    st = []
+    m.hp_find_peaks(cm_hi, sk.n_parts, DEFAULT_PARAMS.peak_thr, buf)
+    st.append(buf.host_status())
+    m.hp_score_limbs(paf_hi, skel, prm, buf)
+    st.append(buf.host_status())
+    m.hp_assemble(skel, prm, buf)
+    st.append(buf.host_status())
+    return buf, st
+
+
+def run_fused(b, ora, materialise, caps=None):
+    m = hp()
+    cfg = b.config
+    sk = cfg.skeleton
+    cap, ccap, pcap = caps or caps_for(ora)
+    N = b.cm.shape[0]
+    buf = m.Buffers(N, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, cap, ccap, pcap, DEV)
+    cm, paf = to_dev(b.cm), to_dev(b.paf)
+    cm_hi = paf_hi = None
+    if materialise:
+        cm_hi = torch.empty((N, sk.n_parts + 1, cfg.H, cfg.W), dtype=torch.float32, device=DEV)
+        paf_hi = torch.empty((N, 2 * sk.n_limbs, cfg.H, cfg.W), dtype=torch.float32, device=DEV)
+    m.hp_postprocess(cm, paf, skel_of(sk), prm_of(), buf, cm_hi, paf_hi)
+    return buf, cm_hi, paf_hi
+
+
+def check_all(buf, ora):
+    assert buf.host_status() == 0
+    assert_lists_equal("peaks", buf.host_peaks()[0], ora["peaks"])
+    assert_lists_equal("candidates", buf.host_cands()[0], ora["candidates"])
+    assert_lists_equal("connections", buf.host_conns()[0], ora["conns"])
+    assert_poses_equal(buf.host_poses()[0], ora["poses"])
+
+
+@pytest.mark.parametrize("cfg", SMALL + [CONFIGS[0], CONFIGS[1]], ids=lambda c: f"syn{c.index}")
+def test_staged_calls_match_oracle(cfg):
+    b = generate(cfg)
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    buf, st = run_staged(b, ora)
+    assert st == [0, 0, 0]
+    check_all(buf, ora)
+
+
+@pytest.mark.parametrize("materialise", [False, True], ids=["fused", "materialised"])
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"syn{c.index}")
+def test_postprocess_small(cfg, materialise):
+    b = generate(cfg)
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    buf, cm_hi, paf_hi = run_fused(b, ora, materialise)
+    check_all(buf, ora)
+    if materialise:
+        for got, lo in ((cm_hi, b.cm), (paf_hi, b.paf)):
+            want = oracle.resize(lo, 8)
+            assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("materialise", [False, True], ids=["fused", "materialised"])
+@pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
+def test_postprocess_full_configs(ci, materialise):
+    """The five workloads at full size, in the launch configuration the benchmark times."""
+    cfg = CONFIGS[ci]
+    print(f"config {ci} materialise={materialise}", flush=True)
+    b = generate(cfg)
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    buf, cm_hi, paf_hi = run_fused(b, ora, materialise)
+    check_all(buf, ora)
+    if materialise:
+        # the maps are large: compare a sample of whole planes bit for bit
+        rng = np.random.default_rng(ci)
+        for got, lo in ((cm_hi, b.cm), (paf_hi, b.paf)):
+            for _ in range(3):
+                n, c = int(rng.integers(lo.shape[0])), int(rng.integers(lo.shape[1]))
+                want = oracle.resize(lo[n, c], 8)
+                assert np.array_equal(got[n, c].cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_results_are_deterministic():
+    b = generate(CONFIGS[2])
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    outs = []
+    for _ in range(3):
+        buf, _, _ = run_fused(b, ora, False)
+        outs.append((buf.host_peaks(), buf.host_cands(), buf.host_conns(), buf.host_poses()))
+    for o in outs[1:]:
+        assert_lists_equal("peaks", o[0][0], outs[0][0][0])
+        assert_lists_equal("candidates", o[1][0], outs[0][1][0])
+        assert_lists_equal("connections", o[2][0], outs[0][2][0])
+        assert_poses_equal(o[3][0], outs[0][3][0])
+
+
+def test_empty_maps_give_empty_results():
+    cfg = SynthConfig(20, COCO18, 2, 12, 17, 0, noise_sd=0.0)
+    b = generate(cfg)
+    assert not b.cm[:, :-1].any()
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    for mat in (False, True):
+        buf, _, _ = run_fused(b, ora, mat, caps=(16, 16, 16))
+        check_all(buf, ora)
+        assert buf.host_peaks()[1].sum() == 0 and buf.host_poses()[1].sum() == 0
+
+
+def test_overflow_is_reported_not_hidden():
+    m = hp()
+    b = generate(CONFIGS[1])
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    true_counts = np.array([[len(p[0]) for p in im] for im in ora["peaks"]])
+    buf, _, _ = run_fused(b, ora, False, caps=(8, 1024, 64))
+    assert buf.host_status() & m.STATUS_PEAK_OVERFLOW
+    assert np.array_equal(buf.host_peaks()[1], true_counts)          # counts report the requirement
+    # candidate overflow: peaks fit, candidate lists do not
+    buf, _, _ = run_fused(b, ora, False, caps=(64, 2, 64))
+    assert buf.host_status() == m.STATUS_CAND_OVERFLOW
+    assert np.array_equal(buf.host_cands()[1], np.array([[len(c[0]) for c in im] for im in ora["candidates"]]))
+    # pose overflow
+    buf, _, _ = run_fused(b, ora, False, caps=(64, 1024, 2))
+    assert buf.host_status() == m.STATUS_POSE_OVERFLOW
+    assert buf.host_poses()[1][0] == len(ora["poses"][0][1])
+    assert_lists_equal("connections", buf.host_conns()[0], ora["conns"])
+
+
+def test_large_lists_sort_outside_lds():
+    """More peaks / candidates than the in-LDS sort holds: pure noise with a permissive PAF rule."""
+    from synth import Params
+    cfg = SynthConfig(21, COCO18, 1, 40, 64, 0, noise_sd=0.2)
+    b = generate(cfg)
+    p = Params(peak_thr=0.05, paf_thr=-1.0, n_samples=4, min_valid_ratio=0.5, min_parts=3)
+    sk = cfg.skeleton
+    # two limbs are enough to reach several thousand candidates each
+    la, lb = sk.limb_a[:2], sk.limb_b[:2]
+    paf = b.paf[:, :4]
+    ora = oracle.postprocess(b.cm, paf, la, lb, p, threads=8)
+    npk = max(len(x[0]) for x in ora["peaks"][0])
+    ncand = max(len(x[0]) for x in ora["candidates"][0])
+    assert npk > 300 and ncand > 5000
+    m = hp()
+    buf = m.Buffers(1, sk.n_parts, 2, cfg.h, cfg.w, 1024, 1 << 17, 4096, DEV)
+    m.hp_postprocess(to_dev(b.cm), to_dev(paf), m.Skeleton(sk.n_parts, la, lb),
+                     m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
+    check_all(buf, ora)
