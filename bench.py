@@ -1,0 +1,180 @@
+"""Benchmark: post-processed frames/s of hp_postprocess on synthetic CM/PAF tensors, with the
+roofline of the dominant HBM-bound kernel and the CPU oracle timed beside it.
+
+A step is one hp_postprocess call (upsampling, peak NMS, compaction, limb scoring, matching,
+assembly) over one batch that is already resident in HBM.  `value` is measured on the form
+that keeps the upsampled maps in registers; the same number of steps is then timed on the
+form that materialises the hi-res maps (its upsampling kernel is the HBM-bound one the
+roofline object describes), and once more with per-kernel event brackets for the kernel times.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# plain (non-packed) fp32 lane operations: 256 CUs x 4 SIMDs x 16 lanes/clk x 2.4 GHz
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=2, help="index into the synthetic workloads (2 = 656x368 batch 8)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work spent on the oracle baseline (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (images are independent; "
+              "a batch would be split across GPUs with no communication). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2108_11826_amd as hp
+    from synth import CONFIGS, generate, DEFAULT_PARAMS as P
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    cfg = CONFIGS[args.config]
+    sk = cfg.skeleton
+    N, K, L, h, w = cfg.batch, sk.n_parts, sk.n_limbs, cfg.h, cfg.w
+    batch = generate(cfg)
+    cm, paf = torch.from_numpy(batch.cm).to(dev), torch.from_numpy(batch.paf).to(dev)
+    skel = hp.Skeleton(K, sk.limb_a, sk.limb_b)
+    prm = hp.Params(P.peak_thr, P.paf_thr, P.n_samples, P.min_valid_ratio, P.min_parts, P.scale)
+    caps = {0: (64, 256, 64), 1: (128, 512, 128), 2: (128, 1024, 128), 3: (2048, 4096, 1024), 4: (1024, 4096, 512)}
+    cap, ccap, pcap = caps[args.config]
+    buf = hp.Buffers(N, K, L, h, w, cap, ccap, pcap, dev)
+    cm_hi = torch.empty((N, K + 1, cfg.H, cfg.W), dtype=torch.float32, device=dev)
+    paf_hi = torch.empty((N, 2 * L, cfg.H, cfg.W), dtype=torch.float32, device=dev)
+
+    def step(materialise):
+        if materialise:
+            hp.hp_postprocess(cm, paf, skel, prm, buf, cm_hi, paf_hi)
+        else:
+            hp.hp_postprocess(cm, paf, skel, prm, buf)
+
+    def timed(materialise):
+        for _ in range(args.warmup):
+            step(materialise)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(materialise)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    # correctness gate (outside the timed regions): the timed launch configuration against the oracle
+    import oracle
+    ora = oracle.postprocess(batch.cm, batch.paf, sk.limb_a, sk.limb_b, P, threads=min(16, len(os.sched_getaffinity(0))))
+    parity = True
+    for materialise in (False, True):
+        step(materialise)
+        torch.cuda.synchronize()
+        poses, _ = buf.host_poses()
+        peaks, _ = buf.host_peaks()
+        ok = buf.host_status() == 0
+        for n in range(N):
+            ok = ok and np.array_equal(poses[n][0], ora["poses"][n][0]) and np.array_equal(poses[n][2], ora["poses"][n][2])
+            for c in range(K):
+                ok = ok and all(np.array_equal(peaks[n][c][q], ora["peaks"][n][c][q]) for q in range(3))
+        parity = parity and bool(ok)
+
+    t_fused = timed(False)
+    t_mat = timed(True)
+
+    # per-kernel times: the same steps again with event brackets around every launch
+    hp.hp_profile_begin(2 * args.steps * 8)
+    for _ in range(args.steps):
+        step(False)
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    prof = hp.hp_profile_end()
+    kern_us = {k: 1e3 * ms / n for k, (ms, n) in prof.items()}
+
+    n_pairs = sum(len(ora["peaks"][n][a][0]) * len(ora["peaks"][n][b][0]) for n in range(N) for a, b in sk.limbs)
+    esz = batch.cm.dtype.itemsize
+    lo_bytes = (batch.cm.size + batch.paf.size) * esz
+    hi_bytes = (cm_hi.numel() + paf_hi.numel()) * 4
+    k1_bytes = lo_bytes + hi_bytes
+    k1_us = kern_us["resize_nms_write"]
+    achieved = k1_bytes / (k1_us * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_resize_nms_write_cfg{args.config}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    roofline = {"kernel": "k_resize_nms<write> (upsampling of all CM+PAF channels + fused peak NMS, hi-res maps "
+                          "materialised; dominant kernel of the materialising form)",
+                "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "bytes_per_launch": k1_bytes, "us_per_launch": round(k1_us, 2)}
+    # fused form: nothing but the lo-res CM is read; the bound is the plain ALUs
+    cm_px = N * K * cfg.H * cfg.W
+    fused_us = kern_us["resize_nms"]
+    fused_ach = 12.0 * cm_px / (fused_us * 1e-6) / 1e12
+    roofline_fused = {"kernel": "k_resize_nms (maps kept in registers; dominant kernel of the timed step)",
+                      "bound": "alu", "achieved": round(fused_ach, 2), "peak": round(ALU_PEAK_TLANEOPS, 1),
+                      "unit": "Tlane-op/s", "frac": round(fused_ach / ALU_PEAK_TLANEOPS, 4),
+                      "ops_per_launch": 12 * cm_px, "us_per_launch": round(fused_us, 2),
+                      "hbm_bytes_per_launch": batch.cm[:, :K].size * esz}
+    score_bytes = 80.0 * n_pairs
+    roofline_scoring = {"kernel": "k_score<hi> (PAF gathered from materialised maps)", "bound": "hbm",
+                        "achieved": round(score_bytes / (kern_us["score_hi"] * 1e-6) / 1e9, 2),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(score_bytes / (kern_us["score_hi"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 6),
+                        "bytes_per_launch": score_bytes, "pairs_per_launch": n_pairs,
+                        "us_per_launch": round(kern_us["score_hi"], 2),
+                        "us_per_launch_lo_res_form": round(kern_us["score_lo"], 2)}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        T = min(16, len(os.sched_getaffinity(0)))
+        t0 = time.perf_counter()
+        oracle.postprocess(batch.cm, batch.paf, sk.limb_a, sk.limb_b, P, threads=T)
+        one = time.perf_counter() - t0
+        reps = max(1, int(args.cpu_seconds / max(one * T, 1e-3)))      # cpu_seconds of CPU work in total
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            oracle.postprocess(batch.cm, batch.paf, sk.limb_a, sk.limb_b, P, threads=T)
+        dt = time.perf_counter() - t0
+        t1 = time.perf_counter()
+        oracle.postprocess(batch.cm, batch.paf, sk.limb_a, sk.limb_b, P, threads=1)
+        dt1 = time.perf_counter() - t1
+        cpu = {"value": round(N * reps / dt, 2), "unit": "frames/s", "cores": T, "kind": "oracle",
+               "sample": f"the same batch of {N} frames of workload {args.config}, {reps} repetitions, "
+                         f"(image, part) and (image, limb) calls farmed over {T} threads",
+               "single_thread_value": round(N / dt1, 2)}
+
+    value = N * args.steps / t_fused
+    out = {
+        "metric": "post-processed frames/s at 656x368 batch 8; achieved HBM GB/s vs peak",
+        "value": round(value, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * t_fused / args.steps, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if esz == 4 else "f16 storage, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}]: {sk.name}, batch {N}, input {cfg.W}x{cfg.H} "
+                               f"(CM {K + 1}x{h}x{w}, PAF {2 * L}x{h}x{w}, x8 upsampling), {cfg.n_people} planted "
+                               f"people per image", "form": "fused (hi-res maps never written)",
+                   "capacities": {"peaks": cap, "candidates": ccap, "persons": pcap}},
+        "parity_with_oracle": parity,
+        "value_materialised": round(N * args.steps / t_mat, 1),
+        "ms_per_step_materialised": round(1e3 * t_mat / args.steps, 5),
+        "kernel_us": {k: round(v, 2) for k, v in sorted(kern_us.items())},
+        "roofline": roofline, "roofline_fused": roofline_fused, "roofline_scoring": roofline_scoring,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -188,6 +188,31 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
                    const hp_poses *poses,
                    void *workspace, size_t ws_bytes, int32_t *status, void *stream);
 
+/* Per-kernel timing, for benchmarks only.  Between hp_profile_begin and hp_profile_end
+ * every kernel the library enqueues (from this process, any stream) is bracketed by a pair
+ * of HIP events recorded on its stream; at most `max_launches` launches are recorded, later
+ * ones run untimed.  hp_profile_end waits for the recorded events (it synchronises with the
+ * streams used), adds the elapsed milliseconds and the launch counts per hp_kernel_id into
+ * the two host arrays of HP_K_COUNT entries (either may be NULL), and leaves profiling off.
+ * Not thread-safe; the event bracket adds a few microseconds of stream time per launch, so
+ * whole-call throughput is measured with profiling off. */
+typedef enum {
+    HP_K_INIT = 0,         /* clears counters and the status word */
+    HP_K_RESIZE_NMS = 1,   /* upsampling + peak detection, maps kept in registers */
+    HP_K_RESIZE_NMS_W = 2, /* upsampling + peak detection, hi-res maps written */
+    HP_K_RESIZE_W = 3,     /* upsampling only, hi-res maps written (hp_resize) */
+    HP_K_NMS_HI = 4,       /* peak detection on materialised maps */
+    HP_K_SORT_PEAKS = 5,
+    HP_K_SCORE_LO = 6,     /* limb scoring, PAF recomputed from lo-res */
+    HP_K_SCORE_HI = 7,     /* limb scoring, PAF read from materialised maps */
+    HP_K_MATCH = 8,
+    HP_K_ASSEMBLE = 9,
+    HP_K_COUNT = 10
+} hp_kernel_id;
+int hp_profile_begin(int max_launches);
+int hp_profile_end(float *total_ms, int32_t *launches);
+const char *hp_kernel_name(int id);
+
 /* Static string for an hp_error value. */
 const char *hp_strerror(int code);
 

@@ -6,8 +6,8 @@ operator 4) in HIP kernels for gfx950.  PyTorch is used for device memory and st
 """
 from .binding import (HPError, Skeleton, Params, Buffers, lib, lib_path, hp_resize, hp_find_peaks,
                       hp_score_limbs, hp_assemble, hp_postprocess, hp_workspace_bytes, hp_strerror,
-                      hp_version, STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW)
+                      hp_version, hp_profile_begin, hp_profile_end, STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW)
 
 __all__ = ["HPError", "Skeleton", "Params", "Buffers", "lib", "lib_path", "hp_resize", "hp_find_peaks",
            "hp_score_limbs", "hp_assemble", "hp_postprocess", "hp_workspace_bytes", "hp_strerror",
-           "hp_version", "STATUS_PEAK_OVERFLOW", "STATUS_CAND_OVERFLOW", "STATUS_POSE_OVERFLOW"]
+           "hp_version", "hp_profile_begin", "hp_profile_end", "STATUS_PEAK_OVERFLOW", "STATUS_CAND_OVERFLOW", "STATUS_POSE_OVERFLOW"]

@@ -17,7 +17,8 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_strerror", "hp_version")
+           "hp_postprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version")
+HP_K_COUNT = 10
 
 
 class HPError(RuntimeError):
@@ -81,6 +82,12 @@ def lib():
         L.hp_postprocess.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
                                      POINTER(_Params), c_void_p, c_void_p, POINTER(_Peaks), POINTER(_Pairs),
                                      POINTER(_Pairs), POINTER(_Poses), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_profile_begin.restype = c_int
+        L.hp_profile_begin.argtypes = [c_int]
+        L.hp_profile_end.restype = c_int
+        L.hp_profile_end.argtypes = [POINTER(c_float), POINTER(c_int32)]
+        L.hp_kernel_name.restype = ctypes.c_char_p
+        L.hp_kernel_name.argtypes = [c_int]
         L.hp_strerror.restype = ctypes.c_char_p
         L.hp_strerror.argtypes = [c_int]
         L.hp_version.restype = c_int
@@ -95,6 +102,18 @@ def hp_strerror(code):
 
 def hp_version():
     return int(lib().hp_version())
+
+
+def hp_profile_begin(max_launches):
+    _check(lib().hp_profile_begin(int(max_launches)), "hp_profile_begin")
+
+
+def hp_profile_end():
+    """{kernel name: (total ms, launches)} of the launches recorded since hp_profile_begin."""
+    ms = (c_float * HP_K_COUNT)()
+    n = (c_int32 * HP_K_COUNT)()
+    _check(lib().hp_profile_end(ms, n), "hp_profile_end")
+    return {lib().hp_kernel_name(k).decode(): (float(ms[k]), int(n[k])) for k in range(HP_K_COUNT) if n[k] > 0}
 
 
 def hp_workspace_bytes(N, K, L, h, w, scale, cap, ccap, pcap):

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "hp_dev.h"
 
 namespace hp {
@@ -106,8 +108,41 @@ static int check_ws(void *workspace, size_t ws_bytes, int N, int K, int L, int c
         if (rc_ != HP_OK) return rc_;     \
     } while (0)
 
-#define HP_LAUNCH(expr)                              \
+// Optional per-kernel event brackets (hp_profile_begin / hp_profile_end).
+struct ProfRecord {
+    hipEvent_t start, stop;
+    int id;
+};
+static bool g_prof_on = false;
+static size_t g_prof_max = 0;
+static std::vector<ProfRecord> g_prof;
+
+struct ProfScope {
+    hipStream_t s;
+    hipEvent_t stop = nullptr;
+    ProfScope(int id, hipStream_t stream) : s(stream)
+    {
+        if (!g_prof_on || g_prof.size() >= g_prof_max) return;
+        ProfRecord r;
+        r.id = id;
+        if (hipEventCreate(&r.start) != hipSuccess) return;
+        if (hipEventCreate(&r.stop) != hipSuccess) {
+            (void)hipEventDestroy(r.start);
+            return;
+        }
+        (void)hipEventRecord(r.start, s);
+        stop = r.stop;
+        g_prof.push_back(r);
+    }
+    ~ProfScope()
+    {
+        if (stop) (void)hipEventRecord(stop, s);
+    }
+};
+
+#define HP_LAUNCH(id, expr)                          \
     do {                                             \
+        ProfScope scope_((id), s);                   \
         if ((expr) != hipSuccess) return HP_ERR_HIP; \
     } while (0)
 
@@ -132,8 +167,9 @@ int hp_resize(const void *src_lo, hp_dtype dt, int N, int C, int h, int w, int s
     if (scale != HP_SCALE) return HP_ERR_UNSUPPORTED;
     HP_TRY(check_dims(N, C, h, w));
     if (((uintptr_t)dst_hi & 15) != 0) return HP_ERR_INVALID_ARG;
-    HP_LAUNCH(launch_resize_nms(src_lo, nullptr, dt, dst_hi, nullptr, N, C, C, 0, 0, h, w, 0.0f, nullptr, nullptr,
-                                0, 0, (hipStream_t)stream));
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_RESIZE_W, launch_resize_nms(src_lo, nullptr, dt, dst_hi, nullptr, N, C, C, 0, 0, h, w, 0.0f,
+                                               nullptr, nullptr, 0, 0, s));
     return HP_OK;
 }
 
@@ -154,9 +190,9 @@ int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, floa
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes < need) return HP_ERR_WORKSPACE;
     ws.peak_stage = (uint64_t *)workspace;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(launch_init(peaks->count, N * K, nullptr, 0, status, s));
-    HP_LAUNCH(launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
-    HP_LAUNCH(launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, W, *peaks, status, s));
+    HP_LAUNCH(HP_K_INIT, launch_init(peaks->count, N * K, nullptr, 0, status, s));
+    HP_LAUNCH(HP_K_NMS_HI, launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
+    HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, W, *peaks, status, s));
     return HP_OK;
 }
 
@@ -177,10 +213,10 @@ int hp_score_limbs(const float *paf_hi, int N, int H, int W, const hp_skeleton *
     HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
     const int K = skel->n_parts, L = skel->n_limbs;
-    HP_LAUNCH(launch_init(cands->count, N * L, nullptr, 0, status, s));
-    HP_LAUNCH(launch_score(paf_hi, nullptr, HP_F32, N, H / HP_SCALE, W / HP_SCALE, tab, K, L, *prm, need, *peaks,
+    HP_LAUNCH(HP_K_INIT, launch_init(cands->count, N * L, nullptr, 0, status, s));
+    HP_LAUNCH(HP_K_SCORE_HI, launch_score(paf_hi, nullptr, HP_F32, N, H / HP_SCALE, W / HP_SCALE, tab, K, L, *prm, need, *peaks,
                            cands->count, ws.cand_stage, cands->cap, ws.ccap2, s));
-    HP_LAUNCH(launch_match(0, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *cands, status, s));
+    HP_LAUNCH(HP_K_MATCH, launch_match(0, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *cands, status, s));
     return HP_OK;
 }
 
@@ -202,9 +238,9 @@ int hp_assemble(const hp_skeleton *skel, const hp_params *prm, int N, const hp_p
     HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
     const int K = skel->n_parts, L = skel->n_limbs;
-    HP_LAUNCH(launch_init(nullptr, 0, nullptr, 0, status, s));
-    HP_LAUNCH(launch_match(2, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
-    HP_LAUNCH(launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
+    HP_LAUNCH(HP_K_INIT, launch_init(nullptr, 0, nullptr, 0, status, s));
+    HP_LAUNCH(HP_K_MATCH, launch_match(2, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
+    HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
     return HP_OK;
 }
 
@@ -232,22 +268,74 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     HP_TRY(check_ws(workspace, ws_bytes, N, K, L, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
 
-    HP_LAUNCH(launch_init(peaks->count, N * K, cands->count, N * L, status, s));
+    HP_LAUNCH(HP_K_INIT, launch_init(peaks->count, N * K, cands->count, N * L, status, s));
     if (cm_hi) {
         // materialising form: every CM and PAF channel is written once, in one launch; peaks come
         // from the values while they are still in registers
-        HP_LAUNCH(launch_resize_nms(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, K, h, w, prm->peak_thr,
+        HP_LAUNCH(HP_K_RESIZE_NMS_W, launch_resize_nms(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, K, h, w, prm->peak_thr,
                                     peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
     } else {
-        HP_LAUNCH(launch_resize_nms(cm_lo, nullptr, dt, nullptr, nullptr, N, K, K + 1, 0, K, h, w, prm->peak_thr,
+        HP_LAUNCH(HP_K_RESIZE_NMS, launch_resize_nms(cm_lo, nullptr, dt, nullptr, nullptr, N, K, K + 1, 0, K, h, w, prm->peak_thr,
                                     peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
     }
-    HP_LAUNCH(launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
-    HP_LAUNCH(launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, cands->count,
+    HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
+    HP_LAUNCH(paf_hi ? HP_K_SCORE_HI : HP_K_SCORE_LO, launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, cands->count,
                            ws.cand_stage, cands->cap, ws.ccap2, s));
-    HP_LAUNCH(launch_match(1, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
-    HP_LAUNCH(launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
+    HP_LAUNCH(HP_K_MATCH, launch_match(1, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
+    HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
     return HP_OK;
+}
+
+int hp_profile_begin(int max_launches)
+{
+    if (max_launches <= 0) return HP_ERR_INVALID_ARG;
+    for (auto &r : g_prof) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_prof.clear();
+    g_prof.reserve((size_t)max_launches);
+    g_prof_max = (size_t)max_launches;
+    g_prof_on = true;
+    return HP_OK;
+}
+
+int hp_profile_end(float *total_ms, int32_t *launches)
+{
+    g_prof_on = false;
+    int rc = HP_OK;
+    if (total_ms) for (int k = 0; k < HP_K_COUNT; ++k) total_ms[k] = 0.0f;
+    if (launches) for (int k = 0; k < HP_K_COUNT; ++k) launches[k] = 0;
+    for (auto &r : g_prof) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+            rc = HP_ERR_HIP;
+        else {
+            if (total_ms) total_ms[r.id] += ms;
+            if (launches) launches[r.id] += 1;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_prof.clear();
+    return rc;
+}
+
+const char *hp_kernel_name(int id)
+{
+    switch (id) {
+    case HP_K_INIT: return "init";
+    case HP_K_RESIZE_NMS: return "resize_nms";
+    case HP_K_RESIZE_NMS_W: return "resize_nms_write";
+    case HP_K_RESIZE_W: return "resize_write";
+    case HP_K_NMS_HI: return "nms_hi";
+    case HP_K_SORT_PEAKS: return "sort_peaks";
+    case HP_K_SCORE_LO: return "score_lo";
+    case HP_K_SCORE_HI: return "score_hi";
+    case HP_K_MATCH: return "match";
+    case HP_K_ASSEMBLE: return "assemble";
+    default: return "unknown";
+    }
 }
 
 const char *hp_strerror(int code)
