@@ -1,0 +1,143 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects invalid calls on the host before anything is enqueued."""
+import ctypes
+import os
+import re
+from ctypes import POINTER, byref, c_int32, c_void_p
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2108_11826_amd import binding
+    if not os.path.exists(binding.lib_path()):
+        from paper_2108_11826_amd import build
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "hp.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(hp_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    from paper_2108_11826_amd import binding
+    names = declared_functions()
+    assert {"hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble", "hp_postprocess",
+            "hp_workspace_bytes", "hp_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_the_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2108_11826_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "oracle")):
+        for f in files:
+            if f.endswith((".py", ".c")):
+                assert "paper_2108_11826_amd" not in open(os.path.join(dirpath, f)).read(), f
+
+
+def test_workspace_bytes(L):
+    a = L.hp_workspace_bytes(8, 18, 19, 46, 82, 8, 128, 1024, 128)
+    b = L.hp_workspace_bytes(8, 18, 19, 46, 82, 8, 256, 1024, 128)
+    c = L.hp_workspace_bytes(16, 18, 19, 46, 82, 8, 128, 1024, 128)
+    assert 0 < a < b and a < c and a % 256 == 0
+    assert L.hp_workspace_bytes(8, 18, 19, 46, 82, 4, 128, 1024, 128) == 0      # scale
+    assert L.hp_workspace_bytes(0, 18, 19, 46, 82, 8, 128, 1024, 128) == 0
+    assert L.hp_workspace_bytes(8, 18, 19, 46, 82, 8, 1 << 20, 1024, 128) == 0  # beyond HP_MAX_CAP
+    assert L.hp_workspace_bytes(8, 99, 19, 46, 82, 8, 128, 1024, 128) == 0      # beyond HP_MAX_PARTS
+
+
+def test_strerror_and_names(L):
+    assert L.hp_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert L.hp_strerror(code) not in (b"ok", b"unknown error")
+    assert L.hp_strerror(-99) == b"unknown error"
+    assert L.hp_version() >= 100
+    assert L.hp_kernel_name(1) == b"resize_nms" and L.hp_kernel_name(99) == b"unknown"
+
+
+FAKE = 0x10000   # a 256-aligned non-null address that is never dereferenced: these calls fail on the host
+
+
+def descriptors(cap=64, ccap=64, pcap=16):
+    from paper_2108_11826_amd import binding as B
+    la = np.array([0, 1], np.int32)
+    lb = np.array([1, 2], np.int32)
+    sk = B.Skeleton(3, la, lb)
+    prm = B.Params()
+    pk = B._Peaks(FAKE, FAKE, FAKE, FAKE, cap)
+    cd = B._Pairs(FAKE, FAKE, FAKE, FAKE, ccap)
+    cn = B._Pairs(FAKE, FAKE, FAKE, FAKE, cap)
+    ps = B._Poses(FAKE, FAKE, FAKE, FAKE, pcap)
+    return sk, prm, pk, cd, cn, ps
+
+
+def test_resize_rejects_bad_calls(L):
+    assert L.hp_resize(None, 0, 1, 1, 4, 4, 8, FAKE, None) == -1
+    assert L.hp_resize(FAKE, 0, 1, 1, 4, 4, 8, None, None) == -1
+    assert L.hp_resize(FAKE, 7, 1, 1, 4, 4, 8, FAKE, None) == -2
+    assert L.hp_resize(FAKE, 0, 1, 1, 4, 4, 4, FAKE, None) == -5
+    assert L.hp_resize(FAKE, 0, 0, 1, 4, 4, 8, FAKE, None) == -1
+    assert L.hp_resize(FAKE, 0, 1, 1, 4, 4, 8, FAKE + 4, None) == -1               # dst not 16-byte aligned
+    assert L.hp_resize(FAKE, 0, 4096, 4096, 64, 64, 8, FAKE, None) == -5           # index space too large
+
+
+def test_postprocess_rejects_bad_calls(L):
+    sk, prm, pk, cd, cn, ps = descriptors()
+    ws = L.hp_workspace_bytes(1, 3, 2, 4, 4, 8, 64, 64, 16)
+    args = lambda **kw: [kw.get("cm", FAKE), FAKE, kw.get("dt", 0), 1, 4, 4, byref(kw.get("sk", sk).c),
+                         byref(kw.get("prm", prm).c), kw.get("cm_hi", None), kw.get("paf_hi", None),
+                         byref(kw.get("pk", pk)), byref(cd), byref(kw.get("cn", cn)), byref(ps),
+                         kw.get("wsp", FAKE), kw.get("wsb", ws), kw.get("status", FAKE), None]
+    assert L.hp_postprocess(*args(cm=None)) == -1
+    assert L.hp_postprocess(*args(status=None)) == -1
+    assert L.hp_postprocess(*args(dt=3)) == -2
+    assert L.hp_postprocess(*args(cm_hi=FAKE)) == -1                # only one of the two optional outputs
+    assert L.hp_postprocess(*args(wsb=ws - 1)) == -3
+    assert L.hp_postprocess(*args(wsp=FAKE + 8)) == -3              # misaligned
+    assert L.hp_postprocess(*args(wsp=None)) == -3
+    from paper_2108_11826_amd import binding as B
+    assert L.hp_postprocess(*args(prm=B.Params(scale=4))) == -5
+    assert L.hp_postprocess(*args(prm=B.Params(n_samples=1))) == -1
+    assert L.hp_postprocess(*args(prm=B.Params(min_valid_ratio=1.5))) == -1
+    bad = B.Skeleton(3, np.array([0, 3], np.int32), np.array([1, 2], np.int32))     # part index out of range
+    assert L.hp_postprocess(*args(sk=bad)) == -1
+    small = B._Pairs(FAKE, FAKE, FAKE, FAKE, 8)                                     # conns cap < peaks cap
+    assert L.hp_postprocess(*args(cn=small)) == -1
+    huge = B._Peaks(FAKE, FAKE, FAKE, FAKE, 1 << 20)
+    assert L.hp_postprocess(*args(pk=huge)) == -5
+
+
+def test_staged_calls_reject_bad_calls(L):
+    sk, prm, pk, cd, cn, ps = descriptors()
+    ws = L.hp_workspace_bytes(1, 3, 2, 4, 4, 8, 64, 64, 16)
+    assert L.hp_find_peaks(None, 1, 4, 3, 32, 32, 0.05, byref(pk), FAKE, ws, FAKE, None) == -1
+    assert L.hp_find_peaks(FAKE, 1, 2, 3, 32, 32, 0.05, byref(pk), FAKE, ws, FAKE, None) == -1     # C_cm < K
+    assert L.hp_find_peaks(FAKE, 1, 4, 3, 32, 32, 0.05, byref(pk), FAKE, 8, FAKE, None) == -3
+    assert L.hp_find_peaks(FAKE, 1, 4, 3, 32, 32, float("nan"), byref(pk), FAKE, ws, FAKE, None) == -1
+    assert L.hp_score_limbs(FAKE, 1, 33, 32, byref(sk.c), byref(prm.c), byref(pk), byref(cd), FAKE, ws, FAKE, None) == -1
+    assert L.hp_score_limbs(FAKE, 1, 32, 32, byref(sk.c), byref(prm.c), byref(pk), byref(cd), FAKE, 16, FAKE, None) == -3
+    assert L.hp_assemble(byref(sk.c), byref(prm.c), 0, byref(pk), byref(cd), byref(cn), byref(ps), FAKE, ws, FAKE, None) == -1
+    assert L.hp_assemble(byref(sk.c), byref(prm.c), 1, byref(pk), byref(cd), byref(cn), byref(ps), FAKE, 16, FAKE, None) == -3
+    assert L.hp_profile_begin(0) == -1
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    from paper_2108_11826_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "lib_path", lambda: "/nonexistent/libhp.so")
+    with pytest.raises(ImportError):
+        binding.lib()
