@@ -26,11 +26,13 @@ static bool layout(void *base, int N, int K, int L, int cap, int ccap, Workspace
         off = align_up(off + bytes, 256);
         return p;
     };
+    ws.peak_ctr = (int32_t *)take(sizeof(int32_t) * (size_t)N * K * kCtrStride);
     ws.peak_stage = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * K * ws.cap2);
+    ws.cand_ctr = (int32_t *)take(sizeof(int32_t) * (size_t)N * L * kCtrStride);
     ws.cand_stage = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * L * ws.ccap2);
     ws.owner = (int32_t *)take(sizeof(int32_t) * (size_t)N * K * cap);
     ws.wslots = (int32_t *)take(sizeof(int32_t) * (size_t)N * ws.wcap * K);
-    ws.wnparts = (int32_t *)take(sizeof(int32_t) * (size_t)N * ws.wcap);
+    ws.wmask = (int32_t *)take(sizeof(int32_t) * (size_t)N * ws.wcap);
     ws.wscore = (float *)take(sizeof(float) * (size_t)N * ws.wcap);
     ws.bytes = off;
     return true;
@@ -184,15 +186,18 @@ int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, floa
     if (!(thr == thr)) return HP_ERR_INVALID_ARG;
     HP_TRY(check_peaks(peaks));
     Workspace ws;
-    // only the peak staging area is used; it is the first region of the common layout
+    // only the peak counters and the peak staging area are used: the first two regions of the
+    // common layout
     ws.cap2 = next_pow2(peaks->cap);
-    size_t need = sizeof(uint64_t) * (size_t)N * K * ws.cap2;
+    const size_t ctr_bytes = align_up(sizeof(int32_t) * (size_t)N * K * kCtrStride, 256);
+    const size_t need = ctr_bytes + sizeof(uint64_t) * (size_t)N * K * ws.cap2;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes < need) return HP_ERR_WORKSPACE;
-    ws.peak_stage = (uint64_t *)workspace;
+    ws.peak_ctr = (int32_t *)workspace;
+    ws.peak_stage = (uint64_t *)((char *)workspace + ctr_bytes);
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_INIT, launch_init(peaks->count, N * K, nullptr, 0, status, s));
-    HP_LAUNCH(HP_K_NMS_HI, launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
-    HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, W, *peaks, status, s));
+    HP_LAUNCH(HP_K_INIT, launch_init(ws.peak_ctr, N * K * kCtrStride, nullptr, 0, status, s));
+    HP_LAUNCH(HP_K_NMS_HI, launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, s));
+    HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, N * K, W, *peaks, status, s));
     return HP_OK;
 }
 
@@ -213,10 +218,10 @@ int hp_score_limbs(const float *paf_hi, int N, int H, int W, const hp_skeleton *
     HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
     const int K = skel->n_parts, L = skel->n_limbs;
-    HP_LAUNCH(HP_K_INIT, launch_init(cands->count, N * L, nullptr, 0, status, s));
+    HP_LAUNCH(HP_K_INIT, launch_init(ws.cand_ctr, N * L * kCtrStride, nullptr, 0, status, s));
     HP_LAUNCH(HP_K_SCORE_HI, launch_score(paf_hi, nullptr, HP_F32, N, H / HP_SCALE, W / HP_SCALE, tab, K, L, *prm, need, *peaks,
-                           cands->count, ws.cand_stage, cands->cap, ws.ccap2, s));
-    HP_LAUNCH(HP_K_MATCH, launch_match(0, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *cands, status, s));
+                           ws.cand_ctr, ws.cand_stage, cands->cap, ws.ccap2, s));
+    HP_LAUNCH(HP_K_MATCH, launch_match(0, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *cands, status, s));
     return HP_OK;
 }
 
@@ -239,7 +244,7 @@ int hp_assemble(const hp_skeleton *skel, const hp_params *prm, int N, const hp_p
     hipStream_t s = (hipStream_t)stream;
     const int K = skel->n_parts, L = skel->n_limbs;
     HP_LAUNCH(HP_K_INIT, launch_init(nullptr, 0, nullptr, 0, status, s));
-    HP_LAUNCH(HP_K_MATCH, launch_match(2, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
+    HP_LAUNCH(HP_K_MATCH, launch_match(2, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
     HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
     return HP_OK;
 }
@@ -268,20 +273,20 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     HP_TRY(check_ws(workspace, ws_bytes, N, K, L, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
 
-    HP_LAUNCH(HP_K_INIT, launch_init(peaks->count, N * K, cands->count, N * L, status, s));
+    HP_LAUNCH(HP_K_INIT, launch_init(ws.peak_ctr, N * K * kCtrStride, ws.cand_ctr, N * L * kCtrStride, status, s));
     if (cm_hi) {
         // materialising form: every CM and PAF channel is written once, in one launch; peaks come
         // from the values while they are still in registers
         HP_LAUNCH(HP_K_RESIZE_NMS_W, launch_resize_nms(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, K, h, w, prm->peak_thr,
-                                    peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
+                                    ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, s));
     } else {
         HP_LAUNCH(HP_K_RESIZE_NMS, launch_resize_nms(cm_lo, nullptr, dt, nullptr, nullptr, N, K, K + 1, 0, K, h, w, prm->peak_thr,
-                                    peaks->count, ws.peak_stage, peaks->cap, ws.cap2, s));
+                                    ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, s));
     }
-    HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
-    HP_LAUNCH(paf_hi ? HP_K_SCORE_HI : HP_K_SCORE_LO, launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, cands->count,
+    HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
+    HP_LAUNCH(paf_hi ? HP_K_SCORE_HI : HP_K_SCORE_LO, launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, ws.cand_ctr,
                            ws.cand_stage, cands->cap, ws.ccap2, s));
-    HP_LAUNCH(HP_K_MATCH, launch_match(1, tab, N, K, L, *peaks, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
+    HP_LAUNCH(HP_K_MATCH, launch_match(1, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
     HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
     return HP_OK;
 }

@@ -2,147 +2,362 @@
 // of the paper's inference engine (Section 2.2.1, operator 4, "parsing human pose
 // topology").  Rules as stated at hp_assemble in hp.h.
 //
-// Limbs are folded in table order, one barrier-separated step per limb; inside a limb all
-// connections are applied at once.  That is exact, not an approximation of the sequential
-// fold: the connections of one limb (a, b) use pairwise distinct peaks of a and of b, a
-// person holds at most one peak per part, hence a person can be the a-side owner of at
-// most one connection and the b-side owner of at most one.  A person that is both already
-// holds parts a and b, so every rule that could change it is a skip (its slot is filled,
-// or a merge partner shares a part).  Every person is therefore changed by at most one
-// connection per limb, and nothing a connection reads is written by another one.  New
-// persons are numbered by a prefix count in connection order, as the sequential fold would.
+// Limbs are folded in table order, one step per limb; inside a limb all connections are
+// applied at once.  That is exact, not an approximation of the sequential fold: the
+// connections of one limb (a, b) use pairwise distinct peaks of a and of b, a person holds at
+// most one peak per part, hence a person can be the a-side owner of at most one connection
+// and the b-side owner of at most one.  A person that is both already holds parts a and b, so
+// every rule that could change it is a skip (its slot is filled, or a merge partner shares a
+// part).  Every person is therefore changed by at most one connection per limb, and nothing a
+// connection reads is written by another one.  New persons are numbered by a prefix count in
+// connection order, as the sequential fold would.
+//
+// One wavefront works on one image.  When the image's tables fit the LDS pools (always, for
+// the workloads of interest) everything after the first gather runs out of LDS: a limb step is
+// a few dependent LDS accesses, not global-memory round trips.  Otherwise the same steps run
+// on tables in the caller's workspace.
 #include "hp_dev.h"
 
 namespace hp {
 
-__global__ __launch_bounds__(kBlock) void k_assemble(LimbTable tab, int K, int L, int min_parts,
-                                                     const int32_t *__restrict__ pcounts,
-                                                     const float *__restrict__ pscore, int cap,
-                                                     const int32_t *__restrict__ mcounts,
-                                                     const int32_t *__restrict__ mi,
-                                                     const int32_t *__restrict__ mj,
-                                                     const float *__restrict__ ms, int mcap,
-                                                     int32_t *owner_all, int32_t *wslots_all, int32_t *wnparts_all,
-                                                     float *wscore_all, int wcap,
-                                                     int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
-                                                     int32_t *pose_counts, int pcap, int32_t *status)
-{
-    __shared__ int scratch[kBlock / kWave + 1];
-    const int n = blockIdx.x;
-    int32_t *owner = owner_all + (size_t)n * K * cap;
-    int32_t *wslots = wslots_all + (size_t)n * wcap * K;
-    int32_t *wnparts = wnparts_all + (size_t)n * wcap;
-    float *wscore = wscore_all + (size_t)n * wcap;
-    const float *psc = pscore + (size_t)n * K * cap;
+constexpr int kPool16 = 40960;   // int16 entries: owner table, person slots, connection ends
+constexpr int kPool32 = 12288;   // 32-bit entries: person part masks and scores, connection and peak scores
 
-    for (int c = 0; c < K; ++c) {
-        int cnt = max(min(pcounts[n * K + c], cap), 0);
-        for (int r = threadIdx.x; r < cnt; r += kBlock) owner[c * cap + r] = -1;
+// Person tables addressed through one interface so that the fold is written once.  A person
+// is K slots (peak rank per part), a bit mask of the filled parts (its part count is the
+// mask's population count; an empty mask marks a person merged away) and a score.
+struct LdsTables {
+    int16_t *owner, *slots;
+    uint32_t *mask;
+    float *score;
+    int ostride, K;
+    __device__ int get_owner(int c, int r) const { return owner[c * ostride + r]; }
+    __device__ void set_owner(int c, int r, int p) { owner[c * ostride + r] = (int16_t)p; }
+    __device__ int get_slot(int p, int c) const { return slots[p * K + c]; }
+    __device__ void set_slot(int p, int c, int r) { slots[p * K + c] = (int16_t)r; }
+    __device__ uint32_t get_mask(int p) const { return mask[p]; }
+    __device__ void set_mask(int p, uint32_t v) { mask[p] = v; }
+    __device__ float get_score(int p) const { return score[p]; }
+    __device__ void set_score(int p, float v) { score[p] = v; }
+};
+
+struct GlobalTables {
+    int32_t *owner, *slots;
+    uint32_t *mask;
+    float *score;
+    int ostride, K;
+    __device__ int get_owner(int c, int r) const { return owner[(size_t)c * ostride + r]; }
+    __device__ void set_owner(int c, int r, int p) { owner[(size_t)c * ostride + r] = p; }
+    __device__ int get_slot(int p, int c) const { return slots[(size_t)p * K + c]; }
+    __device__ void set_slot(int p, int c, int r) { slots[(size_t)p * K + c] = r; }
+    __device__ uint32_t get_mask(int p) const { return mask[p]; }
+    __device__ void set_mask(int p, uint32_t v) { mask[p] = v; }
+    __device__ float get_score(int p) const { return score[p]; }
+    __device__ void set_score(int p, float v) { score[p] = v; }
+};
+
+constexpr uint32_t kDead = 0u;      // a living person holds at least two parts
+
+// Applies connection (i, j, s) of limb (a, b); sa / sb are the scores of the two peaks, pa / pb
+// their owners.  `fresh_id` is the number the person gets if this connection starts one.
+// The masks and scores of both owners are fetched together before any decision, so a limb
+// step is two dependent table reads deep whatever rule applies.
+template <typename Tab>
+__device__ __forceinline__ void apply_connection(Tab &t, int K, int a, int b, int i, int j, float s, float sa,
+                                                 float sb, int pa, int pb, int fresh_id, int max_persons)
+{
+    const uint32_t bit_a = 1u << a, bit_b = 1u << b;
+    const uint32_t ma = pa >= 0 ? t.get_mask(pa) : 0u, mb = pb >= 0 ? t.get_mask(pb) : 0u;
+    const float sca = pa >= 0 ? t.get_score(pa) : 0.0f, scb = pb >= 0 ? t.get_score(pb) : 0.0f;
+    if (pa < 0 && pb < 0) {
+        const int p = fresh_id;
+        if (p < max_persons) {
+            t.set_slot(p, a, i);
+            t.set_slot(p, b, j);
+            t.set_mask(p, bit_a | bit_b);
+            t.set_score(p, sa + sb + s);
+            t.set_owner(a, i, p);
+            t.set_owner(b, j, p);
+        }
+    } else if (pa >= 0 && pb < 0) {
+        if (!(ma & bit_b)) {
+            t.set_slot(pa, b, j);
+            t.set_mask(pa, ma | bit_b);
+            const float sc = sca + sb;
+            t.set_score(pa, sc + s);
+            t.set_owner(b, j, pa);
+        }
+    } else if (pa < 0 && pb >= 0) {
+        if (!(mb & bit_a)) {
+            t.set_slot(pb, a, i);
+            t.set_mask(pb, mb | bit_a);
+            const float sc = scb + sa;
+            t.set_score(pb, sc + s);
+            t.set_owner(a, i, pb);
+        }
+    } else if (pa == pb) {
+        t.set_score(pa, sca + s);
+    } else if ((ma & mb) == 0u) {
+        const int lo = min(pa, pb), hi = max(pa, pb);
+        const uint32_t mhi = pa < pb ? mb : ma;
+        for (int c = 0; c < K; ++c) {
+            if (mhi & (1u << c)) {
+                const int r = t.get_slot(hi, c);
+                t.set_slot(lo, c, r);
+                t.set_owner(c, r, lo);
+            }
+        }
+        t.set_mask(lo, ma | mb);
+        const float sc = (pa < pb) ? sca + scb : scb + sca;
+        t.set_score(lo, sc + s);
+        t.set_mask(hi, kDead);
     }
-    int np = 0;                                  // persons created so far (uniform over the workgroup)
+}
+
+// Alive persons with enough parts, in creation order.
+template <typename Tab>
+__device__ __forceinline__ void emit_persons(const Tab &t, int n, int np, int K, int min_parts,
+                                             int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
+                                             int32_t *pose_counts, int pcap, int32_t *status)
+{
+    const int lane = threadIdx.x;
+    int out = 0;
+    for (int base = 0; base < np; base += kWave) {
+        const int p = base + lane;
+        const uint32_t mk = (p < np) ? t.get_mask(p) : kDead;
+        const int parts = __popc(mk);
+        const bool keep = mk != kDead && parts >= min_parts;
+        const unsigned long long m = __ballot(keep);
+        const int rank = out + __popcll(m & ((1ull << lane) - 1ull));
+        if (keep && rank < pcap) {
+            const size_t o = (size_t)n * pcap + rank;
+            for (int c = 0; c < K; ++c) pose_slots[o * K + c] = (mk >> c) & 1u ? t.get_slot(p, c) : -1;
+            pose_nparts[o] = parts;
+            pose_score[o] = t.get_score(p);
+        }
+        out += __popcll(m);
+    }
+    if (lane == 0) {
+        pose_counts[n] = out;
+        if (out > pcap) atomicOr(status, (int)HP_STATUS_POSE_OVERFLOW);
+    }
+}
+
+__global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L, int min_parts,
+                                                    const int32_t *__restrict__ pcounts,
+                                                    const float *__restrict__ pscore, int cap,
+                                                    const int32_t *__restrict__ mcounts,
+                                                    const int32_t *__restrict__ mi,
+                                                    const int32_t *__restrict__ mj,
+                                                    const float *__restrict__ ms, int mcap,
+                                                    int32_t *owner_all, int32_t *wslots_all, int32_t *wmask_all,
+                                                    float *wscore_all, int wcap,
+                                                    int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
+                                                    int32_t *pose_counts, int pcap, int32_t *status)
+{
+    __shared__ int16_t pool[kPool16];
+    __shared__ uint32_t pool32[kPool32];
+    __shared__ int moff[HP_MAX_LIMBS + 1];
+    const int n = blockIdx.x;
+    const int lane = threadIdx.x;
+    const float *psc = pscore + (size_t)n * K * cap;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+
+    // connection counts -> offsets of each limb in the image's flat connection list
+    const int mc = (lane < L) ? max(min(mcounts[n * L + lane], mcap), 0) : 0;
+    int incl = mc;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int v = __shfl_up(incl, d);
+        if (lane >= d) incl += v;
+    }
+    const int tot = __shfl(incl, kWave - 1);
+    if (lane < L) moff[lane] = incl - mc;
+    if (lane == 0) moff[L] = tot;
+    int cmax = (lane < K) ? max(min(pcounts[n * K + lane], cap), 0) : 0;
+    for (int d = kWave / 2; d > 0; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
     __syncthreads();
 
+    // persons never outnumber connections
+    const bool fits = (long long)K * cmax + (long long)tot * K <= kPool16 && 7LL * tot <= kPool32 &&
+                      (long long)K * cmax <= 65535 && tot < 32767;
+    if (fits) {
+        // LDS tables.  Everything about a connection that does not depend on the fold's state is
+        // gathered once: its two owner-table indices, its two peak ranks, its score and the
+        // scores of its two peaks.
+        int16_t *owner = pool;                      // [K][cmax] person owning each peak, -1 = none
+        int16_t *slots = owner + K * cmax;          // [tot][K]  valid where the person's mask says so
+        uint32_t *pmask = pool32;                   // [tot]     filled parts of a person, 0 = merged away
+        float *pscr = (float *)(pool32 + tot);      // [tot]
+        uint32_t *c_own = pool32 + 2 * tot;         // [tot]     a*cmax+i | (b*cmax+j) << 16
+        uint32_t *c_ij = pool32 + 3 * tot;          // [tot]     i | j << 16
+        float *c_s = (float *)(pool32 + 4 * tot), *c_sa = c_s + tot, *c_sb = c_sa + tot;
+
+        for (int idx = lane; idx < K * cmax; idx += kWave) owner[idx] = -1;
+        constexpr int U = 4;
+        for (int e0 = 0; e0 < tot; e0 += kWave * U) {
+            int vi[U], vj[U], va[U], vb[U];
+            float vs[U], vsa[U], vsb[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int e = e0 + q * kWave + lane;
+                vi[q] = vj[q] = va[q] = vb[q] = 0;
+                vs[q] = 0.0f;
+                if (e < tot) {
+                    int l = 0;
+                    while (moff[l + 1] <= e) ++l;
+                    const size_t idx = (size_t)(n * L + l) * mcap + (e - moff[l]);
+                    vi[q] = mi[idx];
+                    vj[q] = mj[idx];
+                    vs[q] = ms[idx];
+                    va[q] = tab.a[l];
+                    vb[q] = tab.b[l];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int e = e0 + q * kWave + lane;
+                vsa[q] = vsb[q] = 0.0f;
+                if (e < tot) {
+                    vsa[q] = psc[va[q] * cap + vi[q]];
+                    vsb[q] = psc[vb[q] * cap + vj[q]];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int e = e0 + q * kWave + lane;
+                if (e < tot) {
+                    c_own[e] = (uint32_t)(va[q] * cmax + vi[q]) | ((uint32_t)(vb[q] * cmax + vj[q]) << 16);
+                    c_ij[e] = (uint32_t)vi[q] | ((uint32_t)vj[q] << 16);
+                    c_s[e] = vs[q];
+                    c_sa[e] = vsa[q];
+                    c_sb[e] = vsb[q];
+                }
+            }
+        }
+        // lane l keeps limb l's description; the fold reads it with uniform lane reads
+        const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
+        const int my_base = incl - mc;
+        __syncthreads();
+
+        int np = 0;
+        for (int l = 0; l < L; ++l) {
+            const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
+            const int base = __builtin_amdgcn_readlane(my_base, l), cnt = __builtin_amdgcn_readlane(mc, l);
+            const uint32_t bit_a = 1u << a, bit_b = 1u << b;
+            for (int k0 = 0; k0 < cnt; k0 += kWave) {
+                const int k = k0 + lane;
+                const bool act = k < cnt;
+                const int e = act ? base + k : 0;
+                const uint32_t own = c_own[e], ij = c_ij[e];
+                const float s = c_s[e], sa = c_sa[e], sb = c_sb[e];
+                const int oa = own & 0xffffu, ob = own >> 16;
+                const int i = ij & 0xffffu, j = ij >> 16;
+                const int pa = act ? (int)owner[oa] : -1, pb = act ? (int)owner[ob] : -1;
+                const bool has_a = pa >= 0, has_b = pb >= 0;
+                const uint32_t ma = has_a ? pmask[pa] : 0u, mb = has_b ? pmask[pb] : 0u;
+                const float sca = has_a ? pscr[pa] : 0.0f, scb = has_b ? pscr[pb] : 0.0f;
+
+                const bool fresh = act && !has_a && !has_b;
+                const unsigned long long fm = __ballot(fresh);
+                const bool ext_a = has_a && !has_b && !(ma & bit_b);      // the a-side owner gains part b
+                const bool ext_b = !has_a && has_b && !(mb & bit_a);      // the b-side owner gains part a
+                const bool cyc = has_a && pa == pb;
+                const bool mrg = has_a && has_b && pa != pb && (ma & mb) == 0u;
+                if (fresh || ext_a || ext_b || cyc) {
+                    const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
+                    const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
+                    const float s0 = fresh ? sa : has_a ? sca : scb;      // running score, then the new
+                    const float s1 = fresh ? sb : ext_a ? sb : sa;        // peak's score (if any), then s
+                    const float sc = cyc ? s0 : s0 + s1;
+                    pmask[p] = mk;
+                    pscr[p] = sc + s;
+                    if (fresh || ext_b) {
+                        slots[p * K + a] = (int16_t)i;
+                        owner[oa] = (int16_t)p;
+                    }
+                    if (fresh || ext_a) {
+                        slots[p * K + b] = (int16_t)j;
+                        owner[ob] = (int16_t)p;
+                    }
+                }
+                if (mrg) {
+                    const int lo = min(pa, pb), hi = max(pa, pb);
+                    const uint32_t mhi = pa < pb ? mb : ma;
+                    for (int c = 0; c < K; ++c) {
+                        if (mhi & (1u << c)) {
+                            const int16_t r = slots[hi * K + c];
+                            slots[lo * K + c] = r;
+                            owner[c * cmax + r] = (int16_t)lo;
+                        }
+                    }
+                    pmask[lo] = ma | mb;
+                    const float sc = (pa < pb) ? sca + scb : scb + sca;
+                    pscr[lo] = sc + s;
+                    pmask[hi] = kDead;
+                }
+                np += __popcll(fm);
+                __syncthreads();
+            }
+        }
+        LdsTables t;
+        t.owner = owner;
+        t.slots = slots;
+        t.mask = pmask;
+        t.score = pscr;
+        t.ostride = cmax;
+        t.K = K;
+        emit_persons(t, n, min(np, tot), K, min_parts, pose_slots, pose_nparts, pose_score, pose_counts, pcap,
+                     status);
+        return;
+    }
+
+    // tables too large for LDS: the same fold on the workspace tables
+    GlobalTables t;
+    t.owner = owner_all + (size_t)n * K * cap;
+    t.slots = wslots_all + (size_t)n * wcap * K;
+    t.mask = (uint32_t *)wmask_all + (size_t)n * wcap;
+    t.score = wscore_all + (size_t)n * wcap;
+    t.ostride = cap;
+    t.K = K;
+    for (int c = 0; c < K; ++c) {
+        const int cnt = max(min(pcounts[n * K + c], cap), 0);
+        for (int r = lane; r < cnt; r += kWave) t.owner[(size_t)c * cap + r] = -1;
+    }
+    __syncthreads();
+    int np = 0;
     for (int l = 0; l < L; ++l) {
         const int a = tab.a[l], b = tab.b[l];
-        const int cnt = max(min(mcounts[n * L + l], mcap), 0);
+        const int cnt = moff[l + 1] - moff[l];
         const size_t mo = (size_t)(n * L + l) * mcap;
-        for (int base = 0; base < cnt; base += kBlock) {
-            const int k = base + threadIdx.x;
+        for (int k0 = 0; k0 < cnt; k0 += kWave) {
+            const int k = k0 + lane;
             const bool act = k < cnt;
             int i = 0, j = 0, pa = -1, pb = -1;
-            float s = 0.0f;
+            float s = 0.0f, sa = 0.0f, sb = 0.0f;
             if (act) {
                 i = mi[mo + k];
                 j = mj[mo + k];
                 s = ms[mo + k];
-                pa = owner[a * cap + i];
-                pb = owner[b * cap + j];
+                sa = psc[a * cap + i];
+                sb = psc[b * cap + j];
+                pa = t.get_owner(a, i);
+                pb = t.get_owner(b, j);
             }
-            const bool fresh = act && pa < 0 && pb < 0;
-            int total;
-            const int rank = block_flag_scan(fresh, scratch, total);
-            if (fresh) {
-                const int p = np + rank;
-                if (p < wcap) {
-                    for (int c = 0; c < K; ++c) wslots[(size_t)p * K + c] = -1;
-                    wslots[(size_t)p * K + a] = i;
-                    wslots[(size_t)p * K + b] = j;
-                    wnparts[p] = 2;
-                    wscore[p] = psc[a * cap + i] + psc[b * cap + j] + s;
-                    owner[a * cap + i] = p;
-                    owner[b * cap + j] = p;
-                }
-            } else if (act && pa >= 0 && pb < 0) {
-                if (wslots[(size_t)pa * K + b] < 0) {
-                    wslots[(size_t)pa * K + b] = j;
-                    wnparts[pa] += 1;
-                    float sc = wscore[pa] + psc[b * cap + j];
-                    wscore[pa] = sc + s;
-                    owner[b * cap + j] = pa;
-                }
-            } else if (act && pa < 0 && pb >= 0) {
-                if (wslots[(size_t)pb * K + a] < 0) {
-                    wslots[(size_t)pb * K + a] = i;
-                    wnparts[pb] += 1;
-                    float sc = wscore[pb] + psc[a * cap + i];
-                    wscore[pb] = sc + s;
-                    owner[a * cap + i] = pb;
-                }
-            } else if (act && pa == pb) {
-                wscore[pa] = wscore[pa] + s;
-            } else if (act) {
-                const int lo = min(pa, pb), hi = max(pa, pb);
-                bool disjoint = true;
-                for (int c = 0; c < K; ++c)
-                    if (wslots[(size_t)lo * K + c] >= 0 && wslots[(size_t)hi * K + c] >= 0) disjoint = false;
-                if (disjoint) {
-                    for (int c = 0; c < K; ++c) {
-                        int r = wslots[(size_t)hi * K + c];
-                        if (r >= 0) {
-                            wslots[(size_t)lo * K + c] = r;
-                            owner[c * cap + r] = lo;
-                        }
-                    }
-                    wnparts[lo] += wnparts[hi];
-                    float sc = wscore[lo] + wscore[hi];
-                    wscore[lo] = sc + s;
-                    wnparts[hi] = -1;
-                }
-            }
-            np += total;
+            const unsigned long long fm = __ballot(act && pa < 0 && pb < 0);
+            if (act) apply_connection(t, K, a, b, i, j, s, sa, sb, pa, pb, np + __popcll(fm & lt), wcap);
+            np += __popcll(fm);
             __syncthreads();
         }
     }
-
-    // alive persons with enough parts, in creation order
-    int out = 0;
-    np = min(np, wcap);
-    for (int base = 0; base < np; base += kBlock) {
-        const int p = base + threadIdx.x;
-        int parts = (p < np) ? wnparts[p] : -1;
-        const bool keep = parts >= min_parts && parts >= 0;
-        int total;
-        const int rank = out + block_flag_scan(keep, scratch, total);
-        if (keep && rank < pcap) {
-            const size_t o = (size_t)n * pcap + rank;
-            for (int c = 0; c < K; ++c) pose_slots[o * K + c] = wslots[(size_t)p * K + c];
-            pose_nparts[o] = parts;
-            pose_score[o] = wscore[p];
-        }
-        out += total;
-    }
-    if (threadIdx.x == 0) {
-        pose_counts[n] = out;
-        if (out > pcap) atomicOr(status, (int)HP_STATUS_POSE_OVERFLOW);
-    }
+    emit_persons(t, n, min(np, wcap), K, min_parts, pose_slots, pose_nparts, pose_score, pose_counts, pcap, status);
 }
 
 hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,
                            const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
                            int32_t *status, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_assemble, dim3(N), dim3(kBlock), 0, s, T, K, L, min_parts, pk.count, pk.score, pk.cap,
-                       conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner, ws.wslots, ws.wnparts,
+    hipLaunchKernelGGL(k_assemble, dim3(N), dim3(kWave), 0, s, T, K, L, min_parts, pk.count, pk.score, pk.cap,
+                       conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner, ws.wslots, ws.wmask,
                        ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score, poses.count, poses.cap, status);
     return hipGetLastError();
 }

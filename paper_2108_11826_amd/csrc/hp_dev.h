@@ -12,6 +12,8 @@ namespace hp {
 
 constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
 constexpr int kWave = 64;
+constexpr int kCtrStride = 32;    // ints between append counters: atomics on one cache line serialise,
+                                  // so every list gets a line of its own
 constexpr int kLdsSort = 4096;    // 64-bit keys a workgroup sorts in LDS; longer lists sort in global memory
 
 // Limb table passed to kernels by value.
@@ -22,11 +24,13 @@ struct LimbTable {
 
 // Where the pieces of the caller's workspace live (element offsets resolved on the host).
 struct Workspace {
+    int32_t *peak_ctr;      // [N*K][kCtrStride] append counters, one cache line each
+    int32_t *cand_ctr;      // [N*L][kCtrStride]
     uint64_t *peak_stage;   // [N*K][cap2]   unordered (key << 32 | score bits)
     uint64_t *cand_stage;   // [N*L][ccap2]  unordered ((i << 16 | j) << 32 | score bits)
     int32_t *owner;         // [N][K][cap]   person owning each peak
     int32_t *wslots;        // [N][wcap][K]  working person table
-    int32_t *wnparts;       // [N][wcap]     (-1 = merged away)
+    int32_t *wmask;         // [N][wcap]     filled-part bit mask (0 = merged away)
     float *wscore;          // [N][wcap]
     int cap2, ccap2, wcap;
     size_t bytes;
@@ -128,8 +132,9 @@ hipError_t launch_resize_nms(const void *lo_a, const void *lo_b, hp_dtype dt, fl
 hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
                          int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);
 
-hipError_t launch_sort_peaks(uint64_t *stage, int cap, int cap2, int planes, int W, const hp_peaks &pk,
-                             int32_t *status, hipStream_t s);
+// `ctr` are the strided append counters; the dense counts go to pk.count.
+hipError_t launch_sort_peaks(const int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
+                             const hp_peaks &pk, int32_t *status, hipStream_t s);
 
 // PAF sampled either from hi-res fp32 maps (paf_hi != nullptr) or recomputed from lo-res.
 hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
@@ -138,10 +143,11 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
                         hipStream_t s);
 
 // mode 0: staged candidates -> ordered candidate lists; 1: the same, then matching;
-// 2: ordered candidate lists in -> matching.
+// 2: ordered candidate lists in -> matching.  `cctr` are the strided append counters of the
+// staged candidates (modes 0 and 1 copy them to cands.count).
 hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
-                        uint64_t *cstage, int ccap2, const hp_pairs &cands, const hp_pairs &conns,
-                        int32_t *status, hipStream_t s);
+                        const int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
+                        const hp_pairs &conns, int32_t *status, hipStream_t s);
 
 hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,
                            const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,

@@ -6,10 +6,51 @@
 
 namespace hp {
 
+constexpr int kChunk0 = 4;     // PAF samples fetched together by the scorer: first chunk,
+constexpr int kChunk1 = 8;     // later chunks
+constexpr int kRankSort = 256; // lists up to this length are ordered by counting ranks through LDS
+
+// Fetches CH consecutive samples of one candidate together (their loads are in flight at the
+// same time), then takes validity and the running sum in sample order.
+template <typename T, bool FROM_HI, int CH>
+__device__ __forceinline__ void score_chunk(int k0, int S, float fS1, float fdx, float fdy, float fx0, float fy0,
+                                            float ux, float uy, float paf_thr, int max_bad, int H, int W, int h,
+                                            int w, const float *hx, const float *hy, const T *lx, const T *ly,
+                                            float &acc, int &bad)
+{
+    float vx[CH], vy[CH];
+#pragma unroll
+    for (int q = 0; q < CH; ++q) {
+        const int k = min(k0 + q, S - 1);
+        const float t = (float)k / fS1;
+        // samples of a segment between two in-map pixels are in the map; the clamp only guards
+        // against peak lists that were not produced by this library
+        const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
+        const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
+        if (FROM_HI) {
+            const size_t o = (size_t)sy * W + sx;
+            vx[q] = hx[o];
+            vy[q] = hy[o];
+        } else {
+            vx[q] = up_lo(lx, h, w, sy, sx);
+            vy[q] = up_lo(ly, h, w, sy, sx);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < CH; ++q) {
+        if (k0 + q < S && bad <= max_bad) {
+            const float d = __fmaf_rn(vy[q], uy, vx[q] * ux);
+            if (!(d > paf_thr)) ++bad;
+            acc = acc + d;
+        }
+    }
+}
+
 // grid = (chunks, N*L).  Each thread owns candidate pairs p = i * nB + j of its (image, limb),
 // strided by the whole row of workgroups; a score is never reduced across lanes, so the
 // summation order is the sample order.  Accepted pairs are appended unordered, tagged with
-// (i << 16 | j); the matching kernel orders them.
+// (i << 16 | j); the matching kernel orders them.  A pair is dropped as soon as it cannot reach
+// `need` valid samples any more: most pairs of unrelated peaks die in the first chunk.
 template <typename T, bool FROM_HI>
 __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
                                                   int h, int w, LimbTable tab, int K, int L, int S,
@@ -47,31 +88,15 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
         const float ux = fdx / norm, uy = fdy / norm;
         float acc = 0.0f;
         int bad = 0;
-        for (int k = 0; k < S; ++k) {
-            const float t = (float)k / fS1;
-            // samples of a segment between two in-map pixels are in the map; the clamp only
-            // guards against peak lists that were not produced by this library
-            const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
-            const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
-            float vx, vy;
-            if (FROM_HI) {
-                const size_t o = (size_t)sy * W + sx;
-                vx = hx[o];
-                vy = hy[o];
-            } else {
-                vx = up_lo(lx, h, w, sy, sx);
-                vy = up_lo(ly, h, w, sy, sx);
-            }
-            const float d = __fmaf_rn(vy, uy, vx * ux);
-            if (!(d > paf_thr)) {
-                if (++bad > max_bad) break;     // cannot reach `need` valid samples any more
-            }
-            acc = acc + d;
-        }
+        score_chunk<T, FROM_HI, kChunk0>(0, S, fS1, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
+                                         lx, ly, acc, bad);
+        for (int k0 = kChunk0; k0 < S && bad <= max_bad; k0 += kChunk1)
+            score_chunk<T, FROM_HI, kChunk1>(k0, S, fS1, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx,
+                                             hy, lx, ly, acc, bad);
         if (bad > max_bad) continue;
         const float score = acc / fS;
         if (score > 0.0f) {
-            const int slot = atomicAdd(&ccounts[nl], 1);
+            const int slot = atomicAdd(&ccounts[nl * kCtrStride], 1);
             if (slot < ccap)
                 cstage[(size_t)nl * ccap2 + slot] =
                     ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
@@ -114,7 +139,7 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
 template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
                                                   const int32_t *__restrict__ pcounts, int cap,
-                                                  uint64_t *cstage, int ccap2,
+                                                  const int32_t *cctr, uint64_t *cstage, int ccap2,
                                                   int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap,
                                                   int32_t *mcounts, int32_t *mi, int32_t *mj, float *ms, int mcap,
                                                   int32_t *status)
@@ -123,53 +148,118 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
     __shared__ uint32_t usedA[HP_MAX_CAP / 32], usedB[HP_MAX_CAP / 32];
     const int nl = blockIdx.x;
     const int n = nl / L, l = nl - n * L;
-    const int cnt = ccounts[nl];
+    const int cnt = (MODE != 2) ? cctr[nl * kCtrStride] : ccounts[nl];
     const int c = max(min(cnt, ccap), 0);
+    if (MODE != 2 && threadIdx.x == 0) ccounts[nl] = cnt;
     if (cnt > ccap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
-    int n2 = 1;
-    while (n2 < c) n2 <<= 1;
     uint64_t *g = cstage + (size_t)nl * ccap2;
-    const bool in_lds = n2 <= kLdsSort;
-    uint64_t *keys = in_lds ? sk : g;
     const size_t co = (size_t)nl * ccap;
+    const int a = tab.a[l], b = tab.b[l];
+    const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
+    const size_t mo = (size_t)nl * mcap;
+    uint64_t *keys;
 
-    if (MODE != 2) {
-        if (in_lds) {
-            for (int t = threadIdx.x; t < n2; t += kBlock) sk[t] = t < c ? g[t] : ~0ull;
+    if (c <= kRankSort) {
+        // Short list: one element per thread, its rank is the number of smaller keys (keys are
+        // distinct), counted through LDS broadcasts.
+        const int t = threadIdx.x;
+        uint64_t e = ~0ull;
+        if (t < c) {
+            if (MODE != 2)
+                e = g[t];
+            else
+                e = ((uint64_t)(((uint32_t)ci[co + t] << 16) | (uint32_t)cj[co + t]) << 32) |
+                    (uint64_t)__float_as_uint(cs[co + t]);
+        }
+        if (MODE != 2) {
+            sk[t] = e;
+            __syncthreads();
+            if (t < c) {
+                int r = 0;
+                for (int u = 0; u < c; ++u) r += sk[u] < e;
+                ci[co + r] = (int32_t)(e >> 48);
+                cj[co + r] = (int32_t)((e >> 32) & 0xffffu);
+                cs[co + r] = __uint_as_float((uint32_t)e);
+            }
+            if (MODE == 0) return;
+            __syncthreads();
+        }
+        const uint64_t key = (t < c) ? ((uint64_t)(~(uint32_t)e) << 32) | (e >> 32) : ~0ull;
+        sk[t] = key;
+        __syncthreads();
+        int r = 0;
+        if (t < c)
+            for (int u = 0; u < c; ++u) r += sk[u] < key;
+        __syncthreads();
+        if (t < c) sk[r] = key;
+        __syncthreads();
+        keys = sk;
+    } else {
+        int n2 = 1;
+        while (n2 < c) n2 <<= 1;
+        const bool in_lds = n2 <= kLdsSort;
+        keys = in_lds ? sk : g;
+        if (MODE != 2) {
+            if (in_lds) {
+                for (int t = threadIdx.x; t < n2; t += kBlock) sk[t] = t < c ? g[t] : ~0ull;
+            } else {
+                for (int t = c + threadIdx.x; t < n2; t += kBlock) g[t] = ~0ull;
+            }
+            __syncthreads();
+            block_bitonic_sort(keys, n2);
+            for (int t = threadIdx.x; t < c; t += kBlock) {
+                uint64_t e = keys[t];
+                uint32_t ij = (uint32_t)(e >> 32);
+                ci[co + t] = (int32_t)(ij >> 16);
+                cj[co + t] = (int32_t)(ij & 0xffffu);
+                cs[co + t] = __uint_as_float((uint32_t)e);
+                keys[t] = ((uint64_t)(~(uint32_t)e) << 32) | ij;
+            }
+            if (MODE == 0) return;
         } else {
-            for (int t = c + threadIdx.x; t < n2; t += kBlock) g[t] = ~0ull;
+            for (int t = threadIdx.x; t < n2; t += kBlock) {
+                uint64_t e = ~0ull;
+                if (t < c) {
+                    uint32_t ij = ((uint32_t)ci[co + t] << 16) | (uint32_t)cj[co + t];
+                    e = ((uint64_t)(~__float_as_uint(cs[co + t])) << 32) | ij;
+                }
+                keys[t] = e;
+            }
         }
         __syncthreads();
         block_bitonic_sort(keys, n2);
-        for (int t = threadIdx.x; t < c; t += kBlock) {
-            uint64_t e = keys[t];
-            uint32_t ij = (uint32_t)(e >> 32);
-            ci[co + t] = (int32_t)(ij >> 16);
-            cj[co + t] = (int32_t)(ij & 0xffffu);
-            cs[co + t] = __uint_as_float((uint32_t)e);
-            keys[t] = ((uint64_t)(~(uint32_t)e) << 32) | ij;
-        }
-        if (MODE == 0) return;
-    } else {
-        for (int t = threadIdx.x; t < n2; t += kBlock) {
-            uint64_t e = ~0ull;
-            if (t < c) {
-                uint32_t ij = ((uint32_t)ci[co + t] << 16) | (uint32_t)cj[co + t];
-                e = ((uint64_t)(~__float_as_uint(cs[co + t])) << 32) | ij;
-            }
-            keys[t] = e;
-        }
     }
-    const int a = tab.a[l], b = tab.b[l];
-    const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
+
+    // keys[0 .. c) now hold (~score bits) << 32 | (i << 16 | j) in matching order
+    if (c <= kWave) {
+        // One wavefront, one candidate per lane.  The lowest-ranked candidate still alive is
+        // accepted; every candidate sharing a peak with it dies.  One step per connection.
+        if (threadIdx.x >= kWave) return;
+        const int lane = threadIdx.x;
+        const uint64_t e = lane < c ? keys[lane] : ~0ull;
+        const int i = (int)((uint32_t)e >> 16), j = (int)((uint32_t)e & 0xffffu);
+        unsigned long long alive = __ballot(lane < c && i < nA && j < nB);
+        int m = 0;
+        while (alive) {
+            const int r = __ffsll((long long)alive) - 1;
+            const int ir = __builtin_amdgcn_readlane(i, r), jr = __builtin_amdgcn_readlane(j, r);
+            if (lane == r) {
+                mi[mo + m] = i;
+                mj[mo + m] = j;
+                ms[mo + m] = __uint_as_float(~(uint32_t)(e >> 32));
+            }
+            ++m;
+            alive &= ~__ballot(i == ir || j == jr);
+        }
+        if (lane == 0) mcounts[nl] = m;
+        return;
+    }
+
     for (int t = threadIdx.x; t < (nA + 31) / 32; t += kBlock) usedA[t] = 0;
     for (int t = threadIdx.x; t < (nB + 31) / 32; t += kBlock) usedB[t] = 0;
     __syncthreads();
-    block_bitonic_sort(keys, n2);
-
     if (threadIdx.x == 0) {
         const int limit = min(min(nA, nB), mcap);
-        const size_t mo = (size_t)nl * mcap;
         int m = 0;
         for (int t = 0; t < c && m < limit; ++t) {
             uint64_t e = keys[t];
@@ -190,20 +280,20 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
 }
 
 hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
-                        uint64_t *cstage, int ccap2, const hp_pairs &cands, const hp_pairs &conns,
-                        int32_t *status, hipStream_t s)
+                        const int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
+                        const hp_pairs &conns, int32_t *status, hipStream_t s)
 {
     dim3 grid(N * L), block(kBlock);
     if (mode == 0)
-        hipLaunchKernelGGL((k_match<0>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cstage, ccap2, cands.count,
+        hipLaunchKernelGGL((k_match<0>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
                            cands.i, cands.j, cands.score, cands.cap, (int32_t *)nullptr, (int32_t *)nullptr,
                            (int32_t *)nullptr, (float *)nullptr, 0, status);
     else if (mode == 1)
-        hipLaunchKernelGGL((k_match<1>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cstage, ccap2, cands.count,
+        hipLaunchKernelGGL((k_match<1>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
                            cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j, conns.score,
                            conns.cap, status);
     else
-        hipLaunchKernelGGL((k_match<2>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cstage, ccap2, cands.count,
+        hipLaunchKernelGGL((k_match<2>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
                            cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j, conns.score,
                            conns.cap, status);
     return hipGetLastError();

@@ -29,75 +29,63 @@ hipError_t launch_init(int32_t *a, int na, int32_t *b, int nb, int32_t *status, 
 __device__ __forceinline__ void emit_peak(int32_t *counts, uint64_t *stage, int plane, int cap, int cap2,
                                           int key, float u)
 {
-    int slot = atomicAdd(&counts[plane], 1);
+    int slot = atomicAdd(&counts[plane * kCtrStride], 1);
     if (slot < cap)
         stage[(size_t)plane * cap2 + slot] = ((uint64_t)(uint32_t)key << 32) | (uint64_t)__float_as_uint(u);
 }
 
-// One thread owns the 8-row x 4-column hi-res tile rows [8j, 8j+8), columns [8m+4hf, 8m+4hf+4)
-// of one plane: everything it needs (the tile plus a one-pixel halo) is a function of the
-// 3x3 lo-res neighbourhood of node (j, m).  Consecutive threads own consecutive 16-byte
-// column groups, so every row store of a wavefront is one contiguous 1 KiB run.
+// The unit of work is the 8-row x 4-column hi-res tile rows [8j, 8j+8), columns [8m+4hf, 8m+4hf+4)
+// of one plane: the tile plus a one-pixel halo (10 x 6 values) is a function of the 3x3 lo-res
+// neighbourhood of node (j, m).
 //
 // Column X = 8m + t (t = -1..8) reads nodes (m-1, m) with weight (2t+9)/16 for t <= 3 and
 // nodes (m, m+1) with weight (2t-7)/16 for t >= 4; left of node 0 the weight is 0 and right
 // of node w-1 the upper node is clamped.  Rows alike.
-template <typename T, bool WRITE, bool NMS>
-__global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
-                                                       float *__restrict__ hi_a, float *__restrict__ hi_b,
-                                                       int total, int Ca, int Ca_mem, int Cb, int Knms,
-                                                       int h, int w, float thr, int32_t *counts, uint64_t *stage,
-                                                       int cap, int cap2)
+
+template <typename T>
+__device__ __forceinline__ void load_nodes(const T *pl, int h, int w, int j, int m, float (&lo9)[3][3])
 {
-    int g = blockIdx.x * kBlock + threadIdx.x;
-    if (g >= total) return;
-    int hf = g & 1;
-    int q = g >> 1;
-    int m = q % w; q /= w;
-    int j = q % h; q /= h;
-    const int Cg = Ca + Cb;
-    int c = q % Cg;
-    int n = q / Cg;
-
-    // channels [0, Ca) come from tensor a (Ca_mem channels per image), the rest from tensor b
-    const bool in_a = c < Ca;
-    const size_t plane_mem = in_a ? (size_t)n * Ca_mem + c : (size_t)n * Cb + (c - Ca);
-    const T *pl = (in_a ? lo_a : lo_b) + plane_mem * (size_t)h * w;
-    int jr[3] = {max(j - 1, 0), j, min(j + 1, h - 1)};
-    int mc[3] = {max(m - 1, 0), m, min(m + 1, w - 1)};
-
-    // column weights for the 6 columns t = 4hf-1 .. 4hf+4
-    float fx[6];
-    bool lft[6];
-#pragma unroll
-    for (int k = 0; k < 6; ++k) {
-        int t = 4 * hf - 1 + k;
-        lft[k] = t <= 3;
-        fx[k] = lft[k] ? (m == 0 ? 0.0f : (float)(2 * t + 9) * 0.0625f) : (float)(2 * t - 7) * 0.0625f;
-    }
-
-    // horizontal pass on the three source rows
-    float hr[3][6];
+    const int jr[3] = {max(j - 1, 0), j, min(j + 1, h - 1)};
+    const int mc[3] = {max(m - 1, 0), m, min(m + 1, w - 1)};
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
         const T *row = pl + (size_t)jr[r] * w;
-        float vl = ld(row + mc[0]), vc = ld(row + mc[1]), vr = ld(row + mc[2]);
 #pragma unroll
-        for (int k = 0; k < 6; ++k) {
-            float a = lft[k] ? vl : vc;
-            float b = lft[k] ? vc : vr;
-            hr[r][k] = __fmaf_rn(fx[k], b, (1.0f - fx[k]) * a);
+        for (int k = 0; k < 3; ++k) lo9[r][k] = ld(row + mc[k]);
+    }
+}
+
+// Every value of a tile and its halo is a convex combination of its nine nodes, formed with
+// four roundings at most: none exceeds max9 * (1 + 2^-24)^4.  If even that stays below a
+// positive threshold the tile holds no peak (a non-positive max9 gives non-positive values).
+__device__ __forceinline__ bool tile_may_peak(const float (&lo9)[3][3], float thr)
+{
+    if (!(thr > 0.0f)) return true;
+    float mx = lo9[0][0];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int k = 0; k < 3; ++k) mx = fmaxf(mx, lo9[r][k]);
+    return !(mx * 1.000001f < thr);
+}
+
+// Upsamples one tile (with halo) from its nine nodes into v[10][6]: v[r+1][k] is row 8j+r,
+// column 8m+4hf-1+k.
+__device__ __forceinline__ void upsample_tile(const float (&lo9)[3][3], int j, int m, int hf, float (&v)[10][6])
+{
+    float hr[3][6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        const int t = 4 * hf - 1 + k;
+        const bool lft = t <= 3;
+        const float fx = lft ? (m == 0 ? 0.0f : (float)(2 * t + 9) * 0.0625f) : (float)(2 * t - 7) * 0.0625f;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const float a = lft ? lo9[r][0] : lo9[r][1];
+            const float b = lft ? lo9[r][1] : lo9[r][2];
+            hr[r][k] = __fmaf_rn(fx, b, (1.0f - fx) * a);
         }
     }
-
-    const int W = 8 * w, H = 8 * h;
-    const int X0 = 8 * m + 4 * hf, Y0 = 8 * j;
-    const bool do_nms = NMS && c < Knms;      // Knms <= Ca: searched channels lead tensor a
-    const float ninf = -__builtin_huge_valf();
-    const bool xlo_out = X0 == 0, xhi_out = X0 + 4 >= W;
-
-    // vertical pass, rows r = -1..8, rolling three rows for the 3x3 test
-    float v[10][6];
 #pragma unroll
     for (int r = -1; r <= 8; ++r) {
         const bool top = r <= 3;
@@ -105,51 +93,148 @@ __global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo_
         const float gy = (top && j == 0) ? 0.0f : gconst;
 #pragma unroll
         for (int k = 0; k < 6; ++k) {
-            float a = top ? hr[0][k] : hr[1][k];
-            float b = top ? hr[1][k] : hr[2][k];
+            const float a = top ? hr[0][k] : hr[1][k];
+            const float b = top ? hr[1][k] : hr[2][k];
             v[r + 1][k] = __fmaf_rn(gy, b, (1.0f - gy) * a);
         }
     }
+}
 
-    if (WRITE) {
-        float *dst = (in_a ? hi_a : hi_b) + (plane_mem * H + Y0) * (size_t)W + X0;
+// 3x3 test on the 8 x 4 interior of v; halo entries outside the map must not take part.
+// A pixel is a peak when it exceeds thr and its earlier neighbours (row above, left) and is
+// not below its later ones (right, row below).
+__device__ __forceinline__ void tile_peaks(float (&v)[10][6], int j, int h, int X0, int Y0, int W, float thr,
+                                           int32_t *counts, uint64_t *stage, int plane, int cap, int cap2)
+{
+    const float ninf = -__builtin_huge_valf();
+    if (X0 == 0) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            v4f o = {v[r + 1][1], v[r + 1][2], v[r + 1][3], v[r + 1][4]};
-            __builtin_nontemporal_store(o, (v4f *)(dst + (size_t)r * W));
+        for (int r = 0; r < 10; ++r) v[r][0] = ninf;
+    }
+    if (X0 + 4 >= W) {
+#pragma unroll
+        for (int r = 0; r < 10; ++r) v[r][5] = ninf;
+    }
+    if (j == 0) {
+#pragma unroll
+        for (int k = 0; k < 6; ++k) v[0][k] = ninf;
+    }
+    if (j == h - 1) {
+#pragma unroll
+        for (int k = 0; k < 6; ++k) v[9][k] = ninf;
+    }
+    float h3[10][4];     // maximum of the three horizontal neighbours centred on column k+1
+#pragma unroll
+    for (int r = 0; r < 10; ++r)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) h3[r][k] = fmaxf(fmaxf(v[r][k], v[r][k + 1]), v[r][k + 2]);
+    uint32_t found = 0;
+#pragma unroll
+    for (int r = 1; r <= 8; ++r) {
+#pragma unroll
+        for (int k = 1; k <= 4; ++k) {
+            const float u = v[r][k];
+            const float early = fmaxf(fmaxf(h3[r - 1][k - 1], v[r][k - 1]), thr);
+            const float late = fmaxf(h3[r + 1][k - 1], v[r][k + 1]);
+            if (u > early && u >= late) found |= 1u << ((r - 1) * 4 + (k - 1));
         }
     }
-
-    if (do_nms) {
-        // neighbours outside the map do not take part
-        if (xlo_out) {
-#pragma unroll
-            for (int r = 0; r < 10; ++r) v[r][0] = ninf;
-        }
-        if (xhi_out) {
-#pragma unroll
-            for (int r = 0; r < 10; ++r) v[r][5] = ninf;
-        }
-        if (j == 0) {
-#pragma unroll
-            for (int k = 0; k < 6; ++k) v[0][k] = ninf;
-        }
-        if (j == h - 1) {
-#pragma unroll
-            for (int k = 0; k < 6; ++k) v[9][k] = ninf;
-        }
-        const int plane = n * Knms + c;
+    if (found) {
 #pragma unroll
         for (int r = 1; r <= 8; ++r) {
 #pragma unroll
             for (int k = 1; k <= 4; ++k) {
-                float u = v[r][k];
-                float early = fmaxf(fmaxf(v[r - 1][k - 1], v[r - 1][k]), fmaxf(v[r - 1][k + 1], v[r][k - 1]));
-                float late = fmaxf(fmaxf(v[r + 1][k - 1], v[r + 1][k]), fmaxf(v[r + 1][k + 1], v[r][k + 1]));
-                if (u > thr && u > early && u >= late)
-                    emit_peak(counts, stage, plane, cap, cap2, (Y0 + r - 1) * W + X0 + k - 1, u);
+                if (found & (1u << ((r - 1) * 4 + (k - 1))))
+                    emit_peak(counts, stage, plane, cap, cap2, (Y0 + r - 1) * W + X0 + k - 1, v[r][k]);
             }
         }
+    }
+}
+
+// Materialising form: one thread per tile, every tile is upsampled and written; consecutive
+// threads own consecutive 16-byte column groups, so every row store of a wavefront is one
+// contiguous 1 KiB run.  One launch covers channels [0, Ca) of tensor a and all channels of
+// tensor b; the first Knms channels of a are searched for peaks.
+template <typename T, bool NMS>
+__global__ __launch_bounds__(kBlock) void k_resize_write(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
+                                                         float *__restrict__ hi_a, float *__restrict__ hi_b,
+                                                         int total, int Ca, int Ca_mem, int Cb, int Knms,
+                                                         int h, int w, float thr, int32_t *counts, uint64_t *stage,
+                                                         int cap, int cap2)
+{
+    int g = blockIdx.x * kBlock + threadIdx.x;
+    if (g >= total) return;
+    const int hf = g & 1;
+    int q = g >> 1;
+    const int m = q % w; q /= w;
+    const int j = q % h; q /= h;
+    const int Cg = Ca + Cb;
+    const int c = q % Cg;
+    const int n = q / Cg;
+
+    // channels [0, Ca) come from tensor a (Ca_mem channels per image), the rest from tensor b
+    const bool in_a = c < Ca;
+    const size_t plane_mem = in_a ? (size_t)n * Ca_mem + c : (size_t)n * Cb + (c - Ca);
+    const T *pl = (in_a ? lo_a : lo_b) + plane_mem * (size_t)h * w;
+    float lo9[3][3];
+    load_nodes(pl, h, w, j, m, lo9);
+    float v[10][6];
+    upsample_tile(lo9, j, m, hf, v);
+
+    const int W = 8 * w, H = 8 * h;
+    const int X0 = 8 * m + 4 * hf, Y0 = 8 * j;
+    float *dst = (in_a ? hi_a : hi_b) + (plane_mem * H + Y0) * (size_t)W + X0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        v4f o = {v[r + 1][1], v[r + 1][2], v[r + 1][3], v[r + 1][4]};
+        __builtin_nontemporal_store(o, (v4f *)(dst + (size_t)r * W));
+    }
+    if (NMS && c < Knms && tile_may_peak(lo9, thr))      // Knms <= Ca: searched channels lead tensor a
+        tile_peaks(v, j, h, X0, Y0, W, thr, counts, stage, n * Knms + c, cap, cap2);
+}
+
+// Fused form: nothing is written but peaks.  Phase 1, one thread per lo-res node of the K
+// searched channels: can the node's two tiles hold a peak at all?  The nodes that can are
+// queued in LDS; phase 2 spreads their tiles densely over the workgroup, so the upsampling and
+// the 3x3 test are only paid where the map rises to the threshold.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo, int total_nodes, int K,
+                                                       int C_mem, int h, int w, float thr, int32_t *counts,
+                                                       uint64_t *stage, int cap, int cap2)
+{
+    __shared__ int queue[kBlock];
+    __shared__ int scratch[kBlock / kWave + 1];
+    const int node0 = blockIdx.x * kBlock;
+    const int node = node0 + threadIdx.x;
+    bool active = false;
+    if (node < total_nodes) {
+        int q = node;
+        const int m = q % w; q /= w;
+        const int j = q % h; q /= h;
+        const int c = q % K;
+        const int n = q / K;
+        float lo9[3][3];
+        load_nodes(lo + ((size_t)n * C_mem + c) * (size_t)h * w, h, w, j, m, lo9);
+        active = tile_may_peak(lo9, thr);
+    }
+    int n_active;
+    const int pos = block_flag_scan(active, scratch, n_active);
+    if (active) queue[pos] = threadIdx.x;
+    __syncthreads();
+
+    const int W = 8 * w;
+    for (int task = threadIdx.x; task < 2 * n_active; task += kBlock) {
+        int q = node0 + queue[task >> 1];
+        const int hf = task & 1;
+        const int m = q % w; q /= w;
+        const int j = q % h; q /= h;
+        const int c = q % K;
+        const int n = q / K;
+        float lo9[3][3];
+        load_nodes(lo + ((size_t)n * C_mem + c) * (size_t)h * w, h, w, j, m, lo9);
+        float v[10][6];
+        upsample_tile(lo9, j, m, hf, v);
+        tile_peaks(v, j, h, 8 * m + 4 * hf, 8 * j, W, thr, counts, stage, n * K + c, cap, cap2);
     }
 }
 
@@ -158,22 +243,27 @@ static hipError_t launch_resize_nms_t(const T *lo_a, const T *lo_b, float *hi_a,
                                       int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
                                       uint64_t *stage, int cap, int cap2, hipStream_t s)
 {
+    dim3 block(kBlock);
+    if (hi_a == nullptr) {
+        // fused form: only the Knms searched channels of tensor a are visited
+        if (Knms <= 0 || Knms != Ca || Cb != 0) return hipErrorInvalidValue;
+        long long nodes64 = (long long)N * Knms * h * w;
+        if (nodes64 <= 0 || nodes64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
+        int nodes = (int)nodes64;
+        hipLaunchKernelGGL((k_resize_nms<T>), dim3((nodes + kBlock - 1) / kBlock), block, 0, s, lo_a, nodes, Knms,
+                           Ca_mem, h, w, thr, counts, stage, cap, cap2);
+        return hipGetLastError();
+    }
     long long total64 = 2LL * N * (Ca + Cb) * h * w;
     if (total64 <= 0 || total64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
     int total = (int)total64;
-    dim3 grid((total + kBlock - 1) / kBlock), block(kBlock);
-    const bool write = hi_a != nullptr, nms = Knms > 0;
-    if (write && nms)
-        hipLaunchKernelGGL((k_resize_nms<T, true, true>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem,
-                           Cb, Knms, h, w, thr, counts, stage, cap, cap2);
-    else if (write)
-        hipLaunchKernelGGL((k_resize_nms<T, true, false>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem,
-                           Cb, Knms, h, w, thr, counts, stage, cap, cap2);
-    else if (nms)
-        hipLaunchKernelGGL((k_resize_nms<T, false, true>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem,
-                           Cb, Knms, h, w, thr, counts, stage, cap, cap2);
+    dim3 grid((total + kBlock - 1) / kBlock);
+    if (Knms > 0)
+        hipLaunchKernelGGL((k_resize_write<T, true>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem, Cb,
+                           Knms, h, w, thr, counts, stage, cap, cap2);
     else
-        return hipErrorInvalidValue;
+        hipLaunchKernelGGL((k_resize_write<T, false>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem, Cb,
+                           Knms, h, w, thr, counts, stage, cap, cap2);
     return hipGetLastError();
 }
 
@@ -260,19 +350,38 @@ hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int 
 
 // One workgroup per (image, part): sorts the unordered staged peaks by raster key and
 // writes the ordered list.
-__global__ __launch_bounds__(kBlock) void k_sort_peaks(uint64_t *stage, int cap, int cap2, int W,
-                                                       const int32_t *counts, int32_t *px, int32_t *py,
+__global__ __launch_bounds__(kBlock) void k_sort_peaks(const int32_t *ctr, uint64_t *stage, int cap, int cap2, int W,
+                                                       int32_t *counts, int32_t *px, int32_t *py,
                                                        float *ps, int32_t *status)
 {
     __shared__ uint64_t sk[kLdsSort];
     const int plane = blockIdx.x;
-    const int cnt = counts[plane];
+    const int cnt = ctr[plane * kCtrStride];
+    if (threadIdx.x == 0) counts[plane] = cnt;
     const int n = max(min(cnt, cap), 0);
     if (cnt > cap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
     if (n == 0) return;
+    uint64_t *g = stage + (size_t)plane * cap2;
+    const size_t o0 = (size_t)plane * cap;
+    if (n <= kBlock) {
+        // short list: one peak per thread, rank = number of smaller keys, counted through LDS
+        const int t = threadIdx.x;
+        const uint64_t e = t < n ? g[t] : ~0ull;
+        sk[t] = e;
+        __syncthreads();
+        if (t < n) {
+            int r = 0;
+            for (int u = 0; u < n; ++u) r += sk[u] < e;
+            const int key = (int)(e >> 32);
+            const int y = key / W;
+            px[o0 + r] = key - y * W;
+            py[o0 + r] = y;
+            ps[o0 + r] = __uint_as_float((uint32_t)e);
+        }
+        return;
+    }
     int n2 = 1;
     while (n2 < n) n2 <<= 1;
-    uint64_t *g = stage + (size_t)plane * cap2;
     uint64_t *keys;
     if (n2 <= kLdsSort) {
         for (int t = threadIdx.x; t < n2; t += kBlock) sk[t] = t < n ? g[t] : ~0ull;
@@ -286,17 +395,17 @@ __global__ __launch_bounds__(kBlock) void k_sort_peaks(uint64_t *stage, int cap,
     for (int t = threadIdx.x; t < n; t += kBlock) {
         uint64_t e = keys[t];
         int key = (int)(e >> 32);
-        size_t o = (size_t)plane * cap + t;
-        px[o] = key % W;
-        py[o] = key / W;
-        ps[o] = __uint_as_float((uint32_t)e);
+        int y = key / W;
+        px[o0 + t] = key - y * W;
+        py[o0 + t] = y;
+        ps[o0 + t] = __uint_as_float((uint32_t)e);
     }
 }
 
-hipError_t launch_sort_peaks(uint64_t *stage, int cap, int cap2, int planes, int W, const hp_peaks &pk,
-                             int32_t *status, hipStream_t s)
+hipError_t launch_sort_peaks(const int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
+                             const hp_peaks &pk, int32_t *status, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_sort_peaks, dim3(planes), dim3(kBlock), 0, s, stage, cap, cap2, W, pk.count, pk.x, pk.y,
+    hipLaunchKernelGGL(k_sort_peaks, dim3(planes), dim3(kBlock), 0, s, ctr, stage, cap, cap2, W, pk.count, pk.x, pk.y,
                        pk.score, status);
     return hipGetLastError();
 }

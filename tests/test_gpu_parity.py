@@ -199,3 +199,20 @@ def test_large_lists_sort_outside_lds():
     m.hp_postprocess(to_dev(b.cm), to_dev(paf), m.Skeleton(sk.n_parts, la, lb),
                      m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
     check_all(buf, ora)
+
+
+def test_assembly_with_tables_beyond_lds():
+    """An image with more connections than the in-LDS person tables hold: the fold runs on the
+    workspace tables instead and must give the same persons."""
+    from synth import Params
+    cfg = SynthConfig(22, COCO18, 2, 28, 36, 0, noise_sd=0.2)
+    b = generate(cfg)
+    p = Params(peak_thr=0.05, paf_thr=-1.0, n_samples=4, min_valid_ratio=0.5, min_parts=3)
+    sk = cfg.skeleton
+    ora = oracle.postprocess(b.cm, b.paf, sk.limb_a, sk.limb_b, p, threads=8)
+    assert min(sum(len(x[0]) for x in im) for im in ora["conns"]) > 2000
+    m = hp()
+    buf = m.Buffers(2, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, 512, 1 << 15, 1024, DEV)
+    m.hp_postprocess(to_dev(b.cm), to_dev(b.paf), skel_of(sk),
+                     m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
+    check_all(buf, ora)
