@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=2, help="index into the synthetic workloads (2 = 656x368 batch 8)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work spent on the oracle baseline (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device copies of a known size (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (images are independent; "
@@ -88,6 +90,14 @@ def main():
             for c in range(K):
                 ok = ok and all(np.array_equal(peaks[n][c][q], ora["peaks"][n][c][q]) for q in range(3))
         parity = parity and bool(ok)
+
+    if args.calibrate_copy:
+        # a plain copy of exactly 256 MiB in and 256 MiB out, for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     t_fused = timed(False)
     t_mat = timed(True)
