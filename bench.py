@@ -117,15 +117,15 @@ def main():
     lo_bytes = (batch.cm.size + batch.paf.size) * esz
     hi_bytes = (cm_hi.numel() + paf_hi.numel()) * 4
     k1_bytes = lo_bytes + hi_bytes
-    k1_us = kern_us["resize_nms_write"]
+    k1_us = kern_us["resize_write"]
     achieved = k1_bytes / (k1_us * 1e-6) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_resize_nms_write_cfg{args.config}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_resize_write_cfg{args.config}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
-    roofline = {"kernel": "k_resize_nms<write> (upsampling of all CM+PAF channels + fused peak NMS, hi-res maps "
-                          "materialised; dominant kernel of the materialising form)",
+    roofline = {"kernel": "k_resize_write (x8 upsampling of all CM+PAF channels into materialised hi-res maps; "
+                          "dominant kernel of the materialising form)",
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": k1_bytes, "us_per_launch": round(k1_us, 2)}

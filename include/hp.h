@@ -199,15 +199,14 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
 typedef enum {
     HP_K_INIT = 0,         /* clears counters and the status word */
     HP_K_RESIZE_NMS = 1,   /* upsampling + peak detection, maps kept in registers */
-    HP_K_RESIZE_NMS_W = 2, /* upsampling + peak detection, hi-res maps written */
-    HP_K_RESIZE_W = 3,     /* upsampling only, hi-res maps written (hp_resize) */
-    HP_K_NMS_HI = 4,       /* peak detection on materialised maps */
-    HP_K_SORT_PEAKS = 5,
-    HP_K_SCORE_LO = 6,     /* limb scoring, PAF recomputed from lo-res */
-    HP_K_SCORE_HI = 7,     /* limb scoring, PAF read from materialised maps */
-    HP_K_MATCH = 8,
-    HP_K_ASSEMBLE = 9,
-    HP_K_COUNT = 10
+    HP_K_RESIZE_W = 2,     /* upsampling, hi-res maps written (hp_resize, materialising hp_postprocess) */
+    HP_K_NMS_HI = 3,       /* peak detection on materialised maps */
+    HP_K_SORT_PEAKS = 4,
+    HP_K_SCORE_LO = 5,     /* limb scoring, PAF recomputed from lo-res */
+    HP_K_SCORE_HI = 6,     /* limb scoring, PAF read from materialised maps */
+    HP_K_MATCH = 7,
+    HP_K_ASSEMBLE = 8,
+    HP_K_COUNT = 9
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

@@ -170,8 +170,7 @@ int hp_resize(const void *src_lo, hp_dtype dt, int N, int C, int h, int w, int s
     HP_TRY(check_dims(N, C, h, w));
     if (((uintptr_t)dst_hi & 15) != 0) return HP_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_RESIZE_W, launch_resize_nms(src_lo, nullptr, dt, dst_hi, nullptr, N, C, C, 0, 0, h, w, 0.0f,
-                                               nullptr, nullptr, 0, 0, s));
+    HP_LAUNCH(HP_K_RESIZE_W, launch_resize_write(src_lo, nullptr, dt, dst_hi, nullptr, N, C, C, 0, h, w, s));
     return HP_OK;
 }
 
@@ -275,14 +274,12 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
 
     HP_LAUNCH(HP_K_INIT, launch_init(ws.peak_ctr, N * K * kCtrStride, ws.cand_ctr, N * L * kCtrStride, status, s));
     if (cm_hi) {
-        // materialising form: every CM and PAF channel is written once, in one launch; peaks come
-        // from the values while they are still in registers
-        HP_LAUNCH(HP_K_RESIZE_NMS_W, launch_resize_nms(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, K, h, w, prm->peak_thr,
-                                    ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, s));
-    } else {
-        HP_LAUNCH(HP_K_RESIZE_NMS, launch_resize_nms(cm_lo, nullptr, dt, nullptr, nullptr, N, K, K + 1, 0, K, h, w, prm->peak_thr,
-                                    ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, s));
+        // materialising form: every CM and PAF channel is written once, in one launch
+        HP_LAUNCH(HP_K_RESIZE_W, launch_resize_write(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, h, w, s));
     }
+    // peaks come from upsampled values recomputed in registers where the map can reach the threshold
+    HP_LAUNCH(HP_K_RESIZE_NMS, launch_resize_nms(cm_lo, dt, N, K, K + 1, h, w, prm->peak_thr, ws.peak_ctr,
+                                                 ws.peak_stage, peaks->cap, ws.cap2, s));
     HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
     HP_LAUNCH(paf_hi ? HP_K_SCORE_HI : HP_K_SCORE_LO, launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, ws.cand_ctr,
                            ws.cand_stage, cands->cap, ws.ccap2, s));
@@ -331,7 +328,6 @@ const char *hp_kernel_name(int id)
     switch (id) {
     case HP_K_INIT: return "init";
     case HP_K_RESIZE_NMS: return "resize_nms";
-    case HP_K_RESIZE_NMS_W: return "resize_nms_write";
     case HP_K_RESIZE_W: return "resize_write";
     case HP_K_NMS_HI: return "nms_hi";
     case HP_K_SORT_PEAKS: return "sort_peaks";

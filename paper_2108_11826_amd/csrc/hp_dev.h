@@ -122,12 +122,15 @@ __device__ __forceinline__ int block_flag_scan(bool flag, int *scratch, int &tot
 
 hipError_t launch_init(int32_t *a, int na, int32_t *b, int nb, int32_t *status, hipStream_t s);
 
-// Upsampling with optional materialisation (hi_a != nullptr) and optional fused peak detection.
-// One launch covers channels [0, Ca) of tensor a (Ca_mem channels per image in memory) and all
-// Cb channels of tensor b (Cb may be 0); the first Knms channels of tensor a are searched.
-hipError_t launch_resize_nms(const void *lo_a, const void *lo_b, hp_dtype dt, float *hi_a, float *hi_b, int N,
-                             int Ca, int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
-                             uint64_t *stage, int cap, int cap2, hipStream_t s);
+// Upsampling into materialised hi-res maps: channels [0, Ca) of tensor a (Ca_mem channels per
+// image in memory) and all Cb channels of tensor b (Cb may be 0) in one launch.
+hipError_t launch_resize_write(const void *lo_a, const void *lo_b, hp_dtype dt, float *hi_a, float *hi_b, int N,
+                               int Ca, int Ca_mem, int Cb, int h, int w, hipStream_t s);
+
+// Peak search on the upsampled values of channels [0, K) of a lo-res tensor with C_mem channels
+// per image; the upsampled maps stay in registers.
+hipError_t launch_resize_nms(const void *lo, hp_dtype dt, int N, int K, int C_mem, int h, int w, float thr,
+                             int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);
 
 hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
                          int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);

@@ -34,7 +34,7 @@ __device__ __forceinline__ void emit_peak(int32_t *counts, uint64_t *stage, int 
         stage[(size_t)plane * cap2 + slot] = ((uint64_t)(uint32_t)key << 32) | (uint64_t)__float_as_uint(u);
 }
 
-// The unit of work is the 8-row x 4-column hi-res tile rows [8j, 8j+8), columns [8m+4hf, 8m+4hf+4)
+// The unit of work of the peak search is the 8-row x 4-column hi-res tile rows [8j, 8j+8), columns [8m+4hf, 8m+4hf+4)
 // of one plane: the tile plus a one-pixel halo (10 x 6 values) is a function of the 3x3 lo-res
 // neighbourhood of node (j, m).
 //
@@ -151,46 +151,59 @@ __device__ __forceinline__ void tile_peaks(float (&v)[10][6], int j, int h, int 
     }
 }
 
-// Materialising form: one thread per tile, every tile is upsampled and written; consecutive
-// threads own consecutive 16-byte column groups, so every row store of a wavefront is one
-// contiguous 1 KiB run.  One launch covers channels [0, Ca) of tensor a and all channels of
-// tensor b; the first Knms channels of a are searched for peaks.
-template <typename T, bool NMS>
-__global__ __launch_bounds__(kBlock) void k_resize_write(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
-                                                         float *__restrict__ hi_a, float *__restrict__ hi_b,
-                                                         int total, int Ca, int Ca_mem, int Cb, int Knms,
-                                                         int h, int w, float thr, int32_t *counts, uint64_t *stage,
-                                                         int cap, int cap2)
+// Materialising form.  One thread produces one 16-byte group of four pixels of one row and
+// issues exactly one non-temporal store; a workgroup is a 2-D block (column groups of a row) x
+// (R consecutive rows) of one plane, workgroups are numbered in memory order (row groups of a
+// plane, then planes), so consecutive wavefronts write consecutive kilobytes.  Measured on
+// MI355X this order streams at the rate of a plain fill, while threads that each write several
+// rows (a tile per thread) lose a quarter of it and threads that write two adjacent groups lose
+// more than half.  With one store per thread the instruction count per thread decides whether
+// the kernel stays memory-bound: sizes are folded on the host, products use 24-bit multiplies.
+// The four columns of a group share one pair of source nodes, the row one pair of source rows:
+// four loads (L1/L2 hits) per thread.  One launch covers `planes` consecutive planes starting
+// at `plane0`, counted over channels [0, Ca) of tensor a followed by the Cb channels of tensor b.
+template <typename T>
+__global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
+                                                       float *__restrict__ hi_a, float *__restrict__ hi_b,
+                                                       int plane0, int Ca, int Ca_mem, int Cb, int h, int w,
+                                                       int W4, int H, int xsplit)
 {
-    int g = blockIdx.x * kBlock + threadIdx.x;
-    if (g >= total) return;
-    const int hf = g & 1;
-    int q = g >> 1;
-    const int m = q % w; q /= w;
-    const int j = q % h; q /= h;
-    const int Cg = Ca + Cb;
-    const int c = q % Cg;
-    const int n = q / Cg;
+    // blockIdx.x: column part (1 unless a row is wider than a workgroup), y: row group, z: plane
+    const int x4 = blockIdx.x * xsplit + threadIdx.x;
+    const int Y = blockIdx.y * blockDim.y + threadIdx.y;
+    if (x4 >= W4 || Y >= H) return;
 
-    // channels [0, Ca) come from tensor a (Ca_mem channels per image), the rest from tensor b
+    // plane -> tensor, uniform over the workgroup
+    const int plane = plane0 + blockIdx.z;
+    const int Cg = Ca + Cb;
+    const int n = plane / Cg, c = plane - n * Cg;
     const bool in_a = c < Ca;
     const size_t plane_mem = in_a ? (size_t)n * Ca_mem + c : (size_t)n * Cb + (c - Ca);
-    const T *pl = (in_a ? lo_a : lo_b) + plane_mem * (size_t)h * w;
-    float lo9[3][3];
-    load_nodes(pl, h, w, j, m, lo9);
-    float v[10][6];
-    upsample_tile(lo9, j, m, hf, v);
+    const T *p = (in_a ? lo_a : lo_b) + plane_mem * (size_t)(h * w);
+    float *q = (in_a ? hi_a : hi_b) + plane_mem * (size_t)H * (size_t)(4 * W4);
 
-    const int W = 8 * w, H = 8 * h;
-    const int X0 = 8 * m + 4 * hf, Y0 = 8 * j;
-    float *dst = (in_a ? hi_a : hi_b) + (plane_mem * H + Y0) * (size_t)W + X0;
+    const int numy = 2 * Y - 7;
+    const int y0 = numy < 0 ? 0 : numy >> 4;
+    const float gy = numy < 0 ? 0.0f : (float)(numy & 15) * 0.0625f;
+    const int y1 = min(y0 + 1, h - 1);
+    const int numx = 8 * x4 - 7;                  // first column X = 4 * x4
+    const int x0 = numx < 0 ? 0 : numx >> 4;
+    const int x1 = min(x0 + 1, w - 1);
+    const float f0 = (float)(numx & 15) * 0.0625f;
+    const unsigned o0 = (unsigned)__mul24(y0, w), o1 = (unsigned)__mul24(y1, w);
+    const float a0 = ld(p + (o0 + x0)), b0 = ld(p + (o0 + x1));
+    const float a1 = ld(p + (o1 + x0)), b1 = ld(p + (o1 + x1));
+    const float g1 = 1.0f - gy;
+    v4f o;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        v4f o = {v[r + 1][1], v[r + 1][2], v[r + 1][3], v[r + 1][4]};
-        __builtin_nontemporal_store(o, (v4f *)(dst + (size_t)r * W));
+    for (int k = 0; k < 4; ++k) {
+        const float f = numx < 0 ? 0.0f : f0 + 0.125f * (float)k;     // k/16 steps of 2: exact
+        const float r0 = __fmaf_rn(f, b0, (1.0f - f) * a0);
+        const float r1 = __fmaf_rn(f, b1, (1.0f - f) * a1);
+        o[k] = __fmaf_rn(gy, r1, g1 * r0);
     }
-    if (NMS && c < Knms && tile_may_peak(lo9, thr))      // Knms <= Ca: searched channels lead tensor a
-        tile_peaks(v, j, h, X0, Y0, W, thr, counts, stage, n * Knms + c, cap, cap2);
+    const unsigned off = (unsigned)__mul24(Y, W4) + (unsigned)x4;     // in 16-byte units, < 2^29 by the host's check
+    __builtin_nontemporal_store(o, (v4f *)q + off);
 }
 
 // Fused form: nothing is written but peaks.  Phase 1, one thread per lo-res node of the K
@@ -239,43 +252,54 @@ __global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo,
 }
 
 template <typename T>
-static hipError_t launch_resize_nms_t(const T *lo_a, const T *lo_b, float *hi_a, float *hi_b, int N, int Ca,
-                                      int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
+static hipError_t launch_resize_write_t(const T *lo_a, const T *lo_b, float *hi_a, float *hi_b, int N, int Ca,
+                                        int Ca_mem, int Cb, int h, int w, hipStream_t s)
+{
+    const int W4 = 2 * w, H = 8 * h;
+    if ((long long)H * W4 >= (1LL << 29) || H >= (1 << 24) || W4 >= (1 << 24)) return hipErrorInvalidValue;
+    // block = (column groups, rows): a whole row and as many rows as fit 1024 threads (8 at most);
+    // rows wider than 1024 groups are split over blockIdx.x
+    const int bx = W4 <= 1024 ? W4 : 1024;
+    int R = 1024 / bx;
+    if (R > 8) R = 8;
+    const int gx = (W4 + bx - 1) / bx, groups = (H + R - 1) / R;
+    const long long planes = (long long)N * (Ca + Cb);
+    if (planes <= 0 || planes >= (1LL << 31) || groups > 65535) return hipErrorInvalidValue;
+    for (long long p0 = 0; p0 < planes; p0 += 65535) {
+        const long long np = planes - p0 < 65535 ? planes - p0 : 65535;
+        hipLaunchKernelGGL((k_resize_write<T>), dim3(gx, groups, (unsigned)np), dim3(bx, R), 0, s, lo_a, lo_b, hi_a, hi_b,
+                           (int)p0, Ca, Ca_mem, Cb, h, w, W4, H, bx);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_resize_write(const void *lo_a, const void *lo_b, hp_dtype dt, float *hi_a, float *hi_b, int N,
+                               int Ca, int Ca_mem, int Cb, int h, int w, hipStream_t s)
+{
+    if (dt == HP_F16)
+        return launch_resize_write_t((const __half *)lo_a, (const __half *)lo_b, hi_a, hi_b, N, Ca, Ca_mem, Cb, h, w, s);
+    return launch_resize_write_t((const float *)lo_a, (const float *)lo_b, hi_a, hi_b, N, Ca, Ca_mem, Cb, h, w, s);
+}
+
+template <typename T>
+static hipError_t launch_resize_nms_t(const T *lo, int N, int K, int C_mem, int h, int w, float thr, int32_t *counts,
                                       uint64_t *stage, int cap, int cap2, hipStream_t s)
 {
-    dim3 block(kBlock);
-    if (hi_a == nullptr) {
-        // fused form: only the Knms searched channels of tensor a are visited
-        if (Knms <= 0 || Knms != Ca || Cb != 0) return hipErrorInvalidValue;
-        long long nodes64 = (long long)N * Knms * h * w;
-        if (nodes64 <= 0 || nodes64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
-        int nodes = (int)nodes64;
-        hipLaunchKernelGGL((k_resize_nms<T>), dim3((nodes + kBlock - 1) / kBlock), block, 0, s, lo_a, nodes, Knms,
-                           Ca_mem, h, w, thr, counts, stage, cap, cap2);
-        return hipGetLastError();
-    }
-    long long total64 = 2LL * N * (Ca + Cb) * h * w;
-    if (total64 <= 0 || total64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
-    int total = (int)total64;
-    dim3 grid((total + kBlock - 1) / kBlock);
-    if (Knms > 0)
-        hipLaunchKernelGGL((k_resize_write<T, true>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem, Cb,
-                           Knms, h, w, thr, counts, stage, cap, cap2);
-    else
-        hipLaunchKernelGGL((k_resize_write<T, false>), grid, block, 0, s, lo_a, lo_b, hi_a, hi_b, total, Ca, Ca_mem, Cb,
-                           Knms, h, w, thr, counts, stage, cap, cap2);
+    long long nodes64 = (long long)N * K * h * w;
+    if (nodes64 <= 0 || nodes64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
+    int nodes = (int)nodes64;
+    hipLaunchKernelGGL((k_resize_nms<T>), dim3((nodes + kBlock - 1) / kBlock), dim3(kBlock), 0, s, lo, nodes, K, C_mem,
+                       h, w, thr, counts, stage, cap, cap2);
     return hipGetLastError();
 }
 
-hipError_t launch_resize_nms(const void *lo_a, const void *lo_b, hp_dtype dt, float *hi_a, float *hi_b, int N,
-                             int Ca, int Ca_mem, int Cb, int Knms, int h, int w, float thr, int32_t *counts,
-                             uint64_t *stage, int cap, int cap2, hipStream_t s)
+hipError_t launch_resize_nms(const void *lo, hp_dtype dt, int N, int K, int C_mem, int h, int w, float thr,
+                             int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s)
 {
-    if (dt == HP_F16)
-        return launch_resize_nms_t((const __half *)lo_a, (const __half *)lo_b, hi_a, hi_b, N, Ca, Ca_mem, Cb, Knms, h,
-                                   w, thr, counts, stage, cap, cap2, s);
-    return launch_resize_nms_t((const float *)lo_a, (const float *)lo_b, hi_a, hi_b, N, Ca, Ca_mem, Cb, Knms, h, w,
-                               thr, counts, stage, cap, cap2, s);
+    if (dt == HP_F16) return launch_resize_nms_t((const __half *)lo, N, K, C_mem, h, w, thr, counts, stage, cap, cap2, s);
+    return launch_resize_nms_t((const float *)lo, N, K, C_mem, h, w, thr, counts, stage, cap, cap2, s);
 }
 
 // Peak detection on a materialised map.  One thread owns an 8-row x 4-column tile and reads
