@@ -10,30 +10,54 @@ constexpr int kChunk0 = 4;     // PAF samples fetched together by the scorer: fi
 constexpr int kChunk1 = 8;     // later chunks
 constexpr int kRankSort = 256; // lists up to this length are ordered by counting ranks through LDS
 
+// Sample positions along a candidate, t_k = k / (S - 1), divided on the host (the same
+// correctly rounded fp32 quotient the device would form) and passed by value.
+struct SampleT {
+    float t[HP_MAX_SAMPLES];
+};
+
+// The two PAF components of limb l at hi-res pixel (sy, sx), recomputed from the lo-res planes
+// with the upsampling arithmetic (horizontal pass on the two source rows, then vertical); the
+// node indices and weights are shared by the two components.
+template <typename T>
+__device__ __forceinline__ void paf_from_lo(const T *__restrict__ lx, const T *__restrict__ ly, int h, int w, int sy,
+                                            int sx, float &vx, float &vy)
+{
+    int x0, x1, y0, y1;
+    float f, g;
+    axis8(sx, w, x0, x1, f);
+    axis8(sy, h, y0, y1, g);
+    const unsigned r0 = (unsigned)__mul24(y0, w), r1 = (unsigned)__mul24(y1, w);
+    const unsigned o00 = r0 + x0, o01 = r0 + x1, o10 = r1 + x0, o11 = r1 + x1;
+    const float f1 = 1.0f - f, g1 = 1.0f - g;
+    const float ax = ld(lx + o00), bx = ld(lx + o01), cx = ld(lx + o10), dx = ld(lx + o11);
+    const float ay = ld(ly + o00), by = ld(ly + o01), cy = ld(ly + o10), dy = ld(ly + o11);
+    vx = __fmaf_rn(g, __fmaf_rn(f, dx, f1 * cx), g1 * __fmaf_rn(f, bx, f1 * ax));
+    vy = __fmaf_rn(g, __fmaf_rn(f, dy, f1 * cy), g1 * __fmaf_rn(f, by, f1 * ay));
+}
+
 // Fetches CH consecutive samples of one candidate together (their loads are in flight at the
 // same time), then takes validity and the running sum in sample order.
 template <typename T, bool FROM_HI, int CH>
-__device__ __forceinline__ void score_chunk(int k0, int S, float fS1, float fdx, float fdy, float fx0, float fy0,
-                                            float ux, float uy, float paf_thr, int max_bad, int H, int W, int h,
-                                            int w, const float *hx, const float *hy, const T *lx, const T *ly,
+__device__ __forceinline__ void score_chunk(int k0, int S, const SampleT &st, float fdx, float fdy, float fx0,
+                                            float fy0, float ux, float uy, float paf_thr, int max_bad, int H, int W,
+                                            int h, int w, const float *hx, const float *hy, const T *lx, const T *ly,
                                             float &acc, int &bad)
 {
     float vx[CH], vy[CH];
 #pragma unroll
     for (int q = 0; q < CH; ++q) {
-        const int k = min(k0 + q, S - 1);
-        const float t = (float)k / fS1;
+        const float t = st.t[min(k0 + q, S - 1)];
         // samples of a segment between two in-map pixels are in the map; the clamp only guards
         // against peak lists that were not produced by this library
         const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
         const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
         if (FROM_HI) {
-            const size_t o = (size_t)sy * W + sx;
+            const unsigned o = (unsigned)__mul24(sy, W) + (unsigned)sx;
             vx[q] = hx[o];
             vy[q] = hy[o];
         } else {
-            vx[q] = up_lo(lx, h, w, sy, sx);
-            vy[q] = up_lo(ly, h, w, sy, sx);
+            paf_from_lo(lx, ly, h, w, sy, sx, vx[q], vy[q]);
         }
     }
 #pragma unroll
@@ -53,7 +77,7 @@ __device__ __forceinline__ void score_chunk(int k0, int S, float fS1, float fdx,
 // `need` valid samples any more: most pairs of unrelated peaks die in the first chunk.
 template <typename T, bool FROM_HI>
 __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
-                                                  int h, int w, LimbTable tab, int K, int L, int S,
+                                                  int h, int w, LimbTable tab, SampleT st, int K, int L, int S,
                                                   float paf_thr, int need,
                                                   const int32_t *__restrict__ pcounts,
                                                   const int32_t *__restrict__ px, const int32_t *__restrict__ py,
@@ -75,11 +99,16 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
     const float *hy = FROM_HI ? hx + (size_t)H * W : nullptr;
     const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
     const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
-    const float fS1 = (float)(S - 1), fS = (float)S;
+    const float fS = (float)S;
     const int max_bad = S - need;
+    const float inv_nB = 1.0f / (float)nB;
 
     for (; p < P; p += stride) {
-        const int i = p / nB, j = p - i * nB;
+        // i = p / nB through the reciprocal, then made exact
+        int i = (int)((float)p * inv_nB);
+        int j = p - i * nB;
+        while (j < 0) { --i; j += nB; }
+        while (j >= nB) { ++i; j -= nB; }
         const int x0 = xa[i], y0 = ya[i];
         const int dx = xb[j] - x0, dy = yb[j] - y0;
         if (dx == 0 && dy == 0) continue;
@@ -88,10 +117,10 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
         const float ux = fdx / norm, uy = fdy / norm;
         float acc = 0.0f;
         int bad = 0;
-        score_chunk<T, FROM_HI, kChunk0>(0, S, fS1, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
+        score_chunk<T, FROM_HI, kChunk0>(0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
                                          lx, ly, acc, bad);
         for (int k0 = kChunk0; k0 < S && bad <= max_bad; k0 += kChunk1)
-            score_chunk<T, FROM_HI, kChunk1>(k0, S, fS1, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx,
+            score_chunk<T, FROM_HI, kChunk1>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx,
                                              hy, lx, ly, acc, bad);
         if (bad > max_bad) continue;
         const float score = acc / fS;
@@ -115,17 +144,19 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
     if (chunks < 4) chunks = 4;
     if (chunks > 128) chunks = 128;
     dim3 grid(chunks, N * L), block(kBlock);
+    SampleT st;
+    for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
     if (paf_hi)
-        hipLaunchKernelGGL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, K, L,
+        hipLaunchKernelGGL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
                            prm.n_samples, prm.paf_thr, need, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap,
                            ccap2);
     else if (dt == HP_F16)
         hipLaunchKernelGGL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
-                           (const __half *)paf_lo, h, w, T, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
+                           (const __half *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
                            pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
     else
         hipLaunchKernelGGL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
-                           (const float *)paf_lo, h, w, T, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
+                           (const float *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
                            pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
     return hipGetLastError();
 }
