@@ -3,9 +3,12 @@ roofline of the dominant HBM-bound kernel and the CPU oracle timed beside it.
 
 A step is one hp_postprocess call (upsampling, peak NMS, compaction, limb scoring, matching,
 assembly) over one batch that is already resident in HBM.  `value` is measured on the form
-that keeps the upsampled maps in registers; the same number of steps is then timed on the
-form that materialises the hi-res maps (its upsampling kernel is the HBM-bound one the
-roofline object describes), and once more with per-kernel event brackets for the kernel times.
+that keeps the upsampled maps in registers, with the steps issued round-robin on a few HIP
+streams (each with its own output buffers and workspace) so that consecutive batches overlap,
+as the operators of the paper's streaming dataflow do (Section 2.2.1); the one-stream rate is
+reported beside it.  The same number of steps is then timed on the form that materialises the
+hi-res maps (its upsampling kernel is the HBM-bound one the roofline object describes), and
+once more with per-kernel event brackets for the kernel times.
 """
 import argparse
 import json
@@ -29,6 +32,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=2, help="index into the synthetic workloads (2 = 656x368 batch 8)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work spent on the oracle baseline (0 = skip)")
+    ap.add_argument("--streams", type=int, default=4, help="HIP streams the timed steps are spread over")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of a known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -75,6 +79,23 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
+    # several batches in flight: every stream owns its outputs and workspace, the inputs are shared
+    n_streams = max(1, args.streams)
+    lanes = [(torch.cuda.Stream(), hp.Buffers(N, K, L, h, w, cap, ccap, pcap, dev)) for _ in range(n_streams)]
+
+    def timed_streams():
+        def run(k):
+            for i in range(k):
+                st, bf = lanes[i % n_streams]
+                with torch.cuda.stream(st):
+                    hp.hp_postprocess(cm, paf, skel, prm, bf)
+        run(max(args.warmup, 2 * n_streams))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
     # correctness gate (outside the timed regions): the timed launch configuration against the oracle
     import oracle
     ora = oracle.postprocess(batch.cm, batch.paf, sk.limb_a, sk.limb_b, P, threads=min(16, len(os.sched_getaffinity(0))))
@@ -100,6 +121,12 @@ def main():
         torch.cuda.synchronize()
 
     t_fused = timed(False)
+    t_multi = timed_streams()
+    for st, bf in lanes:                      # every lane must hold the oracle's persons too
+        poses, _ = bf.host_poses()
+        ok = bf.host_status() == 0 and all(np.array_equal(poses[n][0], ora["poses"][n][0]) and
+                                           np.array_equal(poses[n][2], ora["poses"][n][2]) for n in range(N))
+        parity = parity and bool(ok)
     t_mat = timed(True)
 
     # per-kernel times: the same steps again with event brackets around every launch
@@ -137,15 +164,21 @@ def main():
                       "bound": "alu", "achieved": round(fused_ach, 2), "peak": round(ALU_PEAK_TLANEOPS, 1),
                       "unit": "Tlane-op/s", "frac": round(fused_ach / ALU_PEAK_TLANEOPS, 4),
                       "ops_per_launch": 12 * cm_px, "us_per_launch": round(fused_us, 2),
+                      "note": "ops are those of the dense definition (12 lane-ops per hi-res CM pixel); the kernel "
+                              "skips tiles whose nine source nodes cannot reach the threshold, so it executes fewer",
                       "hbm_bytes_per_launch": batch.cm[:, :K].size * esz}
     score_bytes = 80.0 * n_pairs
-    roofline_scoring = {"kernel": "k_score<hi> (PAF gathered from materialised maps)", "bound": "hbm",
-                        "achieved": round(score_bytes / (kern_us["score_hi"] * 1e-6) / 1e9, 2),
+    hi_name = "limb_small_hi" if "limb_small_hi" in kern_us else "score_hi"
+    lo_name = "limb_small_lo" if "limb_small_lo" in kern_us else "score_lo"
+    roofline_scoring = {"kernel": f"{hi_name}: limb scoring with PAFs gathered from the materialised maps"
+                                  + (" (one launch with peak ordering and matching)" if hi_name != "score_hi" else ""),
+                        "bound": "hbm",
+                        "achieved": round(score_bytes / (kern_us[hi_name] * 1e-6) / 1e9, 2),
                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(score_bytes / (kern_us["score_hi"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 6),
+                        "frac": round(score_bytes / (kern_us[hi_name] * 1e-6) / 1e9 / HBM_PEAK_GBS, 6),
                         "bytes_per_launch": score_bytes, "pairs_per_launch": n_pairs,
-                        "us_per_launch": round(kern_us["score_hi"], 2),
-                        "us_per_launch_lo_res_form": round(kern_us["score_lo"], 2)}
+                        "us_per_launch": round(kern_us[hi_name], 2),
+                        "us_per_launch_lo_res_form": round(kern_us[lo_name], 2)}
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -166,20 +199,25 @@ def main():
                          f"(image, part) and (image, limb) calls farmed over {T} threads",
                "single_thread_value": round(N / dt1, 2)}
 
-    value = N * args.steps / t_fused
+    value = N * args.steps / t_multi
     out = {
         "metric": "post-processed frames/s at 656x368 batch 8; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(1e3 * t_fused / args.steps, 5), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(1e3 * t_multi / args.steps, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if esz == 4 else "f16 storage, f32 arithmetic", "data": "synthetic",
         "config": {"workload": f"configs[{args.config}]: {sk.name}, batch {N}, input {cfg.W}x{cfg.H} "
                                f"(CM {K + 1}x{h}x{w}, PAF {2 * L}x{h}x{w}, x8 upsampling), {cfg.n_people} planted "
                                f"people per image", "form": "fused (hi-res maps never written)",
+                   "streams_in_flight": n_streams,
                    "capacities": {"peaks": cap, "candidates": ccap, "persons": pcap}},
         "parity_with_oracle": parity,
+        "value_one_stream": round(N * args.steps / t_fused, 1),
+        "ms_per_step_one_stream": round(1e3 * t_fused / args.steps, 5),
         "value_materialised": round(N * args.steps / t_mat, 1),
         "ms_per_step_materialised": round(1e3 * t_mat / args.steps, 5),
         "kernel_us": {k: round(v, 2) for k, v in sorted(kern_us.items())},
+        "kernel_us_note": "HIP-event brackets around each launch; the bracket itself adds 2-5 us, "
+                          "see profiles/ for rocprofv3 kernel durations",
         "roofline": roofline, "roofline_fused": roofline_fused, "roofline_scoring": roofline_scoring,
         "cpu_baseline": cpu,
     }

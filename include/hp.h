@@ -206,7 +206,9 @@ typedef enum {
     HP_K_SCORE_HI = 6,     /* limb scoring, PAF read from materialised maps */
     HP_K_MATCH = 7,
     HP_K_ASSEMBLE = 8,
-    HP_K_COUNT = 9
+    HP_K_LIMB_SMALL_LO = 9,  /* peak ordering + limb scoring + matching in one launch (small */
+    HP_K_LIMB_SMALL_HI = 10, /* capacities); PAF recomputed from lo-res / read from materialised maps */
+    HP_K_COUNT = 11
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

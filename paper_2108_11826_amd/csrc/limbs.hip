@@ -70,6 +70,30 @@ __device__ __forceinline__ void score_chunk(int k0, int S, const SampleT &st, fl
     }
 }
 
+// Scores the candidate from pixel (x0, y0) to pixel (x1, y1).  Returns whether it is accepted
+// (enough valid samples and a positive mean); the first kChunk0 samples decide for most pairs.
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ bool score_pair(int x0, int y0, int x1, int y1, int S, const SampleT &st, float paf_thr,
+                                           int max_bad, int H, int W, int h, int w, const float *hx, const float *hy,
+                                           const T *lx, const T *ly, float &score)
+{
+    const int dx = x1 - x0, dy = y1 - y0;
+    if (dx == 0 && dy == 0) return false;
+    const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)x0, fy0 = (float)y0;
+    const float norm = sqrtf((float)(dx * dx + dy * dy));
+    const float ux = fdx / norm, uy = fdy / norm;
+    float acc = 0.0f;
+    int bad = 0;
+    score_chunk<T, FROM_HI, kChunk0>(0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
+                                     acc, bad);
+    for (int k0 = kChunk0; k0 < S && bad <= max_bad; k0 += kChunk1)
+        score_chunk<T, FROM_HI, kChunk1>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy, lx,
+                                         ly, acc, bad);
+    if (bad > max_bad) return false;
+    score = acc / (float)S;
+    return score > 0.0f;
+}
+
 // grid = (chunks, N*L).  Each thread owns candidate pairs p = i * nB + j of its (image, limb),
 // strided by the whole row of workgroups; a score is never reduced across lanes, so the
 // summation order is the sample order.  Accepted pairs are appended unordered, tagged with
@@ -99,7 +123,6 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
     const float *hy = FROM_HI ? hx + (size_t)H * W : nullptr;
     const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
     const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
-    const float fS = (float)S;
     const int max_bad = S - need;
     const float inv_nB = 1.0f / (float)nB;
 
@@ -109,22 +132,9 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
         int j = p - i * nB;
         while (j < 0) { --i; j += nB; }
         while (j >= nB) { ++i; j -= nB; }
-        const int x0 = xa[i], y0 = ya[i];
-        const int dx = xb[j] - x0, dy = yb[j] - y0;
-        if (dx == 0 && dy == 0) continue;
-        const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)x0, fy0 = (float)y0;
-        const float norm = sqrtf((float)(dx * dx + dy * dy));
-        const float ux = fdx / norm, uy = fdy / norm;
-        float acc = 0.0f;
-        int bad = 0;
-        score_chunk<T, FROM_HI, kChunk0>(0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
-                                         lx, ly, acc, bad);
-        for (int k0 = kChunk0; k0 < S && bad <= max_bad; k0 += kChunk1)
-            score_chunk<T, FROM_HI, kChunk1>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx,
-                                             hy, lx, ly, acc, bad);
-        if (bad > max_bad) continue;
-        const float score = acc / fS;
-        if (score > 0.0f) {
+        float score;
+        if (score_pair<T, FROM_HI>(xa[i], ya[i], xb[j], yb[j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
+                                   score)) {
             const int slot = atomicAdd(&ccounts[nl * kCtrStride], 1);
             if (slot < ccap)
                 cstage[(size_t)nl * ccap2 + slot] =
@@ -308,6 +318,202 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
         }
         mcounts[nl] = m;
     }
+}
+
+// Small-list form of peak ordering + limb scoring + matching in one launch, used when the
+// capacities promise at most kSmallPeaks peaks per (image, part) and kSmallCands candidates per
+// (image, limb).  Workgroups [0, N*L) each own one (image, limb): they order the two staged
+// peak lists in LDS (rank = number of smaller raster keys), score every pair from the LDS
+// coordinates, collect the accepted ones in LDS, order them by (i, j) for the candidate output
+// and by (score desc, i, j) for the greedy matching.  Workgroups [N*L, N*L + N*K) each order one
+// staged peak list and write the caller's peak arrays.  Results are identical to the general
+// kernels; only the number of launches and global-memory round trips differs.
+constexpr int kSmallPeaks = 256;
+constexpr int kSmallCands = 1024;
+constexpr int kSmallBlock = 1024;
+
+template <typename T, bool FROM_HI>
+__global__ __launch_bounds__(kSmallBlock) void k_limb_small(
+    const float *__restrict__ paf_hi, const T *__restrict__ paf_lo, int h, int w, LimbTable tab, SampleT st, int K,
+    int L, int NL, int S, float paf_thr, int need, const int32_t *__restrict__ peak_ctr,
+    const uint64_t *__restrict__ peak_stage, int cap, int cap2, int32_t *pcounts, int32_t *px, int32_t *py, float *ps,
+    int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap, int32_t *mcounts, int32_t *mi, int32_t *mj,
+    float *ms, int mcap, int32_t *status)
+{
+    __shared__ uint64_t sk[kSmallCands];
+    __shared__ int lxy[4][kSmallPeaks];          // xA, yA, xB, yB in rank order
+    __shared__ int lds_cnt;
+    __shared__ uint32_t usedA[kSmallPeaks / 32], usedB[kSmallPeaks / 32];
+    const int tid = threadIdx.x;
+    const int H = 8 * h, W = 8 * w;
+
+    if ((int)blockIdx.x >= NL) {
+        // peak writer: one (image, part) list
+        const int plane = blockIdx.x - NL;
+        const int cnt = peak_ctr[plane * kCtrStride];
+        const int n = max(min(cnt, cap), 0);
+        if (tid == 0) {
+            pcounts[plane] = cnt;
+            if (cnt > cap) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
+        }
+        const uint64_t e = tid < n ? peak_stage[(size_t)plane * cap2 + tid] : ~0ull;
+        if (tid < kSmallPeaks) sk[tid] = e;
+        __syncthreads();
+        if (tid < n) {
+            int r = 0;
+            for (int u = 0; u < n; ++u) r += sk[u] < e;
+            const int key = (int)(e >> 32);
+            const int y = key / W;
+            const size_t o = (size_t)plane * cap + r;
+            px[o] = key - y * W;
+            py[o] = y;
+            ps[o] = __uint_as_float((uint32_t)e);
+        }
+        return;
+    }
+
+    const int nl = blockIdx.x;
+    const int n = nl / L, l = nl - n * L;
+    const int a = tab.a[l], b = tab.b[l];
+    const int pa = n * K + a, pb = n * K + b;
+    const int nA = max(min(peak_ctr[pa * kCtrStride], cap), 0), nB = max(min(peak_ctr[pb * kCtrStride], cap), 0);
+
+    // order the two peak lists: threads [0, 256) take list A, [256, 512) list B
+    {
+        const int half = tid >> 8, t = tid & (kSmallPeaks - 1);
+        const int cnt = half == 0 ? nA : nB;
+        const bool mine = half < 2 && t < cnt;
+        const uint64_t e = mine ? peak_stage[(size_t)(half == 0 ? pa : pb) * cap2 + t] : ~0ull;
+        if (half < 2) sk[tid] = e;
+        if (tid == 0) lds_cnt = 0;
+        __syncthreads();
+        if (mine) {
+            const uint64_t *skh = sk + half * kSmallPeaks;
+            int r = 0;
+            for (int u = 0; u < cnt; ++u) r += skh[u] < e;
+            const int key = (int)(e >> 32);
+            const int y = key / W;
+            lxy[2 * half][r] = key - y * W;
+            lxy[2 * half + 1][r] = y;
+        }
+        __syncthreads();
+    }
+
+    // score every pair; accepted ones go to the LDS list, tagged (i << 16 | j) << 32 | score bits
+    {
+        const float *hx = FROM_HI ? paf_hi + ((size_t)n * 2 * L + 2 * l) * (size_t)H * W : nullptr;
+        const float *hy = FROM_HI ? hx + (size_t)H * W : nullptr;
+        const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
+        const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
+        const int P = nA * nB, max_bad = S - need;
+        const float inv_nB = 1.0f / (float)nB;
+        for (int p = tid; p < P; p += kSmallBlock) {
+            int i = (int)((float)p * inv_nB);
+            int j = p - i * nB;
+            while (j < 0) { --i; j += nB; }
+            while (j >= nB) { ++i; j -= nB; }
+            float score;
+            if (score_pair<T, FROM_HI>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx,
+                                       hy, lx, ly, score)) {
+                const int slot = atomicAdd(&lds_cnt, 1);
+                if (slot < kSmallCands)
+                    sk[slot] = ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+            }
+        }
+        __syncthreads();
+    }
+
+    const int cnt = lds_cnt;
+    const int c = min(cnt, min(ccap, kSmallCands));
+    if (tid == 0) {
+        ccounts[nl] = cnt;
+        if (cnt > ccap) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
+    }
+    // candidates in (i, j) order
+    const uint64_t e = tid < c ? sk[tid] : ~0ull;
+    const size_t co = (size_t)nl * ccap;
+    if (tid < c) {
+        int r = 0;
+        for (int u = 0; u < c; ++u) r += sk[u] < e;
+        ci[co + r] = (int32_t)(e >> 48);
+        cj[co + r] = (int32_t)((e >> 32) & 0xffffu);
+        cs[co + r] = __uint_as_float((uint32_t)e);
+    }
+    __syncthreads();
+    // matching order: (~score bits) << 32 | (i << 16 | j), ascending
+    const uint64_t key = tid < c ? ((uint64_t)(~(uint32_t)e) << 32) | (e >> 32) : ~0ull;
+    if (tid < c) sk[tid] = key;
+    if (tid < kSmallPeaks / 32) usedA[tid] = usedB[tid] = 0;
+    __syncthreads();
+    int r2 = 0;
+    if (tid < c)
+        for (int u = 0; u < c; ++u) r2 += sk[u] < key;
+    __syncthreads();
+    if (tid < c) sk[r2] = key;
+    __syncthreads();
+
+    const size_t mo = (size_t)nl * mcap;
+    if (tid >= kWave) return;
+    if (c <= kWave) {
+        // one candidate per lane: the lowest-ranked one still alive is accepted, every candidate
+        // sharing a peak with it dies; one step per connection
+        const uint64_t k = tid < c ? sk[tid] : ~0ull;
+        const int i = (int)((uint32_t)k >> 16), j = (int)((uint32_t)k & 0xffffu);
+        unsigned long long alive = __ballot(tid < c);
+        int m = 0;
+        while (alive) {
+            const int r = __ffsll((long long)alive) - 1;
+            const int ir = __builtin_amdgcn_readlane(i, r), jr = __builtin_amdgcn_readlane(j, r);
+            if (tid == r) {
+                mi[mo + m] = i;
+                mj[mo + m] = j;
+                ms[mo + m] = __uint_as_float(~(uint32_t)(k >> 32));
+            }
+            ++m;
+            alive &= ~__ballot(i == ir || j == jr);
+        }
+        if (tid == 0) mcounts[nl] = m;
+    } else if (tid == 0) {
+        const int limit = min(min(nA, nB), mcap);
+        int m = 0;
+        for (int t = 0; t < c && m < limit; ++t) {
+            const uint64_t k = sk[t];
+            const uint32_t i = (uint32_t)k >> 16, j = (uint32_t)k & 0xffffu;
+            if ((usedA[i >> 5] >> (i & 31)) & 1u) continue;
+            if ((usedB[j >> 5] >> (j & 31)) & 1u) continue;
+            usedA[i >> 5] |= 1u << (i & 31);
+            usedB[j >> 5] |= 1u << (j & 31);
+            mi[mo + m] = (int32_t)i;
+            mj[mo + m] = (int32_t)j;
+            ms[mo + m] = __uint_as_float(~(uint32_t)(k >> 32));
+            ++m;
+        }
+        mcounts[nl] = m;
+    }
+}
+
+bool limb_small_applies(int cap, int ccap) { return cap <= kSmallPeaks && ccap <= kSmallCands; }
+
+hipError_t launch_limb_small(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                             const LimbTable &T, int K, int L, const hp_params &prm, int need,
+                             const int32_t *peak_ctr, const uint64_t *peak_stage, int cap2, const hp_peaks &pk,
+                             const hp_pairs &cands, const hp_pairs &conns, int32_t *status, hipStream_t s)
+{
+    SampleT st;
+    for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
+    dim3 grid(N * L + N * K), block(kSmallBlock);
+#define HP_LIMB_SMALL_ARGS(LO)                                                                                        \
+    paf_hi, LO, h, w, T, st, K, L, N *L, prm.n_samples, prm.paf_thr, need, peak_ctr, peak_stage, pk.cap, cap2,        \
+        pk.count, pk.x, pk.y, pk.score, cands.count, cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i,   \
+        conns.j, conns.score, conns.cap, status
+    if (paf_hi)
+        hipLaunchKernelGGL((k_limb_small<float, true>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const float *)nullptr));
+    else if (dt == HP_F16)
+        hipLaunchKernelGGL((k_limb_small<__half, false>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
+    else
+        hipLaunchKernelGGL((k_limb_small<float, false>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
+#undef HP_LIMB_SMALL_ARGS
+    return hipGetLastError();
 }
 
 hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
