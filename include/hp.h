@@ -117,9 +117,16 @@ typedef struct {
 /* Bytes of device workspace that hp_find_peaks, hp_score_limbs, hp_assemble and
  * hp_postprocess need for these sizes (cap = peaks per (image, part), ccap =
  * candidates per (image, limb), pcap = persons per image).  0 if a size is
- * invalid.  The workspace must be 256-byte aligned; its contents need not be
- * preserved between calls and two calls running concurrently must not share it. */
+ * invalid.  The workspace must be 256-byte aligned and two calls running
+ * concurrently must not share it. */
 size_t hp_workspace_bytes(int N, int K, int L, int h, int w, int scale, int cap, int ccap, int pcap);
+
+/* Clears a workspace (enqueues one fill kernel on `stream`).  The workspace holds
+ * the append counters of the peak and candidate lists, which every call expects
+ * to find at zero and leaves at zero.  Call it once after allocating the
+ * workspace, again whenever the sizes it is used with (N, K, L, cap, ccap) change,
+ * and after a call that returned HP_ERR_HIP; ws_bytes must be a multiple of 4. */
+int hp_workspace_init(void *workspace, size_t ws_bytes, void *stream);
 
 /* Upsampling ("resizing", Section 2.2; imaging operations, Section 2.3).
  * dst_hi[n][c][Y][X] = bilinear sample of src_lo[n][c] at ((Y+1/2)/s - 1/2,

@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
-EXPORTS = ("hp_workspace_bytes", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
+EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
            "hp_postprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version")
 HP_K_COUNT = 11
 
@@ -67,6 +67,8 @@ def lib():
         L = ctypes.CDLL(path)
         L.hp_workspace_bytes.restype = c_size_t
         L.hp_workspace_bytes.argtypes = [c_int] * 9
+        L.hp_workspace_init.restype = c_int
+        L.hp_workspace_init.argtypes = [c_void_p, c_size_t, c_void_p]
         L.hp_resize.restype = c_int
         L.hp_resize.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
         L.hp_find_peaks.restype = c_int
@@ -114,6 +116,12 @@ def hp_profile_end():
     n = (c_int32 * HP_K_COUNT)()
     _check(lib().hp_profile_end(ms, n), "hp_profile_end")
     return {lib().hp_kernel_name(k).decode(): (float(ms[k]), int(n[k])) for k in range(HP_K_COUNT) if n[k] > 0}
+
+
+def hp_workspace_init(workspace):
+    """Clears a workspace tensor (uint8, on the GPU) on the current stream."""
+    _check(lib().hp_workspace_init(_dev(workspace, torch.uint8), c_size_t(workspace.numel()), _stream()),
+           "hp_workspace_init")
 
 
 def hp_workspace_bytes(N, K, L, h, w, scale, cap, ccap, pcap):
@@ -181,6 +189,9 @@ class Buffers:
         if self.ws_bytes == 0:
             raise HPError(-1, "hp_workspace_bytes")
         self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, device=device)
+        with torch.cuda.device(self.workspace.device):
+            _check(lib().hp_workspace_init(c_void_p(self.workspace.data_ptr()), c_size_t(self.ws_bytes), _stream()),
+                   "hp_workspace_init")
         self.peaks = _Peaks(self.px.data_ptr(), self.py.data_ptr(), self.ps.data_ptr(), self.pcount.data_ptr(), cap)
         self.cands = _Pairs(self.ci.data_ptr(), self.cj.data_ptr(), self.cs.data_ptr(), self.ccount.data_ptr(), ccap)
         self.conns = _Pairs(self.mi.data_ptr(), self.mj.data_ptr(), self.ms.data_ptr(), self.mcount.data_ptr(), cap)
@@ -268,3 +279,31 @@ def hp_postprocess(cm_lo, paf_lo, skel, prm, buf, cm_hi=None, paf_hi=None):
                                 ctypes.byref(buf.peaks), ctypes.byref(buf.cands), ctypes.byref(buf.conns),
                                 ctypes.byref(buf.poses), wsp, wsb, _dev(buf.status), _stream()),
            "hp_postprocess")
+
+
+class PostprocessCall:
+    """hp_postprocess with its arguments marshalled once, for loops that repeat the same call.
+
+    The tensors, descriptors and the stream are fixed at construction (the stream defaults to the
+    current torch stream); calling the object enqueues one hp_postprocess on that stream.
+    """
+
+    def __init__(self, cm_lo, paf_lo, skel, prm, buf, cm_hi=None, paf_hi=None, stream=None):
+        N, C_cm, h, w = cm_lo.shape
+        if cm_lo.dtype != paf_lo.dtype:
+            raise TypeError("cm_lo and paf_lo must share a dtype")
+        self._keep = (cm_lo, paf_lo, skel, prm, buf, cm_hi, paf_hi, stream)
+        wsp, wsb = buf.ws()
+        st = stream if stream is not None else torch.cuda.current_stream()
+        self._fn = lib().hp_postprocess
+        self._args = (_dev(cm_lo), _dev(paf_lo), _dtype_code(cm_lo), N, h, w, ctypes.byref(skel.c),
+                      ctypes.byref(prm.c),
+                      _dev(cm_hi, torch.float32) if cm_hi is not None else None,
+                      _dev(paf_hi, torch.float32) if paf_hi is not None else None,
+                      ctypes.byref(buf.peaks), ctypes.byref(buf.cands), ctypes.byref(buf.conns),
+                      ctypes.byref(buf.poses), wsp, wsb, _dev(buf.status), c_void_p(st.cuda_stream))
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != 0:
+            raise HPError(rc, "hp_postprocess")

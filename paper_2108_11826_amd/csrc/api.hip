@@ -44,11 +44,14 @@ static int check_skeleton(const hp_skeleton *sk, LimbTable &tab)
     if (sk->n_parts <= 0 || sk->n_limbs <= 0) return HP_ERR_INVALID_ARG;
     if (sk->n_parts > HP_MAX_PARTS || sk->n_limbs > HP_MAX_LIMBS) return HP_ERR_UNSUPPORTED;
     memset(&tab, 0, sizeof(tab));
+    for (int c = 0; c < HP_MAX_PARTS; ++c) tab.writer[c] = -1;
     for (int l = 0; l < sk->n_limbs; ++l) {
         int a = sk->limb_a[l], b = sk->limb_b[l];
         if (a < 0 || a >= sk->n_parts || b < 0 || b >= sk->n_parts || a == b) return HP_ERR_INVALID_ARG;
         tab.a[l] = (int8_t)a;
         tab.b[l] = (int8_t)b;
+        if (tab.writer[a] < 0) tab.writer[a] = (int8_t)l;
+        if (tab.writer[b] < 0) tab.writer[b] = (int8_t)l;
     }
     return HP_OK;
 }
@@ -272,14 +275,13 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     HP_TRY(check_ws(workspace, ws_bytes, N, K, L, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
 
-    HP_LAUNCH(HP_K_INIT, launch_init(ws.peak_ctr, N * K * kCtrStride, ws.cand_ctr, N * L * kCtrStride, status, s));
     if (cm_hi) {
         // materialising form: every CM and PAF channel is written once, in one launch
         HP_LAUNCH(HP_K_RESIZE_W, launch_resize_write(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, h, w, s));
     }
     // peaks come from upsampled values recomputed in registers where the map can reach the threshold
     HP_LAUNCH(HP_K_RESIZE_NMS, launch_resize_nms(cm_lo, dt, N, K, K + 1, h, w, prm->peak_thr, ws.peak_ctr,
-                                                 ws.peak_stage, peaks->cap, ws.cap2, s));
+                                                 ws.peak_stage, peaks->cap, ws.cap2, status, s));
     if (limb_small_applies(peaks->cap, cands->cap)) {
         // small capacities: peak ordering, scoring and matching in one launch
         HP_LAUNCH(paf_hi ? HP_K_LIMB_SMALL_HI : HP_K_LIMB_SMALL_LO, launch_limb_small(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, ws.peak_ctr,
@@ -345,6 +347,14 @@ const char *hp_kernel_name(int id)
     case HP_K_ASSEMBLE: return "assemble";
     default: return "unknown";
     }
+}
+
+int hp_workspace_init(void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes == 0 || (ws_bytes & 3) != 0) return HP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_INIT, launch_zero(workspace, ws_bytes, s));
+    return HP_OK;
 }
 
 const char *hp_strerror(int code)

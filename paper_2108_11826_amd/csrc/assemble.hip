@@ -153,13 +153,18 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
                                                     int32_t *owner_all, int32_t *wslots_all, int32_t *wmask_all,
                                                     float *wscore_all, int wcap,
                                                     int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
-                                                    int32_t *pose_counts, int pcap, int32_t *status)
+                                                    int32_t *pose_counts, int pcap, int32_t *status,
+                                                    int32_t *peak_ctr, int32_t *cand_ctr)
 {
     __shared__ int16_t pool[kPool16];
     __shared__ uint32_t pool32[kPool32];
     __shared__ int moff[HP_MAX_LIMBS + 1];
     const int n = blockIdx.x;
     const int lane = threadIdx.x;
+    // last kernel of a call: every append counter of this image has been consumed by now;
+    // clearing them here leaves the workspace ready for the next call
+    if (peak_ctr && lane < K) peak_ctr[(n * K + lane) * kCtrStride] = 0;
+    if (cand_ctr && lane < L) cand_ctr[(n * L + lane) * kCtrStride] = 0;
     const float *psc = pscore + (size_t)n * K * cap;
     const unsigned long long lt = (1ull << lane) - 1ull;
 
@@ -358,7 +363,8 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
 {
     hipLaunchKernelGGL(k_assemble, dim3(N), dim3(kWave), 0, s, T, K, L, min_parts, pk.count, pk.score, pk.cap,
                        conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner, ws.wslots, ws.wmask,
-                       ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score, poses.count, poses.cap, status);
+                       ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score, poses.count, poses.cap, status,
+                       ws.peak_ctr, ws.cand_ctr);
     return hipGetLastError();
 }
 

@@ -20,6 +20,7 @@ constexpr int kLdsSort = 4096;    // 64-bit keys a workgroup sorts in LDS; longe
 struct LimbTable {
     int8_t a[HP_MAX_LIMBS];
     int8_t b[HP_MAX_LIMBS];
+    int8_t writer[HP_MAX_PARTS];   // first limb that uses the part (it publishes the part's peak list), -1 if none
 };
 
 // Where the pieces of the caller's workspace live (element offsets resolved on the host).
@@ -129,14 +130,17 @@ hipError_t launch_resize_write(const void *lo_a, const void *lo_b, hp_dtype dt, 
 
 // Peak search on the upsampled values of channels [0, K) of a lo-res tensor with C_mem channels
 // per image; the upsampled maps stay in registers.
+// A non-null `status` is cleared by this launch.
 hipError_t launch_resize_nms(const void *lo, hp_dtype dt, int N, int K, int C_mem, int h, int w, float thr,
-                             int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);
+                             int32_t *counts, uint64_t *stage, int cap, int cap2, int32_t *status, hipStream_t s);
+
+hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
 hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
                          int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);
 
 // `ctr` are the strided append counters; the dense counts go to pk.count.
-hipError_t launch_sort_peaks(const int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
+hipError_t launch_sort_peaks(int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
                              const hp_peaks &pk, int32_t *status, hipStream_t s);
 
 // PAF sampled either from hi-res fp32 maps (paf_hi != nullptr) or recomputed from lo-res.
@@ -149,7 +153,7 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
 // 2: ordered candidate lists in -> matching.  `cctr` are the strided append counters of the
 // staged candidates (modes 0 and 1 copy them to cands.count).
 hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
-                        const int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
+                        int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
                         const hp_pairs &conns, int32_t *status, hipStream_t s);
 
 // Peak ordering + scoring + matching in one launch for small capacities (see limb_small_applies).
@@ -159,6 +163,7 @@ hipError_t launch_limb_small(const float *paf_hi, const void *paf_lo, hp_dtype d
                              const int32_t *peak_ctr, const uint64_t *peak_stage, int cap2, const hp_peaks &pk,
                              const hp_pairs &cands, const hp_pairs &conns, int32_t *status, hipStream_t s);
 
+// Also clears the image's append counters, which leaves the workspace ready for the next call.
 hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,
                            const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
                            int32_t *status, hipStream_t s);

@@ -180,7 +180,7 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
 template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
                                                   const int32_t *__restrict__ pcounts, int cap,
-                                                  const int32_t *cctr, uint64_t *cstage, int ccap2,
+                                                  int32_t *cctr, uint64_t *cstage, int ccap2,
                                                   int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap,
                                                   int32_t *mcounts, int32_t *mi, int32_t *mj, float *ms, int mcap,
                                                   int32_t *status)
@@ -191,7 +191,13 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
     const int n = nl / L, l = nl - n * L;
     const int cnt = (MODE != 2) ? cctr[nl * kCtrStride] : ccounts[nl];
     const int c = max(min(cnt, ccap), 0);
-    if (MODE != 2 && threadIdx.x == 0) ccounts[nl] = cnt;
+    if (MODE != 2) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            ccounts[nl] = cnt;
+            cctr[nl * kCtrStride] = 0;        // sole reader of this list: leave it ready for the next call
+        }
+    }
     if (cnt > ccap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
     uint64_t *g = cstage + (size_t)nl * ccap2;
     const size_t co = (size_t)nl * ccap;
@@ -325,8 +331,8 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
 // (image, limb).  Workgroups [0, N*L) each own one (image, limb): they order the two staged
 // peak lists in LDS (rank = number of smaller raster keys), score every pair from the LDS
 // coordinates, collect the accepted ones in LDS, order them by (i, j) for the candidate output
-// and by (score desc, i, j) for the greedy matching.  Workgroups [N*L, N*L + N*K) each order one
-// staged peak list and write the caller's peak arrays.  Results are identical to the general
+// and by (score desc, i, j) for the greedy matching.  The workgroup of the first limb that uses a
+// part also writes the part's ordered peak list to the caller's arrays.  Results are identical to the general
 // kernels; only the number of launches and global-memory round trips differs.
 constexpr int kSmallPeaks = 256;
 constexpr int kSmallCands = 1024;
@@ -347,54 +353,71 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
     const int tid = threadIdx.x;
     const int H = 8 * h, W = 8 * w;
 
-    if ((int)blockIdx.x >= NL) {
-        // peak writer: one (image, part) list
-        const int plane = blockIdx.x - NL;
-        const int cnt = peak_ctr[plane * kCtrStride];
-        const int n = max(min(cnt, cap), 0);
-        if (tid == 0) {
-            pcounts[plane] = cnt;
-            if (cnt > cap) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
-        }
-        const uint64_t e = tid < n ? peak_stage[(size_t)plane * cap2 + tid] : ~0ull;
-        if (tid < kSmallPeaks) sk[tid] = e;
-        __syncthreads();
-        if (tid < n) {
-            int r = 0;
-            for (int u = 0; u < n; ++u) r += sk[u] < e;
-            const int key = (int)(e >> 32);
-            const int y = key / W;
-            const size_t o = (size_t)plane * cap + r;
-            px[o] = key - y * W;
-            py[o] = y;
-            ps[o] = __uint_as_float((uint32_t)e);
-        }
-        return;
-    }
-
     const int nl = blockIdx.x;
     const int n = nl / L, l = nl - n * L;
     const int a = tab.a[l], b = tab.b[l];
     const int pa = n * K + a, pb = n * K + b;
     const int nA = max(min(peak_ctr[pa * kCtrStride], cap), 0), nB = max(min(peak_ctr[pb * kCtrStride], cap), 0);
 
-    // order the two peak lists: threads [0, 256) take list A, [256, 512) list B
+    // order the two peak lists: threads [0, 256) take list A, [256, 512) list B.  The first limb
+    // that uses a part also publishes the part's ordered list and its count.
     {
         const int half = tid >> 8, t = tid & (kSmallPeaks - 1);
+        const int plane = half == 0 ? pa : pb;
         const int cnt = half == 0 ? nA : nB;
         const bool mine = half < 2 && t < cnt;
-        const uint64_t e = mine ? peak_stage[(size_t)(half == 0 ? pa : pb) * cap2 + t] : ~0ull;
+        const bool publish = half < 2 && tab.writer[half == 0 ? a : b] == l;
+        const uint64_t e = mine ? peak_stage[(size_t)plane * cap2 + t] : ~0ull;
         if (half < 2) sk[tid] = e;
         if (tid == 0) lds_cnt = 0;
+        if (publish && t == 0) {
+            const int raw = peak_ctr[plane * kCtrStride];
+            pcounts[plane] = raw;
+            if (raw > cap) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
+        }
         __syncthreads();
         if (mine) {
             const uint64_t *skh = sk + half * kSmallPeaks;
             int r = 0;
             for (int u = 0; u < cnt; ++u) r += skh[u] < e;
             const int key = (int)(e >> 32);
-            const int y = key / W;
-            lxy[2 * half][r] = key - y * W;
+            const int y = key / W, x = key - y * W;
+            lxy[2 * half][r] = x;
             lxy[2 * half + 1][r] = y;
+            if (publish) {
+                const size_t o = (size_t)plane * cap + r;
+                px[o] = x;
+                py[o] = y;
+                ps[o] = __uint_as_float((uint32_t)e);
+            }
+        }
+        __syncthreads();
+    }
+    // parts that no limb uses are published by the image's first limb
+    if (l == 0) {
+        for (int c = 0; c < K; ++c) {
+            if (tab.writer[c] >= 0) continue;
+            const int plane = n * K + c;
+            const int raw = peak_ctr[plane * kCtrStride];
+            const int cnt = max(min(raw, cap), 0);
+            const uint64_t e = tid < cnt ? peak_stage[(size_t)plane * cap2 + tid] : ~0ull;
+            __syncthreads();
+            if (tid < kSmallPeaks) sk[tid] = e;
+            if (tid == 0) {
+                pcounts[plane] = raw;
+                if (raw > cap) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
+            }
+            __syncthreads();
+            if (tid < cnt) {
+                int r = 0;
+                for (int u = 0; u < cnt; ++u) r += sk[u] < e;
+                const int key = (int)(e >> 32);
+                const int y = key / W;
+                const size_t o = (size_t)plane * cap + r;
+                px[o] = key - y * W;
+                py[o] = y;
+                ps[o] = __uint_as_float((uint32_t)e);
+            }
         }
         __syncthreads();
     }
@@ -501,7 +524,7 @@ hipError_t launch_limb_small(const float *paf_hi, const void *paf_lo, hp_dtype d
 {
     SampleT st;
     for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
-    dim3 grid(N * L + N * K), block(kSmallBlock);
+    dim3 grid(N * L), block(kSmallBlock);
 #define HP_LIMB_SMALL_ARGS(LO)                                                                                        \
     paf_hi, LO, h, w, T, st, K, L, N *L, prm.n_samples, prm.paf_thr, need, peak_ctr, peak_stage, pk.cap, cap2,        \
         pk.count, pk.x, pk.y, pk.score, cands.count, cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i,   \
@@ -517,7 +540,7 @@ hipError_t launch_limb_small(const float *paf_hi, const void *paf_lo, hp_dtype d
 }
 
 hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
-                        const int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
+                        int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
                         const hp_pairs &conns, int32_t *status, hipStream_t s)
 {
     dim3 grid(N * L), block(kBlock);

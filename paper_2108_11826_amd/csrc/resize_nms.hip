@@ -213,10 +213,12 @@ __global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo, int total_nodes, int K,
                                                        int C_mem, int h, int w, float thr, int32_t *counts,
-                                                       uint64_t *stage, int cap, int cap2)
+                                                       uint64_t *stage, int cap, int cap2, int32_t *status)
 {
     __shared__ int queue[kBlock];
     __shared__ int scratch[kBlock / kWave + 1];
+    // first kernel of hp_postprocess: it clears the status word (no kernel of this launch sets bits)
+    if (status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
     const int node0 = blockIdx.x * kBlock;
     const int node = node0 + threadIdx.x;
     bool active = false;
@@ -285,21 +287,39 @@ hipError_t launch_resize_write(const void *lo_a, const void *lo_b, hp_dtype dt, 
 
 template <typename T>
 static hipError_t launch_resize_nms_t(const T *lo, int N, int K, int C_mem, int h, int w, float thr, int32_t *counts,
-                                      uint64_t *stage, int cap, int cap2, hipStream_t s)
+                                      uint64_t *stage, int cap, int cap2, int32_t *status, hipStream_t s)
 {
     long long nodes64 = (long long)N * K * h * w;
     if (nodes64 <= 0 || nodes64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
     int nodes = (int)nodes64;
     hipLaunchKernelGGL((k_resize_nms<T>), dim3((nodes + kBlock - 1) / kBlock), dim3(kBlock), 0, s, lo, nodes, K, C_mem,
-                       h, w, thr, counts, stage, cap, cap2);
+                       h, w, thr, counts, stage, cap, cap2, status);
     return hipGetLastError();
 }
 
 hipError_t launch_resize_nms(const void *lo, hp_dtype dt, int N, int K, int C_mem, int h, int w, float thr,
-                             int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s)
+                             int32_t *counts, uint64_t *stage, int cap, int cap2, int32_t *status, hipStream_t s)
 {
-    if (dt == HP_F16) return launch_resize_nms_t((const __half *)lo, N, K, C_mem, h, w, thr, counts, stage, cap, cap2, s);
-    return launch_resize_nms_t((const float *)lo, N, K, C_mem, h, w, thr, counts, stage, cap, cap2, s);
+    if (dt == HP_F16)
+        return launch_resize_nms_t((const __half *)lo, N, K, C_mem, h, w, thr, counts, stage, cap, cap2, status, s);
+    return launch_resize_nms_t((const float *)lo, N, K, C_mem, h, w, thr, counts, stage, cap, cap2, status, s);
+}
+
+__global__ void k_zero(uint32_t *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0u;
+}
+
+hipError_t launch_zero(void *p, size_t bytes, hipStream_t s)
+{
+    const size_t n = bytes / 4;
+    size_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_zero, dim3((unsigned)blocks), dim3(kBlock), 0, s, (uint32_t *)p, n);
+    return hipGetLastError();
 }
 
 // Peak detection on a materialised map.  One thread owns an 8-row x 4-column tile and reads
@@ -374,14 +394,18 @@ hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int 
 
 // One workgroup per (image, part): sorts the unordered staged peaks by raster key and
 // writes the ordered list.
-__global__ __launch_bounds__(kBlock) void k_sort_peaks(const int32_t *ctr, uint64_t *stage, int cap, int cap2, int W,
+__global__ __launch_bounds__(kBlock) void k_sort_peaks(int32_t *ctr, uint64_t *stage, int cap, int cap2, int W,
                                                        int32_t *counts, int32_t *px, int32_t *py,
                                                        float *ps, int32_t *status)
 {
     __shared__ uint64_t sk[kLdsSort];
     const int plane = blockIdx.x;
     const int cnt = ctr[plane * kCtrStride];
-    if (threadIdx.x == 0) counts[plane] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        counts[plane] = cnt;
+        ctr[plane * kCtrStride] = 0;          // this workgroup is the list's only reader: leave it ready for the next call
+    }
     const int n = max(min(cnt, cap), 0);
     if (cnt > cap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_PEAK_OVERFLOW);
     if (n == 0) return;
@@ -426,7 +450,7 @@ __global__ __launch_bounds__(kBlock) void k_sort_peaks(const int32_t *ctr, uint6
     }
 }
 
-hipError_t launch_sort_peaks(const int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
+hipError_t launch_sort_peaks(int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
                              const hp_peaks &pk, int32_t *status, hipStream_t s)
 {
     hipLaunchKernelGGL(k_sort_peaks, dim3(planes), dim3(kBlock), 0, s, ctr, stage, cap, cap2, W, pk.count, pk.x, pk.y,

@@ -216,3 +216,19 @@ def test_assembly_with_tables_beyond_lds():
     m.hp_postprocess(to_dev(b.cm), to_dev(b.paf), skel_of(sk),
                      m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
     check_all(buf, ora)
+
+
+def test_parts_used_by_no_limb_are_still_listed():
+    """A skeleton whose limb table leaves parts out: their peak lists must still come back
+    (small capacities: the one-launch limb kernel publishes them; large: the general kernels)."""
+    cfg = SMALL[3]
+    b = generate(cfg)
+    sk = cfg.skeleton
+    la, lb = sk.limb_a[5:9], sk.limb_b[5:9]
+    paf = np.ascontiguousarray(b.paf[:, 10:18])
+    ora = oracle.postprocess(b.cm, paf, la, lb, DEFAULT_PARAMS, threads=4)
+    m = hp()
+    for caps in ((64, 256, 64), (512, 4096, 64)):
+        buf = m.Buffers(b.cm.shape[0], sk.n_parts, 4, cfg.h, cfg.w, *caps, DEV)
+        m.hp_postprocess(to_dev(b.cm), to_dev(paf), m.Skeleton(sk.n_parts, la, lb), prm_of(), buf)
+        check_all(buf, ora)

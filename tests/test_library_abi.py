@@ -133,6 +133,9 @@ def test_staged_calls_reject_bad_calls(L):
     assert L.hp_assemble(byref(sk.c), byref(prm.c), 0, byref(pk), byref(cd), byref(cn), byref(ps), FAKE, ws, FAKE, None) == -1
     assert L.hp_assemble(byref(sk.c), byref(prm.c), 1, byref(pk), byref(cd), byref(cn), byref(ps), FAKE, 16, FAKE, None) == -3
     assert L.hp_profile_begin(0) == -1
+    assert L.hp_workspace_init(None, 1024, None) == -3
+    assert L.hp_workspace_init(FAKE + 4, 1024, None) == -3
+    assert L.hp_workspace_init(FAKE, 1022, None) == -3
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):
