@@ -20,8 +20,12 @@
 
 namespace hp {
 
-constexpr int kPool16 = 40960;   // int16 entries: owner table, person slots, connection ends
-constexpr int kPool32 = 12288;   // 32-bit entries: person part masks and scores, connection and peak scores
+// LDS pool sizes of the two builds of the kernel (int16 entries: owner table and person slots;
+// 32-bit entries: connection records, person masks and scores).  The small build leaves room
+// for several workgroups per CU, which matters when calls on several streams overlap: a
+// workgroup of the large build owns most of a CU's LDS.
+constexpr int kPool16Large = 40960, kPool32Large = 12288;
+constexpr int kPool16Small = 12288, kPool32Small = 4096;
 
 // Person tables addressed through one interface so that the fold is written once.  A person
 // is K slots (peak rank per part), a bit mask of the filled parts (its part count is the
@@ -143,6 +147,7 @@ __device__ __forceinline__ void emit_persons(const Tab &t, int n, int np, int K,
     }
 }
 
+template <int kPool16, int kPool32>
 __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L, int min_parts,
                                                     const int32_t *__restrict__ pcounts,
                                                     const float *__restrict__ pscore, int cap,
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
                                                     int32_t *peak_ctr, int32_t *cand_ctr)
 {
     __shared__ int16_t pool[kPool16];
-    __shared__ uint32_t pool32[kPool32];
+    __shared__ __align__(16) uint32_t pool32[kPool32];
     __shared__ int moff[HP_MAX_LIMBS + 1];
     const int n = blockIdx.x;
     const int lane = threadIdx.x;
@@ -182,22 +187,25 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
     for (int d = kWave / 2; d > 0; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
     __syncthreads();
 
-    // persons never outnumber connections
-    const bool fits = (long long)K * cmax + (long long)tot * K <= kPool16 && 7LL * tot <= kPool32 &&
-                      (long long)K * cmax <= 65535 && tot < 32767;
+    // persons never outnumber connections; one spare person, owner entry and slot row absorb the
+    // stores of lanes that have nothing to write, so the fold runs without branches
+    const int tot2 = (tot + 2) & ~1;              // persons incl. the spare, kept even for 8-byte alignment
+    const bool fits = (long long)K * cmax + 1 + (long long)tot2 * K <= kPool16 && 7LL * tot2 <= kPool32 &&
+                      (long long)K * cmax < 65535 && tot < 32766;
     if (fits) {
         // LDS tables.  Everything about a connection that does not depend on the fold's state is
         // gathered once: its two owner-table indices, its two peak ranks, its score and the
         // scores of its two peaks.
-        int16_t *owner = pool;                      // [K][cmax] person owning each peak, -1 = none
-        int16_t *slots = owner + K * cmax;          // [tot][K]  valid where the person's mask says so
-        uint32_t *pmask = pool32;                   // [tot]     filled parts of a person, 0 = merged away
-        float *pscr = (float *)(pool32 + tot);      // [tot]
-        uint32_t *c_own = pool32 + 2 * tot;         // [tot]     a*cmax+i | (b*cmax+j) << 16
-        uint32_t *c_ij = pool32 + 3 * tot;          // [tot]     i | j << 16
-        float *c_s = (float *)(pool32 + 4 * tot), *c_sa = c_s + tot, *c_sb = c_sa + tot;
+        uint4 *rec = (uint4 *)pool32;                        // [tot]  a*cmax+i | (b*cmax+j)<<16, i | j<<16, s, score of peak a
+        float *c_sb = (float *)(pool32 + 4 * tot2);          // [tot]  score of peak b
+        uint2 *pst = (uint2 *)(pool32 + 5 * tot2);           // [tot + 1] person: filled-part mask (0 = merged away), score
+        int16_t *owner = pool;                               // [K * cmax + 1] person owning each peak, -1 = none
+        int16_t *slots = owner + K * cmax + 1;               // [tot + 1][K] valid where the person's mask says so
+        const int spare_p = tot, spare_o = K * cmax;
 
         for (int idx = lane; idx < K * cmax; idx += kWave) owner[idx] = -1;
+        const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
+        const int my_base = incl - mc;
         constexpr int U = 4;
         for (int e0 = 0; e0 < tot; e0 += kWave * U) {
             int vi[U], vj[U], va[U], vb[U];
@@ -205,17 +213,20 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
 #pragma unroll
             for (int q = 0; q < U; ++q) {
                 const int e = e0 + q * kWave + lane;
-                vi[q] = vj[q] = va[q] = vb[q] = 0;
+                // the limb of flat connection e: the number of limbs that end at or before e
+                int l = 0;
+                for (int t = 0; t < L; ++t) l += __builtin_amdgcn_readlane(incl, t) <= e;
+                l = min(l, L - 1);
+                va[q] = __shfl(my_a, l);
+                vb[q] = __shfl(my_b, l);
+                const int k = e - __shfl(my_base, l);
+                vi[q] = vj[q] = 0;
                 vs[q] = 0.0f;
                 if (e < tot) {
-                    int l = 0;
-                    while (moff[l + 1] <= e) ++l;
-                    const size_t idx = (size_t)(n * L + l) * mcap + (e - moff[l]);
+                    const size_t idx = (size_t)(n * L + l) * mcap + k;
                     vi[q] = mi[idx];
                     vj[q] = mj[idx];
                     vs[q] = ms[idx];
-                    va[q] = tab.a[l];
-                    vb[q] = tab.b[l];
                 }
             }
 #pragma unroll
@@ -231,21 +242,18 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
             for (int q = 0; q < U; ++q) {
                 const int e = e0 + q * kWave + lane;
                 if (e < tot) {
-                    c_own[e] = (uint32_t)(va[q] * cmax + vi[q]) | ((uint32_t)(vb[q] * cmax + vj[q]) << 16);
-                    c_ij[e] = (uint32_t)vi[q] | ((uint32_t)vj[q] << 16);
-                    c_s[e] = vs[q];
-                    c_sa[e] = vsa[q];
+                    rec[e] = make_uint4((uint32_t)(va[q] * cmax + vi[q]) | ((uint32_t)(vb[q] * cmax + vj[q]) << 16),
+                                        (uint32_t)vi[q] | ((uint32_t)vj[q] << 16), __float_as_uint(vs[q]),
+                                        __float_as_uint(vsa[q]));
                     c_sb[e] = vsb[q];
                 }
             }
         }
-        // lane l keeps limb l's description; the fold reads it with uniform lane reads
-        const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
-        const int my_base = incl - mc;
         __syncthreads();
 
         int np = 0;
         for (int l = 0; l < L; ++l) {
+            // lane l holds limb l's description; read it with uniform lane reads
             const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
             const int base = __builtin_amdgcn_readlane(my_base, l), cnt = __builtin_amdgcn_readlane(mc, l);
             const uint32_t bit_a = 1u << a, bit_b = 1u << b;
@@ -253,14 +261,16 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
                 const int k = k0 + lane;
                 const bool act = k < cnt;
                 const int e = act ? base + k : 0;
-                const uint32_t own = c_own[e], ij = c_ij[e];
-                const float s = c_s[e], sa = c_sa[e], sb = c_sb[e];
-                const int oa = own & 0xffffu, ob = own >> 16;
-                const int i = ij & 0xffffu, j = ij >> 16;
+                const uint4 r = rec[e];
+                const float sb = c_sb[e];
+                const float s = __uint_as_float(r.z), sa = __uint_as_float(r.w);
+                const int oa = r.x & 0xffffu, ob = r.x >> 16;
+                const int i = r.y & 0xffffu, j = r.y >> 16;
                 const int pa = act ? (int)owner[oa] : -1, pb = act ? (int)owner[ob] : -1;
                 const bool has_a = pa >= 0, has_b = pb >= 0;
-                const uint32_t ma = has_a ? pmask[pa] : 0u, mb = has_b ? pmask[pb] : 0u;
-                const float sca = has_a ? pscr[pa] : 0.0f, scb = has_b ? pscr[pb] : 0.0f;
+                const uint2 sta = pst[max(pa, 0)], stb = pst[max(pb, 0)];
+                const uint32_t ma = has_a ? sta.x : 0u, mb = has_b ? stb.x : 0u;
+                const float sca = __uint_as_float(sta.y), scb = __uint_as_float(stb.y);
 
                 const bool fresh = act && !has_a && !has_b;
                 const unsigned long long fm = __ballot(fresh);
@@ -268,51 +278,62 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
                 const bool ext_b = !has_a && has_b && !(mb & bit_a);      // the b-side owner gains part a
                 const bool cyc = has_a && pa == pb;
                 const bool mrg = has_a && has_b && pa != pb && (ma & mb) == 0u;
-                if (fresh || ext_a || ext_b || cyc) {
-                    const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
-                    const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
-                    const float s0 = fresh ? sa : has_a ? sca : scb;      // running score, then the new
-                    const float s1 = fresh ? sb : ext_a ? sb : sa;        // peak's score (if any), then s
-                    const float sc = cyc ? s0 : s0 + s1;
-                    pmask[p] = mk;
-                    pscr[p] = sc + s;
-                    if (fresh || ext_b) {
-                        slots[p * K + a] = (int16_t)i;
-                        owner[oa] = (int16_t)p;
-                    }
-                    if (fresh || ext_a) {
-                        slots[p * K + b] = (int16_t)j;
-                        owner[ob] = (int16_t)p;
-                    }
-                }
-                if (mrg) {
-                    const int lo = min(pa, pb), hi = max(pa, pb);
-                    const uint32_t mhi = pa < pb ? mb : ma;
-                    for (int c = 0; c < K; ++c) {
-                        if (mhi & (1u << c)) {
-                            const int16_t r = slots[hi * K + c];
-                            slots[lo * K + c] = r;
-                            owner[c * cmax + r] = (int16_t)lo;
+                const bool upd = fresh || ext_a || ext_b || cyc;
+                const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
+                const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
+                const float s0 = fresh ? sa : has_a ? sca : scb;          // running score, then the new
+                const float s1 = (fresh || ext_a) ? sb : sa;              // peak's score (if any), then s
+                const float sc = cyc ? s0 : s0 + s1;
+                const bool wa = fresh || ext_b, wb = fresh || ext_a;
+                pst[upd ? p : spare_p] = make_uint2(mk, __float_as_uint(sc + s));
+                slots[(wa ? p : spare_p) * K + a] = (int16_t)i;
+                owner[wa ? oa : spare_o] = (int16_t)p;
+                slots[(wb ? p : spare_p) * K + b] = (int16_t)j;
+                owner[wb ? ob : spare_o] = (int16_t)p;
+                if (__any(mrg)) {
+                    if (mrg) {
+                        const int lo = min(pa, pb), hi = max(pa, pb);
+                        const uint32_t mhi = pa < pb ? mb : ma;
+                        for (int c = 0; c < K; ++c) {
+                            if (mhi & (1u << c)) {
+                                const int16_t rr = slots[hi * K + c];
+                                slots[lo * K + c] = rr;
+                                owner[c * cmax + rr] = (int16_t)lo;
+                            }
                         }
+                        const float scm = (pa < pb) ? sca + scb : scb + sca;
+                        pst[lo] = make_uint2(ma | mb, __float_as_uint(scm + s));
+                        pst[hi] = make_uint2(kDead, 0u);
                     }
-                    pmask[lo] = ma | mb;
-                    const float sc = (pa < pb) ? sca + scb : scb + sca;
-                    pscr[lo] = sc + s;
-                    pmask[hi] = kDead;
                 }
                 np += __popcll(fm);
                 __syncthreads();
             }
         }
-        LdsTables t;
-        t.owner = owner;
-        t.slots = slots;
-        t.mask = pmask;
-        t.score = pscr;
-        t.ostride = cmax;
-        t.K = K;
-        emit_persons(t, n, min(np, tot), K, min_parts, pose_slots, pose_nparts, pose_score, pose_counts, pcap,
-                     status);
+
+        // alive persons with enough parts, in creation order
+        np = min(np, tot);
+        int out = 0;
+        for (int base = 0; base < np; base += kWave) {
+            const int p = base + lane;
+            const uint2 st = pst[min(p, tot)];
+            const uint32_t mk = p < np ? st.x : kDead;
+            const int parts = __popc(mk);
+            const bool keep = mk != kDead && parts >= min_parts;
+            const unsigned long long m = __ballot(keep);
+            const int rank = out + __popcll(m & lt);
+            if (keep && rank < pcap) {
+                const size_t o = (size_t)n * pcap + rank;
+                for (int c = 0; c < K; ++c) pose_slots[o * K + c] = (mk >> c) & 1u ? (int)slots[p * K + c] : -1;
+                pose_nparts[o] = parts;
+                pose_score[o] = __uint_as_float(st.y);
+            }
+            out += __popcll(m);
+        }
+        if (lane == 0) {
+            pose_counts[n] = out;
+            if (out > pcap) atomicOr(status, (int)HP_STATUS_POSE_OVERFLOW);
+        }
         return;
     }
 
@@ -361,10 +382,18 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
                            const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
                            int32_t *status, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_assemble, dim3(N), dim3(kWave), 0, s, T, K, L, min_parts, pk.count, pk.score, pk.cap,
-                       conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner, ws.wslots, ws.wmask,
-                       ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score, poses.count, poses.cap, status,
-                       ws.peak_ctr, ws.cand_ctr);
+    // few peaks per part: the tables of an image almost surely fit the small pools (if they do
+    // not, the fold runs on the workspace tables, slower but the same)
+    if (pk.cap <= 256)
+        hipLaunchKernelGGL((k_assemble<kPool16Small, kPool32Small>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
+                           pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
+                           ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
+                           poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr);
+    else
+        hipLaunchKernelGGL((k_assemble<kPool16Large, kPool32Large>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
+                           pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
+                           ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
+                           poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr);
     return hipGetLastError();
 }
 

@@ -51,14 +51,10 @@ template <> __device__ __forceinline__ float ld<__half>(const __half *p) { retur
 // One axis of the x8 half-pixel bilinear map: output index X reads nodes i0, i1 with weight f on i1.
 __device__ __forceinline__ void axis8(int X, int n, int &i0, int &i1, float &f)
 {
-    int num = 2 * X - 7;                       // 16 * source coordinate
-    if (num < 0) {
-        i0 = 0;
-        f = 0.0f;
-    } else {
-        i0 = num >> 4;
-        f = (float)(num & 15) * 0.0625f;
-    }
+    // 16 * source coordinate; left of node 0 it is clamped to 0, which gives node 0 and weight 0
+    const int num = max(2 * X - 7, 0);
+    i0 = num >> 4;
+    f = (float)(num & 15) * 0.0625f;
     i1 = min(i0 + 1, n - 1);
 }
 

@@ -6,8 +6,14 @@
 
 namespace hp {
 
-constexpr int kChunk0 = 4;     // PAF samples fetched together by the scorer: first chunk,
-constexpr int kChunk1 = 8;     // later chunks
+// How many PAF samples the scorer fetches together.  A pair dies at its (S - need + 1)-th bad
+// sample, three with the usual parameters, and a wavefront keeps going while any lane lives.
+// Few pairs (latency matters): 4 samples, then the rest 8 at a time.  Many pairs of mostly
+// unrelated peaks (throughput matters): 3, then one at a time for two steps (after five
+// samples almost every wavefront has no pair left), then the rest.
+struct ChunksLatency { static constexpr int first = 4, singles = 0; };
+struct ChunksThroughput { static constexpr int first = 3, singles = 2; };
+constexpr int kChunkRest = 8;
 constexpr int kRankSort = 256; // lists up to this length are ordered by counting ranks through LDS
 
 // Sample positions along a candidate, t_k = k / (S - 1), divided on the host (the same
@@ -71,8 +77,8 @@ __device__ __forceinline__ void score_chunk(int k0, int S, const SampleT &st, fl
 }
 
 // Scores the candidate from pixel (x0, y0) to pixel (x1, y1).  Returns whether it is accepted
-// (enough valid samples and a positive mean); the first kChunk0 samples decide for most pairs.
-template <typename T, bool FROM_HI>
+// (enough valid samples and a positive mean); CH is the chunk schedule.
+template <typename T, bool FROM_HI, typename CH>
 __device__ __forceinline__ bool score_pair(int x0, int y0, int x1, int y1, int S, const SampleT &st, float paf_thr,
                                            int max_bad, int H, int W, int h, int w, const float *hx, const float *hy,
                                            const T *lx, const T *ly, float &score)
@@ -84,11 +90,19 @@ __device__ __forceinline__ bool score_pair(int x0, int y0, int x1, int y1, int S
     const float ux = fdx / norm, uy = fdy / norm;
     float acc = 0.0f;
     int bad = 0;
-    score_chunk<T, FROM_HI, kChunk0>(0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
-                                     acc, bad);
-    for (int k0 = kChunk0; k0 < S && bad <= max_bad; k0 += kChunk1)
-        score_chunk<T, FROM_HI, kChunk1>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy, lx,
-                                         ly, acc, bad);
+    score_chunk<T, FROM_HI, CH::first>(0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
+                                       acc, bad);
+    int k0 = CH::first;
+#pragma unroll
+    for (int q = 0; q < CH::singles; ++q) {
+        if (k0 < S && bad <= max_bad)
+            score_chunk<T, FROM_HI, 1>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
+                                       acc, bad);
+        ++k0;
+    }
+    for (; k0 < S && bad <= max_bad; k0 += kChunkRest)
+        score_chunk<T, FROM_HI, kChunkRest>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
+                                            lx, ly, acc, bad);
     if (bad > max_bad) return false;
     score = acc / (float)S;
     return score > 0.0f;
@@ -133,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
         while (j < 0) { --i; j += nB; }
         while (j >= nB) { ++i; j -= nB; }
         float score;
-        if (score_pair<T, FROM_HI>(xa[i], ya[i], xb[j], yb[j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
+        if (score_pair<T, FROM_HI, ChunksThroughput>(xa[i], ya[i], xb[j], yb[j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
                                    score)) {
             const int slot = atomicAdd(&ccounts[nl * kCtrStride], 1);
             if (slot < ccap)
@@ -436,7 +450,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
             while (j < 0) { --i; j += nB; }
             while (j >= nB) { ++i; j -= nB; }
             float score;
-            if (score_pair<T, FROM_HI>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx,
+            if (score_pair<T, FROM_HI, ChunksLatency>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx,
                                        hy, lx, ly, score)) {
                 const int slot = atomicAdd(&lds_cnt, 1);
                 if (slot < kSmallCands)
