@@ -139,6 +139,44 @@ def main():
     prof = hp.hp_profile_end()
     kern_us = {k: 1e3 * ms / n for k, (ms, n) in prof.items()}
 
+    # the staged calls (hp_resize -> hp_find_peaks -> hp_score_limbs -> hp_assemble) on the materialised
+    # maps: their peak search reads the hi-res confidence maps from HBM, the general scorer gathers PAFs
+    staged_steps = max(3, min(args.steps, 50))
+
+    def staged():
+        hp.hp_find_peaks(cm_hi, K, P.peak_thr, buf)
+        hp.hp_score_limbs(paf_hi, skel, prm, buf)
+        hp.hp_assemble(skel, prm, buf)
+
+    step(True)
+    staged()
+    torch.cuda.synchronize()
+    poses, _ = buf.host_poses()
+    ok = buf.host_status() == 0 and all(np.array_equal(poses[n][0], ora["poses"][n][0]) and
+                                        np.array_equal(poses[n][2], ora["poses"][n][2]) for n in range(N))
+    parity = parity and bool(ok)
+    hp.hp_profile_begin(staged_steps * 8)
+    for _ in range(staged_steps):
+        staged()
+    torch.cuda.synchronize()
+    staged_us = {k: 1e3 * ms / n for k, (ms, n) in hp.hp_profile_end().items()}
+
+    # what a plain fill of the same number of bytes reaches on this GPU (the practical ceiling of a
+    # write-dominated kernel), timed with events on the same stream
+    fill_t = torch.empty(((cm_hi.numel() + paf_hi.numel()),), dtype=torch.float32, device=dev)
+    for _ in range(3):
+        fill_t.fill_(1.0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fills = 20
+    e0.record()
+    for _ in range(fills):
+        fill_t.fill_(1.0)
+    e1.record()
+    torch.cuda.synchronize()
+    fill_us = 1e3 * e0.elapsed_time(e1) / fills
+    fill_gbs = fill_t.numel() * 4 / (fill_us * 1e-6) / 1e9
+    del fill_t
+
     n_pairs = sum(len(ora["peaks"][n][a][0]) * len(ora["peaks"][n][b][0]) for n in range(N) for a, b in sk.limbs)
     esz = batch.cm.dtype.itemsize
     lo_bytes = (batch.cm.size + batch.paf.size) * esz
@@ -155,7 +193,16 @@ def main():
                           "dominant kernel of the materialising form)",
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "bytes_per_launch": k1_bytes, "us_per_launch": round(k1_us, 2)}
+                "bytes_per_launch": k1_bytes, "us_per_launch": round(k1_us, 2),
+                "plain_fill_same_bytes": {"us": round(fill_us, 2), "GB/s": round(fill_gbs, 1),
+                                          "frac_of_fill": round(achieved / fill_gbs, 4)}}
+    # staged peak search: reads K of the K+1 hi-res confidence maps once, writes peaks only
+    nms_bytes = N * K * cfg.H * cfg.W * 4
+    nms_ach = nms_bytes / (staged_us["nms_hi"] * 1e-6) / 1e9
+    roofline_nms_hi = {"kernel": "k_nms_hi (hp_find_peaks: 3x3 thresholded NMS on the materialised hi-res CMs)",
+                       "bound": "hbm", "achieved": round(nms_ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(nms_ach / HBM_PEAK_GBS, 4), "bytes_per_launch": nms_bytes,
+                       "us_per_launch": round(staged_us["nms_hi"], 2)}
     # fused form: nothing but the lo-res CM is read; the bound is the plain ALUs
     cm_px = N * K * cfg.H * cfg.W
     fused_us = kern_us["resize_nms"]
@@ -218,7 +265,9 @@ def main():
         "kernel_us": {k: round(v, 2) for k, v in sorted(kern_us.items())},
         "kernel_us_note": "HIP-event brackets around each launch; the bracket itself adds 2-5 us, "
                           "see profiles/ for rocprofv3 kernel durations",
-        "roofline": roofline, "roofline_fused": roofline_fused, "roofline_scoring": roofline_scoring,
+        "staged_kernel_us": {k: round(v, 2) for k, v in sorted(staged_us.items())},
+        "roofline": roofline, "roofline_fused": roofline_fused, "roofline_nms_hi": roofline_nms_hi,
+        "roofline_scoring": roofline_scoring,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -162,15 +162,40 @@ __device__ __forceinline__ void tile_peaks(float (&v)[10][6], int j, int h, int 
 // The four columns of a group share one pair of source nodes, the row one pair of source rows:
 // four loads (L1/L2 hits) per thread.  One launch covers `planes` consecutive planes starting
 // at `plane0`, counted over channels [0, Ca) of tensor a followed by the Cb channels of tensor b.
+//
+// The source is 64 times smaller than the output, but a workgroup that finds its source rows
+// in no cache waits a full memory round trip before its only store, and with every workgroup
+// of the write front in that state the kernel runs a third slower (measured after a kernel
+// that had swept the caches: 94 us instead of 65 us for 447 MB).  So the workgroups of the
+// first `warm_planes` planes, which are dispatched first, begin by streaming both source
+// tensors through the caches, 16 bytes per thread and step (`vec_a`, `vec_b` 16-byte units;
+// 0 = skip); every later workgroup then finds its rows in the shared cache.
 template <typename T>
 __global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
                                                        float *__restrict__ hi_a, float *__restrict__ hi_b,
                                                        int plane0, int Ca, int Ca_mem, int Cb, int h, int w,
-                                                       int W4, int H, int xsplit)
+                                                       int W4, int H, int xsplit, unsigned vec_a, unsigned vec_b,
+                                                       unsigned warm_planes)
 {
     // blockIdx.x: column part (1 unless a row is wider than a workgroup), y: row group, z: plane
     const int x4 = blockIdx.x * xsplit + threadIdx.x;
     const int Y = blockIdx.y * blockDim.y + threadIdx.y;
+    if (blockIdx.z < warm_planes) {
+        const unsigned nthr = blockDim.x * blockDim.y;
+        const unsigned stride = gridDim.x * gridDim.y * warm_planes * nthr;
+        const unsigned first = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * nthr +
+                               threadIdx.y * blockDim.x + threadIdx.x;
+        uint32_t seen = 0;
+        for (unsigned i = first; i < vec_a; i += stride) {
+            const uint4 v = ((const uint4 *)lo_a)[i];
+            seen |= (v.x ^ v.y) | (v.z ^ v.w);
+        }
+        for (unsigned i = first; i < vec_b; i += stride) {
+            const uint4 v = ((const uint4 *)lo_b)[i];
+            seen |= (v.x ^ v.y) | (v.z ^ v.w);
+        }
+        asm volatile("" ::"v"(seen));        // the loads are wanted for their effect on the caches
+    }
     if (x4 >= W4 || Y >= H) return;
 
     // plane -> tensor, uniform over the workgroup
@@ -267,10 +292,21 @@ static hipError_t launch_resize_write_t(const T *lo_a, const T *lo_b, float *hi_
     const int gx = (W4 + bx - 1) / bx, groups = (H + R - 1) / R;
     const long long planes = (long long)N * (Ca + Cb);
     if (planes <= 0 || planes >= (1LL << 31) || groups > 65535) return hipErrorInvalidValue;
+    // source tensors in 16-byte units for the cache-warming pass of the first launch (a hint:
+    // skipped for a pointer that is not 16-byte aligned; a tail shorter than 16 bytes is left out)
+    auto units = [&](const T *p, long long channels) -> unsigned {
+        if (!p || ((uintptr_t)p & 15) != 0) return 0u;
+        return (unsigned)((unsigned long long)N * channels * h * w * sizeof(T) / 16);    // < 2^28 by check_dims
+    };
+    const unsigned vec_a = units(lo_a, Ca_mem), vec_b = units(lo_b, Cb);
+    // the planes whose workgroups share that pass: about two workgroups per compute unit
+    long long warm = (512 + (long long)gx * groups - 1) / ((long long)gx * groups);
+    if (warm > planes) warm = planes;
+    if ((vec_a | vec_b) == 0u) warm = 0;
     for (long long p0 = 0; p0 < planes; p0 += 65535) {
         const long long np = planes - p0 < 65535 ? planes - p0 : 65535;
         hipLaunchKernelGGL((k_resize_write<T>), dim3(gx, groups, (unsigned)np), dim3(bx, R), 0, s, lo_a, lo_b, hi_a, hi_b,
-                           (int)p0, Ca, Ca_mem, Cb, h, w, W4, H, bx);
+                           (int)p0, Ca, Ca_mem, Cb, h, w, W4, H, bx, vec_a, vec_b, p0 == 0 ? (unsigned)warm : 0u);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -375,20 +411,136 @@ __global__ __launch_bounds__(kBlock) void k_nms_hi(const float *__restrict__ cm,
     }
 }
 
+// Peak detection on a materialised map whose rows are whole 16-byte groups: the memory-bound
+// form.  A wavefront owns a strip of R rows x 62 column groups (248 pixels): lane l reads group
+// 62 * strip_column - 1 + l, one 16-byte streaming load per row and R + 2 rows, all issued
+// before the first use.  The pixel left of a group and the pixel right of it come from the
+// neighbouring lanes, so lanes 0 and 63 only supply those and produce no output (their groups
+// belong to the next strips); groups and rows outside the map read as -inf.
+//
+// At 8 TB/s a pixel is worth 0.5 ns of one compute unit's time... the instruction budget is a
+// dozen vector instructions per pixel, so the test is arranged to need few: the 3x3 maximum m
+// comes from horizontal 3-maxima shared by three rows (4 max per pixel), a pixel is a
+// candidate when u >= m and u > thr (2 compares), and only candidates (a fraction of a
+// percent) go on to the tie-break against their four earlier neighbours.  Everything that is
+// the same for a whole wavefront (strip position, row addresses, edge cases) is computed on
+// the scalar unit: the strip comes from the block index, never from a division.
+constexpr int kStripRows = 16, kStripGroups = kWave - 2, kStripsPerBlock = 4;
+
+template <int R, bool EDGE>
+__device__ __forceinline__ void strip_peaks(const float *__restrict__ pl, int H, int W, int W4, int sx, int Y0, int lane,
+                                            float thr, int32_t *counts, uint64_t *stage, int plane, int cap, int cap2)
+{
+    const float ninf = -__builtin_huge_valf();
+    const int cg = sx * kStripGroups - 1 + lane;
+    const bool inb = !EDGE || (cg >= 0 && cg < W4);
+    const unsigned lane_off = 4u * (unsigned)(inb ? cg : 0);
+    v4f v[R + 2];
+#pragma unroll
+    for (int r = 0; r < R + 2; ++r) {
+        const int Y = Y0 + r - 1;                                  // uniform
+        const float *row = pl + (size_t)(unsigned)(EDGE ? min(max(Y, 0), H - 1) : Y) * (unsigned)W;
+        v[r] = __builtin_nontemporal_load((const v4f *)(row + lane_off));
+        if (EDGE && !(inb && Y >= 0 && Y < H)) v[r] = (v4f){ninf, ninf, ninf, ninf};
+    }
+    // window of three rows: horizontal 3-maxima of the row above (ha), the row (hc) and the row
+    // below (hb); left / right neighbour pixels of the row above (la, ra) and of the row (lc, rc).
+    // Lane 0 and lane 63 get their own value back from the shuffles: never used.
+    float ha[4], hc[4], hb[4], la, ra, lc, rc, lb, rb;
+    auto row_max3 = [&](const v4f &x, float (&h3)[4], float &l, float &r) {
+        l = __shfl_up(x.w, 1);
+        r = __shfl_down(x.x, 1);
+        h3[0] = fmaxf(fmaxf(l, x.x), x.y);
+        h3[1] = fmaxf(fmaxf(x.x, x.y), x.z);
+        h3[2] = fmaxf(fmaxf(x.y, x.z), x.w);
+        h3[3] = fmaxf(fmaxf(x.z, x.w), r);
+    };
+    row_max3(v[0], ha, la, ra);
+    row_max3(v[1], hc, lc, rc);
+    const bool out_lane = inb && lane != 0 && lane != kWave - 1;
+    const int key0 = Y0 * W + 4 * cg;
+#pragma unroll
+    for (int r = 1; r <= R; ++r) {
+        row_max3(v[r + 1], hb, lb, rb);             // every lane of the wavefront takes part in the shuffles
+        bool cand[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float u = v[r][k];
+            const float m = fmaxf(fmaxf(ha[k], hc[k]), hb[k]);
+            cand[k] = u >= m && u > thr;            // rows and groups outside the map hold -inf: never candidates
+        }
+        if (out_lane && (cand[0] || cand[1] || cand[2] || cand[3])) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (!cand[k]) continue;
+                // not below any neighbour; a peak if it also exceeds the four earlier ones
+                const float u = v[r][k];
+                const float ul = k == 0 ? la : v[r - 1][k - 1], ur = k == 3 ? ra : v[r - 1][k + 1];
+                const float lft = k == 0 ? lc : v[r][k - 1];
+                const float early = fmaxf(fmaxf(ul, v[r - 1][k]), fmaxf(ur, lft));
+                if (u > early) emit_peak(counts, stage, plane, cap, cap2, key0 + (r - 1) * W + k, u);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            ha[k] = hc[k];
+            hc[k] = hb[k];
+        }
+        la = lc; ra = rc;
+        lc = lb; rc = rb;
+    }
+}
+
+// block = (64, kStripsPerBlock): one wavefront per strip, strips below each other;
+// grid = (strips across, groups of strips down, planes)
+template <int R>
+__global__ __launch_bounds__(kWave *kStripsPerBlock) void k_nms_hi_strip(const float *__restrict__ cm, int plane0,
+                                                                         int C_cm, int K, int H, int W, int W4,
+                                                                         float thr, int32_t *counts, uint64_t *stage,
+                                                                         int cap, int cap2)
+{
+    const int lane = threadIdx.x;
+    const int sx = blockIdx.x;
+    const int sy = blockIdx.y * kStripsPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.y);
+    const int Y0 = sy * R;
+    if (Y0 >= H) return;
+    const int plane = plane0 + blockIdx.z;
+    const int n = plane / K, c = plane - n * K;
+    const float *pl = cm + ((size_t)n * C_cm + c) * (size_t)H * W;
+    const bool edge = sx == 0 || (sx + 1) * kStripGroups + 1 > W4 || Y0 == 0 || Y0 + R + 1 > H;
+    if (edge)
+        strip_peaks<R, true>(pl, H, W, W4, sx, Y0, lane, thr, counts, stage, plane, cap, cap2);
+    else
+        strip_peaks<R, false>(pl, H, W, W4, sx, Y0, lane, thr, counts, stage, plane, cap, cap2);
+}
+
 hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
                          int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s)
 {
+    if (W % 4 == 0 && ((uintptr_t)cm_hi % 16) == 0) {
+        constexpr int R = kStripRows;
+        const int W4 = W / 4;
+        const int strips_x = (W4 + kStripGroups - 1) / kStripGroups, strips_y = (H + R - 1) / R;
+        const int groups_y = (strips_y + kStripsPerBlock - 1) / kStripsPerBlock;
+        const long long planes = (long long)N * K;
+        if (planes <= 0 || planes >= (1LL << 31) || groups_y > 65535 || (long long)H * W >= (1LL << 31))
+            return hipErrorInvalidValue;
+        for (long long p0 = 0; p0 < planes; p0 += 65535) {
+            const long long np = planes - p0 < 65535 ? planes - p0 : 65535;
+            hipLaunchKernelGGL((k_nms_hi_strip<R>), dim3(strips_x, groups_y, (unsigned)np), dim3(kWave, kStripsPerBlock), 0,
+                               s, cm_hi, (int)p0, C_cm, K, H, W, W4, thr, counts, stage, cap, cap2);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     int tiles_x = (W + 3) / 4, tiles_y = (H + 7) / 8;
     long long total64 = (long long)N * K * tiles_x * tiles_y;
     if (total64 <= 0 || total64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
     int total = (int)total64;
     dim3 grid((total + kBlock - 1) / kBlock), block(kBlock);
-    if (W % 4 == 0 && ((uintptr_t)cm_hi % 16) == 0)
-        hipLaunchKernelGGL((k_nms_hi<true>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
-                           counts, stage, cap, cap2);
-    else
-        hipLaunchKernelGGL((k_nms_hi<false>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
-                           counts, stage, cap, cap2);
+    hipLaunchKernelGGL((k_nms_hi<false>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
+                       counts, stage, cap, cap2);
     return hipGetLastError();
 }
 

@@ -232,3 +232,25 @@ def test_parts_used_by_no_limb_are_still_listed():
         buf = m.Buffers(b.cm.shape[0], sk.n_parts, 4, cfg.h, cfg.w, *caps, DEV)
         m.hp_postprocess(to_dev(b.cm), to_dev(paf), m.Skeleton(sk.n_parts, la, lb), prm_of(), buf)
         check_all(buf, ora)
+
+
+@pytest.mark.parametrize("shape", [(37, 53), (9, 7), (1, 1), (3, 250), (40, 248), (41, 252), (16, 496), (64, 500), (5, 4)],
+                         ids=lambda s: f"{s[0]}x{s[1]}")
+def test_find_peaks_on_arbitrary_maps(shape):
+    """hp_find_peaks on given hi-res maps of any size: widths that are whole 16-byte groups take the
+    strip kernel (one, two and three strips across, ragged last strip, rows not a multiple of the
+    strip height), others the general one.  Values are quantised so that ties and plateaus abound."""
+    m = hp()
+    H, W = shape
+    rng = np.random.default_rng(H * 1000 + W)
+    N, K = 2, 3
+    maps = (rng.integers(0, 12, size=(N, K + 1, H, W)) / 16.0).astype(np.float32)
+    maps[0, 0, :, :] = 0.5                       # one plateau over a whole plane
+    maps[1, 1, H - 1, W - 1] = 2.0               # a peak in the last corner
+    maps[1, 2, 0, 0] = 2.0                       # and in the first
+    want = [[oracle.find_peaks(maps[n, c], 0.05) for c in range(K)] for n in range(N)]
+    cap = max(16, max(len(p[0]) for im in want for p in im) + 4)
+    buf = m.Buffers(N, K, 1, max(1, H // 8), max(1, W // 8), cap, 16, 16, DEV)
+    m.hp_find_peaks(to_dev(maps), K, 0.05, buf)
+    assert buf.host_status() == 0
+    assert_lists_equal("peaks", buf.host_peaks()[0], want)
