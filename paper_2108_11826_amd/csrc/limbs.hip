@@ -6,14 +6,13 @@
 
 namespace hp {
 
-// How many PAF samples the scorer fetches together.  A pair dies at its (S - need + 1)-th bad
-// sample, three with the usual parameters, and a wavefront keeps going while any lane lives.
-// Few pairs (latency matters): 4 samples, then the rest 8 at a time.  Many pairs of mostly
-// unrelated peaks (throughput matters): 3, then one at a time for two steps (after five
-// samples almost every wavefront has no pair left), then the rest.
-struct ChunksLatency { static constexpr int first = 4, singles = 0; };
-struct ChunksThroughput { static constexpr int first = 3, singles = 2; };
-constexpr int kChunkRest = 8;
+// How many PAF samples a full score fetches together (first, then `rest` at a time); a pair
+// dies at its (S - need + 1)-th bad sample, three with the usual parameters, and a wavefront
+// keeps going while any lane lives.  Few pairs, one launch (latency matters): 4 samples, then
+// the rest 8 at a time.  Survivors of the general scorer's screen: two at a time, which keeps
+// the register count low enough for eight wavefronts per SIMD.
+struct ChunksLatency { static constexpr int first = 4, singles = 0, rest = 8; };
+struct ChunksSurvivor { static constexpr int first = 2, singles = 0, rest = 2; };
 constexpr int kRankSort = 256; // lists up to this length are ordered by counting ranks through LDS
 
 // Sample positions along a candidate, t_k = k / (S - 1), divided on the host (the same
@@ -22,9 +21,28 @@ struct SampleT {
     float t[HP_MAX_SAMPLES];
 };
 
+// Two horizontally adjacent nodes in one load (the pair is only aligned like a single node).
+struct FloatPair { float a, b; };
+struct HalfPair { __half a, b; };
+__device__ __forceinline__ void ld_pair(const float *p, float &a, float &b)
+{
+    const FloatPair v = *reinterpret_cast<const FloatPair *>(p);
+    a = v.a;
+    b = v.b;
+}
+__device__ __forceinline__ void ld_pair(const __half *p, float &a, float &b)
+{
+    const HalfPair v = *reinterpret_cast<const HalfPair *>(p);
+    a = __half2float(v.a);
+    b = __half2float(v.b);
+}
+
 // The two PAF components of limb l at hi-res pixel (sy, sx), recomputed from the lo-res planes
 // with the upsampling arithmetic (horizontal pass on the two source rows, then vertical); the
-// node indices and weights are shared by the two components.
+// node indices and weights are shared by the two components.  The two nodes of a row are
+// neighbours in memory and come in one load; in the last column, where the upper node is
+// clamped onto the lower one, the pair is read one node to the left and its second half is
+// used twice.
 template <typename T>
 __device__ __forceinline__ void paf_from_lo(const T *__restrict__ lx, const T *__restrict__ ly, int h, int w, int sy,
                                             int sx, float &vx, float &vy)
@@ -34,10 +52,23 @@ __device__ __forceinline__ void paf_from_lo(const T *__restrict__ lx, const T *_
     axis8(sx, w, x0, x1, f);
     axis8(sy, h, y0, y1, g);
     const unsigned r0 = (unsigned)__mul24(y0, w), r1 = (unsigned)__mul24(y1, w);
-    const unsigned o00 = r0 + x0, o01 = r0 + x1, o10 = r1 + x0, o11 = r1 + x1;
     const float f1 = 1.0f - f, g1 = 1.0f - g;
-    const float ax = ld(lx + o00), bx = ld(lx + o01), cx = ld(lx + o10), dx = ld(lx + o11);
-    const float ay = ld(ly + o00), by = ld(ly + o01), cy = ld(ly + o10), dy = ld(ly + o11);
+    float ax, bx, cx, dx, ay, by, cy, dy;
+    if (w >= 2) {
+        const int xs = min(x0, w - 2);
+        const bool last = x0 > xs;
+        ld_pair(lx + (r0 + xs), ax, bx);
+        ld_pair(lx + (r1 + xs), cx, dx);
+        ld_pair(ly + (r0 + xs), ay, by);
+        ld_pair(ly + (r1 + xs), cy, dy);
+        if (last) {
+            ax = bx; cx = dx;
+            ay = by; cy = dy;
+        }
+    } else {
+        ax = bx = ld(lx + r0); cx = dx = ld(lx + r1);
+        ay = by = ld(ly + r0); cy = dy = ld(ly + r1);
+    }
     vx = __fmaf_rn(g, __fmaf_rn(f, dx, f1 * cx), g1 * __fmaf_rn(f, bx, f1 * ax));
     vy = __fmaf_rn(g, __fmaf_rn(f, dy, f1 * cy), g1 * __fmaf_rn(f, by, f1 * ay));
 }
@@ -100,35 +131,80 @@ __device__ __forceinline__ bool score_pair(int x0, int y0, int x1, int y1, int S
                                        acc, bad);
         ++k0;
     }
-    for (; k0 < S && bad <= max_bad; k0 += kChunkRest)
-        score_chunk<T, FROM_HI, kChunkRest>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
+    for (; k0 < S && bad <= max_bad; k0 += CH::rest)
+        score_chunk<T, FROM_HI, CH::rest>(k0, S, st, fdx, fdy, fx0, fy0, ux, uy, paf_thr, max_bad, H, W, h, w, hx, hy,
                                             lx, ly, acc, bad);
     if (bad > max_bad) return false;
     score = acc / (float)S;
     return score > 0.0f;
 }
 
-// grid = (chunks, N*L).  Each thread owns candidate pairs p = i * nB + j of its (image, limb),
-// strided by the whole row of workgroups; a score is never reduced across lanes, so the
-// summation order is the sample order.  Accepted pairs are appended unordered, tagged with
-// (i << 16 | j); the matching kernel orders them.  A pair is dropped as soon as it cannot reach
-// `need` valid samples any more: most pairs of unrelated peaks die in the first chunk.
+// General scorer.  grid = (tiles, N*L); a workgroup owns a tile of peak pairs of its (image,
+// limb): 64 peaks j of part b, one per lane, times a range of peaks i of part a, whose
+// coordinates sit in LDS; the workgroup's four wavefronts take every fourth i each, so short
+// lists still occupy all of them.  A score is never reduced across lanes, so the summation
+// order is the sample order.
+//
+// Most pairs join unrelated peaks and are rejected because too few samples are valid.  Which
+// samples are looked at first does not change that verdict, and a pair that is rejected emits
+// nothing, so rejection is decided as cheaply as possible, in two steps.
+//
+// Screen (every pair).  Sample 0 lies on peak A and sample S-1 on peak B (t = 0 and t = 1 round
+// to the end points exactly), so the PAF there is a property of the peak, fetched once per peak
+// and limb instead of once per pair; one more sample (k = 1) is fetched.  The unit vector is
+// approximated, u' = (dx, dy) * rsq(dx^2 + dy^2): rsq is good to one unit in the last place and
+// the exact u carries two roundings, so u' and u differ by less than 3e-7 relative and the
+// projection d' = fma(py, u'y, px * u'x) differs from the exact d by less than
+// 5e-7 * (|px| + |py|).  A sample is counted as invalid only if d' + 4e-6 * (|px| + |py|) is
+// still below the threshold, i.e. only when the exact test is certain to fail; a pair is
+// dropped when more than S - need samples are invalid for certain.  The screen therefore drops
+// nothing that the full score would keep.
+//
+// Survivors (a few percent) are queued in LDS and handled by whole wavefronts of survivors,
+// with the exact unit vector: first the validity of all samples, one at a time in the order
+// 0, S-1, 1, 2, ... with each lane leaving at its (S - need + 1)-th invalid sample; what is
+// left after that is scored in full, in sample order.  Accepted pairs are appended unordered,
+// tagged with (i << 16 | j), and ordered by the matching kernel.
+constexpr float kScreenMargin = 4e-6f;
+constexpr int kTileI = 256;           // peaks of part a staged in LDS at a time
+constexpr int kTileJ = kWave;         // peaks of part b of a tile: one per lane
+constexpr int kScreenUnroll = 2;      // pairs a thread screens between two looks at the queue (more costs occupancy)
+constexpr int kQueue = 512;           // survivors ring of one wavefront; >= 64 * (kScreenUnroll + 1), power of two
+
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ void paf_at(const float *hx, const float *hy, const T *lx, const T *ly, int h, int w, int W,
+                                       int y, int x, float &vx, float &vy)
+{
+    if (FROM_HI) {
+        const unsigned o = (unsigned)__mul24(y, W) + (unsigned)x;
+        vx = hx[o];
+        vy = hy[o];
+    } else {
+        paf_from_lo(lx, ly, h, w, y, x, vx, vy);
+    }
+}
+
 template <typename T, bool FROM_HI>
 __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
                                                   int h, int w, LimbTable tab, SampleT st, int K, int L, int S,
-                                                  float paf_thr, int need,
+                                                  float paf_thr, int need, int tiles_j, int sub_tiles,
                                                   const int32_t *__restrict__ pcounts,
                                                   const int32_t *__restrict__ px, const int32_t *__restrict__ py,
                                                   int cap, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2)
 {
+    __shared__ int4 sA[kTileI];                 // x, y, PAF x bits, PAF y bits at the peak
+    __shared__ int2 sB[kTileJ];                 // x, y
+    __shared__ uint32_t queues[kBlock / kWave][kQueue];   // i << 16 | j_local of pairs that passed the screen
+    const int tid = threadIdx.x;
     const int nl = blockIdx.y;
     const int n = nl / L, l = nl - n * L;
     const int a = tab.a[l], b = tab.b[l];
     const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
-    const int P = nA * nB;
-    const int stride = gridDim.x * kBlock;
-    int p = blockIdx.x * kBlock + threadIdx.x;
-    if (p - (int)threadIdx.x >= P) return;
+    const int ti = blockIdx.x / tiles_j, tj = blockIdx.x - ti * tiles_j;
+    const int j0 = tj * kTileJ;
+    const int i_begin = ti * sub_tiles * kTileI;
+    if (j0 >= nB || i_begin >= nA) return;      // uniform over the workgroup
+    const int i_end = min(i_begin + sub_tiles * kTileI, nA);
 
     const int32_t *xa = px + (size_t)(n * K + a) * cap, *ya = py + (size_t)(n * K + a) * cap;
     const int32_t *xb = px + (size_t)(n * K + b) * cap, *yb = py + (size_t)(n * K + b) * cap;
@@ -138,22 +214,122 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
     const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
     const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
     const int max_bad = S - need;
-    const float inv_nB = 1.0f / (float)nB;
 
-    for (; p < P; p += stride) {
-        // i = p / nB through the reciprocal, then made exact
-        int i = (int)((float)p * inv_nB);
-        int j = p - i * nB;
-        while (j < 0) { --i; j += nB; }
-        while (j >= nB) { ++i; j -= nB; }
+    // this thread's peak of part b and the PAF there (sample S-1 of every pair it ends)
+    const int lane = tid & (kWave - 1), wv = tid >> 6;
+    const int j = j0 + lane;
+    const bool jv = j < nB;
+    int xB = 0, yB = 0;
+    float pBx = 0.0f, pBy = 0.0f;
+    if (jv) {
+        xB = xb[j];
+        yB = yb[j];
+        paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, min(max(yB, 0), H - 1), min(max(xB, 0), W - 1), pBx, pBy);
+    }
+    const float mB = kScreenMargin * (fabsf(pBx) + fabsf(pBy));
+    if (wv == 0) sB[lane] = make_int2(xB, yB);
+    // every wavefront queues its own survivors: the ring and its two counters are private to
+    // it, so that no wavefront ever waits for another one's survivors
+    uint32_t *queue = queues[wv];
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+    int q_head = 0, q_tail = 0;                 // uniform over the wavefront
+
+    // a queued pair: exact validity of its samples with early exit, then the full score
+    auto score_queued = [&](uint32_t e) {
+        const int i = (int)(e >> 16), jl = (int)(e & 0xffffu);
+        const int4 A = sA[i & (kTileI - 1)];
+        const int2 B = sB[jl];
+        const int dx = B.x - A.x, dy = B.y - A.y;              // not both zero: the screen dropped those
+        const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)A.x, fy0 = (float)A.y;
+        const float norm = sqrtf((float)(dx * dx + dy * dy));
+        const float ux = fdx / norm, uy = fdy / norm;
+        float ex, ey;
+        paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, min(max(B.y, 0), H - 1), min(max(B.x, 0), W - 1), ex, ey);
+        int bad = (__fmaf_rn(__uint_as_float((uint32_t)A.w), uy, __uint_as_float((uint32_t)A.z) * ux) > paf_thr ? 0 : 1) +
+                  (S >= 2 && !(__fmaf_rn(ey, uy, ex * ux) > paf_thr) ? 1 : 0);
+        for (int k = 1; k < S - 1 && bad <= max_bad; ++k) {
+            const float t = st.t[k];
+            const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
+            const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
+            float vx, vy;
+            paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, vx, vy);
+            if (!(__fmaf_rn(vy, uy, vx * ux) > paf_thr)) ++bad;
+        }
+        if (bad > max_bad) return;
         float score;
-        if (score_pair<T, FROM_HI, ChunksThroughput>(xa[i], ya[i], xb[j], yb[j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
-                                   score)) {
+        if (score_pair<T, FROM_HI, ChunksSurvivor>(A.x, A.y, B.x, B.y, S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly,
+                                                   score)) {
             const int slot = atomicAdd(&ccounts[nl * kCtrStride], 1);
             if (slot < ccap)
                 cstage[(size_t)nl * ccap2 + slot] =
-                    ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+                    ((uint64_t)(((uint32_t)i << 16) | (uint32_t)(j0 + jl)) << 32) | (uint64_t)__float_as_uint(score);
         }
+    };
+
+    for (int i0 = i_begin; i0 < i_end; i0 += kTileI) {
+        const int ni = min(kTileI, i_end - i0);
+        __syncthreads();                        // the previous tile's queue is empty, sA is free
+        if (tid < ni) {
+            const int x = xa[i0 + tid], y = ya[i0 + tid];
+            float vx, vy;
+            paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, min(max(y, 0), H - 1), min(max(x, 0), W - 1), vx, vy);
+            sA[tid] = make_int4(x, y, (int)__float_as_uint(vx), (int)__float_as_uint(vy));
+        }
+        __syncthreads();
+        constexpr int kWaves = kBlock / kWave;
+        for (int ii = wv; ii < ni; ii += kWaves * kScreenUnroll) {
+            // the screen of kScreenUnroll pairs, written without branches so that the loads of
+            // all of them are in flight together (idle slots repeat the tile's last peak and
+            // are masked at the end; all sample coordinates are clamped into the map)
+            bool pass[kScreenUnroll];
+            float sux[kScreenUnroll], suy[kScreenUnroll], svx[kScreenUnroll], svy[kScreenUnroll];
+            int sbad[kScreenUnroll];
+#pragma unroll
+            for (int u = 0; u < kScreenUnroll; ++u) {
+                const int4 A = sA[min(ii + kWaves * u, ni - 1)];
+                const int dx = xB - A.x, dy = yB - A.y;
+                pass[u] = ii + kWaves * u < ni && jv && (dx != 0 || dy != 0);
+                const float fdx = (float)dx, fdy = (float)dy;
+                const float rn = __builtin_amdgcn_rsqf((float)max(dx * dx + dy * dy, 1));
+                const float ux = fdx * rn, uy = fdy * rn;
+                const float pAx = __uint_as_float((uint32_t)A.z), pAy = __uint_as_float((uint32_t)A.w);
+                // certainly invalid: the projection plus its error bound is below the threshold
+                const float d0 = __fmaf_rn(pAy, uy, pAx * ux) + kScreenMargin * (fabsf(pAx) + fabsf(pAy));
+                const float dl = __fmaf_rn(pBy, uy, pBx * ux) + mB;
+                sbad[u] = (d0 < paf_thr ? 1 : 0) + (dl < paf_thr ? 1 : 0);
+                sux[u] = ux;
+                suy[u] = uy;
+                const float t = st.t[1];
+                const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, (float)A.x) + 0.5f), 0), W - 1);
+                const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, (float)A.y) + 0.5f), 0), H - 1);
+                paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, svx[u], svy[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < kScreenUnroll; ++u) {
+                const float d1 = __fmaf_rn(svy[u], suy[u], svx[u] * sux[u]) + kScreenMargin * (fabsf(svx[u]) + fabsf(svy[u]));
+                if (S >= 3 && d1 < paf_thr) ++sbad[u];
+                pass[u] = pass[u] && sbad[u] <= max_bad;
+            }
+            // survivors join the wavefront's queue
+#pragma unroll
+            for (int u = 0; u < kScreenUnroll; ++u) {
+                const unsigned long long m = __ballot(pass[u]);
+                if (pass[u])
+                    queue[(q_tail + __popcll(m & lanes_below)) & (kQueue - 1)] = ((uint32_t)(i0 + ii + kWaves * u) << 16) | (uint32_t)lane;
+                q_tail += __popcll(m);
+            }
+            // the queue is written and read by the lanes of one wavefront only
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            while (q_tail - q_head >= kWave) {
+                score_queued(queue[(q_head + lane) & (kQueue - 1)]);
+                q_head += kWave;
+            }
+        }
+        // the tile's coordinates go away: finish its survivors
+        if (lane < q_tail - q_head) score_queued(queue[(q_head + lane) & (kQueue - 1)]);
+        q_head = q_tail;
     }
 }
 
@@ -162,26 +338,29 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
                         const hp_peaks &pk, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
                         hipStream_t s)
 {
-    // enough workgroups per (image, limb) to spread cap^2 pairs, few enough that idle ones are cheap
-    long long pairs = (long long)pk.cap * pk.cap;
-    int chunks = (int)((pairs + kBlock * 16 - 1) / (kBlock * 16));
-    if (chunks < 4) chunks = 4;
-    if (chunks > 128) chunks = 128;
-    dim3 grid(chunks, N * L), block(kBlock);
+    // tiles of kTileJ peaks of part b x (sub_tiles * kTileI) peaks of part a cover cap x cap pairs;
+    // workgroups whose tile lies beyond the actual counts leave at once, so their number is kept
+    // moderate by letting a workgroup walk over several tiles of part a
+    const int tiles_j = (pk.cap + kTileJ - 1) / kTileJ;
+    const int tiles_i = (pk.cap + kTileI - 1) / kTileI;
+    int sub_tiles = (tiles_i * tiles_j + 1023) / 1024;
+    if (sub_tiles < 1) sub_tiles = 1;
+    const int tiles = ((tiles_i + sub_tiles - 1) / sub_tiles) * tiles_j;
+    dim3 grid(tiles, N * L), block(kBlock);
     SampleT st;
     for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
     if (paf_hi)
         hipLaunchKernelGGL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
-                           prm.n_samples, prm.paf_thr, need, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap,
-                           ccap2);
+                           prm.n_samples, prm.paf_thr, need, tiles_j, sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts,
+                           cstage, ccap, ccap2);
     else if (dt == HP_F16)
         hipLaunchKernelGGL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
-                           (const __half *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
-                           pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
+                           (const __half *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
+                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
     else
         hipLaunchKernelGGL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
-                           (const float *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, pk.count, pk.x,
-                           pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
+                           (const float *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
+                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
     return hipGetLastError();
 }
 

@@ -467,9 +467,9 @@ __device__ __forceinline__ void strip_peaks(const float *__restrict__ pl, int H,
         for (int k = 0; k < 4; ++k) {
             const float u = v[r][k];
             const float m = fmaxf(fmaxf(ha[k], hc[k]), hb[k]);
-            cand[k] = u >= m && u > thr;            // rows and groups outside the map hold -inf: never candidates
+            cand[k] = (u >= m) & (u > thr);         // rows and groups outside the map hold -inf: never candidates
         }
-        if (out_lane && (cand[0] || cand[1] || cand[2] || cand[3])) {
+        if (out_lane & (cand[0] | cand[1] | cand[2] | cand[3])) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (!cand[k]) continue;
