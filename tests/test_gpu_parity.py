@@ -254,3 +254,45 @@ def test_find_peaks_on_arbitrary_maps(shape):
     m.hp_find_peaks(to_dev(maps), K, 0.05, buf)
     assert buf.host_status() == 0
     assert_lists_equal("peaks", buf.host_peaks()[0], want)
+
+
+@pytest.mark.parametrize("which", ["just_above", "equal"])
+def test_scorer_at_the_validity_threshold(which):
+    """The general scorer screens pairs with an approximate unit vector plus an error margin before
+    it scores them exactly; pairs whose samples sit exactly on, or one float above, the validity
+    threshold are where a screen that dropped too much would show.  Constant PAF (1/16, 0): every
+    sample of a pair projects to ux / 16 exactly, and all pairs along (3k, 4k) share ux = fl(0.6)."""
+    m = hp()
+    h, w = 40, 60
+    H, W = 8 * h, 8 * w
+    K, L = 2, 1
+    rng = np.random.default_rng(7)
+    xa = rng.integers(0, W - 200, size=300)
+    ya = rng.integers(0, H - 260, size=300)
+    order = np.lexsort((xa, ya))
+    xa, ya = xa[order].astype(np.int32), ya[order].astype(np.int32)
+    ks = rng.integers(1, 60, size=300)
+    xb, yb = xa + 3 * ks, ya + 4 * ks                      # B_i - A_i = k (3, 4), and many near-misses with other A
+    order = np.lexsort((xb, yb))
+    xb, yb = xb[order].astype(np.int32), yb[order].astype(np.int32)
+    paf_lo = np.zeros((1, 2, h, w), np.float32)
+    paf_lo[0, 0] = 0.0625
+    d = np.float32(np.float32(3.0) / np.float32(5.0)) * np.float32(0.0625)
+    thr = float(d) if which == "equal" else float(np.nextafter(d, np.float32(-1)))
+    p = DEFAULT_PARAMS
+    want = oracle.score_limb(paf_lo[0, 0], paf_lo[0, 1], 8, xa, ya, xb, yb, p.n_samples, thr, p.min_valid_ratio)
+    on_axis = sum(1 for i, j in zip(want[0], want[1]) if (xb[j] - xa[i]) * 4 == (yb[j] - ya[i]) * 3)
+    assert (on_axis > 100) if which == "just_above" else (on_axis == 0)
+    cap = 512
+    buf = m.Buffers(1, K, L, h, w, cap, 1 << 16, 16, DEV)
+    buf.pcount.copy_(torch.tensor([[len(xa), len(xb)]], dtype=torch.int32))
+    for t, v in ((buf.px, (xa, xb)), (buf.py, (ya, yb))):
+        host = np.zeros((1, K, cap), np.int32)
+        host[0, 0, :len(v[0])] = v[0]
+        host[0, 1, :len(v[1])] = v[1]
+        t.copy_(torch.from_numpy(host))
+    paf_hi = m.hp_resize(to_dev(paf_lo))
+    assert np.all(paf_hi[0, 0].cpu().numpy() == np.float32(0.0625))
+    m.hp_score_limbs(paf_hi, m.Skeleton(K, [0], [1]), m.Params(p.peak_thr, thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
+    assert buf.host_status() == 0
+    assert_lists_equal("candidates", buf.host_cands()[0], [[want]])
