@@ -20,6 +20,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hp_oracle.c")
+_SRC_PRE = os.path.join(_HERE, "hp_pre_oracle.c")
 
 
 def _cpu_has_fma():
@@ -38,9 +39,10 @@ def build(force=False):
     out = []
     for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
         so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
-        if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(_SRC):
+        newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_PRE))
+        if force or not os.path.exists(so) or os.path.getmtime(so) < newest:
             cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-                   "-shared", "-Wall", "-Wextra", *extra, _SRC, "-o", so, "-lm"]
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
     return out
@@ -79,6 +81,9 @@ def lib():
         L.hpo_assemble.restype = ci
         L.hpo_assemble.argtypes = [ci, ci, i32p, i32p, f32p, ci, i32p, i32p, i32p, f32p,
                                    ci, ci, ci, i32p, i32p, f32p]
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        L.hpq_preprocess.restype = None
+        L.hpq_preprocess.argtypes = [u8p, ci, ci, ci, ci, ci, ci, ci, f32p, f32p, f32p]
         _lib = L
     return _lib
 
@@ -110,6 +115,18 @@ def resize(lo, s=8):
     hi = np.empty(lo.shape[:-2] + (s * h, s * w), dtype=np.float32)
     lib().hpo_resize(_f32(lo), planes, h, w, s, _f32(hi))
     return hi
+
+
+def preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False):
+    """uint8 [N, Hs, Ws, C] -> fp32 [N, C, Hd, Wd] (pre-processing operator, hp_pre_oracle.c)."""
+    im = np.ascontiguousarray(images, dtype=np.uint8)
+    N, Hs, Ws, C = im.shape
+    al = np.ascontiguousarray(np.broadcast_to(np.asarray(alpha, np.float32), (C,)))
+    be = np.ascontiguousarray(np.broadcast_to(np.asarray(beta, np.float32), (C,)))
+    out = np.empty((N, C, Hd, Wd), np.float32)
+    lib().hpq_preprocess(im.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), N, Hs, Ws, C, int(Hd), int(Wd),
+                         1 if reverse_channels else 0, _f32(al), _f32(be), _f32(out))
+    return out
 
 
 def find_peaks(plane_hi, thr):
