@@ -195,6 +195,23 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
                    const hp_poses *poses,
                    void *workspace, size_t ws_bytes, int32_t *status, void *stream);
 
+/* Pre-processing (Section 2.2.1, operator 2: decoded images are resized and switched to the
+ * channel-first layout the network expects; Section 2.2 names "resizing and data layout
+ * switching").  src: device uint8 [N][Hs][Ws][C], interleaved channels, C = 1..4; dst: device
+ * fp32 or fp16 (`out_dt`) [N][C][Hd][Wd].
+ *   dst[n][c][Y][X] = fma(alpha[c], u, beta[c]),
+ * u = bilinear sample of channel c (channel C-1-c when reverse_channels != 0) of image n at
+ * ((Y+1/2) Hs/Hd - 1/2, (X+1/2) Ws/Wd - 1/2) with edge clamping, computed in fp32 on the 0..255
+ * values: along an axis, num = (2X+1) Ws - Wd, den = 2 Wd, lower node x0 = floor(num/den) and
+ * weight f = (float)(num mod den) / (float)den on the upper node min(x0+1, Ws-1) (x0 = 0, f = 0
+ * when num < 0); horizontal pass r = fma(f, v[x1], (1-f)*v[x0]) on the two source rows, then the
+ * same form vertically.  fp16 output is the fp32 result rounded to nearest even.
+ * alpha, beta: host arrays of C floats, read before the call returns.  Sizes up to 16384 per
+ * side; N and Hd / 16 up to 65535.  Allocates nothing; enqueues one kernel on `stream`. */
+int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst,
+                  int Hd, int Wd, int reverse_channels, const float *alpha, const float *beta,
+                  void *stream);
+
 /* Per-kernel timing, for benchmarks only.  Between hp_profile_begin and hp_profile_end
  * every kernel the library enqueues (from this process, any stream) is bracketed by a pair
  * of HIP events recorded on its stream; at most `max_launches` launches are recorded, later
@@ -215,7 +232,8 @@ typedef enum {
     HP_K_ASSEMBLE = 8,
     HP_K_LIMB_SMALL_LO = 9,  /* peak ordering + limb scoring + matching in one launch (small */
     HP_K_LIMB_SMALL_HI = 10, /* capacities); PAF recomputed from lo-res / read from materialised maps */
-    HP_K_COUNT = 11
+    HP_K_PREPROCESS = 11,    /* hp_preprocess */
+    HP_K_COUNT = 12
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

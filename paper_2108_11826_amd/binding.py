@@ -17,8 +17,8 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version")
-HP_K_COUNT = 11
+           "hp_postprocess", "hp_preprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version")
+HP_K_COUNT = 12
 
 
 class HPError(RuntimeError):
@@ -84,6 +84,9 @@ def lib():
         L.hp_postprocess.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
                                      POINTER(_Params), c_void_p, c_void_p, POINTER(_Peaks), POINTER(_Pairs),
                                      POINTER(_Pairs), POINTER(_Poses), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_preprocess.restype = c_int
+        L.hp_preprocess.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int,
+                                    POINTER(c_float), POINTER(c_float), c_void_p]
         L.hp_profile_begin.restype = c_int
         L.hp_profile_begin.argtypes = [c_int]
         L.hp_profile_end.restype = c_int
@@ -279,6 +282,18 @@ def hp_postprocess(cm_lo, paf_lo, skel, prm, buf, cm_hi=None, paf_hi=None):
                                 ctypes.byref(buf.peaks), ctypes.byref(buf.cands), ctypes.byref(buf.conns),
                                 ctypes.byref(buf.poses), wsp, wsb, _dev(buf.status), _stream()),
            "hp_postprocess")
+
+
+def hp_preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False, out=None, dtype=torch.float32):
+    """images uint8 [N, Hs, Ws, C] on the GPU -> `dtype` [N, C, Hd, Wd] (resize + channel-first + scale/offset)."""
+    N, Hs, Ws, C = images.shape
+    if out is None:
+        out = torch.empty((N, C, Hd, Wd), dtype=dtype, device=images.device)
+    al = (c_float * C)(*np.broadcast_to(np.asarray(alpha, np.float32), (C,)).tolist())
+    be = (c_float * C)(*np.broadcast_to(np.asarray(beta, np.float32), (C,)).tolist())
+    _check(lib().hp_preprocess(_dev(images, torch.uint8), N, Hs, Ws, C, _dtype_code(out), _dev(out), int(Hd), int(Wd),
+                               1 if reverse_channels else 0, al, be, _stream()), "hp_preprocess")
+    return out
 
 
 class PostprocessCall:

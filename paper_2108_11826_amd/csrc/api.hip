@@ -296,6 +296,20 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     return HP_OK;
 }
 
+int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst, int Hd, int Wd,
+                  int reverse_channels, const float *alpha, const float *beta, void *stream)
+{
+    if (!src || !dst || !alpha || !beta) return HP_ERR_INVALID_ARG;
+    if (out_dt != HP_F32 && out_dt != HP_F16) return HP_ERR_DTYPE;
+    if (N <= 0 || Hs <= 0 || Ws <= 0 || Hd <= 0 || Wd <= 0 || C <= 0) return HP_ERR_INVALID_ARG;
+    if (C > 4 || Hs > 16384 || Ws > 16384 || Hd > 16384 || Wd > 16384 || N > 65535) return HP_ERR_UNSUPPORTED;
+    if (((uintptr_t)dst & (out_dt == HP_F32 ? 3 : 1)) != 0) return HP_ERR_INVALID_ARG;
+    if (C == 4 && ((uintptr_t)src & 3) != 0) return HP_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_PREPROCESS, launch_preprocess(src, N, Hs, Ws, C, out_dt, dst, Hd, Wd, reverse_channels, alpha, beta, s));
+    return HP_OK;
+}
+
 int hp_profile_begin(int max_launches)
 {
     if (max_launches <= 0) return HP_ERR_INVALID_ARG;
@@ -345,6 +359,7 @@ const char *hp_kernel_name(int id)
     case HP_K_LIMB_SMALL_LO: return "limb_small_lo";
     case HP_K_LIMB_SMALL_HI: return "limb_small_hi";
     case HP_K_ASSEMBLE: return "assemble";
+    case HP_K_PREPROCESS: return "preprocess";
     default: return "unknown";
     }
 }

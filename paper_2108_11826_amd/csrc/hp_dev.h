@@ -164,4 +164,8 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
                            const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
                            int32_t *status, hipStream_t s);
 
+// Pre-processing: uint8 [N][Hs][Ws][C] -> `out_dt` [N][C][Hd][Wd]; alpha / beta are host arrays of C.
+hipError_t launch_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst, int Hd, int Wd,
+                             int reverse_channels, const float *alpha, const float *beta, hipStream_t s);
+
 }  // namespace hp
