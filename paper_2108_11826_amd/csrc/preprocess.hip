@@ -13,7 +13,7 @@
 
 namespace hp {
 
-constexpr int kPreRows = 4;       // rows per thread
+constexpr int kPreRows = 2;       // rows per thread
 constexpr int kPreThreads = 512;   // most threads of a workgroup: (column groups of a row) x (row groups)
 
 struct PreParams {
