@@ -144,3 +144,23 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "lib_path", lambda: "/nonexistent/libhp.so")
     with pytest.raises(ImportError):
         binding.lib()
+
+
+def test_preprocess_rejects_bad_calls(L):
+    from ctypes import c_float
+    fake = c_void_p(0x1000)                        # never dereferenced: every call below fails on the host
+    al, be = (c_float * 4)(1, 1, 1, 1), (c_float * 4)(0, 0, 0, 0)
+    ok = (fake, 1, 8, 8, 3, 0, fake, 8, 8, 0, al, be, None)
+
+    def call(**kw):
+        names = ("src", "N", "Hs", "Ws", "C", "dt", "dst", "Hd", "Wd", "rev", "alpha", "beta", "stream")
+        a = dict(zip(names, ok))
+        a.update(kw)
+        return L.hp_preprocess(*[a[k] for k in names])
+
+    assert call(src=None) == -1 and call(dst=None) == -1 and call(alpha=None) == -1 and call(beta=None) == -1
+    assert call(N=0) == -1 and call(Hs=0) == -1 and call(Wd=-3) == -1 and call(C=0) == -1
+    assert call(dt=7) == -2
+    assert call(C=5) == -5 and call(Ws=20000) == -5 and call(Hd=16385) == -5 and call(N=70000) == -5
+    assert call(dst=c_void_p(0x1002)) == -1        # fp32 output must be 4-byte aligned
+    assert call(C=4, src=c_void_p(0x1001)) == -1   # four-channel pixels are read as aligned words
