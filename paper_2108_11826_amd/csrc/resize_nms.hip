@@ -160,31 +160,37 @@ __device__ __forceinline__ void tile_peaks(float (&v)[10][6], int j, int h, int 
 // more than half.  With one store per thread the instruction count per thread decides whether
 // the kernel stays memory-bound: sizes are folded on the host, products use 24-bit multiplies.
 // The four columns of a group share one pair of source nodes, the row one pair of source rows:
-// four loads (L1/L2 hits) per thread.  One launch covers `planes` consecutive planes starting
-// at `plane0`, counted over channels [0, Ca) of tensor a followed by the Cb channels of tensor b.
+// four loads (L1/L2 hits) per thread.  The grid is (row groups [x column parts], channels,
+// images), the channels counted over [0, Ca) of tensor a followed by the Cb channels of tensor
+// b, so that a workgroup finds its plane from its block index with a compare and two
+// multiplications on the scalar unit, without a division in front of every wavefront's loads.
 //
 // The source is 64 times smaller than the output, but a workgroup that finds its source rows
 // in no cache waits a full memory round trip before its only store, and with every workgroup
 // of the write front in that state the kernel runs a third slower (measured after a kernel
-// that had swept the caches: 94 us instead of 65 us for 447 MB).  So the workgroups of the
-// first `warm_planes` planes, which are dispatched first, begin by streaming both source
-// tensors through the caches, 16 bytes per thread and step (`vec_a`, `vec_b` 16-byte units;
-// 0 = skip); every later workgroup then finds its rows in the shared cache.
+// that had swept the caches: 94 us instead of 65 us for 447 MB).  So the first `warm_blocks`
+// workgroups, which are dispatched first, begin by streaming both source tensors through the
+// caches, 16 bytes per thread and step (`vec_a`, `vec_b` 16-byte units; 0 = skip); every later
+// workgroup then finds its rows in the shared cache.
 template <typename T>
 __global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_a, const T *__restrict__ lo_b,
                                                        float *__restrict__ hi_a, float *__restrict__ hi_b,
-                                                       int plane0, int Ca, int Ca_mem, int Cb, int h, int w,
-                                                       int W4, int H, int xsplit, unsigned vec_a, unsigned vec_b,
-                                                       unsigned warm_planes)
+                                                       int c0, int n0, int Ca, int Ca_mem, int Cb, int h, int w,
+                                                       int W4, int H, int xparts, int bx, int rows, int grid_x,
+                                                       int grid_y, unsigned vec_a, unsigned vec_b,
+                                                       unsigned warm_blocks)
 {
-    // blockIdx.x: column part (1 unless a row is wider than a workgroup), y: row group, z: plane
-    const int x4 = blockIdx.x * xsplit + threadIdx.x;
-    const int Y = blockIdx.y * blockDim.y + threadIdx.y;
-    if (blockIdx.z < warm_planes) {
-        const unsigned nthr = blockDim.x * blockDim.y;
-        const unsigned stride = gridDim.x * gridDim.y * warm_planes * nthr;
-        const unsigned first = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * nthr +
-                               threadIdx.y * blockDim.x + threadIdx.x;
+    // Every wavefront lives for one load and one store, so what stands between its start and its
+    // loads counts: the block shape comes as arguments (not from the dispatch packet), and all
+    // four pointers are brought into registers with the first batch of argument loads instead of
+    // where a branch first needs them.
+    asm volatile("" ::"s"(lo_a), "s"(lo_b), "s"(hi_a), "s"(hi_b));
+    // blockIdx.x: row group (times the column parts of rows wider than a workgroup), y: channel, z: image
+    const unsigned block_linear = (blockIdx.z * grid_y + blockIdx.y) * grid_x + blockIdx.x;
+    if (block_linear < warm_blocks) {
+        const unsigned nthr = bx * rows;
+        const unsigned stride = warm_blocks * nthr;
+        const unsigned first = block_linear * nthr + threadIdx.y * bx + threadIdx.x;
         uint32_t seen = 0;
         for (unsigned i = first; i < vec_a; i += stride) {
             const uint4 v = ((const uint4 *)lo_a)[i];
@@ -196,14 +202,16 @@ __global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_
         }
         asm volatile("" ::"v"(seen));        // the loads are wanted for their effect on the caches
     }
+    const int group = xparts == 1 ? (int)blockIdx.x : (int)(blockIdx.x / xparts);
+    const int xpart = xparts == 1 ? 0 : (int)(blockIdx.x - group * xparts);
+    const int x4 = xpart * bx + threadIdx.x;
+    const int Y = group * rows + threadIdx.y;
     if (x4 >= W4 || Y >= H) return;
 
     // plane -> tensor, uniform over the workgroup
-    const int plane = plane0 + blockIdx.z;
-    const int Cg = Ca + Cb;
-    const int n = plane / Cg, c = plane - n * Cg;
+    const int c = c0 + blockIdx.y, n = n0 + blockIdx.z;
     const bool in_a = c < Ca;
-    const size_t plane_mem = in_a ? (size_t)n * Ca_mem + c : (size_t)n * Cb + (c - Ca);
+    const size_t plane_mem = (size_t)n * (in_a ? Ca_mem : Cb) + (in_a ? c : c - Ca);
     const T *p = (in_a ? lo_a : lo_b) + plane_mem * (size_t)(h * w);
     float *q = (in_a ? hi_a : hi_b) + plane_mem * (size_t)H * (size_t)(4 * W4);
 
@@ -285,13 +293,13 @@ static hipError_t launch_resize_write_t(const T *lo_a, const T *lo_b, float *hi_
     const int W4 = 2 * w, H = 8 * h;
     if ((long long)H * W4 >= (1LL << 29) || H >= (1 << 24) || W4 >= (1 << 24)) return hipErrorInvalidValue;
     // block = (column groups, rows): a whole row and as many rows as fit 1024 threads (8 at most);
-    // rows wider than 1024 groups are split over blockIdx.x
+    // rows wider than 1024 groups are split into column parts
     const int bx = W4 <= 1024 ? W4 : 1024;
     int R = 1024 / bx;
     if (R > 8) R = 8;
-    const int gx = (W4 + bx - 1) / bx, groups = (H + R - 1) / R;
-    const long long planes = (long long)N * (Ca + Cb);
-    if (planes <= 0 || planes >= (1LL << 31) || groups > 65535) return hipErrorInvalidValue;
+    const int xparts = (W4 + bx - 1) / bx, groups = (H + R - 1) / R;
+    const int Cg = Ca + Cb;
+    if (N <= 0 || Cg <= 0 || (long long)groups * xparts >= (1LL << 31)) return hipErrorInvalidValue;
     // source tensors in 16-byte units for the cache-warming pass of the first launch (a hint:
     // skipped for a pointer that is not 16-byte aligned; a tail shorter than 16 bytes is left out)
     auto units = [&](const T *p, long long channels) -> unsigned {
@@ -299,16 +307,21 @@ static hipError_t launch_resize_write_t(const T *lo_a, const T *lo_b, float *hi_
         return (unsigned)((unsigned long long)N * channels * h * w * sizeof(T) / 16);    // < 2^28 by check_dims
     };
     const unsigned vec_a = units(lo_a, Ca_mem), vec_b = units(lo_b, Cb);
-    // the planes whose workgroups share that pass: about two workgroups per compute unit
-    long long warm = (512 + (long long)gx * groups - 1) / ((long long)gx * groups);
-    if (warm > planes) warm = planes;
-    if ((vec_a | vec_b) == 0u) warm = 0;
-    for (long long p0 = 0; p0 < planes; p0 += 65535) {
-        const long long np = planes - p0 < 65535 ? planes - p0 : 65535;
-        hipLaunchKernelGGL((k_resize_write<T>), dim3(gx, groups, (unsigned)np), dim3(bx, R), 0, s, lo_a, lo_b, hi_a, hi_b,
-                           (int)p0, Ca, Ca_mem, Cb, h, w, W4, H, bx, vec_a, vec_b, p0 == 0 ? (unsigned)warm : 0u);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    // the workgroups that share that pass: about two per compute unit
+    const long long first_blocks = (long long)groups * xparts * (Cg < 65535 ? Cg : 65535) * (N < 65535 ? N : 65535);
+    const unsigned warm = (vec_a | vec_b) == 0u ? 0u : (unsigned)(first_blocks < 512 ? first_blocks : 512);
+    bool first = true;
+    for (int n0 = 0; n0 < N; n0 += 65535) {
+        const int nn = N - n0 < 65535 ? N - n0 : 65535;
+        for (int c0 = 0; c0 < Cg; c0 += 65535) {
+            const int nc = Cg - c0 < 65535 ? Cg - c0 : 65535;
+            hipLaunchKernelGGL((k_resize_write<T>), dim3(groups * xparts, nc, nn), dim3(bx, R), 0, s, lo_a, lo_b, hi_a,
+                               hi_b, c0, n0, Ca, Ca_mem, Cb, h, w, W4, H, xparts, bx, R, groups * xparts, nc, vec_a, vec_b,
+                               first ? warm : 0u);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            first = false;
+        }
     }
     return hipSuccess;
 }

@@ -296,3 +296,40 @@ def test_scorer_at_the_validity_threshold(which):
     m.hp_score_limbs(paf_hi, m.Skeleton(K, [0], [1]), m.Params(p.peak_thr, thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
     assert buf.host_status() == 0
     assert_lists_equal("candidates", buf.host_cands()[0], [[want]])
+
+
+PARAM_CASES = [
+    dict(n_samples=2, min_valid_ratio=0.8),          # end points only
+    dict(n_samples=3, min_valid_ratio=0.8),          # one interior sample: the one the screen looks at
+    dict(n_samples=10, min_valid_ratio=1.0),         # no invalid sample allowed
+    dict(n_samples=10, min_valid_ratio=0.0),         # nothing is ever rejected for invalid samples
+    dict(n_samples=10, min_valid_ratio=0.55),        # more invalid samples allowed than the screen examines
+    dict(n_samples=64, min_valid_ratio=0.8),         # HP_MAX_SAMPLES
+    dict(n_samples=7, min_valid_ratio=0.8, paf_thr=-0.5, peak_thr=0.02),
+    dict(n_samples=10, min_valid_ratio=0.8, min_parts=1),
+    dict(n_samples=10, min_valid_ratio=0.8, min_parts=19),
+]
+
+
+@pytest.mark.parametrize("large_caps", [False, True], ids=["one_launch", "general"])
+@pytest.mark.parametrize("kw", PARAM_CASES, ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+def test_postprocess_parameter_corners(kw, large_caps):
+    """Sample counts and validity ratios at their corners, through the one-launch limb kernel (small
+    capacities) and through the general scorer with its screen (large capacities)."""
+    from synth import Params
+    cfg = SynthConfig(30, COCO18, 2, 24, 31, 5, noise_sd=0.03, dropout=0.1, n_spurious=6)
+    b = generate(cfg)
+    p = Params(**{**dict(peak_thr=0.05, paf_thr=0.05, n_samples=10, min_valid_ratio=0.8, min_parts=3), **kw})
+    sk = cfg.skeleton
+    ora = oracle.postprocess(b.cm, b.paf, sk.limb_a, sk.limb_b, p, threads=8)
+    pk = max(len(x[0]) for im in ora["peaks"] for x in im)
+    cc = max(len(x[0]) for im in ora["candidates"] for x in im)
+    pp = max(len(x[1]) for x in ora["poses"])
+    m = hp()
+    caps = (512, max(4096, cc + 8), max(64, pp + 8)) if large_caps else (max(16, pk + 8), cc + 8, max(16, pp + 8))
+    if not large_caps and (caps[0] > 256 or caps[1] > 1024):
+        pytest.skip("lists too long for the one-launch kernel")
+    buf = m.Buffers(cfg.batch, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, *caps, DEV)
+    prm = m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8)
+    m.hp_postprocess(to_dev(b.cm), to_dev(b.paf), skel_of(sk), prm, buf)
+    check_all(buf, ora)
