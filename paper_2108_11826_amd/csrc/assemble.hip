@@ -190,125 +190,146 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
     // persons never outnumber connections; one spare person, owner entry and slot row absorb the
     // stores of lanes that have nothing to write, so the fold runs without branches
     const int tot2 = (tot + 2) & ~1;              // persons incl. the spare, kept even for 8-byte alignment
-    const bool fits = (long long)K * cmax + 1 + (long long)tot2 * K <= kPool16 && 7LL * tot2 <= kPool32 &&
+    const bool fits = (long long)K * cmax + 1 + (long long)tot2 * K <= kPool16 && 2LL * tot2 <= kPool32 &&
                       (long long)K * cmax < 65535 && tot < 32766;
     if (fits) {
-        // LDS tables.  Everything about a connection that does not depend on the fold's state is
-        // gathered once: its two owner-table indices, its two peak ranks, its score and the
-        // scores of its two peaks.
-        uint4 *rec = (uint4 *)pool32;                        // [tot]  a*cmax+i | (b*cmax+j)<<16, i | j<<16, s, score of peak a
-        float *c_sb = (float *)(pool32 + 4 * tot2);          // [tot]  score of peak b
-        uint2 *pst = (uint2 *)(pool32 + 5 * tot2);           // [tot + 1] person: filled-part mask (0 = merged away), score
+        // LDS tables: owner of each peak, person slots, person state.  What a connection brings
+        // along (its two peak ranks, its score, the scores of its two peaks) does not depend on
+        // the fold's state, so it is fetched ahead of the fold, a group of kGroup limbs at a
+        // time: lane k holds connection k of each limb of the group in registers (a limb with
+        // more than 64 connections fetches the rest when its turn comes).  The loads of the next
+        // group are issued while the current one is folded, the dependent ones (peak scores,
+        // which need the ranks) half a group later, so the fold seldom waits for memory.
+        uint2 *pst = (uint2 *)pool32;                        // [tot + 1] person: filled-part mask (0 = merged away), score
         int16_t *owner = pool;                               // [K * cmax + 1] person owning each peak, -1 = none
         int16_t *slots = owner + K * cmax + 1;               // [tot + 1][K] valid where the person's mask says so
         const int spare_p = tot, spare_o = K * cmax;
 
         for (int idx = lane; idx < K * cmax; idx += kWave) owner[idx] = -1;
         const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
-        const int my_base = incl - mc;
-        constexpr int U = 4;
-        for (int e0 = 0; e0 < tot; e0 += kWave * U) {
-            int vi[U], vj[U], va[U], vb[U];
-            float vs[U], vsa[U], vsb[U];
+        constexpr int kGroup = 8;
+        struct Group {
+            int i[kGroup], j[kGroup];
+            float s[kGroup], sa[kGroup], sb[kGroup];
+        };
+        // ranks and score of connection `lane` of the limbs of group g
+        auto fetch_conn = [&](int g, Group &q) {
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int e = e0 + q * kWave + lane;
-                // the limb of flat connection e: the number of limbs that end at or before e
-                int l = 0;
-                for (int t = 0; t < L; ++t) l += __builtin_amdgcn_readlane(incl, t) <= e;
-                l = min(l, L - 1);
-                va[q] = __shfl(my_a, l);
-                vb[q] = __shfl(my_b, l);
-                const int k = e - __shfl(my_base, l);
-                vi[q] = vj[q] = 0;
-                vs[q] = 0.0f;
-                if (e < tot) {
-                    const size_t idx = (size_t)(n * L + l) * mcap + k;
-                    vi[q] = mi[idx];
-                    vj[q] = mj[idx];
-                    vs[q] = ms[idx];
+            for (int u = 0; u < kGroup; ++u) {
+                const int l = g * kGroup + u;
+                const int cnt = l < L ? __builtin_amdgcn_readlane(mc, min(l, kWave - 1)) : 0;
+                q.i[u] = q.j[u] = 0;
+                q.s[u] = 0.0f;
+                if (lane < cnt) {
+                    const size_t idx = (size_t)(n * L + l) * mcap + lane;
+                    q.i[u] = mi[idx];
+                    q.j[u] = mj[idx];
+                    q.s[u] = ms[idx];
                 }
             }
+        };
+        // scores of its two peaks
+        auto fetch_peak = [&](int g, Group &q) {
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int e = e0 + q * kWave + lane;
-                vsa[q] = vsb[q] = 0.0f;
-                if (e < tot) {
-                    vsa[q] = psc[va[q] * cap + vi[q]];
-                    vsb[q] = psc[vb[q] * cap + vj[q]];
+            for (int u = 0; u < kGroup; ++u) {
+                const int l = g * kGroup + u;
+                const int cnt = l < L ? __builtin_amdgcn_readlane(mc, min(l, kWave - 1)) : 0;
+                const int a = __builtin_amdgcn_readlane(my_a, min(l, kWave - 1)), b = __builtin_amdgcn_readlane(my_b, min(l, kWave - 1));
+                q.sa[u] = q.sb[u] = 0.0f;
+                if (lane < cnt) {
+                    q.sa[u] = psc[a * cap + q.i[u]];
+                    q.sb[u] = psc[b * cap + q.j[u]];
                 }
             }
-#pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int e = e0 + q * kWave + lane;
-                if (e < tot) {
-                    rec[e] = make_uint4((uint32_t)(va[q] * cmax + vi[q]) | ((uint32_t)(vb[q] * cmax + vj[q]) << 16),
-                                        (uint32_t)vi[q] | ((uint32_t)vj[q] << 16), __float_as_uint(vs[q]),
-                                        __float_as_uint(vsa[q]));
-                    c_sb[e] = vsb[q];
-                }
-            }
-        }
-        __syncthreads();
+        };
 
         int np = 0;
-        for (int l = 0; l < L; ++l) {
-            // lane l holds limb l's description; read it with uniform lane reads
-            const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
-            const int base = __builtin_amdgcn_readlane(my_base, l), cnt = __builtin_amdgcn_readlane(mc, l);
+        // one connection per lane: applies connection (i, j, s) of limb (a, b) where `act`
+        auto fold = [&](bool act, int a, int b, int i, int j, float s, float sa, float sb) {
             const uint32_t bit_a = 1u << a, bit_b = 1u << b;
-            for (int k0 = 0; k0 < cnt; k0 += kWave) {
-                const int k = k0 + lane;
-                const bool act = k < cnt;
-                const int e = act ? base + k : 0;
-                const uint4 r = rec[e];
-                const float sb = c_sb[e];
-                const float s = __uint_as_float(r.z), sa = __uint_as_float(r.w);
-                const int oa = r.x & 0xffffu, ob = r.x >> 16;
-                const int i = r.y & 0xffffu, j = r.y >> 16;
-                const int pa = act ? (int)owner[oa] : -1, pb = act ? (int)owner[ob] : -1;
-                const bool has_a = pa >= 0, has_b = pb >= 0;
-                const uint2 sta = pst[max(pa, 0)], stb = pst[max(pb, 0)];
-                const uint32_t ma = has_a ? sta.x : 0u, mb = has_b ? stb.x : 0u;
-                const float sca = __uint_as_float(sta.y), scb = __uint_as_float(stb.y);
+            const int oa = act ? a * cmax + i : spare_o, ob = act ? b * cmax + j : spare_o;
+            const int pa = act ? (int)owner[oa] : -1, pb = act ? (int)owner[ob] : -1;
+            const bool has_a = pa >= 0, has_b = pb >= 0;
+            const uint2 sta = pst[max(pa, 0)], stb = pst[max(pb, 0)];
+            const uint32_t ma = has_a ? sta.x : 0u, mb = has_b ? stb.x : 0u;
+            const float sca = __uint_as_float(sta.y), scb = __uint_as_float(stb.y);
 
-                const bool fresh = act && !has_a && !has_b;
-                const unsigned long long fm = __ballot(fresh);
-                const bool ext_a = has_a && !has_b && !(ma & bit_b);      // the a-side owner gains part b
-                const bool ext_b = !has_a && has_b && !(mb & bit_a);      // the b-side owner gains part a
-                const bool cyc = has_a && pa == pb;
-                const bool mrg = has_a && has_b && pa != pb && (ma & mb) == 0u;
-                const bool upd = fresh || ext_a || ext_b || cyc;
-                const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
-                const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
-                const float s0 = fresh ? sa : has_a ? sca : scb;          // running score, then the new
-                const float s1 = (fresh || ext_a) ? sb : sa;              // peak's score (if any), then s
-                const float sc = cyc ? s0 : s0 + s1;
-                const bool wa = fresh || ext_b, wb = fresh || ext_a;
-                pst[upd ? p : spare_p] = make_uint2(mk, __float_as_uint(sc + s));
-                slots[(wa ? p : spare_p) * K + a] = (int16_t)i;
-                owner[wa ? oa : spare_o] = (int16_t)p;
-                slots[(wb ? p : spare_p) * K + b] = (int16_t)j;
-                owner[wb ? ob : spare_o] = (int16_t)p;
-                if (__any(mrg)) {
-                    if (mrg) {
-                        const int lo = min(pa, pb), hi = max(pa, pb);
-                        const uint32_t mhi = pa < pb ? mb : ma;
-                        for (int c = 0; c < K; ++c) {
-                            if (mhi & (1u << c)) {
-                                const int16_t rr = slots[hi * K + c];
-                                slots[lo * K + c] = rr;
-                                owner[c * cmax + rr] = (int16_t)lo;
-                            }
+            const bool fresh = act && !has_a && !has_b;
+            const unsigned long long fm = __ballot(fresh);
+            const bool ext_a = has_a && !has_b && !(ma & bit_b);      // the a-side owner gains part b
+            const bool ext_b = !has_a && has_b && !(mb & bit_a);      // the b-side owner gains part a
+            const bool cyc = has_a && pa == pb;
+            const bool mrg = has_a && has_b && pa != pb && (ma & mb) == 0u;
+            const bool upd = fresh || ext_a || ext_b || cyc;
+            const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
+            const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
+            const float s0 = fresh ? sa : has_a ? sca : scb;          // running score, then the new
+            const float s1 = (fresh || ext_a) ? sb : sa;              // peak's score (if any), then s
+            const float sc = cyc ? s0 : s0 + s1;
+            const bool wa = fresh || ext_b, wb = fresh || ext_a;
+            pst[upd ? p : spare_p] = make_uint2(mk, __float_as_uint(sc + s));
+            slots[(wa ? p : spare_p) * K + a] = (int16_t)i;
+            owner[wa ? oa : spare_o] = (int16_t)p;
+            slots[(wb ? p : spare_p) * K + b] = (int16_t)j;
+            owner[wb ? ob : spare_o] = (int16_t)p;
+            if (__any(mrg)) {
+                if (mrg) {
+                    const int lo = min(pa, pb), hi = max(pa, pb);
+                    const uint32_t mhi = pa < pb ? mb : ma;
+                    for (int c = 0; c < K; ++c) {
+                        if (mhi & (1u << c)) {
+                            const int16_t rr = slots[hi * K + c];
+                            slots[lo * K + c] = rr;
+                            owner[c * cmax + rr] = (int16_t)lo;
                         }
-                        const float scm = (pa < pb) ? sca + scb : scb + sca;
-                        pst[lo] = make_uint2(ma | mb, __float_as_uint(scm + s));
-                        pst[hi] = make_uint2(kDead, 0u);
                     }
+                    const float scm = (pa < pb) ? sca + scb : scb + sca;
+                    pst[lo] = make_uint2(ma | mb, __float_as_uint(scm + s));
+                    pst[hi] = make_uint2(kDead, 0u);
                 }
-                np += __popcll(fm);
-                __syncthreads();
             }
+            np += __popcll(fm);
+            __syncthreads();
+        };
+        // folds the limbs of group g from `cur`; issues the loads of group g + 1 into `nxt`
+        auto run_group = [&](int g, const Group &cur, Group &nxt) {
+            const bool more = (g + 1) * kGroup < L;
+            if (more) fetch_conn(g + 1, nxt);
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                const int l = g * kGroup + u;
+                if (u == kGroup / 2 && more) fetch_peak(g + 1, nxt);
+                if (l >= L) continue;
+                // lane l holds limb l's description; read it with uniform lane reads
+                const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
+                const int cnt = __builtin_amdgcn_readlane(mc, l);
+                fold(lane < cnt, a, b, cur.i[u], cur.j[u], cur.s[u], cur.sa[u], cur.sb[u]);
+                for (int k0 = kWave; k0 < cnt; k0 += kWave) {
+                    // a long limb: the rest of its connections, fetched now
+                    const int k = k0 + lane;
+                    const bool act = k < cnt;
+                    int i = 0, j = 0;
+                    float s = 0.0f, sa = 0.0f, sb = 0.0f;
+                    if (act) {
+                        const size_t idx = (size_t)(n * L + l) * mcap + k;
+                        i = mi[idx];
+                        j = mj[idx];
+                        s = ms[idx];
+                        sa = psc[a * cap + i];
+                        sb = psc[b * cap + j];
+                    }
+                    fold(act, a, b, i, j, s, sa, sb);
+                }
+            }
+        };
+        __syncthreads();                          // owner table initialised
+        Group ga, gb;
+        fetch_conn(0, ga);
+        fetch_peak(0, ga);
+        for (int g = 0; g * kGroup < L; g += 2) {
+            run_group(g, ga, gb);
+            if ((g + 1) * kGroup >= L) break;
+            run_group(g + 1, gb, ga);
         }
 
         // alive persons with enough parts, in creation order
