@@ -44,7 +44,7 @@ def main():
     import numpy as np
     import torch
     import paper_2108_11826_amd as hp
-    from synth import CONFIGS, generate, DEFAULT_PARAMS as P
+    from synth import CONFIGS, BENCH_CAPS, generate, DEFAULT_PARAMS as P
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -57,8 +57,7 @@ def main():
     cm, paf = torch.from_numpy(batch.cm).to(dev), torch.from_numpy(batch.paf).to(dev)
     skel = hp.Skeleton(K, sk.limb_a, sk.limb_b)
     prm = hp.Params(P.peak_thr, P.paf_thr, P.n_samples, P.min_valid_ratio, P.min_parts, P.scale)
-    caps = {0: (64, 256, 64), 1: (128, 512, 128), 2: (128, 1024, 128), 3: (2048, 4096, 1024), 4: (1024, 4096, 512)}
-    cap, ccap, pcap = caps[args.config]
+    cap, ccap, pcap = BENCH_CAPS[args.config]
     buf = hp.Buffers(N, K, L, h, w, cap, ccap, pcap, dev)
     cm_hi = torch.empty((N, K + 1, cfg.H, cfg.W), dtype=torch.float32, device=dev)
     paf_hi = torch.empty((N, 2 * L, cfg.H, cfg.W), dtype=torch.float32, device=dev)

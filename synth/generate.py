@@ -48,6 +48,10 @@ class Params:
 
 DEFAULT_PARAMS = Params()
 
+# Output capacities (peaks per (image, part), candidates per (image, limb), persons per image) that the
+# benchmark provisions for each workload; the parity tests run the same launch configuration.
+BENCH_CAPS = {0: (64, 256, 64), 1: (128, 512, 128), 2: (128, 1024, 128), 3: (2048, 4096, 1024), 4: (1024, 4096, 512)}
+
 
 @dataclass(frozen=True)
 class SynthConfig:

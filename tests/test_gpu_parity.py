@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle
-from synth import CONFIGS, COCO18, BODY25, SynthConfig, generate, DEFAULT_PARAMS
+from synth import CONFIGS, BENCH_CAPS, COCO18, BODY25, SynthConfig, generate, DEFAULT_PARAMS
 from parity import assert_lists_equal, assert_poses_equal, run_oracle, caps_for, close
 
 pytestmark = pytest.mark.gpu
@@ -124,7 +124,7 @@ def test_postprocess_full_configs(ci, materialise):
     print(f"config {ci} materialise={materialise}", flush=True)
     b = generate(cfg)
     ora = run_oracle(b, DEFAULT_PARAMS)
-    buf, cm_hi, paf_hi = run_fused(b, ora, materialise)
+    buf, cm_hi, paf_hi = run_fused(b, ora, materialise, caps=BENCH_CAPS[ci])
     check_all(buf, ora)
     if materialise:
         # the maps are large: compare a sample of whole planes bit for bit
