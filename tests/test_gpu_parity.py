@@ -333,3 +333,36 @@ def test_postprocess_parameter_corners(kw, large_caps):
     prm = m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8)
     m.hp_postprocess(to_dev(b.cm), to_dev(b.paf), skel_of(sk), prm, buf)
     check_all(buf, ora)
+
+
+def _random_configs():
+    """A spread of small workloads drawn from a fixed seed: sizes, people, noise, storage type,
+    skeleton, truncation and clustering all vary together."""
+    rng = np.random.default_rng(424242)
+    out = []
+    for k in range(14):
+        sk = BODY25 if rng.random() < 0.35 else COCO18
+        h, w = int(rng.integers(3, 40)), int(rng.integers(3, 56))
+        out.append(SynthConfig(100 + k, sk, int(rng.integers(1, 5)), h, w, int(rng.integers(0, 9)),
+                               scale_lo=20.0, scale_hi=float(rng.integers(40, 160)),
+                               noise_sd=float(rng.choice([0.0, 0.01, 0.03, 0.06])),
+                               dropout=float(rng.choice([0.0, 0.15, 0.3])), n_spurious=int(rng.integers(0, 12)),
+                               truncation=bool(rng.random() < 0.4), clustered=bool(rng.random() < 0.3),
+                               dtype="float16" if rng.random() < 0.4 else "float32"))
+    return out
+
+
+@pytest.mark.parametrize("form", ["fused", "materialised", "staged"])
+@pytest.mark.parametrize("cfg", _random_configs(), ids=lambda c: f"rnd{c.index}-{c.skeleton.name}-{c.batch}x{c.h}x{c.w}-{c.dtype}")
+def test_random_small_workloads(cfg, form):
+    b = generate(cfg)
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    caps = caps_for(ora)
+    if cfg.index % 2:                    # every other one through the general kernels
+        caps = (max(caps[0], 300), max(caps[1], 2048), caps[2])
+    if form == "staged":
+        buf, st = run_staged(b, ora, caps)
+        assert st == [0, 0, 0]
+    else:
+        buf, _, _ = run_fused(b, ora, form == "materialised", caps)
+    check_all(buf, ora)
