@@ -184,10 +184,11 @@ int hp_assemble(const hp_skeleton *skel, const hp_params *prm, int N,
  * hp_score_limbs -> hp_assemble.  cm_lo: device [N][K+1][h][w], paf_lo: device
  * [N][2L][h][w], both of `dt`.  cm_hi / paf_hi are optional outputs (device
  * fp32 [N][K+1][8h][8w] and [N][2L][8h][8w]): when both are NULL the
- * upsampled maps are never written to memory (peaks are found on values kept
- * in registers, PAF samples are recomputed from the lo-res tensors with the
- * same arithmetic); when both are given they are materialised as hp_resize
- * would.  Giving only one of them is an error. */
+ * upsampled maps are never written to memory; when both are given they are
+ * materialised as hp_resize would.  Giving only one of them is an error.
+ * In both cases peaks are found on upsampled values kept in registers and PAF
+ * samples are recomputed from the lo-res tensor with the same arithmetic,
+ * which gives the bits the materialised maps hold. */
 int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w,
                    const hp_skeleton *skel, const hp_params *prm,
                    float *cm_hi, float *paf_hi,
@@ -226,14 +227,13 @@ typedef enum {
     HP_K_RESIZE_W = 2,     /* upsampling, hi-res maps written (hp_resize, materialising hp_postprocess) */
     HP_K_NMS_HI = 3,       /* peak detection on materialised maps */
     HP_K_SORT_PEAKS = 4,
-    HP_K_SCORE_LO = 5,     /* limb scoring, PAF recomputed from lo-res */
-    HP_K_SCORE_HI = 6,     /* limb scoring, PAF read from materialised maps */
+    HP_K_SCORE_LO = 5,     /* limb scoring, PAF recomputed from lo-res (hp_postprocess) */
+    HP_K_SCORE_HI = 6,     /* limb scoring, PAF read from materialised maps (hp_score_limbs) */
     HP_K_MATCH = 7,
     HP_K_ASSEMBLE = 8,
-    HP_K_LIMB_SMALL_LO = 9,  /* peak ordering + limb scoring + matching in one launch (small */
-    HP_K_LIMB_SMALL_HI = 10, /* capacities); PAF recomputed from lo-res / read from materialised maps */
-    HP_K_PREPROCESS = 11,    /* hp_preprocess */
-    HP_K_COUNT = 12
+    HP_K_LIMB_SMALL = 9,     /* peak ordering + limb scoring + matching in one launch (small capacities) */
+    HP_K_PREPROCESS = 10,    /* hp_preprocess */
+    HP_K_COUNT = 11
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

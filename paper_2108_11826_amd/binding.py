@@ -18,7 +18,7 @@ STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
            "hp_postprocess", "hp_preprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version")
-HP_K_COUNT = 12
+HP_K_COUNT = 11
 
 
 class HPError(RuntimeError):

@@ -282,14 +282,17 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     // peaks come from upsampled values recomputed in registers where the map can reach the threshold
     HP_LAUNCH(HP_K_RESIZE_NMS, launch_resize_nms(cm_lo, dt, N, K, K + 1, h, w, prm->peak_thr, ws.peak_ctr,
                                                  ws.peak_stage, peaks->cap, ws.cap2, status, s));
+    // limbs are scored on PAF values recomputed from the lo-res tensor in both forms: they are the
+    // same bits as the materialised maps hold, and the lo-res tensor stays in cache where gathers
+    // from the 64 times larger maps would not
     if (limb_small_applies(peaks->cap, cands->cap)) {
         // small capacities: peak ordering, scoring and matching in one launch
-        HP_LAUNCH(paf_hi ? HP_K_LIMB_SMALL_HI : HP_K_LIMB_SMALL_LO, launch_limb_small(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, ws.peak_ctr,
-                                                     ws.peak_stage, ws.cap2, *peaks, *cands, *conns, status, s));
+        HP_LAUNCH(HP_K_LIMB_SMALL, launch_limb_small(paf_lo, dt, N, h, w, tab, K, L, *prm, need, ws.peak_ctr,
+                                                        ws.peak_stage, ws.cap2, *peaks, *cands, *conns, status, s));
     } else {
         HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
-        HP_LAUNCH(paf_hi ? HP_K_SCORE_HI : HP_K_SCORE_LO, launch_score(paf_hi, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, ws.cand_ctr,
-                               ws.cand_stage, cands->cap, ws.ccap2, s));
+        HP_LAUNCH(HP_K_SCORE_LO, launch_score(nullptr, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, ws.cand_ctr,
+                                              ws.cand_stage, cands->cap, ws.ccap2, s));
         HP_LAUNCH(HP_K_MATCH, launch_match(1, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
     }
     HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
@@ -356,8 +359,7 @@ const char *hp_kernel_name(int id)
     case HP_K_SCORE_LO: return "score_lo";
     case HP_K_SCORE_HI: return "score_hi";
     case HP_K_MATCH: return "match";
-    case HP_K_LIMB_SMALL_LO: return "limb_small_lo";
-    case HP_K_LIMB_SMALL_HI: return "limb_small_hi";
+    case HP_K_LIMB_SMALL: return "limb_small";
     case HP_K_ASSEMBLE: return "assemble";
     case HP_K_PREPROCESS: return "preprocess";
     default: return "unknown";

@@ -154,10 +154,10 @@ hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const
 
 // Peak ordering + scoring + matching in one launch for small capacities (see limb_small_applies).
 bool limb_small_applies(int cap, int ccap);
-hipError_t launch_limb_small(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
-                             const LimbTable &T, int K, int L, const hp_params &prm, int need,
-                             const int32_t *peak_ctr, const uint64_t *peak_stage, int cap2, const hp_peaks &pk,
-                             const hp_pairs &cands, const hp_pairs &conns, int32_t *status, hipStream_t s);
+hipError_t launch_limb_small(const void *paf_lo, hp_dtype dt, int N, int h, int w, const LimbTable &T, int K, int L,
+                             const hp_params &prm, int need, const int32_t *peak_ctr, const uint64_t *peak_stage,
+                             int cap2, const hp_peaks &pk, const hp_pairs &cands, const hp_pairs &conns,
+                             int32_t *status, hipStream_t s);
 
 // Also clears the image's append counters, which leaves the workspace ready for the next call.
 hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,

@@ -531,9 +531,9 @@ constexpr int kSmallPeaks = 256;
 constexpr int kSmallCands = 1024;
 constexpr int kSmallBlock = 1024;
 
-template <typename T, bool FROM_HI>
+template <typename T>
 __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
-    const float *__restrict__ paf_hi, const T *__restrict__ paf_lo, int h, int w, LimbTable tab, SampleT st, int K,
+    const T *__restrict__ paf_lo, int h, int w, LimbTable tab, SampleT st, int K,
     int L, int NL, int S, float paf_thr, int need, const int32_t *__restrict__ peak_ctr,
     const uint64_t *__restrict__ peak_stage, int cap, int cap2, int32_t *pcounts, int32_t *px, int32_t *py, float *ps,
     int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap, int32_t *mcounts, int32_t *mi, int32_t *mj,
@@ -617,10 +617,9 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
 
     // score every pair; accepted ones go to the LDS list, tagged (i << 16 | j) << 32 | score bits
     {
-        const float *hx = FROM_HI ? paf_hi + ((size_t)n * 2 * L + 2 * l) * (size_t)H * W : nullptr;
-        const float *hy = FROM_HI ? hx + (size_t)H * W : nullptr;
-        const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
-        const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
+        const float *hx = nullptr, *hy = nullptr;          // the PAFs are recomputed from the lo-res planes
+        const T *lx = paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
+        const T *ly = lx + (size_t)h * w;
         const int P = nA * nB, max_bad = S - need;
         const float inv_nB = 1.0f / (float)nB;
         for (int p = tid; p < P; p += kSmallBlock) {
@@ -629,7 +628,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
             while (j < 0) { --i; j += nB; }
             while (j >= nB) { ++i; j -= nB; }
             float score;
-            if (score_pair<T, FROM_HI, ChunksLatency>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx,
+            if (score_pair<T, false, ChunksLatency>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx,
                                        hy, lx, ly, score)) {
                 const int slot = atomicAdd(&lds_cnt, 1);
                 if (slot < kSmallCands)
@@ -710,24 +709,22 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
 
 bool limb_small_applies(int cap, int ccap) { return cap <= kSmallPeaks && ccap <= kSmallCands; }
 
-hipError_t launch_limb_small(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
-                             const LimbTable &T, int K, int L, const hp_params &prm, int need,
-                             const int32_t *peak_ctr, const uint64_t *peak_stage, int cap2, const hp_peaks &pk,
-                             const hp_pairs &cands, const hp_pairs &conns, int32_t *status, hipStream_t s)
+hipError_t launch_limb_small(const void *paf_lo, hp_dtype dt, int N, int h, int w, const LimbTable &T, int K, int L,
+                             const hp_params &prm, int need, const int32_t *peak_ctr, const uint64_t *peak_stage,
+                             int cap2, const hp_peaks &pk, const hp_pairs &cands, const hp_pairs &conns,
+                             int32_t *status, hipStream_t s)
 {
     SampleT st;
     for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
     dim3 grid(N * L), block(kSmallBlock);
 #define HP_LIMB_SMALL_ARGS(LO)                                                                                        \
-    paf_hi, LO, h, w, T, st, K, L, N *L, prm.n_samples, prm.paf_thr, need, peak_ctr, peak_stage, pk.cap, cap2,        \
-        pk.count, pk.x, pk.y, pk.score, cands.count, cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i,   \
-        conns.j, conns.score, conns.cap, status
-    if (paf_hi)
-        hipLaunchKernelGGL((k_limb_small<float, true>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const float *)nullptr));
-    else if (dt == HP_F16)
-        hipLaunchKernelGGL((k_limb_small<__half, false>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
+    LO, h, w, T, st, K, L, N *L, prm.n_samples, prm.paf_thr, need, peak_ctr, peak_stage, pk.cap, cap2, pk.count, pk.x, \
+        pk.y, pk.score, cands.count, cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j,          \
+        conns.score, conns.cap, status
+    if (dt == HP_F16)
+        hipLaunchKernelGGL((k_limb_small<__half>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
     else
-        hipLaunchKernelGGL((k_limb_small<float, false>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
+        hipLaunchKernelGGL((k_limb_small<float>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
 #undef HP_LIMB_SMALL_ARGS
     return hipGetLastError();
 }
