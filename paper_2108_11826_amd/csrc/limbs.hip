@@ -364,6 +364,47 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
     return hipGetLastError();
 }
 
+// Greedy one-to-one matching by one wavefront.  keys[0 .. c) hold the candidates in matching
+// order as (~score bits) << 32 | (i << 16 | j).  They are taken 64 at a time, one per lane: a
+// candidate whose peak i or j is already used (bit maps usedA / usedB in LDS, cleared by the
+// caller) is out; of the rest the lowest lane is accepted, every candidate of the chunk that
+// shares a peak with it dies, and so on: one step per connection instead of one per candidate.
+// The order of acceptance is the order of the sequential scan.  Called by all 64 lanes of one
+// wavefront; returns the number of connections written to mi / mj / ms (at most `limit`).
+__device__ __forceinline__ int wave_greedy_match(const uint64_t *keys, int c, int nA, int nB, int limit, uint32_t *usedA,
+                                                 uint32_t *usedB, int32_t *mi, int32_t *mj, float *ms)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int m = 0;
+    for (int base = 0; base < c && m < limit; base += kWave) {
+        const bool have = base + lane < c;
+        const uint64_t e = have ? keys[base + lane] : ~0ull;
+        const uint32_t i = (uint32_t)e >> 16, j = (uint32_t)e & 0xffffu;
+        // indices beyond the peak lists are only possible for candidate lists this library did not write
+        bool ok = have && i < (uint32_t)nA && j < (uint32_t)nB;
+        if (ok) ok = !((usedA[i >> 5] >> (i & 31)) & 1u) && !((usedB[j >> 5] >> (j & 31)) & 1u);
+        unsigned long long alive = __ballot(ok);
+        while (alive && m < limit) {
+            const int r = __ffsll((long long)alive) - 1;
+            const uint32_t ir = __builtin_amdgcn_readlane(i, r), jr = __builtin_amdgcn_readlane(j, r);
+            if (lane == r) {
+                mi[m] = (int32_t)i;
+                mj[m] = (int32_t)j;
+                ms[m] = __uint_as_float(~(uint32_t)(e >> 32));
+                usedA[i >> 5] |= 1u << (i & 31);
+                usedB[j >> 5] |= 1u << (j & 31);
+            }
+            ++m;
+            alive &= ~__ballot(i == ir || j == jr);
+        }
+        // the bit maps are written and read by this wavefront only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    return m;
+}
+
 // One workgroup per (image, limb).
 //   MODE 0: staged candidates -> sorted by (i, j) -> candidate lists.
 //   MODE 1: the same, then sorted by (score desc, i, j) -> greedy matching -> connections.
@@ -471,52 +512,12 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
     }
 
     // keys[0 .. c) now hold (~score bits) << 32 | (i << 16 | j) in matching order
-    if (c <= kWave) {
-        // One wavefront, one candidate per lane.  The lowest-ranked candidate still alive is
-        // accepted; every candidate sharing a peak with it dies.  One step per connection.
-        if (threadIdx.x >= kWave) return;
-        const int lane = threadIdx.x;
-        const uint64_t e = lane < c ? keys[lane] : ~0ull;
-        const int i = (int)((uint32_t)e >> 16), j = (int)((uint32_t)e & 0xffffu);
-        unsigned long long alive = __ballot(lane < c && i < nA && j < nB);
-        int m = 0;
-        while (alive) {
-            const int r = __ffsll((long long)alive) - 1;
-            const int ir = __builtin_amdgcn_readlane(i, r), jr = __builtin_amdgcn_readlane(j, r);
-            if (lane == r) {
-                mi[mo + m] = i;
-                mj[mo + m] = j;
-                ms[mo + m] = __uint_as_float(~(uint32_t)(e >> 32));
-            }
-            ++m;
-            alive &= ~__ballot(i == ir || j == jr);
-        }
-        if (lane == 0) mcounts[nl] = m;
-        return;
-    }
-
     for (int t = threadIdx.x; t < (nA + 31) / 32; t += kBlock) usedA[t] = 0;
     for (int t = threadIdx.x; t < (nB + 31) / 32; t += kBlock) usedB[t] = 0;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        const int limit = min(min(nA, nB), mcap);
-        int m = 0;
-        for (int t = 0; t < c && m < limit; ++t) {
-            uint64_t e = keys[t];
-            uint32_t ij = (uint32_t)e;
-            uint32_t i = ij >> 16, j = ij & 0xffffu;
-            if (i >= (uint32_t)nA || j >= (uint32_t)nB) continue;   // only possible for foreign candidate lists
-            if ((usedA[i >> 5] >> (i & 31)) & 1u) continue;
-            if ((usedB[j >> 5] >> (j & 31)) & 1u) continue;
-            usedA[i >> 5] |= 1u << (i & 31);
-            usedB[j >> 5] |= 1u << (j & 31);
-            mi[mo + m] = (int32_t)i;
-            mj[mo + m] = (int32_t)j;
-            ms[mo + m] = __uint_as_float(~(uint32_t)(e >> 32));
-            ++m;
-        }
-        mcounts[nl] = m;
-    }
+    if (threadIdx.x >= kWave) return;
+    const int m = wave_greedy_match(keys, c, nA, nB, min(min(nA, nB), mcap), usedA, usedB, mi + mo, mj + mo, ms + mo);
+    if (threadIdx.x == 0) mcounts[nl] = m;
 }
 
 // Small-list form of peak ordering + limb scoring + matching in one launch, used when the
@@ -669,42 +670,8 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
 
     const size_t mo = (size_t)nl * mcap;
     if (tid >= kWave) return;
-    if (c <= kWave) {
-        // one candidate per lane: the lowest-ranked one still alive is accepted, every candidate
-        // sharing a peak with it dies; one step per connection
-        const uint64_t k = tid < c ? sk[tid] : ~0ull;
-        const int i = (int)((uint32_t)k >> 16), j = (int)((uint32_t)k & 0xffffu);
-        unsigned long long alive = __ballot(tid < c);
-        int m = 0;
-        while (alive) {
-            const int r = __ffsll((long long)alive) - 1;
-            const int ir = __builtin_amdgcn_readlane(i, r), jr = __builtin_amdgcn_readlane(j, r);
-            if (tid == r) {
-                mi[mo + m] = i;
-                mj[mo + m] = j;
-                ms[mo + m] = __uint_as_float(~(uint32_t)(k >> 32));
-            }
-            ++m;
-            alive &= ~__ballot(i == ir || j == jr);
-        }
-        if (tid == 0) mcounts[nl] = m;
-    } else if (tid == 0) {
-        const int limit = min(min(nA, nB), mcap);
-        int m = 0;
-        for (int t = 0; t < c && m < limit; ++t) {
-            const uint64_t k = sk[t];
-            const uint32_t i = (uint32_t)k >> 16, j = (uint32_t)k & 0xffffu;
-            if ((usedA[i >> 5] >> (i & 31)) & 1u) continue;
-            if ((usedB[j >> 5] >> (j & 31)) & 1u) continue;
-            usedA[i >> 5] |= 1u << (i & 31);
-            usedB[j >> 5] |= 1u << (j & 31);
-            mi[mo + m] = (int32_t)i;
-            mj[mo + m] = (int32_t)j;
-            ms[mo + m] = __uint_as_float(~(uint32_t)(k >> 32));
-            ++m;
-        }
-        mcounts[nl] = m;
-    }
+    const int m = wave_greedy_match(sk, c, nA, nB, min(min(nA, nB), mcap), usedA, usedB, mi + mo, mj + mo, ms + mo);
+    if (tid == 0) mcounts[nl] = m;
 }
 
 bool limb_small_applies(int cap, int ccap) { return cap <= kSmallPeaks && ccap <= kSmallCands; }
