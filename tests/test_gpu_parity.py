@@ -366,3 +366,24 @@ def test_random_small_workloads(cfg, form):
     else:
         buf, _, _ = run_fused(b, ora, form == "materialised", caps)
     check_all(buf, ora)
+
+
+def test_maximum_capacities():
+    """The largest capacities the library accepts (16384 peaks per part, 2^20 candidates per limb):
+    the launch shapes derived from them must be valid, whatever little the lists hold."""
+    cfg = SynthConfig(40, COCO18, 1, 12, 15, 2, noise_sd=0.02)
+    b = generate(cfg)
+    sk = cfg.skeleton
+    la, lb = sk.limb_a[:3], sk.limb_b[:3]
+    paf = np.ascontiguousarray(b.paf[:, :6])
+    ora = oracle.postprocess(b.cm, paf, la, lb, DEFAULT_PARAMS, threads=4)
+    m = hp()
+    buf = m.Buffers(1, sk.n_parts, 3, cfg.h, cfg.w, 16384, 1 << 20, 4096, DEV)
+    skel = m.Skeleton(sk.n_parts, la, lb)
+    m.hp_postprocess(to_dev(b.cm), to_dev(paf), skel, prm_of(), buf)
+    check_all(buf, ora)
+    # and the staged calls with the same buffers
+    m.hp_find_peaks(m.hp_resize(to_dev(b.cm)), sk.n_parts, DEFAULT_PARAMS.peak_thr, buf)
+    m.hp_score_limbs(m.hp_resize(to_dev(paf)), skel, prm_of(), buf)
+    m.hp_assemble(skel, prm_of(), buf)
+    check_all(buf, ora)
