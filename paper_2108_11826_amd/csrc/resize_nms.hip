@@ -243,8 +243,10 @@ __global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_
 // searched channels: can the node's two tiles hold a peak at all?  The nodes that can are
 // queued in LDS; phase 2 spreads their tiles densely over the workgroup, so the upsampling and
 // the 3x3 test are only paid where the map rises to the threshold.
+// (Six wavefronts per SIMD: the 80 registers that leaves still hold a tile without spilling, and
+// the denser maps gain 5-8 % over the compiler's own choice of 95 registers and five wavefronts.)
 template <typename T>
-__global__ __launch_bounds__(kBlock) void k_resize_nms(const T *__restrict__ lo, int total_nodes, int K,
+__global__ __launch_bounds__(kBlock, 6) void k_resize_nms(const T *__restrict__ lo, int total_nodes, int K,
                                                        int C_mem, int h, int w, float thr, int32_t *counts,
                                                        uint64_t *stage, int cap, int cap2, int32_t *status)
 {
