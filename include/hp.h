@@ -208,7 +208,7 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
  * when num < 0); horizontal pass r = fma(f, v[x1], (1-f)*v[x0]) on the two source rows, then the
  * same form vertically.  fp16 output is the fp32 result rounded to nearest even.
  * alpha, beta: host arrays of C floats, read before the call returns.  Sizes up to 16384 per
- * side; N and Hd / 16 up to 65535.  Allocates nothing; enqueues one kernel on `stream`. */
+ * side, N up to 65535.  Allocates nothing; enqueues one kernel on `stream`. */
 int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst,
                   int Hd, int Wd, int reverse_channels, const float *alpha, const float *beta,
                   void *stream);

@@ -387,6 +387,6 @@ const char *hp_strerror(int code)
     }
 }
 
-int hp_version(void) { return 100; }
+int hp_version(void) { return 200; }
 
 }  // extern "C"
