@@ -375,6 +375,7 @@ __device__ __forceinline__ int wave_greedy_match(const uint64_t *keys, int c, in
                                                  uint32_t *usedB, int32_t *mi, int32_t *mj, float *ms)
 {
     const int lane = threadIdx.x & (kWave - 1);
+    const bool more_chunks = c > kWave;          // a single chunk needs no memory of used peaks
     int m = 0;
     for (int base = 0; base < c && m < limit; base += kWave) {
         const bool have = base + lane < c;
@@ -382,7 +383,7 @@ __device__ __forceinline__ int wave_greedy_match(const uint64_t *keys, int c, in
         const uint32_t i = (uint32_t)e >> 16, j = (uint32_t)e & 0xffffu;
         // indices beyond the peak lists are only possible for candidate lists this library did not write
         bool ok = have && i < (uint32_t)nA && j < (uint32_t)nB;
-        if (ok) ok = !((usedA[i >> 5] >> (i & 31)) & 1u) && !((usedB[j >> 5] >> (j & 31)) & 1u);
+        if (ok && more_chunks) ok = !((usedA[i >> 5] >> (i & 31)) & 1u) && !((usedB[j >> 5] >> (j & 31)) & 1u);
         unsigned long long alive = __ballot(ok);
         while (alive && m < limit) {
             const int r = __ffsll((long long)alive) - 1;
@@ -391,8 +392,10 @@ __device__ __forceinline__ int wave_greedy_match(const uint64_t *keys, int c, in
                 mi[m] = (int32_t)i;
                 mj[m] = (int32_t)j;
                 ms[m] = __uint_as_float(~(uint32_t)(e >> 32));
-                usedA[i >> 5] |= 1u << (i & 31);
-                usedB[j >> 5] |= 1u << (j & 31);
+                if (more_chunks) {
+                    usedA[i >> 5] |= 1u << (i & 31);
+                    usedB[j >> 5] |= 1u << (j & 31);
+                }
             }
             ++m;
             alive &= ~__ballot(i == ir || j == jr);
@@ -538,12 +541,13 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
     int L, int NL, int S, float paf_thr, int need, const int32_t *__restrict__ peak_ctr,
     const uint64_t *__restrict__ peak_stage, int cap, int cap2, int32_t *pcounts, int32_t *px, int32_t *py, float *ps,
     int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap, int32_t *mcounts, int32_t *mi, int32_t *mj,
-    float *ms, int mcap, int32_t *status)
+    float *ms, int mcap, int32_t *status, int planes_in_lds)
 {
     __shared__ uint64_t sk[kSmallCands];
     __shared__ int lxy[4][kSmallPeaks];          // xA, yA, xB, yB in rank order
     __shared__ int lds_cnt;
     __shared__ uint32_t usedA[kSmallPeaks / 32], usedB[kSmallPeaks / 32];
+    extern __shared__ uint32_t lds_paf[];        // the limb's two lo-res PAF planes, when they fit
     const int tid = threadIdx.x;
     const int H = 8 * h, W = 8 * w;
 
@@ -552,6 +556,18 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
     const int a = tab.a[l], b = tab.b[l];
     const int pa = n * K + a, pb = n * K + b;
     const int nA = max(min(peak_ctr[pa * kCtrStride], cap), 0), nB = max(min(peak_ctr[pb * kCtrStride], cap), 0);
+
+    // The x and y planes of a limb lie one after the other.  Every sample of the workgroup's
+    // pairs reads them, and the first reads find them in no cache (two dependent rounds of such
+    // reads were 6 of the kernel's 15 us), so they are copied to LDS up front, while the peak
+    // lists are being ordered; the scoring then runs out of LDS.
+    const T *planes = paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
+    if (planes_in_lds) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(planes);
+        const int words = (int)((size_t)2 * h * w * sizeof(T) / 4);
+#pragma unroll 8
+        for (int t = tid; t < words; t += kSmallBlock) lds_paf[t] = src[t];
+    }
 
     // order the two peak lists: threads [0, 256) take list A, [256, 512) list B.  The first limb
     // that uses a part also publishes the part's ordered list and its count.
@@ -618,24 +634,28 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
 
     // score every pair; accepted ones go to the LDS list, tagged (i << 16 | j) << 32 | score bits
     {
-        const float *hx = nullptr, *hy = nullptr;          // the PAFs are recomputed from the lo-res planes
-        const T *lx = paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
-        const T *ly = lx + (size_t)h * w;
         const int P = nA * nB, max_bad = S - need;
         const float inv_nB = 1.0f / (float)nB;
-        for (int p = tid; p < P; p += kSmallBlock) {
-            int i = (int)((float)p * inv_nB);
-            int j = p - i * nB;
-            while (j < 0) { --i; j += nB; }
-            while (j >= nB) { ++i; j -= nB; }
-            float score;
-            if (score_pair<T, false, ChunksLatency>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx,
-                                       hy, lx, ly, score)) {
-                const int slot = atomicAdd(&lds_cnt, 1);
-                if (slot < kSmallCands)
-                    sk[slot] = ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+        auto score_all = [&](const T *lx, const T *ly) {
+            const float *hx = nullptr, *hy = nullptr;          // the PAFs are recomputed from the lo-res planes
+            for (int p = tid; p < P; p += kSmallBlock) {
+                int i = (int)((float)p * inv_nB);
+                int j = p - i * nB;
+                while (j < 0) { --i; j += nB; }
+                while (j >= nB) { ++i; j -= nB; }
+                float score;
+                if (score_pair<T, false, ChunksLatency>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h,
+                                                        w, hx, hy, lx, ly, score)) {
+                    const int slot = atomicAdd(&lds_cnt, 1);
+                    if (slot < kSmallCands)
+                        sk[slot] = ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+                }
             }
-        }
+        };
+        if (planes_in_lds)
+            score_all(reinterpret_cast<const T *>(lds_paf), reinterpret_cast<const T *>(lds_paf) + (size_t)h * w);
+        else
+            score_all(planes, planes + (size_t)h * w);
         __syncthreads();
     }
 
@@ -684,14 +704,19 @@ hipError_t launch_limb_small(const void *paf_lo, hp_dtype dt, int N, int h, int 
     SampleT st;
     for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
     dim3 grid(N * L), block(kSmallBlock);
+    // the two PAF planes of a limb go to LDS when they fit beside the kernel's own tables (and can
+    // be copied as whole 32-bit words)
+    const size_t plane_bytes = (size_t)2 * h * w * (dt == HP_F16 ? 2 : 4);
+    const int in_lds = plane_bytes <= 48 * 1024 && plane_bytes % 4 == 0 && ((uintptr_t)paf_lo & 3) == 0;
+    const size_t lds = in_lds ? plane_bytes : 0;
 #define HP_LIMB_SMALL_ARGS(LO)                                                                                        \
     LO, h, w, T, st, K, L, N *L, prm.n_samples, prm.paf_thr, need, peak_ctr, peak_stage, pk.cap, cap2, pk.count, pk.x, \
         pk.y, pk.score, cands.count, cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j,          \
-        conns.score, conns.cap, status
+        conns.score, conns.cap, status, in_lds
     if (dt == HP_F16)
-        hipLaunchKernelGGL((k_limb_small<__half>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
+        hipLaunchKernelGGL((k_limb_small<__half>), grid, block, lds, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
     else
-        hipLaunchKernelGGL((k_limb_small<float>), grid, block, 0, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
+        hipLaunchKernelGGL((k_limb_small<float>), grid, block, lds, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
 #undef HP_LIMB_SMALL_ARGS
     return hipGetLastError();
 }
