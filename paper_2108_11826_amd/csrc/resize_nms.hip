@@ -428,7 +428,7 @@ __global__ __launch_bounds__(kBlock) void k_nms_hi(const float *__restrict__ cm,
 
 // Peak detection on a materialised map whose rows are whole 16-byte groups: the memory-bound
 // form.  A wavefront owns a strip of R rows x 62 column groups (248 pixels): lane l reads group
-// 62 * strip_column - 1 + l, one 16-byte streaming load per row and R + 2 rows, all issued
+// 62 * strip_column - 1 + l, one 16-byte load per row and R + 2 rows, all issued
 // before the first use.  The pixel left of a group and the pixel right of it come from the
 // neighbouring lanes, so lanes 0 and 63 only supply those and produce no output (their groups
 // belong to the next strips); groups and rows outside the map read as -inf.
@@ -455,7 +455,7 @@ __device__ __forceinline__ void strip_peaks(const float *__restrict__ pl, int H,
     for (int r = 0; r < R + 2; ++r) {
         const int Y = Y0 + r - 1;                                  // uniform
         const float *row = pl + (size_t)(unsigned)(EDGE ? min(max(Y, 0), H - 1) : Y) * (unsigned)W;
-        v[r] = __builtin_nontemporal_load((const v4f *)(row + lane_off));
+        v[r] = *(const v4f *)(row + lane_off);       // cached loads: the halo rows are read again by the strips next door
         if (EDGE && !(inb && Y >= 0 && Y < H)) v[r] = (v4f){ninf, ninf, ninf, ninf};
     }
     // window of three rows: horizontal 3-maxima of the row above (ha), the row (hc) and the row
