@@ -2,18 +2,19 @@
 // decoded images are resized and switched to the channel-first layout the network expects).
 // Arithmetic as stated at hp_preprocess in hp.h.
 //
-// The kernel is written from the output: a thread produces 4 consecutive pixels of kRows
+// The kernel is written from the output: a thread produces 4 consecutive pixels of kPreRows
 // consecutive rows for all channels, so every store is one 16-byte (fp32) or 8-byte (fp16)
 // piece of a row that the wavefront completes to a contiguous kilobyte, and the interleaved
 // source pixel is read once for all its channels, as one 32-bit word where the layout allows.
-// The column cells and weights are computed once per thread and serve all its rows.
+// The column cells and weights are computed once per thread and serve all its rows (measured
+// for 64 frames 640x360 -> 656x368: 1 row per thread 44.7 us, 2 rows 45.8, 4 rows 49.8, 8 rows 56.3).
 #include <type_traits>
 
 #include "hp_dev.h"
 
 namespace hp {
 
-constexpr int kPreRows = 2;       // rows per thread
+constexpr int kPreRows = 1;       // rows per thread
 constexpr int kPreThreads = 512;   // most threads of a workgroup: (column groups of a row) x (row groups)
 
 struct PreParams {
