@@ -16,8 +16,10 @@
  *     HIP device; hp_skeleton / hp_params / the hp_* descriptor structs are read
  *     on the host before the call returns, the arrays inside descriptors are
  *     device memory.  The caller owns every buffer.  The library allocates and
- *     frees nothing and never synchronises: all work is enqueued on `stream`
- *     (a hipStream_t passed as void*; NULL = the default stream).
+ *     frees no device memory and the operator calls never synchronise: all work
+ *     is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  Only the hp_batcher_* calls keep host state, a thread and HIP
+ *     events of their own, and block where their comments say so.
  *   - Return value: HP_OK or a negative hp_error, decided on the host before
  *     anything is enqueued (invalid calls enqueue nothing).
  *   - Conditions only the device can see (a list longer than its capacity) are
@@ -49,7 +51,10 @@ typedef enum {
     HP_ERR_DTYPE = -2,         /* unknown hp_dtype */
     HP_ERR_WORKSPACE = -3,     /* workspace smaller than hp_workspace_bytes() or misaligned */
     HP_ERR_HIP = -4,           /* a launch failed (hipGetLastError) */
-    HP_ERR_UNSUPPORTED = -5    /* a size beyond the built limits (see HP_MAX_*) */
+    HP_ERR_UNSUPPORTED = -5,   /* a size beyond the built limits (see HP_MAX_*) */
+    HP_ERR_BUSY = -6,          /* hp_batcher: every lane is collecting, running or held by the caller */
+    HP_ERR_TIMEOUT = -7,       /* hp_batcher: the wait ended before the condition held */
+    HP_ERR_STATE = -8          /* hp_batcher: call out of order (commit without acquire, release of a lane not held) */
 } hp_error;
 
 typedef enum {
@@ -212,6 +217,122 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
 int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst,
                   int Hd, int Wd, int reverse_channels, const float *alpha, const float *beta,
                   void *stream);
+
+/* ---- Streaming front with a dynamic batch slot ---------------------------------------------
+ * Section 2.2.1 runs the operators asynchronously, a FIFO between each pair; Section 2.2.2 puts a
+ * batch slot in front of the GPU operator that collects more input tensors only while the GPU is
+ * the bottleneck, so that batches grow under load and stay small (low per-image delay) otherwise.
+ * Here the post-processing operator is the GPU operator, and hp_batcher is that slot in front of
+ * hp_postprocess:
+ *   - the caller provides n_lanes "lanes", each the buffers of one batch of up to max_batch frames
+ *     (frame staging, outputs, workspace, status word) and a HIP stream of its own;
+ *   - frames are handed in one at a time (hp_batcher_submit copies a frame into the open lane;
+ *     hp_batcher_acquire / hp_batcher_commit let the producer write it there itself);
+ *   - a frame that arrives while fewer than `depth` batches are running starts the open batch at
+ *     once; while `depth` batches are running the open batch keeps collecting (up to max_batch) and
+ *     starts when a running batch completes.  Batches start, complete and are handed out in
+ *     arrival order, so frames leave in the order they came;
+ *   - hp_batcher_next hands out the oldest finished batch: image b of the lane's outputs belongs to
+ *     the b-th frame of the batch, exactly what hp_postprocess returns for that frame alone or in
+ *     any other batch (images are independent).  The lane is the caller's until hp_batcher_release.
+ * A batcher keeps one host thread (it waits for the running batches) and two HIP events per lane.
+ * Thread model: one producer thread (acquire / commit / submit / flush) and one consumer thread
+ * (next / release) may run concurrently; they may be the same thread. */
+typedef struct {
+    void *cm_lo;          /* device [max_batch][K+1][h][w] of the batcher's dtype: frame staging */
+    void *paf_lo;         /* device [max_batch][2L][h][w] */
+    hp_peaks peaks;       /* all outputs sized for max_batch images, as for hp_postprocess */
+    hp_pairs cands;
+    hp_pairs conns;
+    hp_poses poses;
+    void *workspace;      /* hp_workspace_bytes(max_batch, ...), cleared once with hp_workspace_init */
+    size_t ws_bytes;
+    int32_t *status;      /* device int32 */
+    void *stream;         /* hipStream_t; lanes must not share streams for batches to overlap */
+} hp_lane;
+
+typedef struct {
+    int32_t max_batch;    /* 1..HP_MAX_BATCH frames per batch */
+    int32_t depth;        /* 1..n_lanes batches allowed to run at once */
+    int32_t n_lanes;      /* 1..HP_MAX_LANES; depth + 1 or more lets a batch collect while `depth` run */
+} hp_batcher_config;
+
+enum { HP_MAX_BATCH = 1024, HP_MAX_LANES = 64 };
+
+typedef struct {
+    int32_t lane;         /* index of the lane that holds the results */
+    int32_t n_frames;     /* frames in the batch */
+    int32_t rc;           /* what hp_postprocess returned for the batch */
+    int32_t reserved;
+    uint64_t seq;         /* batches are numbered 0, 1, 2, ... in start order */
+    int64_t start_ns;     /* host clock (ns since hp_batcher_create) when the batch was enqueued */
+    int64_t done_ns;      /* host clock when its completion was seen */
+} hp_batch_info;
+
+typedef struct hp_batcher hp_batcher;
+
+/* Creates a batcher on the current device for lo-res tensors [.][K+1 | 2L][h][w] of `dt`.  The
+ * skeleton, parameters and lane descriptors are copied; the buffers they point to stay the
+ * caller's and must outlive the batcher.  Checks everything hp_postprocess would check for a
+ * batch of max_batch frames. */
+int hp_batcher_create(hp_dtype dt, int h, int w, const hp_skeleton *skel, const hp_params *prm,
+                      const hp_batcher_config *cfg, const hp_lane *lanes, hp_batcher **out);
+
+/* Waits for the running batches, stops the thread, destroys the events.  Lanes still held or
+ * finished are dropped; an open batch that never started is discarded. */
+int hp_batcher_destroy(hp_batcher *b);
+
+/* Place for the next frame: *cm_slot / *paf_slot point into the open lane's staging tensors
+ * (device memory, one frame each).  Waits up to timeout_ms for a free lane (0: not at all, < 0:
+ * without limit) and returns HP_ERR_BUSY otherwise.  One place at a time: HP_ERR_STATE when the
+ * previous one is not committed yet. */
+int hp_batcher_acquire(hp_batcher *b, int timeout_ms, void **cm_slot, void **paf_slot);
+
+/* The acquired frame is handed over under the caller's `tag`.  When ready == 0 the frame is being
+ * written by work already enqueued on producer_stream and the batch is ordered after that work
+ * (an event, no host wait); when ready != 0 the frame is complete in memory and producer_stream is
+ * ignored. */
+int hp_batcher_commit(hp_batcher *b, uint64_t tag, void *producer_stream, int ready);
+
+/* hp_batcher_acquire + two device-to-device copies of one frame (cm_frame: device [K+1][h][w],
+ * paf_frame: device [2L][h][w]) enqueued on the lane's stream + hp_batcher_commit.  `ready` and
+ * producer_stream say, as for hp_batcher_commit, whether the source frame is still being written. */
+int hp_batcher_submit(hp_batcher *b, int timeout_ms, const void *cm_frame, const void *paf_frame,
+                      uint64_t tag, void *producer_stream, int ready);
+
+/* Closes the open batch whatever its size (end of a stream of frames). */
+int hp_batcher_flush(hp_batcher *b);
+
+/* Oldest finished batch: fills *info, and tags[0..n_frames) / commit_ns[0..n_frames) (host arrays
+ * of max_batch entries, either may be NULL) with the frames' tags and hand-over times.  Waits up
+ * to timeout_ms (0: not at all, < 0: without limit); HP_ERR_TIMEOUT when none finished in time,
+ * HP_ERR_STATE when none can finish (nothing running or waiting) and the wait has no limit. */
+int hp_batcher_next(hp_batcher *b, int timeout_ms, hp_batch_info *info, uint64_t *tags, int64_t *commit_ns);
+
+/* Gives a lane handed out by hp_batcher_next back for new frames. */
+int hp_batcher_release(hp_batcher *b, int lane);
+
+/* The batch-slot decisions alone, in virtual time, for tests and capacity planning (no GPU call).
+ * Frame k arrives at arrival_ns[k] (non-decreasing); a batch of n frames started at t is finished
+ * at t + service_base_ns + n * service_per_frame_ns, completions are seen in start order, and the
+ * consumer releases a lane the moment it is handed out; a frame that finds every lane taken
+ * waits for the next release.  Outputs (host arrays of n_frames): the sequence number and size of
+ * each frame's batch and the time its completion is seen. */
+int hp_batch_simulate(int n_frames, const int64_t *arrival_ns, const hp_batcher_config *cfg,
+                      int64_t service_base_ns, int64_t service_per_frame_ns,
+                      int64_t *batch_seq, int32_t *batch_size, int64_t *done_ns);
+
+/* Load generator, for benchmarks only.  Hands n_frames frames to `b` from the calling thread,
+ * frame k at interarrival_ns * k after the start (0: as fast as they are taken), while a second
+ * thread takes the finished batches and releases their lanes at once.  With copy_frames != 0,
+ * frame k is src frame k % n_src (cm_src: device [n_src][K+1][h][w], paf_src likewise) copied
+ * with hp_batcher_submit; otherwise the staging tensors are used as they are (acquire + commit,
+ * nothing written).  Outputs (host arrays of n_frames, may be NULL): the time from a frame's
+ * scheduled arrival to the seen completion of its batch, and its batch's size; *elapsed_ns: first
+ * arrival to last completion.  The batcher must be idle at the call and is idle after it. */
+int hp_batcher_drive(hp_batcher *b, int n_frames, int64_t interarrival_ns, int copy_frames,
+                     const void *cm_src, const void *paf_src, int n_src,
+                     int64_t *latency_ns, int32_t *batch_size, int64_t *elapsed_ns);
 
 /* Per-kernel timing, for benchmarks only.  Between hp_profile_begin and hp_profile_end
  * every kernel the library enqueues (from this process, any stream) is bracketed by a pair

@@ -6,7 +6,7 @@ fallback: if the library is missing, loading raises.
 """
 import ctypes
 import os
-from ctypes import POINTER, Structure, c_float, c_int, c_int32, c_size_t, c_void_p
+from ctypes import POINTER, Structure, c_float, c_int, c_int32, c_int64, c_size_t, c_uint64, c_void_p
 
 import numpy as np
 import torch
@@ -17,7 +17,10 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version")
+           "hp_postprocess", "hp_preprocess", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
+           "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
+HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
 HP_K_COUNT = 11
 
 
@@ -48,6 +51,21 @@ class _Pairs(Structure):
 class _Poses(Structure):
     _fields_ = [("slots", c_void_p), ("nparts", c_void_p), ("score", c_void_p), ("count", c_void_p),
                 ("cap", c_int32)]
+
+
+class _Lane(Structure):
+    _fields_ = [("cm_lo", c_void_p), ("paf_lo", c_void_p), ("peaks", _Peaks), ("cands", _Pairs), ("conns", _Pairs),
+                ("poses", _Poses), ("workspace", c_void_p), ("ws_bytes", c_size_t), ("status", c_void_p),
+                ("stream", c_void_p)]
+
+
+class _BatcherConfig(Structure):
+    _fields_ = [("max_batch", c_int32), ("depth", c_int32), ("n_lanes", c_int32)]
+
+
+class _BatchInfo(Structure):
+    _fields_ = [("lane", c_int32), ("n_frames", c_int32), ("rc", c_int32), ("reserved", c_int32),
+                ("seq", c_uint64), ("start_ns", c_int64), ("done_ns", c_int64)]
 
 
 def lib_path():
@@ -87,6 +105,29 @@ def lib():
         L.hp_preprocess.restype = c_int
         L.hp_preprocess.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int,
                                     POINTER(c_float), POINTER(c_float), c_void_p]
+        L.hp_batcher_create.restype = c_int
+        L.hp_batcher_create.argtypes = [c_int, c_int, c_int, POINTER(_Skeleton), POINTER(_Params),
+                                        POINTER(_BatcherConfig), POINTER(_Lane), POINTER(c_void_p)]
+        L.hp_batcher_destroy.restype = c_int
+        L.hp_batcher_destroy.argtypes = [c_void_p]
+        L.hp_batcher_acquire.restype = c_int
+        L.hp_batcher_acquire.argtypes = [c_void_p, c_int, POINTER(c_void_p), POINTER(c_void_p)]
+        L.hp_batcher_commit.restype = c_int
+        L.hp_batcher_commit.argtypes = [c_void_p, c_uint64, c_void_p, c_int]
+        L.hp_batcher_submit.restype = c_int
+        L.hp_batcher_submit.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_uint64, c_void_p, c_int]
+        L.hp_batcher_flush.restype = c_int
+        L.hp_batcher_flush.argtypes = [c_void_p]
+        L.hp_batcher_next.restype = c_int
+        L.hp_batcher_next.argtypes = [c_void_p, c_int, POINTER(_BatchInfo), POINTER(c_uint64), POINTER(c_int64)]
+        L.hp_batcher_release.restype = c_int
+        L.hp_batcher_release.argtypes = [c_void_p, c_int]
+        L.hp_batch_simulate.restype = c_int
+        L.hp_batch_simulate.argtypes = [c_int, POINTER(c_int64), POINTER(_BatcherConfig), c_int64, c_int64,
+                                        POINTER(c_int64), POINTER(c_int32), POINTER(c_int64)]
+        L.hp_batcher_drive.restype = c_int
+        L.hp_batcher_drive.argtypes = [c_void_p, c_int, c_int64, c_int, c_void_p, c_void_p, c_int,
+                                       POINTER(c_int64), POINTER(c_int32), POINTER(c_int64)]
         L.hp_profile_begin.restype = c_int
         L.hp_profile_begin.argtypes = [c_int]
         L.hp_profile_end.restype = c_int
@@ -322,3 +363,120 @@ class PostprocessCall:
         rc = self._fn(*self._args)
         if rc != 0:
             raise HPError(rc, "hp_postprocess")
+
+
+# ---- streaming front: the dynamic batch slot in front of hp_postprocess ------------------------
+
+class BatcherLanes:
+    """Caller-owned buffers of a batcher: per lane a stream, frame staging for max_batch frames and a Buffers."""
+
+    def __init__(self, n_lanes, max_batch, K, L, h, w, cap, ccap, pcap, dtype=torch.float32, device="cuda:0"):
+        self.n_lanes, self.max_batch = int(n_lanes), int(max_batch)
+        self.dtype, self.h, self.w, self.K, self.L = dtype, h, w, K, L
+        with torch.cuda.device(device):
+            self.streams = [torch.cuda.Stream() for _ in range(self.n_lanes)]
+            self.cm = [torch.zeros((max_batch, K + 1, h, w), dtype=dtype, device=device) for _ in range(self.n_lanes)]
+            self.paf = [torch.zeros((max_batch, 2 * L, h, w), dtype=dtype, device=device) for _ in range(self.n_lanes)]
+            self.buf = [Buffers(max_batch, K, L, h, w, cap, ccap, pcap, device) for _ in range(self.n_lanes)]
+            torch.cuda.synchronize()
+        self.c = (_Lane * self.n_lanes)()
+        for l in range(self.n_lanes):
+            b = self.buf[l]
+            self.c[l] = _Lane(self.cm[l].data_ptr(), self.paf[l].data_ptr(), b.peaks, b.cands, b.conns, b.poses,
+                              b.workspace.data_ptr(), b.ws_bytes, b.status.data_ptr(), self.streams[l].cuda_stream)
+
+    def slot_of(self, cm_ptr):
+        """(lane, index) of the frame place whose CM pointer hp_batcher_acquire returned."""
+        for l, t in enumerate(self.cm):
+            off = cm_ptr - t.data_ptr()
+            if 0 <= off < t.numel() * t.element_size():
+                return l, off // (t[0].numel() * t.element_size())
+        raise ValueError("pointer outside the staging tensors")
+
+
+def hp_batcher_create(skel, prm, lanes, depth):
+    """Returns the batcher handle; `lanes` (a BatcherLanes) must outlive it."""
+    cfg = _BatcherConfig(lanes.max_batch, int(depth), lanes.n_lanes)
+    out = c_void_p()
+    dt = HP_F32 if lanes.dtype == torch.float32 else HP_F16
+    _check(lib().hp_batcher_create(dt, lanes.h, lanes.w, ctypes.byref(skel.c), ctypes.byref(prm.c), ctypes.byref(cfg),
+                                   lanes.c, ctypes.byref(out)), "hp_batcher_create")
+    return out
+
+
+def hp_batcher_destroy(b):
+    _check(lib().hp_batcher_destroy(b), "hp_batcher_destroy")
+
+
+def hp_batcher_acquire(b, timeout_ms=0):
+    """(cm pointer, paf pointer) of the next frame's place, or None when every lane is taken."""
+    cm, paf = c_void_p(), c_void_p()
+    rc = lib().hp_batcher_acquire(b, int(timeout_ms), ctypes.byref(cm), ctypes.byref(paf))
+    if rc == HP_ERR_BUSY:
+        return None
+    _check(rc, "hp_batcher_acquire")
+    return cm.value, paf.value
+
+
+def hp_batcher_commit(b, tag, producer_stream=None, ready=False):
+    st = c_void_p(producer_stream.cuda_stream) if producer_stream is not None else _stream()
+    _check(lib().hp_batcher_commit(b, int(tag), st, 1 if ready else 0), "hp_batcher_commit")
+
+
+def hp_batcher_submit(b, cm_frame, paf_frame, tag, timeout_ms=0, producer_stream=None, ready=False):
+    """False when every lane is taken (nothing submitted)."""
+    st = c_void_p(producer_stream.cuda_stream) if producer_stream is not None else _stream()
+    rc = lib().hp_batcher_submit(b, int(timeout_ms), _dev(cm_frame), _dev(paf_frame), int(tag), st, 1 if ready else 0)
+    if rc == HP_ERR_BUSY:
+        return False
+    _check(rc, "hp_batcher_submit")
+    return True
+
+
+def hp_batcher_flush(b):
+    _check(lib().hp_batcher_flush(b), "hp_batcher_flush")
+
+
+def hp_batcher_next(b, max_batch, timeout_ms=-1):
+    """Oldest finished batch as a dict (lane, n_frames, seq, start_ns, done_ns, tags, commit_ns), None on time-out."""
+    info = _BatchInfo()
+    tags = (c_uint64 * max_batch)()
+    cns = (c_int64 * max_batch)()
+    rc = lib().hp_batcher_next(b, int(timeout_ms), ctypes.byref(info), tags, cns)
+    if rc == HP_ERR_TIMEOUT:
+        return None
+    _check(rc, "hp_batcher_next")
+    _check(info.rc, "hp_postprocess (batch %d)" % info.seq)
+    n = info.n_frames
+    return dict(lane=info.lane, n_frames=n, seq=info.seq, start_ns=info.start_ns, done_ns=info.done_ns,
+                tags=[int(tags[k]) for k in range(n)], commit_ns=[int(cns[k]) for k in range(n)])
+
+
+def hp_batcher_release(b, lane):
+    _check(lib().hp_batcher_release(b, int(lane)), "hp_batcher_release")
+
+
+def hp_batch_simulate(arrival_ns, max_batch, depth, n_lanes, service_base_ns, service_per_frame_ns):
+    """Virtual-time run of the batch-slot decisions: (batch_seq, batch_size, done_ns) per frame."""
+    arr = np.ascontiguousarray(arrival_ns, np.int64)
+    n = len(arr)
+    seq, size, done = np.zeros(n, np.int64), np.zeros(n, np.int32), np.zeros(n, np.int64)
+    cfg = _BatcherConfig(int(max_batch), int(depth), int(n_lanes))
+    _check(lib().hp_batch_simulate(n, arr.ctypes.data_as(POINTER(c_int64)), ctypes.byref(cfg),
+                                   int(service_base_ns), int(service_per_frame_ns),
+                                   seq.ctypes.data_as(POINTER(c_int64)), size.ctypes.data_as(POINTER(c_int32)),
+                                   done.ctypes.data_as(POINTER(c_int64))), "hp_batch_simulate")
+    return seq, size, done
+
+
+def hp_batcher_drive(b, n_frames, interarrival_ns, cm_src=None, paf_src=None):
+    """Load generator: (latency_ns, batch_size, elapsed_ns); frames are copied from cm_src / paf_src when given."""
+    lat, size = np.zeros(n_frames, np.int64), np.zeros(n_frames, np.int32)
+    el = c_int64()
+    copy = cm_src is not None
+    _check(lib().hp_batcher_drive(b, int(n_frames), int(interarrival_ns), 1 if copy else 0,
+                                  _dev(cm_src) if copy else None, _dev(paf_src) if copy else None,
+                                  int(cm_src.shape[0]) if copy else 0,
+                                  lat.ctypes.data_as(POINTER(c_int64)), size.ctypes.data_as(POINTER(c_int32)),
+                                  ctypes.byref(el)), "hp_batcher_drive")
+    return lat, size, int(el.value)

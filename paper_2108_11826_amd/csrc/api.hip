@@ -256,7 +256,23 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
                    const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
                    void *workspace, size_t ws_bytes, int32_t *status, void *stream)
 {
+    return hp::postprocess(cm_lo, paf_lo, dt, N, N, h, w, skel, prm, cm_hi, paf_hi, peaks, cands, conns, poses,
+                           workspace, ws_bytes, status, stream, false);
+}
+
+}  // extern "C"
+
+// The operator on the first N images of buffers laid out for N_layout >= N images: every per-image
+// region of the workspace sits where a call on N_layout images puts it, so calls with different N
+// can share one workspace without clearing it in between (each call leaves its counters at zero).
+// With check_only set, the arguments are checked and nothing is enqueued.
+int hp::postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int N_layout, int h, int w,
+                    const hp_skeleton *skel, const hp_params *prm, float *cm_hi, float *paf_hi,
+                    const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
+                    void *workspace, size_t ws_bytes, int32_t *status, void *stream, bool check_only)
+{
     if (!cm_lo || !paf_lo || !status) return HP_ERR_INVALID_ARG;
+    if (N <= 0 || N > N_layout) return HP_ERR_INVALID_ARG;
     if (dt != HP_F32 && dt != HP_F16) return HP_ERR_DTYPE;
     if ((cm_hi == nullptr) != (paf_hi == nullptr)) return HP_ERR_INVALID_ARG;
     LimbTable tab;
@@ -264,7 +280,7 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     HP_TRY(check_skeleton(skel, tab));
     HP_TRY(check_params(prm, need));
     const int K = skel->n_parts, L = skel->n_limbs;
-    HP_TRY(check_dims(N, K + 1 + 2 * L, h, w));
+    HP_TRY(check_dims(N_layout, K + 1 + 2 * L, h, w));
     HP_TRY(check_peaks(peaks));
     HP_TRY(check_pairs(cands, HP_MAX_CCAP));
     HP_TRY(check_pairs(conns, HP_MAX_CAP));
@@ -272,7 +288,8 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     if (conns->cap < peaks->cap) return HP_ERR_INVALID_ARG;
     if (cm_hi && ((((uintptr_t)cm_hi) | ((uintptr_t)paf_hi)) & 15) != 0) return HP_ERR_INVALID_ARG;
     Workspace ws;
-    HP_TRY(check_ws(workspace, ws_bytes, N, K, L, peaks->cap, cands->cap, ws));
+    HP_TRY(check_ws(workspace, ws_bytes, N_layout, K, L, peaks->cap, cands->cap, ws));
+    if (check_only) return HP_OK;
     hipStream_t s = (hipStream_t)stream;
 
     if (cm_hi) {
@@ -298,6 +315,8 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
     HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
     return HP_OK;
 }
+
+extern "C" {
 
 int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst, int Hd, int Wd,
                   int reverse_channels, const float *alpha, const float *beta, void *stream)
@@ -383,10 +402,13 @@ const char *hp_strerror(int code)
     case HP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case HP_ERR_HIP: return "kernel launch failed";
     case HP_ERR_UNSUPPORTED: return "size beyond the built limits";
+    case HP_ERR_BUSY: return "every lane is taken";
+    case HP_ERR_TIMEOUT: return "timed out";
+    case HP_ERR_STATE: return "call out of order";
     default: return "unknown error";
     }
 }
 
-int hp_version(void) { return 200; }
+int hp_version(void) { return 300; }
 
 }  // extern "C"

@@ -168,4 +168,11 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
 hipError_t launch_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst, int Hd, int Wd,
                              int reverse_channels, const float *alpha, const float *beta, hipStream_t s);
 
+// hp_postprocess on the first N images of outputs and a workspace laid out for N_layout >= N images;
+// check_only: validate the arguments, enqueue nothing.
+int postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int N_layout, int h, int w,
+                const hp_skeleton *skel, const hp_params *prm, float *cm_hi, float *paf_hi,
+                const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
+                void *workspace, size_t ws_bytes, int32_t *status, void *stream, bool check_only);
+
 }  // namespace hp

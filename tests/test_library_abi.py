@@ -164,3 +164,42 @@ def test_preprocess_rejects_bad_calls(L):
     assert call(C=5) == -5 and call(Ws=20000) == -5 and call(Hd=16385) == -5 and call(N=70000) == -5
     assert call(dst=c_void_p(0x1002)) == -1        # fp32 output must be 4-byte aligned
     assert call(C=4, src=c_void_p(0x1001)) == -1   # four-channel pixels are read as aligned words
+
+
+def test_batcher_rejects_bad_calls(L):
+    from paper_2108_11826_amd import binding as B
+    sk, prm, pk, cd, cn, ps = descriptors()
+    ws = L.hp_workspace_bytes(4, 3, 2, 4, 4, 8, 64, 64, 16)
+
+    def lanes(n, shared=False, wsp=FAKE, wsb=ws):
+        arr = (B._Lane * n)()
+        for l in range(n):
+            base = FAKE if shared else FAKE * (l + 1)
+            arr[l] = B._Lane(base, base, pk, cd, cn, ps, wsp + (0 if shared else l * 0x100000), wsb, base, None)
+        return arr
+
+    def create(cfg=(4, 1, 2), dt=0, h=4, w=4, skel=sk, params=prm, ln=None, out=True):
+        c = B._BatcherConfig(*cfg)
+        handle = c_void_p()
+        rc = L.hp_batcher_create(dt, h, w, byref(skel.c) if skel else None, byref(params.c) if params else None,
+                                 byref(c), ln if ln is not None else lanes(cfg[2]), byref(handle) if out else None)
+        assert handle.value is None           # no batcher comes out of a failed call
+        return rc
+
+    assert create(out=False) == -1
+    assert create(skel=None) == -1 and create(params=None) == -1
+    assert create(dt=5) == -2
+    assert create(cfg=(0, 1, 2)) == -1 and create(cfg=(4, 0, 2)) == -1 and create(cfg=(4, 3, 2)) == -1
+    assert create(cfg=(4, 1, 65)) == -5 and create(cfg=(2048, 1, 2)) == -5
+    assert create(h=0) == -1
+    assert create(ln=lanes(2, shared=True)) == -1                  # lanes must not share buffers
+    assert create(ln=lanes(2, wsb=ws - 256)) == -3                 # workspace sized for fewer frames than max_batch
+    assert create(ln=lanes(2, wsp=FAKE + 8)) == -3
+    assert create(params=B.Params(scale=4)) == -5
+    assert create(params=B.Params(n_samples=1)) == -1
+    # the other entry points refuse a null handle
+    assert L.hp_batcher_destroy(None) == -1 and L.hp_batcher_flush(None) == -1
+    assert L.hp_batcher_release(None, 0) == -1 and L.hp_batcher_commit(None, 0, None, 1) == -1
+    assert L.hp_batcher_next(None, 0, None, None, None) == -1
+    assert L.hp_batcher_drive(None, 1, 0, 0, None, None, 0, None, None, None) == -1
+    assert L.hp_strerror(-6) != L.hp_strerror(-7) != L.hp_strerror(-8) != b"unknown error"
