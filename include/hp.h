@@ -294,9 +294,10 @@ int hp_batcher_acquire(hp_batcher *b, int timeout_ms, void **cm_slot, void **paf
  * ignored. */
 int hp_batcher_commit(hp_batcher *b, uint64_t tag, void *producer_stream, int ready);
 
-/* hp_batcher_acquire + two device-to-device copies of one frame (cm_frame: device [K+1][h][w],
- * paf_frame: device [2L][h][w]) enqueued on the lane's stream + hp_batcher_commit.  `ready` and
- * producer_stream say, as for hp_batcher_commit, whether the source frame is still being written. */
+/* hp_batcher_acquire + a device-to-device copy of one frame (cm_frame: device [K+1][h][w],
+ * paf_frame: device [2L][h][w]; one small kernel enqueued on the lane's stream) + hp_batcher_commit.
+ * `ready` and producer_stream say, as for hp_batcher_commit, whether the source frame is still
+ * being written. */
 int hp_batcher_submit(hp_batcher *b, int timeout_ms, const void *cm_frame, const void *paf_frame,
                       uint64_t tag, void *producer_stream, int ready);
 

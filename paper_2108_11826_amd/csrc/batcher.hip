@@ -1,6 +1,7 @@
 // Streaming front of the operator: the dynamic batch slot of Section 2.2.2 in front of
 // hp_postprocess (hp_batcher_*), its virtual-time simulation and a load generator.
-// Host code only; every decision is taken by BatchPolicy, every GPU step by hp_postprocess.
+// Host code but for one copy kernel; every decision is taken by BatchPolicy, every step of the
+// operator by hp_postprocess.
 #include <string.h>
 
 #include <atomic>
@@ -30,7 +31,7 @@ struct Lane {
 
 struct hp_batcher {
     std::mutex mu;
-    std::condition_variable cv_run;    // a batch started (wakes the waiting thread)
+    std::condition_variable cv_run;    // a batch started (wakes the batcher's thread)
     std::condition_variable cv_done;   // a batch finished
     std::condition_variable cv_free;   // a lane was released
     hp::BatchPolicy pol;
@@ -43,6 +44,7 @@ struct hp_batcher {
     size_t cm_frame_bytes, paf_frame_bytes;
     uint64_t next_seq = 0;
     int acq_lane = -1, acq_index = -1;
+    std::deque<int> handoff;           // started batches the batcher's thread still has to enqueue, in order
     bool stop = false;
     std::thread waiter;
     std::chrono::steady_clock::time_point t0;
@@ -59,37 +61,91 @@ namespace hp {
 
 static size_t elem_bytes(hp_dtype dt) { return dt == HP_F16 ? 2 : 4; }
 
-// Enqueues the batches the policy decided to start.  Called with b->mu held.
-static void start_lanes(hp_batcher *b, const std::vector<int> &start)
+// Copies one frame (its CM and its PAF tensor) into a lane's staging tensors in one launch,
+// 16 bytes per thread; a launch costs the host a fraction of what two memcpy calls do.
+__global__ __launch_bounds__(kBlock) void k_copy_frame(const uint4 *__restrict__ cm_src, uint4 *__restrict__ cm_dst,
+                                                       unsigned n_cm, const uint4 *__restrict__ paf_src,
+                                                       uint4 *__restrict__ paf_dst, unsigned n_paf)
 {
-    for (int l : start) {
-        Lane &ln = b->lanes[(size_t)l];
-        const int n = b->pol.frames(l);
-        ln.info.lane = l;
-        ln.info.n_frames = n;
-        ln.info.seq = b->next_seq++;
-        ln.info.reserved = 0;
-        ln.info.start_ns = b->now();
-        ln.info.done_ns = 0;
-        int rc = postprocess(ln.d.cm_lo, ln.d.paf_lo, b->dt, n, b->max_batch, b->h, b->w, &b->skel, &b->prm, nullptr,
-                             nullptr, &ln.d.peaks, &ln.d.cands, &ln.d.conns, &ln.d.poses, ln.d.workspace, ln.d.ws_bytes,
-                             ln.d.status, ln.d.stream, false);
-        // the event is recorded even after a failed call: the lane then completes at once and
-        // carries the error to hp_batcher_next
-        if (hipEventRecord(ln.done_ev, (hipStream_t)ln.d.stream) != hipSuccess && rc == HP_OK) rc = HP_ERR_HIP;
-        ln.info.rc = rc;
-    }
-    if (!start.empty()) b->cv_run.notify_one();
+    const unsigned t = blockIdx.x * kBlock + threadIdx.x;
+    if (t < n_cm)
+        cm_dst[t] = cm_src[t];
+    else if (t - n_cm < n_paf)
+        paf_dst[t - n_cm] = paf_src[t - n_cm];
 }
 
-// The batcher's thread: waits for the oldest running batch, marks it finished, starts what the
-// policy releases.  Exits when asked to stop and nothing is running.
-static void waiter_main(hp_batcher *b)
+static hipError_t copy_frame(const void *cm_src, void *cm_dst, size_t cm_bytes, const void *paf_src, void *paf_dst,
+                             size_t paf_bytes, hipStream_t s)
+{
+    const uintptr_t bits = (uintptr_t)cm_src | (uintptr_t)cm_dst | (uintptr_t)paf_src | (uintptr_t)paf_dst | cm_bytes | paf_bytes;
+    if ((bits & 15) == 0 && (cm_bytes + paf_bytes) / 16 < (1ull << 31)) {
+        const unsigned n_cm = (unsigned)(cm_bytes / 16), n_paf = (unsigned)(paf_bytes / 16);
+        const unsigned blocks = (n_cm + n_paf + kBlock - 1) / kBlock;
+        k_copy_frame<<<blocks, kBlock, 0, s>>>((const uint4 *)cm_src, (uint4 *)cm_dst, n_cm, (const uint4 *)paf_src,
+                                              (uint4 *)paf_dst, n_paf);
+        return hipGetLastError();
+    }
+    hipError_t e = hipMemcpyAsync(cm_dst, cm_src, cm_bytes, hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return e;
+    return hipMemcpyAsync(paf_dst, paf_src, paf_bytes, hipMemcpyDeviceToDevice, s);
+}
+
+// Enqueues one batch: the operator on the lane's first n frames, then the event that marks its end.
+// The lane is in the running state, so nothing else touches its buffers; may run without b->mu.
+static void launch_lane(hp_batcher *b, int l)
+{
+    Lane &ln = b->lanes[(size_t)l];
+    ln.info.start_ns = b->now();
+    int rc = postprocess(ln.d.cm_lo, ln.d.paf_lo, b->dt, ln.info.n_frames, b->max_batch, b->h, b->w, &b->skel, &b->prm,
+                         nullptr, nullptr, &ln.d.peaks, &ln.d.cands, &ln.d.conns, &ln.d.poses, ln.d.workspace,
+                         ln.d.ws_bytes, ln.d.status, ln.d.stream, false);
+    // the event is recorded even after a failed call: the lane then completes at once and
+    // carries the error to hp_batcher_next
+    if (hipEventRecord(ln.done_ev, (hipStream_t)ln.d.stream) != hipSuccess && rc == HP_OK) rc = HP_ERR_HIP;
+    ln.info.rc = rc;
+}
+
+// Takes over the batches the policy decided to start.  Called with b->mu held.  A batch that
+// starts while nothing else runs is enqueued here and now, on the caller's thread: the GPU is
+// idle and the frame's delay is what counts.  Otherwise the batcher's thread enqueues it, so
+// that a producer handing in frames under load never pays for kernel launches.
+static void take_over(hp_batcher *b, const std::vector<int> &start, bool may_launch_here)
+{
+    if (start.empty()) return;
+    const bool idle_before = b->handoff.empty() && b->pol.running() == (int)start.size();
+    for (int l : start) {
+        Lane &ln = b->lanes[(size_t)l];
+        ln.info.lane = l;
+        ln.info.n_frames = b->pol.frames(l);
+        ln.info.seq = b->next_seq++;
+        ln.info.reserved = 0;
+        ln.info.rc = HP_OK;
+        ln.info.start_ns = ln.info.done_ns = 0;
+        if (may_launch_here && idle_before && l == start.front())
+            launch_lane(b, l);
+        else
+            b->handoff.push_back(l);
+    }
+    b->cv_run.notify_one();
+}
+
+// The batcher's thread: enqueues the batches handed to it, in order, and polls the end of the
+// oldest running batch (it spins only while a batch is in flight, and sleeps otherwise); a
+// finished batch releases what the policy starts next.  Exits when asked to stop and nothing runs.
+static void dispatcher_main(hp_batcher *b)
 {
     (void)hipSetDevice(b->device);
     std::unique_lock<std::mutex> lk(b->mu);
     for (;;) {
-        b->cv_run.wait(lk, [&] { return b->stop || b->pol.oldest_running() >= 0; });
+        b->cv_run.wait(lk, [&] { return b->stop || !b->handoff.empty() || b->pol.oldest_running() >= 0; });
+        if (!b->handoff.empty()) {
+            const int l = b->handoff.front();
+            b->handoff.pop_front();
+            lk.unlock();
+            launch_lane(b, l);
+            lk.lock();
+            continue;
+        }
         const int l = b->pol.oldest_running();
         if (l < 0) {
             if (b->stop) return;
@@ -97,14 +153,19 @@ static void waiter_main(hp_batcher *b)
         }
         Lane &ln = b->lanes[(size_t)l];
         lk.unlock();
-        const hipError_t e = hipEventSynchronize(ln.done_ev);
+        const hipError_t e = hipEventQuery(ln.done_ev);
+        if (e == hipErrorNotReady) {
+            __builtin_ia32_pause();
+            lk.lock();
+            continue;
+        }
         const int64_t t = b->now();
         lk.lock();
         if (e != hipSuccess && ln.info.rc == HP_OK) ln.info.rc = HP_ERR_HIP;
         ln.info.done_ns = t;
         std::vector<int> start;
         b->pol.complete(start);
-        start_lanes(b, start);
+        take_over(b, start, false);
         b->cv_done.notify_all();
     }
 }
@@ -191,7 +252,7 @@ int hp_batcher_create(hp_dtype dt, int h, int w, const hp_skeleton *skel, const 
         delete b;
         return rc;
     }
-    b->waiter = std::thread(waiter_main, b);
+    b->waiter = std::thread(dispatcher_main, b);
     *out = b;
     return HP_OK;
 }
@@ -254,7 +315,7 @@ int hp_batcher_commit(hp_batcher *b, uint64_t tag, void *producer_stream, int re
     ln.commit_ns[(size_t)b->acq_index] = b->now();
     std::vector<int> start;
     b->pol.commit(start);
-    start_lanes(b, start);
+    take_over(b, start, true);
     return HP_OK;
 }
 
@@ -276,8 +337,7 @@ int hp_batcher_submit(hp_batcher *b, int timeout_ms, const void *cm_frame, const
     bool ok = true;
     if (!ready && producer_stream != (void *)ls)
         ok = hipEventRecord(ev, (hipStream_t)producer_stream) == hipSuccess && hipStreamWaitEvent(ls, ev, 0) == hipSuccess;
-    ok = ok && hipMemcpyAsync(cm_slot, cm_frame, b->cm_frame_bytes, hipMemcpyDeviceToDevice, ls) == hipSuccess;
-    ok = ok && hipMemcpyAsync(paf_slot, paf_frame, b->paf_frame_bytes, hipMemcpyDeviceToDevice, ls) == hipSuccess;
+    ok = ok && copy_frame(cm_frame, cm_slot, b->cm_frame_bytes, paf_frame, paf_slot, b->paf_frame_bytes, ls) == hipSuccess;
     if (!ok) {
         std::unique_lock<std::mutex> lk(b->mu);
         b->pol.cancel();
@@ -292,7 +352,7 @@ int hp_batcher_flush(hp_batcher *b)
     std::unique_lock<std::mutex> lk(b->mu);
     std::vector<int> start;
     if (!b->pol.flush(start)) return HP_ERR_STATE;
-    start_lanes(b, start);
+    take_over(b, start, true);
     return HP_OK;
 }
 
