@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the synthetic workloads (2 = 656x368 batch 8)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work spent on the oracle baseline (0 = skip)")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams the timed steps are spread over")
+    ap.add_argument("--streaming-sweep", action="store_true",
+                    help="print one JSON line per (batch slot, offered load) point of the streaming front and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of a known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -61,6 +63,35 @@ def main():
     buf = hp.Buffers(N, K, L, h, w, cap, ccap, pcap, dev)
     cm_hi = torch.empty((N, K + 1, cfg.H, cfg.W), dtype=torch.float32, device=dev)
     paf_hi = torch.empty((N, 2 * L, cfg.H, cfg.W), dtype=torch.float32, device=dev)
+
+    def streaming_point(max_batch, depth, n_lanes, offered_fps, n_frames, copy):
+        """Frames handed one at a time to the streaming front (hp_batcher_*) at a fixed rate (0 = as fast as they are
+        taken): achieved rate, mean batch size (per batch) and the delay from a frame's arrival to its result."""
+        lanes = hp.BatcherLanes(n_lanes, max_batch, K, L, h, w, cap, ccap, pcap, cm.dtype, dev)
+        reps = (max_batch + N - 1) // N
+        for l in range(n_lanes):
+            lanes.cm[l].copy_(cm.repeat(reps, 1, 1, 1)[:max_batch])
+            lanes.paf[l].copy_(paf.repeat(reps, 1, 1, 1)[:max_batch])
+        torch.cuda.synchronize()
+        bt = hp.hp_batcher_create(skel, prm, lanes, depth)
+        gap = int(round(1e9 / offered_fps)) if offered_fps else 0
+        src = (cm, paf) if copy else (None, None)
+        hp.hp_batcher_drive(bt, min(200, n_frames), gap, *src)
+        lat, size, elapsed = hp.hp_batcher_drive(bt, n_frames, gap, *src)
+        hp.hp_batcher_destroy(bt)
+        return {"max_batch": max_batch, "batches_in_flight": depth, "lanes": n_lanes,
+                "frames": "copied into the slot (one launch per frame)" if copy else "already in the slot",
+                "offered_fps": offered_fps if offered_fps else "unlimited", "fps": round(n_frames / elapsed * 1e9, 1),
+                "mean_batch": round(float(np.mean(1.0 / size)) ** -1, 2),
+                "latency_us_p50": round(float(np.percentile(lat, 50)) / 1e3, 1),
+                "latency_us_p99": round(float(np.percentile(lat, 99)) / 1e3, 1)}
+
+    if args.streaming_sweep:
+        for copy in (True, False):
+            for mb, depth, n_lanes in ((1, 2, 3), (N, 1, 3), (N, 2, 4), (N, 3, 5), (4 * N, 2, 4)):
+                for load in (10_000, 50_000, 100_000, 200_000, 400_000, 0):
+                    print(json.dumps(streaming_point(mb, depth, n_lanes, load, 4000, copy)), flush=True)
+        return
 
     call_fused = hp.PostprocessCall(cm, paf, skel, prm, buf)
     call_mat = hp.PostprocessCall(cm, paf, skel, prm, buf, cm_hi, paf_hi)
@@ -254,6 +285,14 @@ def main():
                   "parity_with_oracle": pre_ok}
     del pre_src, pre_dst
 
+    # the streaming front: frames arrive one at a time, the batch slot grows only while batches are running
+    streaming = {
+        "what": "hp_batcher_* (dynamic batch slot in front of hp_postprocess, Section 2.2.2): frames of this workload handed "
+                "in one at a time by the library's load generator; latency = scheduled arrival -> result seen on the host",
+        "dynamic_batching": [streaming_point(N, 2, 4, load, 2000, True) for load in (10_000, 100_000, 200_000, 0)],
+        "no_batching": [streaming_point(1, 2, 3, load, 2000, True) for load in (10_000, 0)],
+    }
+
     cpu = None
     if args.cpu_seconds > 0:
         T = min(16, len(os.sched_getaffinity(0)))
@@ -296,6 +335,7 @@ def main():
         "roofline": roofline, "roofline_fused": roofline_fused, "roofline_nms_hi": roofline_nms_hi,
         "roofline_scoring": roofline_scoring,
         "preprocess": preprocess,
+        "streaming": streaming,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
