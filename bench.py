@@ -8,7 +8,7 @@ streams (each with its own output buffers and workspace) so that consecutive bat
 as the operators of the paper's streaming dataflow do (Section 2.2.1); the one-stream rate is
 reported beside it.  The same number of steps is then timed on the form that materialises the
 hi-res maps (its upsampling kernel is the HBM-bound one the roofline object describes), and
-once more with per-kernel event brackets for the kernel times.
+once more with per-kernel event stamps for the kernel times.
 """
 import argparse
 import json
@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the synthetic workloads (2 = 656x368 batch 8)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work spent on the oracle baseline (0 = skip)")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams the timed steps are spread over")
+    ap.add_argument("--no-streaming", action="store_true", help="skip the streaming-front measurement")
     ap.add_argument("--streaming-sweep", action="store_true",
                     help="print one JSON line per (batch slot, offered load) point of the streaming front and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -159,7 +160,7 @@ def main():
         parity = parity and bool(ok)
     t_mat = timed(True)
 
-    # per-kernel times: the same steps again with event brackets around every launch
+    # per-kernel times: the same steps again with every launch stamped by a pair of events
     hp.hp_profile_begin(2 * args.steps * 8)
     for _ in range(args.steps):
         step(False)
@@ -286,7 +287,7 @@ def main():
     del pre_src, pre_dst
 
     # the streaming front: frames arrive one at a time, the batch slot grows only while batches are running
-    streaming = {
+    streaming = None if args.no_streaming else {
         "what": "hp_batcher_* (dynamic batch slot in front of hp_postprocess, Section 2.2.2): frames of this workload handed "
                 "in one at a time by the library's load generator; latency = scheduled arrival -> result seen on the host",
         "dynamic_batching": [streaming_point(N, 2, 4, load, 2000, True) for load in (10_000, 100_000, 200_000, 0)],
@@ -329,8 +330,8 @@ def main():
         "value_materialised": round(N * args.steps / t_mat, 1),
         "ms_per_step_materialised": round(1e3 * t_mat / args.steps, 5),
         "kernel_us": {k: round(v, 2) for k, v in sorted(kern_us.items())},
-        "kernel_us_note": "HIP-event brackets around each launch; the bracket itself adds 2-5 us, "
-                          "see profiles/ for rocprofv3 kernel durations",
+        "kernel_us_note": "each launch carries a pair of HIP events stamped with the kernel's begin and end "
+                          "(extended launch call); profiles/ holds the rocprofv3 durations of the same command",
         "staged_kernel_us": {k: round(v, 2) for k, v in sorted(staged_us.items())},
         "roofline": roofline, "roofline_fused": roofline_fused, "roofline_nms_hi": roofline_nms_hi,
         "roofline_scoring": roofline_scoring,

@@ -335,14 +335,15 @@ int hp_batcher_drive(hp_batcher *b, int n_frames, int64_t interarrival_ns, int c
                      const void *cm_src, const void *paf_src, int n_src,
                      int64_t *latency_ns, int32_t *batch_size, int64_t *elapsed_ns);
 
-/* Per-kernel timing, for benchmarks only.  Between hp_profile_begin and hp_profile_end
- * every kernel the library enqueues (from this process, any stream) is bracketed by a pair
- * of HIP events recorded on its stream; at most `max_launches` launches are recorded, later
- * ones run untimed.  hp_profile_end waits for the recorded events (it synchronises with the
- * streams used), adds the elapsed milliseconds and the launch counts per hp_kernel_id into
- * the two host arrays of HP_K_COUNT entries (either may be NULL), and leaves profiling off.
- * Not thread-safe; the event bracket adds a few microseconds of stream time per launch, so
- * whole-call throughput is measured with profiling off. */
+/* Per-kernel timing, for benchmarks only.  Between hp_profile_begin and hp_profile_end every
+ * kernel the library enqueues for an operator call (from this process, any stream) is launched
+ * together with a pair of HIP events that receive the kernel's own begin and end times; at most
+ * `max_launches` launches are recorded, later ones run untimed.  hp_profile_end waits for the
+ * recorded events (it synchronises with the streams used), adds the elapsed milliseconds and the
+ * launch counts per hp_kernel_id into the two host arrays of HP_K_COUNT entries (either may be
+ * NULL), and leaves profiling off.  The times are kernel durations as a profiler reports them;
+ * nothing is added to the stream, but a timed launch costs the host more, so whole-call
+ * throughput is measured with profiling off. */
 typedef enum {
     HP_K_INIT = 0,         /* clears counters and the status word */
     HP_K_RESIZE_NMS = 1,   /* upsampling + peak detection, maps kept in registers */

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "hp_dev.h"
@@ -113,41 +114,45 @@ static int check_ws(void *workspace, size_t ws_bytes, int N, int K, int L, int c
         if (rc_ != HP_OK) return rc_;     \
     } while (0)
 
-// Optional per-kernel event brackets (hp_profile_begin / hp_profile_end).
+// Optional per-kernel timing (hp_profile_begin / hp_profile_end): every kernel launched inside a
+// ProfScope gets a pair of events stamped with its begin and end times.
 struct ProfRecord {
     hipEvent_t start, stop;
     int id;
 };
+static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static size_t g_prof_max = 0;
 static std::vector<ProfRecord> g_prof;
+static thread_local int t_prof_id = -1;   // kernel id of the enclosing HP_LAUNCH, -1 outside
+
+bool launch_events(hipEvent_t &start, hipEvent_t &stop)
+{
+    if (t_prof_id < 0) return false;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof_on || g_prof.size() >= g_prof_max) return false;
+    ProfRecord r;
+    r.id = t_prof_id;
+    if (hipEventCreate(&r.start) != hipSuccess) return false;
+    if (hipEventCreate(&r.stop) != hipSuccess) {
+        (void)hipEventDestroy(r.start);
+        return false;
+    }
+    g_prof.push_back(r);
+    start = r.start;
+    stop = r.stop;
+    return true;
+}
 
 struct ProfScope {
-    hipStream_t s;
-    hipEvent_t stop = nullptr;
-    ProfScope(int id, hipStream_t stream) : s(stream)
-    {
-        if (!g_prof_on || g_prof.size() >= g_prof_max) return;
-        ProfRecord r;
-        r.id = id;
-        if (hipEventCreate(&r.start) != hipSuccess) return;
-        if (hipEventCreate(&r.stop) != hipSuccess) {
-            (void)hipEventDestroy(r.start);
-            return;
-        }
-        (void)hipEventRecord(r.start, s);
-        stop = r.stop;
-        g_prof.push_back(r);
-    }
-    ~ProfScope()
-    {
-        if (stop) (void)hipEventRecord(stop, s);
-    }
+    int saved;
+    explicit ProfScope(int id) : saved(t_prof_id) { t_prof_id = id; }
+    ~ProfScope() { t_prof_id = saved; }
 };
 
 #define HP_LAUNCH(id, expr)                          \
     do {                                             \
-        ProfScope scope_((id), s);                   \
+        ProfScope scope_((id));                      \
         if ((expr) != hipSuccess) return HP_ERR_HIP; \
     } while (0)
 
@@ -335,6 +340,7 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
 int hp_profile_begin(int max_launches)
 {
     if (max_launches <= 0) return HP_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
     for (auto &r : g_prof) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -348,6 +354,7 @@ int hp_profile_begin(int max_launches)
 
 int hp_profile_end(float *total_ms, int32_t *launches)
 {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
     g_prof_on = false;
     int rc = HP_OK;
     if (total_ms) for (int k = 0; k < HP_K_COUNT; ++k) total_ms[k] = 0.0f;

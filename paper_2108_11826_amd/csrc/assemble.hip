@@ -406,12 +406,12 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
     // few peaks per part: the tables of an image almost surely fit the small pools (if they do
     // not, the fold runs on the workspace tables, slower but the same)
     if (pk.cap <= 256)
-        hipLaunchKernelGGL((k_assemble<kPool16Small, kPool32Small>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
+        HP_KERNEL((k_assemble<kPool16Small, kPool32Small>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
                            pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
                            ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
                            poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr);
     else
-        hipLaunchKernelGGL((k_assemble<kPool16Large, kPool32Large>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
+        HP_KERNEL((k_assemble<kPool16Large, kPool32Large>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
                            pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
                            ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
                            poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr);

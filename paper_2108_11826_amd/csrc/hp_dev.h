@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
@@ -114,6 +115,23 @@ __device__ __forceinline__ int block_flag_scan(bool flag, int *scratch, int &tot
     total = tot;
     return before + within;
 }
+
+// ---- kernel launches --------------------------------------------------------
+// Per-kernel timing (hp_profile_begin / hp_profile_end): when it is on, launch_events hands out a
+// fresh pair of events and the launch goes through the extended launch call, which stamps them
+// with the kernel's own begin and end times (no extra packets on the stream, so the measured time
+// is the kernel's duration as a profiler reports it).  Otherwise it returns false and the launch
+// is an ordinary one.
+bool launch_events(hipEvent_t &start, hipEvent_t &stop);
+
+#define HP_KERNEL(kernel, grid, block, lds, stream, ...)                                             \
+    do {                                                                                             \
+        hipEvent_t ev0_ = nullptr, ev1_ = nullptr;                                                   \
+        if (hp::launch_events(ev0_, ev1_))                                                           \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ev0_, ev1_, 0, __VA_ARGS__);     \
+        else                                                                                         \
+            hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                       \
+    } while (0)
 
 // ---- launchers (each enqueues on `s` and returns the launch error) ----------
 

@@ -350,15 +350,15 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
     SampleT st;
     for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
     if (paf_hi)
-        hipLaunchKernelGGL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
+        HP_KERNEL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
                            prm.n_samples, prm.paf_thr, need, tiles_j, sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts,
                            cstage, ccap, ccap2);
     else if (dt == HP_F16)
-        hipLaunchKernelGGL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
+        HP_KERNEL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
                            (const __half *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
                            sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
     else
-        hipLaunchKernelGGL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
+        HP_KERNEL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
                            (const float *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
                            sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
     return hipGetLastError();
@@ -714,9 +714,9 @@ hipError_t launch_limb_small(const void *paf_lo, hp_dtype dt, int N, int h, int 
         pk.y, pk.score, cands.count, cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j,          \
         conns.score, conns.cap, status, in_lds
     if (dt == HP_F16)
-        hipLaunchKernelGGL((k_limb_small<__half>), grid, block, lds, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
+        HP_KERNEL((k_limb_small<__half>), grid, block, lds, s, HP_LIMB_SMALL_ARGS((const __half *)paf_lo));
     else
-        hipLaunchKernelGGL((k_limb_small<float>), grid, block, lds, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
+        HP_KERNEL((k_limb_small<float>), grid, block, lds, s, HP_LIMB_SMALL_ARGS((const float *)paf_lo));
 #undef HP_LIMB_SMALL_ARGS
     return hipGetLastError();
 }
@@ -727,15 +727,15 @@ hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const
 {
     dim3 grid(N * L), block(kBlock);
     if (mode == 0)
-        hipLaunchKernelGGL((k_match<0>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
+        HP_KERNEL((k_match<0>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
                            cands.i, cands.j, cands.score, cands.cap, (int32_t *)nullptr, (int32_t *)nullptr,
                            (int32_t *)nullptr, (float *)nullptr, 0, status);
     else if (mode == 1)
-        hipLaunchKernelGGL((k_match<1>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
+        HP_KERNEL((k_match<1>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
                            cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j, conns.score,
                            conns.cap, status);
     else
-        hipLaunchKernelGGL((k_match<2>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
+        HP_KERNEL((k_match<2>), grid, block, 0, s, T, K, L, pk.count, pk.cap, cctr, cstage, ccap2, cands.count,
                            cands.i, cands.j, cands.score, cands.cap, conns.count, conns.i, conns.j, conns.score,
                            conns.cap, status);
     return hipGetLastError();

@@ -183,9 +183,9 @@ template <int C, typename OUT, bool VEC>
 static void launch_pre_r(dim3 grid, dim3 block, hipStream_t s, const uint8_t *src, OUT *dst, const PreParams &p, bool reverse)
 {
     if (reverse)
-        hipLaunchKernelGGL((k_preprocess<C, OUT, VEC, true>), grid, block, 0, s, src, dst, p);
+        HP_KERNEL((k_preprocess<C, OUT, VEC, true>), grid, block, 0, s, src, dst, p);
     else
-        hipLaunchKernelGGL((k_preprocess<C, OUT, VEC, false>), grid, block, 0, s, src, dst, p);
+        HP_KERNEL((k_preprocess<C, OUT, VEC, false>), grid, block, 0, s, src, dst, p);
 }
 
 template <int C>

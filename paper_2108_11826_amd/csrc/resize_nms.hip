@@ -22,7 +22,7 @@ hipError_t launch_init(int32_t *a, int na, int32_t *b, int nb, int32_t *status, 
 {
     int n = na > nb ? na : nb;
     if (n < 1) n = 1;
-    hipLaunchKernelGGL(k_init, dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, a, na, b, nb, status);
+    HP_KERNEL(k_init, dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, a, na, b, nb, status);
     return hipGetLastError();
 }
 
@@ -317,7 +317,7 @@ static hipError_t launch_resize_write_t(const T *lo_a, const T *lo_b, float *hi_
         const int nn = N - n0 < 65535 ? N - n0 : 65535;
         for (int c0 = 0; c0 < Cg; c0 += 65535) {
             const int nc = Cg - c0 < 65535 ? Cg - c0 : 65535;
-            hipLaunchKernelGGL((k_resize_write<T>), dim3(groups * xparts, nc, nn), dim3(bx, R), 0, s, lo_a, lo_b, hi_a,
+            HP_KERNEL((k_resize_write<T>), dim3(groups * xparts, nc, nn), dim3(bx, R), 0, s, lo_a, lo_b, hi_a,
                                hi_b, c0, n0, Ca, Ca_mem, Cb, h, w, W4, H, xparts, bx, R, groups * xparts, nc, vec_a, vec_b,
                                first ? warm : 0u);
             hipError_t e = hipGetLastError();
@@ -343,7 +343,7 @@ static hipError_t launch_resize_nms_t(const T *lo, int N, int K, int C_mem, int 
     long long nodes64 = (long long)N * K * h * w;
     if (nodes64 <= 0 || nodes64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
     int nodes = (int)nodes64;
-    hipLaunchKernelGGL((k_resize_nms<T>), dim3((nodes + kBlock - 1) / kBlock), dim3(kBlock), 0, s, lo, nodes, K, C_mem,
+    HP_KERNEL((k_resize_nms<T>), dim3((nodes + kBlock - 1) / kBlock), dim3(kBlock), 0, s, lo, nodes, K, C_mem,
                        h, w, thr, counts, stage, cap, cap2, status);
     return hipGetLastError();
 }
@@ -369,7 +369,7 @@ hipError_t launch_zero(void *p, size_t bytes, hipStream_t s)
     size_t blocks = (n + kBlock - 1) / kBlock;
     if (blocks > 65536) blocks = 65536;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(k_zero, dim3((unsigned)blocks), dim3(kBlock), 0, s, (uint32_t *)p, n);
+    HP_KERNEL(k_zero, dim3((unsigned)blocks), dim3(kBlock), 0, s, (uint32_t *)p, n);
     return hipGetLastError();
 }
 
@@ -542,7 +542,7 @@ hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int 
             return hipErrorInvalidValue;
         for (long long p0 = 0; p0 < planes; p0 += 65535) {
             const long long np = planes - p0 < 65535 ? planes - p0 : 65535;
-            hipLaunchKernelGGL((k_nms_hi_strip<R>), dim3(strips_x, groups_y, (unsigned)np), dim3(kWave, kStripsPerBlock), 0,
+            HP_KERNEL((k_nms_hi_strip<R>), dim3(strips_x, groups_y, (unsigned)np), dim3(kWave, kStripsPerBlock), 0,
                                s, cm_hi, (int)p0, C_cm, K, H, W, W4, thr, counts, stage, cap, cap2);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
@@ -554,7 +554,7 @@ hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int 
     if (total64 <= 0 || total64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
     int total = (int)total64;
     dim3 grid((total + kBlock - 1) / kBlock), block(kBlock);
-    hipLaunchKernelGGL((k_nms_hi<false>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
+    HP_KERNEL((k_nms_hi<false>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
                        counts, stage, cap, cap2);
     return hipGetLastError();
 }
@@ -614,7 +614,7 @@ hipError_t launch_sort_peaks(int32_t *ctr, uint64_t *stage, int cap, int cap2, i
 {
     const int parts = (cap + kBlock - 1) / kBlock;
     const size_t lds = sizeof(uint32_t) * (size_t)((cap + 3) & ~3);         // <= 64 KB: cap <= HP_MAX_CAP
-    hipLaunchKernelGGL(k_sort_peaks, dim3(planes, parts), dim3(kBlock), lds, s, ctr, stage, cap, cap2, W, pk.count, pk.x,
+    HP_KERNEL(k_sort_peaks, dim3(planes, parts), dim3(kBlock), lds, s, ctr, stage, cap, cap2, W, pk.count, pk.x,
                        pk.y, pk.score, status);
     return hipGetLastError();
 }
