@@ -21,6 +21,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hp_oracle.c")
 _SRC_PRE = os.path.join(_HERE, "hp_pre_oracle.c")
+_SRC_DRAW = os.path.join(_HERE, "hp_draw_oracle.c")
 
 
 def _cpu_has_fma():
@@ -39,10 +40,10 @@ def build(force=False):
     out = []
     for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
         so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
-        newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_PRE))
+        newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_PRE), os.path.getmtime(_SRC_DRAW))
         if force or not os.path.exists(so) or os.path.getmtime(so) < newest:
             cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, "-o", so, "-lm"]
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
     return out
@@ -84,6 +85,12 @@ def lib():
         u8p = ctypes.POINTER(ctypes.c_uint8)
         L.hpq_preprocess.restype = None
         L.hpq_preprocess.argtypes = [u8p, ci, ci, ci, ci, ci, ci, ci, f32p, f32p, f32p]
+        L.hpv_in_capsule.restype = ci
+        L.hpv_in_capsule.argtypes = [ci] * 7
+        L.hpv_in_disc.restype = ci
+        L.hpv_in_disc.argtypes = [ci] * 5
+        L.hpv_draw.restype = None
+        L.hpv_draw.argtypes = [u8p, u8p, ci, ci, ci, ci, ci, ci, ci, i32p, i32p, i32p, i32p, ci, i32p, ci, u8p, u8p, ci, ci]
         _lib = L
     return _lib
 
@@ -126,6 +133,35 @@ def preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False):
     out = np.empty((N, C, Hd, Wd), np.float32)
     lib().hpq_preprocess(im.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), N, Hs, Ws, C, int(Hd), int(Wd),
                          1 if reverse_channels else 0, _f32(al), _f32(be), _f32(out))
+    return out
+
+
+def in_capsule(px, py, ax, ay, bx, by, thickness):
+    return bool(lib().hpv_in_capsule(int(px), int(py), int(ax), int(ay), int(bx), int(by), int(thickness)))
+
+
+def in_disc(px, py, cx, cy, radius):
+    return bool(lib().hpv_in_disc(int(px), int(py), int(cx), int(cy), int(radius)))
+
+
+def draw_poses(frames, H, W, limb_a, limb_b, peak_x, peak_y, slots, limb_rgb, part_rgb, thickness, radius):
+    """Visualisation operator (hp_draw_oracle.c): frames uint8 [N, Hf, Wf, C] -> frames with the poses drawn.
+
+    peak_x / peak_y: int32 [N, K, cap] on a W x H map; slots: per image an int32 [n_persons, K] array of peak
+    ranks (-1 = part missing); limb_rgb [L, 3], part_rgb [K, 3] uint8."""
+    fr = np.ascontiguousarray(frames, np.uint8)
+    N, Hf, Wf, C = fr.shape
+    la, lb = np.ascontiguousarray(limb_a, np.int32), np.ascontiguousarray(limb_b, np.int32)
+    x, y = np.ascontiguousarray(peak_x, np.int32), np.ascontiguousarray(peak_y, np.int32)
+    K, cap = x.shape[1], x.shape[2]
+    lrgb, prgb = np.ascontiguousarray(limb_rgb, np.uint8), np.ascontiguousarray(part_rgb, np.uint8)
+    assert lrgb.shape == (len(la), 3) and prgb.shape == (K, 3)
+    out = np.empty_like(fr)
+    u8 = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    for n in range(N):
+        sl = np.ascontiguousarray(slots[n], np.int32).reshape(-1, K)
+        lib().hpv_draw(u8(fr[n]), u8(out[n]), Hf, Wf, C, int(H), int(W), K, len(la), _i32(la), _i32(lb), _i32(x[n]),
+                       _i32(y[n]), cap, _i32(sl), len(sl), u8(lrgb), u8(prgb), int(thickness), int(radius))
     return out
 
 
