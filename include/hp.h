@@ -218,6 +218,27 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
                   int Hd, int Wd, int reverse_channels, const float *alpha, const float *beta,
                   void *stream);
 
+/* Visualisation (Section 2.2.1, operator 5: the pose topology is placed onto the original image).
+ * src / dst: device uint8 [N][Hf][Wf][C], interleaved channels, C = 3 or 4 (a fourth channel is
+ * copied unchanged); dst may be src (drawing in place), otherwise the two must not overlap.
+ * peaks / poses: as written by hp_postprocess or hp_assemble for the same N images, peak
+ * coordinates on a W x H map (only peaks->x, peaks->y, peaks->cap, poses->slots, poses->count and
+ * poses->cap are read; counts above cap are clamped).  Rules, all in exact integer arithmetic:
+ *   - a peak at map pixel (x, y) lands on frame pixel (floor((2x+1) Wf / (2W)), floor((2y+1) Hf / (2H)));
+ *   - limb l of a person that holds both its parts covers the pixels within thickness / 2 of the
+ *     segment between the two parts' frame pixels, in colour limb_rgb[l]; a part c the person holds
+ *     covers the pixels within `radius` of its frame pixel, in colour part_rgb[c] (Euclidean
+ *     distances between pixel coordinates, bounds included);
+ *   - painter's order: persons in list order, for each its limbs in table order, then its parts in
+ *     index order; a pixel gets the colour of the last primitive covering it, else the source pixel.
+ * limb_rgb / part_rgb: host arrays of n_limbs x 3 and n_parts x 3 bytes, read before the call
+ * returns.  Frame and map sides up to 16384, N up to 65535, thickness and radius 0..1024.
+ * Allocates nothing; enqueues one kernel on `stream`. */
+int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
+                  const hp_skeleton *skel, const hp_peaks *peaks, const hp_poses *poses,
+                  const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
+                  void *stream);
+
 /* ---- Streaming front with a dynamic batch slot ---------------------------------------------
  * Section 2.2.1 runs the operators asynchronously, a FIFO between each pair; Section 2.2.2 puts a
  * batch slot in front of the GPU operator that collects more input tensors only while the GPU is
@@ -356,7 +377,8 @@ typedef enum {
     HP_K_ASSEMBLE = 8,
     HP_K_LIMB_SMALL = 9,     /* peak ordering + limb scoring + matching in one launch (small capacities) */
     HP_K_PREPROCESS = 10,    /* hp_preprocess */
-    HP_K_COUNT = 11
+    HP_K_DRAW = 11,          /* hp_draw_poses */
+    HP_K_COUNT = 12
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

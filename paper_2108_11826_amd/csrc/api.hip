@@ -337,6 +337,32 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
     return HP_OK;
 }
 
+int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
+                  const hp_skeleton *skel, const hp_peaks *peaks, const hp_poses *poses, const uint8_t *limb_rgb,
+                  const uint8_t *part_rgb, int thickness, int radius, void *stream)
+{
+    if (!src || !dst || !limb_rgb || !part_rgb) return HP_ERR_INVALID_ARG;
+    LimbTable tab;
+    HP_TRY(check_skeleton(skel, tab));
+    if (!peaks || !peaks->x || !peaks->y || peaks->cap <= 0) return HP_ERR_INVALID_ARG;
+    if (!poses || !poses->slots || !poses->count || poses->cap <= 0) return HP_ERR_INVALID_ARG;
+    if (N <= 0 || Hf <= 0 || Wf <= 0 || H <= 0 || W <= 0 || thickness < 0 || radius < 0) return HP_ERR_INVALID_ARG;
+    if (C != 3 && C != 4) return HP_ERR_UNSUPPORTED;
+    if (Hf > 16384 || Wf > 16384 || H > 16384 || W > 16384 || N > 65535 || thickness > 1024 || radius > 1024 ||
+        peaks->cap > HP_MAX_CAP)
+        return HP_ERR_UNSUPPORTED;
+    if (src != dst) {
+        // partial overlap would let one workgroup read what another has already painted
+        const size_t bytes = (size_t)N * Hf * Wf * C;
+        const uintptr_t a = (uintptr_t)src, b = (uintptr_t)dst;
+        if (a < b + bytes && b < a + bytes) return HP_ERR_INVALID_ARG;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_DRAW, launch_draw(src, dst, N, Hf, Wf, C, H, W, tab, skel->n_parts, skel->n_limbs, *peaks, *poses,
+                                     limb_rgb, part_rgb, thickness, radius, s));
+    return HP_OK;
+}
+
 int hp_profile_begin(int max_launches)
 {
     if (max_launches <= 0) return HP_ERR_INVALID_ARG;
@@ -388,6 +414,7 @@ const char *hp_kernel_name(int id)
     case HP_K_LIMB_SMALL: return "limb_small";
     case HP_K_ASSEMBLE: return "assemble";
     case HP_K_PREPROCESS: return "preprocess";
+    case HP_K_DRAW: return "draw";
     default: return "unknown";
     }
 }

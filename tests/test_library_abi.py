@@ -203,3 +203,25 @@ def test_batcher_rejects_bad_calls(L):
     assert L.hp_batcher_next(None, 0, None, None, None) == -1
     assert L.hp_batcher_drive(None, 1, 0, 0, None, None, 0, None, None, None) == -1
     assert L.hp_strerror(-6) != L.hp_strerror(-7) != L.hp_strerror(-8) != b"unknown error"
+
+
+def test_draw_rejects_bad_calls(L):
+    from ctypes import c_uint8
+    sk, prm, pk, cd, cn, ps = descriptors()
+    rgb = (c_uint8 * 96)()
+    a, b = c_void_p(0x100000), c_void_p(0x900000)
+    ok = dict(src=a, dst=b, N=1, Hf=8, Wf=8, C=3, H=8, W=8, skel=byref(sk.c), pk=byref(pk), ps=byref(ps), lrgb=rgb,
+              prgb=rgb, t=2, r=2, stream=None)
+
+    def call(**kw):
+        x = dict(ok)
+        x.update(kw)
+        return L.hp_draw_poses(*[x[k] for k in ("src", "dst", "N", "Hf", "Wf", "C", "H", "W", "skel", "pk", "ps",
+                                                 "lrgb", "prgb", "t", "r", "stream")])
+
+    assert call(src=None) == -1 and call(dst=None) == -1 and call(lrgb=None) == -1 and call(prgb=None) == -1
+    assert call(skel=None) == -1 and call(pk=None) == -1 and call(ps=None) == -1
+    assert call(N=0) == -1 and call(Hf=0) == -1 and call(W=-1) == -1 and call(t=-1) == -1 and call(r=-2) == -1
+    assert call(C=1) == -5 and call(C=5) == -5
+    assert call(Wf=20000) == -5 and call(H=16385) == -5 and call(N=70000) == -5 and call(t=2000) == -5
+    assert call(dst=c_void_p(0x100000 + 50)) == -1          # overlaps the source without being it
