@@ -233,11 +233,15 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
  *     index order; a pixel gets the colour of the last primitive covering it, else the source pixel.
  * limb_rgb / part_rgb: host arrays of n_limbs x 3 and n_parts x 3 bytes, read before the call
  * returns.  Frame and map sides up to 16384, N up to 65535, thickness and radius 0..1024.
- * Allocates nothing; enqueues one kernel on `stream`. */
+ * workspace: device memory of hp_draw_workspace_bytes(N, n_parts, n_limbs, poses->cap, Hf, Wf)
+ * bytes, 256-byte aligned, no need to clear it (it receives the images' primitives in painter's
+ * order and one bit per frame tile); two calls running concurrently must not share it.
+ * Allocates nothing; enqueues two kernels on `stream`. */
+size_t hp_draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf);
 int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
                   const hp_skeleton *skel, const hp_peaks *peaks, const hp_poses *poses,
                   const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
-                  void *stream);
+                  void *workspace, size_t ws_bytes, void *stream);
 
 /* ---- Streaming front with a dynamic batch slot ---------------------------------------------
  * Section 2.2.1 runs the operators asynchronously, a FIFO between each pair; Section 2.2.2 puts a
@@ -377,8 +381,9 @@ typedef enum {
     HP_K_ASSEMBLE = 8,
     HP_K_LIMB_SMALL = 9,     /* peak ordering + limb scoring + matching in one launch (small capacities) */
     HP_K_PREPROCESS = 10,    /* hp_preprocess */
-    HP_K_DRAW = 11,          /* hp_draw_poses */
-    HP_K_COUNT = 12
+    HP_K_DRAW_LIST = 11,     /* hp_draw_poses: the images' primitives listed in painter's order */
+    HP_K_DRAW = 12,          /* hp_draw_poses: the frames painted */
+    HP_K_COUNT = 13
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

@@ -17,11 +17,11 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_draw_poses", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_postprocess", "hp_preprocess", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
-HP_K_COUNT = 12
+HP_K_COUNT = 13
 
 
 class HPError(RuntimeError):
@@ -108,7 +108,9 @@ def lib():
         L.hp_draw_poses.restype = c_int
         L.hp_draw_poses.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
                                     POINTER(_Peaks), POINTER(_Poses), POINTER(ctypes.c_uint8), POINTER(ctypes.c_uint8),
-                                    c_int, c_int, c_void_p]
+                                    c_int, c_int, c_void_p, c_size_t, c_void_p]
+        L.hp_draw_workspace_bytes.restype = c_size_t
+        L.hp_draw_workspace_bytes.argtypes = [c_int] * 6
         L.hp_batcher_create.restype = c_int
         L.hp_batcher_create.argtypes = [c_int, c_int, c_int, POINTER(_Skeleton), POINTER(_Params),
                                         POINTER(_BatcherConfig), POINTER(_Lane), POINTER(c_void_p)]
@@ -341,11 +343,23 @@ def hp_preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False, out=None,
     return out
 
 
-def hp_draw_poses(frames, H, W, skel, buf, limb_rgb, part_rgb, thickness=4, radius=4, out=None):
-    """frames uint8 [N, Hf, Wf, C] on the GPU -> the frames with buf's poses drawn (out may be `frames` itself)."""
+def hp_draw_workspace_bytes(N, K, L, pcap, Hf, Wf):
+    return int(lib().hp_draw_workspace_bytes(int(N), int(K), int(L), int(pcap), int(Hf), int(Wf)))
+
+
+def hp_draw_poses(frames, H, W, skel, buf, limb_rgb, part_rgb, thickness=4, radius=4, out=None, workspace=None):
+    """frames uint8 [N, Hf, Wf, C] on the GPU -> the frames with buf's poses drawn (out may be `frames` itself).
+
+    `workspace` is a uint8 GPU tensor of hp_draw_workspace_bytes(N, K, L, pcap, Hf, Wf) bytes; without one, a tensor kept
+    on `buf` is used (allocated at the first call)."""
     N, Hf, Wf, C = frames.shape
     if out is None:
         out = torch.empty_like(frames)
+    if workspace is None:
+        workspace = getattr(buf, "draw_workspace", None)
+        need = hp_draw_workspace_bytes(N, skel.n_parts, skel.n_limbs, buf.pcap, Hf, Wf)
+        if workspace is None or workspace.numel() < need:
+            workspace = buf.draw_workspace = torch.empty((need,), dtype=torch.uint8, device=frames.device)
     lrgb = np.ascontiguousarray(limb_rgb, np.uint8)
     prgb = np.ascontiguousarray(part_rgb, np.uint8)
     if lrgb.shape != (skel.n_limbs, 3) or prgb.shape != (skel.n_parts, 3):
@@ -353,7 +367,8 @@ def hp_draw_poses(frames, H, W, skel, buf, limb_rgb, part_rgb, thickness=4, radi
     u8 = lambda a: a.ctypes.data_as(POINTER(ctypes.c_uint8))
     _check(lib().hp_draw_poses(_dev(frames, torch.uint8), _dev(out, torch.uint8), N, Hf, Wf, C, int(H), int(W),
                                ctypes.byref(skel.c), ctypes.byref(buf.peaks), ctypes.byref(buf.poses), u8(lrgb), u8(prgb),
-                               int(thickness), int(radius), _stream()), "hp_draw_poses")
+                               int(thickness), int(radius), _dev(workspace, torch.uint8), c_size_t(workspace.numel()),
+                               _stream()), "hp_draw_poses")
     return out
 
 

@@ -337,9 +337,16 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
     return HP_OK;
 }
 
+size_t hp_draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf)
+{
+    if (N <= 0 || K <= 0 || L <= 0 || pcap <= 0 || K > HP_MAX_PARTS || L > HP_MAX_LIMBS) return 0;
+    if (Hf <= 0 || Wf <= 0 || Hf > 16384 || Wf > 16384) return 0;
+    return draw_workspace_bytes(N, K, L, pcap, Hf, Wf);
+}
+
 int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
                   const hp_skeleton *skel, const hp_peaks *peaks, const hp_poses *poses, const uint8_t *limb_rgb,
-                  const uint8_t *part_rgb, int thickness, int radius, void *stream)
+                  const uint8_t *part_rgb, int thickness, int radius, void *workspace, size_t ws_bytes, void *stream)
 {
     if (!src || !dst || !limb_rgb || !part_rgb) return HP_ERR_INVALID_ARG;
     LimbTable tab;
@@ -357,9 +364,13 @@ int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C
         const uintptr_t a = (uintptr_t)src, b = (uintptr_t)dst;
         if (a < b + bytes && b < a + bytes) return HP_ERR_INVALID_ARG;
     }
+    const int K = skel->n_parts, L = skel->n_limbs;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes < draw_workspace_bytes(N, K, L, poses->cap, Hf, Wf))
+        return HP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_DRAW, launch_draw(src, dst, N, Hf, Wf, C, H, W, tab, skel->n_parts, skel->n_limbs, *peaks, *poses,
-                                     limb_rgb, part_rgb, thickness, radius, s));
+    HP_LAUNCH(HP_K_DRAW_LIST, launch_draw_list(N, Hf, Wf, H, W, tab, K, L, *peaks, *poses, thickness, radius, workspace, s));
+    HP_LAUNCH(HP_K_DRAW, launch_draw_tiles(src, dst, N, Hf, Wf, C, H, W, tab, K, L, *peaks, *poses, limb_rgb, part_rgb,
+                                           thickness, radius, workspace, s));
     return HP_OK;
 }
 
@@ -414,6 +425,7 @@ const char *hp_kernel_name(int id)
     case HP_K_LIMB_SMALL: return "limb_small";
     case HP_K_ASSEMBLE: return "assemble";
     case HP_K_PREPROCESS: return "preprocess";
+    case HP_K_DRAW_LIST: return "draw_list";
     case HP_K_DRAW: return "draw";
     default: return "unknown";
     }

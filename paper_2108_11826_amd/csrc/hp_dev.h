@@ -186,11 +186,16 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
 hipError_t launch_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst, int Hd, int Wd,
                              int reverse_channels, const float *alpha, const float *beta, hipStream_t s);
 
-// Visualisation: limbs (capsules) and parts (discs) of every person painted over the frames; limb_rgb / part_rgb
-// are host arrays of L x 3 and K x 3 bytes.
-hipError_t launch_draw(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W, const LimbTable &T,
-                       int K, int L, const hp_peaks &pk, const hp_poses &poses, const uint8_t *limb_rgb,
-                       const uint8_t *part_rgb, int thickness, int radius, hipStream_t s);
+// Visualisation: limbs (capsules) and parts (discs) of every person painted over the frames.  launch_draw_list
+// writes every image's primitives, in painter's order, into the workspace; launch_draw_tiles paints them.
+// limb_rgb / part_rgb are host arrays of L x 3 and K x 3 bytes.
+size_t draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf);
+hipError_t launch_draw_list(int N, int Hf, int Wf, int H, int W, const LimbTable &T, int K, int L, const hp_peaks &pk,
+                            const hp_poses &poses, int thickness, int radius, void *workspace, hipStream_t s);
+hipError_t launch_draw_tiles(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
+                             const LimbTable &T, int K, int L, const hp_peaks &pk, const hp_poses &poses,
+                             const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
+                             const void *workspace, hipStream_t s);
 
 // hp_postprocess on the first N images of outputs and a workspace laid out for N_layout >= N images;
 // check_only: validate the arguments, enqueue nothing.

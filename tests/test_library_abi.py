@@ -210,14 +210,20 @@ def test_draw_rejects_bad_calls(L):
     sk, prm, pk, cd, cn, ps = descriptors()
     rgb = (c_uint8 * 96)()
     a, b = c_void_p(0x100000), c_void_p(0x900000)
+    L.hp_draw_workspace_bytes.restype = ctypes.c_size_t
+    need = L.hp_draw_workspace_bytes(1, 3, 2, 16, 8, 8)
+    assert need > 0 and need % 16 == 0 and L.hp_draw_workspace_bytes(2, 3, 2, 16, 8, 8) > need
+    assert L.hp_draw_workspace_bytes(1, 3, 2, 16, 4096, 4096) > need
+    assert L.hp_draw_workspace_bytes(0, 3, 2, 16, 8, 8) == 0 and L.hp_draw_workspace_bytes(1, 99, 2, 16, 8, 8) == 0
+    assert L.hp_draw_workspace_bytes(1, 3, 2, 16, 0, 8) == 0 and L.hp_draw_workspace_bytes(1, 3, 2, 16, 8, 20000) == 0
     ok = dict(src=a, dst=b, N=1, Hf=8, Wf=8, C=3, H=8, W=8, skel=byref(sk.c), pk=byref(pk), ps=byref(ps), lrgb=rgb,
-              prgb=rgb, t=2, r=2, stream=None)
+              prgb=rgb, t=2, r=2, ws=c_void_p(FAKE), wsb=ctypes.c_size_t(need), stream=None)
 
     def call(**kw):
         x = dict(ok)
         x.update(kw)
         return L.hp_draw_poses(*[x[k] for k in ("src", "dst", "N", "Hf", "Wf", "C", "H", "W", "skel", "pk", "ps",
-                                                 "lrgb", "prgb", "t", "r", "stream")])
+                                                 "lrgb", "prgb", "t", "r", "ws", "wsb", "stream")])
 
     assert call(src=None) == -1 and call(dst=None) == -1 and call(lrgb=None) == -1 and call(prgb=None) == -1
     assert call(skel=None) == -1 and call(pk=None) == -1 and call(ps=None) == -1
@@ -225,3 +231,4 @@ def test_draw_rejects_bad_calls(L):
     assert call(C=1) == -5 and call(C=5) == -5
     assert call(Wf=20000) == -5 and call(H=16385) == -5 and call(N=70000) == -5 and call(t=2000) == -5
     assert call(dst=c_void_p(0x100000 + 50)) == -1          # overlaps the source without being it
+    assert call(ws=None) == -3 and call(ws=c_void_p(FAKE + 16)) == -3 and call(wsb=ctypes.c_size_t(need - 1)) == -3
