@@ -7,29 +7,27 @@
 //
 // Two launches.  k_draw_list, one workgroup per image, walks the person table once and writes the
 // image's primitives, in painter's order, as 16-byte records (end points in frame coordinates, id,
-// and the largest cross product a covered pixel can have) into the workspace.  k_draw_tiles, one
-// workgroup per tile of 64 x 16 pixels, reads the records 256 at a time (coalesced), keeps those
-// whose bounding box and line can meet the tile, packed in order in LDS, and then every wavefront
-// paints one strip of 64 x 4 pixels: 64 lanes test 64 kept records at a time against the strip, the
-// few that can touch it are broadcast from lane to scalar registers, newest first, and each lane
-// decides its four neighbouring pixels with 32-bit integer tests.  Most tiles keep nothing and only
-// copy their pixels.  Crowded places cost a wavefront a walk over one strip's records only, which
-// keeps the longest wavefront short: with larger regions per workgroup the few crowded ones decided
-// the kernel's duration (measured: 2 to 5 times slower).
+// and the largest cross product a covered pixel can have) into the workspace, plus one bit per
+// frame tile that says whether any primitive can touch it.  k_draw_tiles, one workgroup per tile
+// of 64 x 16 pixels, copies untouched tiles and rasterises the others primitive by primitive
+// instead of testing every pixel against every primitive: the records are read 512 at a time
+// (coalesced), those whose bounding box and line can meet the tile are kept in LDS, and each
+// thread then takes (record, row) pairs: the covered pixels of a row are an interval (a capsule
+// is convex) whose ends follow exactly from two integer square roots and four exact integer
+// divisions, and the thread raises the owner word of each pixel in it to (rank of the record,
+// colour id) with an LDS atomic max, which is the painter's order.  A thread finally owns four
+// neighbouring pixels, looks up their owners and writes them once.  Testing the pixels of a strip
+// against every record that touches it (the first version of this kernel) cost 200 instructions
+// per (strip, record) pair for the sixteen or so pixels a thin limb covers there, and that
+// arithmetic, not memory, set the kernel's duration.
 #include <string.h>
 
 #include "hp_dev.h"
 
 namespace hp {
 
-#ifndef HP_DRAW_STRIPS
-#define HP_DRAW_STRIPS 1
-#endif
-constexpr int kStrips = HP_DRAW_STRIPS;       // strips a wavefront paints, one after the other (measured: 1 is best
-                                              // on crowded frames, where the longest wavefront decides)
-constexpr int kStripH = 4;                    // rows of a strip: one per 16 lanes
-constexpr int kTileW = 64, kTileH = kStripH * kStrips * (kBlock / kWave);   // pixels a workgroup paints
-static_assert(kStripH * 16 == kWave && kTileW == 4 * 16, "a lane paints four neighbouring pixels of one row");
+constexpr int kTileW = 64, kTileH = 16;   // pixels a workgroup paints; a thread owns four neighbouring pixels of a row
+static_assert(kTileW * kTileH == 4 * kBlock, "four pixels per thread");
 
 // Per-primitive tables, indexed by id = limb index, or n_limbs + part index.  Passed by value and copied to LDS
 // through constant indices: a kernel argument indexed per lane would be unpacked by long select chains.
@@ -54,10 +52,12 @@ struct DrawRecord {
     int cmax;     // limbs: floor(sqrt(thickness^2 |B - A|^2 / 4)), the largest |(P - A) x (B - A)| of a covered pixel
 };
 
-// Frame pixel that contains the centre of map pixel x.
+// Frame pixel that contains the centre of map pixel x: floor((2x + 1) n_frame / (2 n_map)).  With x inside the map
+// (a peak is; anything else is clamped so that the arithmetic stays in range) the product is below 2^30.
 __device__ __forceinline__ int to_frame(int x, int n_map, int n_frame)
 {
-    return (int)(((long long)(2 * x + 1) * n_frame) / (2LL * n_map));
+    x = min(max(x, 0), n_map - 1);
+    return (int)((unsigned)((2 * x + 1) * n_frame) / (unsigned)(2 * n_map));
 }
 
 // End points are frame coordinates below 16384, packed as x | y << 16.
@@ -86,14 +86,16 @@ __device__ __forceinline__ bool far_from_line(int a, int b, int cmax, int cx2, i
     return abs(cross2) > 2 * cmax + __mul24(ex2, abs(dy)) + __mul24(ey2, abs(dx));
 }
 
-__global__ __launch_bounds__(kBlock) void k_draw_list(const int32_t *__restrict__ peak_x, const int32_t *__restrict__ peak_y,
+constexpr int kListBlock = 1024;   // one workgroup per image walks its persons: as wide as a workgroup gets
+
+__global__ __launch_bounds__(kListBlock) void k_draw_list(const int32_t *__restrict__ peak_x, const int32_t *__restrict__ peak_y,
                                                       const int32_t *__restrict__ slots,
                                                       const int32_t *__restrict__ pose_count, DrawTables tab, DrawParams P,
                                                       DrawRecord *__restrict__ records, int32_t *__restrict__ record_count,
                                                       uint32_t *__restrict__ tile_mask)
 {
     __shared__ uint8_t s_part_a[HP_MAX_LIMBS], s_part_b[HP_MAX_LIMBS];
-    __shared__ int s_scan[kBlock / kWave + 1];
+    __shared__ int s_scan[kListBlock / kWave + 1];
     extern __shared__ uint32_t s_mask[];   // one bit per tile: can any primitive touch it?
     const int n = blockIdx.x, tid = threadIdx.x;
     if (tid == 0) {
@@ -103,13 +105,13 @@ __global__ __launch_bounds__(kBlock) void k_draw_list(const int32_t *__restrict_
             s_part_b[i] = tab.b[i];
         }
     }
-    for (int i = tid; i < P.mask_words; i += kBlock) s_mask[i] = 0;
+    for (int i = tid; i < P.mask_words; i += kListBlock) s_mask[i] = 0;
     __syncthreads();
     const int per_person = P.L + P.K;
     const int items = min(pose_count[n], P.pcap) * per_person;
     DrawRecord *out = records + (size_t)n * P.list_cap;
     int total = 0;
-    for (int base = 0; base < items; base += kBlock) {
+    for (int base = 0; base < items; base += kListBlock) {
         const int q = base + tid;
         bool keep = false;
         DrawRecord rec = {0, 0, 0, 0};
@@ -124,12 +126,8 @@ __global__ __launch_bounds__(kBlock) void k_draw_list(const int32_t *__restrict_
             if (ia >= 0 && ib >= 0 && ia < P.cap && ib < P.cap) {
                 keep = true;
                 const size_t oa = ((size_t)n * P.K + a) * P.cap + ia, ob = ((size_t)n * P.K + b) * P.cap + ib;
-                // a peak of the map lands inside the frame; the clamps only keep the integer geometry
-                // within range should the lists hold anything else
-                const int ax = min(max(to_frame(peak_x[oa], P.W, P.Wf), 0), P.Wf - 1);
-                const int ay = min(max(to_frame(peak_y[oa], P.H, P.Hf), 0), P.Hf - 1);
-                const int bx = min(max(to_frame(peak_x[ob], P.W, P.Wf), 0), P.Wf - 1);
-                const int by = min(max(to_frame(peak_y[ob], P.H, P.Hf), 0), P.Hf - 1);
+                const int ax = to_frame(peak_x[oa], P.W, P.Wf), ay = to_frame(peak_y[oa], P.H, P.Hf);
+                const int bx = to_frame(peak_x[ob], P.W, P.Wf), by = to_frame(peak_y[ob], P.H, P.Hf);
                 rec.a = pack_xy(ax, ay);
                 rec.b = pack_xy(bx, by);
                 if (limb) {
@@ -161,7 +159,74 @@ __global__ __launch_bounds__(kBlock) void k_draw_list(const int32_t *__restrict_
     }
     if (tid == 0) record_count[n] = total;
     __syncthreads();
-    for (int i = tid; i < P.mask_words; i += kBlock) tile_mask[(size_t)n * P.mask_words + i] = s_mask[i];
+    for (int i = tid; i < P.mask_words; i += kListBlock) tile_mask[(size_t)n * P.mask_words + i] = s_mask[i];
+}
+
+// floor(n / d) for d > 0, exact: the quotient of two 32-bit integers is either an integer (then the double
+// division is exact) or at least 1 / d away from one, far more than a double's rounding error.
+__device__ __forceinline__ int floor_div(int n, int d) { return (int)floor((double)n / (double)d); }
+
+// Largest h >= 0 with h * h <= v (v >= 0, below 2^31).
+__device__ __forceinline__ int isqrt(int v)
+{
+    int h = (int)sqrtf((float)v);
+    while (h * h > v) --h;
+    while ((h + 1) * (h + 1) <= v) ++h;
+    return h;
+}
+
+// Pixels of row y covered by a record: the interval [xl, xr] (empty when xl > xr), exact.
+//   part: |x - ax| <= isqrt(radius^2 - (y - ay)^2);
+//   limb: the union of the two end discs (radius^2 -> floor(thickness^2 / 4); a pixel in an end disc is within
+//   thickness / 2 of the segment wherever its projection falls) and of the middle part, 0 < t < L2 and |c| <= cmax
+//   with t = (P - A).(B - A) and c = (P - A) x (B - A), both linear in x.  The capsule is convex, so the union is
+//   one interval: its ends are the smallest left end and the largest right end of the parts present.
+__device__ __forceinline__ void row_interval(const DrawRecord &rec, bool limb, int y, int th2_quarter, int r2,
+                                             int &xl, int &xr)
+{
+    const int ax = px_of(rec.a), ay = py_of(rec.a), bx = px_of(rec.b), by = py_of(rec.b);
+    xl = 1 << 20;
+    xr = -(1 << 20);
+    const int uy = y - ay;
+    const int remA = (limb ? th2_quarter : r2) - uy * uy;
+    if (remA >= 0) {
+        const int h = isqrt(remA);
+        xl = ax - h;
+        xr = ax + h;
+    }
+    if (!limb) return;
+    const int vy = y - by, remB = th2_quarter - vy * vy;
+    if (remB >= 0) {
+        const int h = isqrt(remB);
+        xl = min(xl, bx - h);
+        xr = max(xr, bx + h);
+    }
+    // middle part, in k = x - ax:  -cmax <= k dy - uy dx <= cmax  and  0 < k dx + uy dy < L2
+    const int dx = bx - ax, dy = by - ay, L2 = dx * dx + dy * dy;
+    const int e = uy * dx, g = uy * dy;
+    int lo = -(1 << 20), hi = 1 << 20;
+    if (dy > 0) {
+        lo = max(lo, -floor_div(rec.cmax - e, dy));       // ceil((e - cmax) / dy)
+        hi = min(hi, floor_div(rec.cmax + e, dy));
+    } else if (dy < 0) {
+        lo = max(lo, -floor_div(rec.cmax + e, -dy));      // ceil((-cmax - e) / -dy)
+        hi = min(hi, floor_div(rec.cmax - e, -dy));
+    } else if (abs(e) > rec.cmax) {
+        return;
+    }
+    if (dx > 0) {
+        lo = max(lo, floor_div(-g, dx) + 1);              // k dx > -g
+        hi = min(hi, -floor_div(g - L2, dx) - 1);         // k dx < L2 - g
+    } else if (dx < 0) {
+        lo = max(lo, floor_div(g - L2, -dx) + 1);         // k (-dx) > g - L2
+        hi = min(hi, -floor_div(-g, -dx) - 1);            // k (-dx) < g
+    } else if (g <= 0 || g >= L2) {
+        return;
+    }
+    if (lo <= hi) {
+        xl = min(xl, ax + lo);
+        xr = max(xr, ax + hi);
+    }
 }
 
 template <int C, bool VEC>
@@ -171,15 +236,18 @@ __global__ __launch_bounds__(kBlock) void k_draw_tiles(const uint8_t *src, uint8
                                                        const uint32_t *__restrict__ tile_mask, DrawTables tab,
                                                        DrawParams P)
 {
-    constexpr int kChunk = 2 * kBlock;   // records looked at per round: two per thread, one memory round trip
+    constexpr int kRound = 2 * kBlock;   // records looked at per round: two per thread, one memory round trip
     __shared__ uint32_t s_rgb[HP_MAX_LIMBS + HP_MAX_PARTS];
-    __shared__ int t_a[kChunk], t_b[kChunk], t_id[kChunk], t_cmax[kChunk];
-    __shared__ int s_scan[kBlock / kWave + 1];
+    __shared__ DrawRecord s_rec[kRound];            // records that can meet the tile
+    __shared__ int s_rank[kRound];                  // their ranks in painter's order
+    __shared__ int s_owner[kTileW * kTileH];        // per pixel: (rank + 1) << 7 | id of the last primitive covering it
+    __shared__ int s_kept;
 
     const int n = blockIdx.z;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+    const int tid = threadIdx.x;
     const int tile_x0 = blockIdx.x * kTileW, tile_y0 = blockIdx.y * kTileH;
-    const int x0 = tile_x0 + 4 * (lane & 15);
+    const int x0 = tile_x0 + 4 * (tid & 15), y = tile_y0 + (tid >> 4);   // this thread's four pixels
+    const bool inside = y < P.Hf && x0 < P.Wf;
     const int r2 = P.radius * P.radius;
     // tiles no primitive can touch (most of them) skip the records altogether
     const int tile = blockIdx.y * P.tiles_x + blockIdx.x;
@@ -189,187 +257,115 @@ __global__ __launch_bounds__(kBlock) void k_draw_tiles(const uint8_t *src, uint8
     const DrawRecord *list = records + (size_t)n * P.list_cap;
 
     // this thread's pixels are on their way while the records are looked at
+    const size_t row = ((size_t)n * P.Hf + y) * P.Wf;
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-    uint32_t w[kStrips][4];
-    bool inside[kStrips];
-#pragma unroll
-    for (int i = 0; i < kStrips; ++i) {
-        const int y = tile_y0 + (wv * kStrips + i) * kStripH + (lane >> 4);
-        inside[i] = y < P.Hf && x0 < P.Wf;
-        w[i][0] = w[i][1] = w[i][2] = w[i][3] = 0;
-        if (VEC && inside[i]) {
-            const size_t row = ((size_t)n * P.Hf + y) * P.Wf;
-            if (C == 3) {
-                const uint32_t *s = (const uint32_t *)(src + (row + x0) * 3);
-                w[i][0] = __builtin_nontemporal_load(s);
-                w[i][1] = __builtin_nontemporal_load(s + 1);
-                w[i][2] = __builtin_nontemporal_load(s + 2);
-            } else {
-                const v4u v = __builtin_nontemporal_load((const v4u *)(src + (row + x0) * 4));
-                w[i][0] = v[0];
-                w[i][1] = v[1];
-                w[i][2] = v[2];
-                w[i][3] = v[3];
-            }
-        }
-    }
-    if (count > 0 && tid == 0) {
-        // colours by id; tab is a kernel argument, so the copy goes through constant indices
-#pragma unroll
-        for (int i = 0; i < HP_MAX_LIMBS + HP_MAX_PARTS; ++i) s_rgb[i] = tab.rgb[i];
-    }
-
-    int best[kStrips][4];   // id of the last primitive covering each of the lane's pixels
-#pragma unroll
-    for (int i = 0; i < kStrips; ++i) best[i][0] = best[i][1] = best[i][2] = best[i][3] = -1;
-
-    auto meets_tile = [&](const DrawRecord &rec) {
-        const bool limb = rec.id < P.L;
-        return box_meets(rec.a, rec.b, limb ? P.reach : P.radius, tile_x0, tile_y0, kTileW, kTileH) &&
-               !(limb && far_from_line(rec.a, rec.b, rec.cmax, 2 * tile_x0 + kTileW - 1, 2 * tile_y0 + kTileH - 1,
-                                       kTileW - 1, kTileH - 1));
-    };
-
-    for (int base = 0; base < count; base += kChunk) {
-        // the records that can meet the tile, packed in order
-        const int q0 = base + tid, q1 = base + kBlock + tid;
-        DrawRecord rec0 = {0, 0, 0, 0}, rec1 = {0, 0, 0, 0};
-        if (q0 < count) rec0 = list[q0];
-        if (q1 < count) rec1 = list[q1];
-        const bool keep0 = q0 < count && meets_tile(rec0), keep1 = q1 < count && meets_tile(rec1);
-        int kept0, kept1 = 0, pos1 = 0;
-        const int pos0 = block_flag_scan(keep0, s_scan, kept0);
-        if (base + kBlock < count) pos1 = block_flag_scan(keep1, s_scan, kept1);   // the same for every thread
-        const int kept = kept0 + kept1;
-        if (kept == 0) continue;   // the same for every thread
-        if (keep0) {
-            t_a[pos0] = rec0.a;
-            t_b[pos0] = rec0.b;
-            t_id[pos0] = rec0.id;
-            t_cmax[pos0] = rec0.cmax;
-        }
-        if (keep1) {
-            t_a[kept0 + pos1] = rec1.a;
-            t_b[kept0 + pos1] = rec1.b;
-            t_id[kept0 + pos1] = rec1.id;
-            t_cmax[kept0 + pos1] = rec1.cmax;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < kStrips; ++i) {
-            // One strip of the wavefront: the kept records are walked backwards, 64 at a time.  Every lane tests one
-            // record against the strip; those that can touch it are broadcast (lane to scalar registers), newest first.
-            const int strip_y0 = tile_y0 + (wv * kStrips + i) * kStripH, y = strip_y0 + (lane >> 4);
-            int open = inside[i] ? 0xF : 0;   // pixels this round has not decided yet; a later round overrides an earlier one
-            for (int k0 = (kept - 1) & ~(kWave - 1); k0 >= 0 && __ballot(open != 0); k0 -= kWave) {
-                const int k = k0 + lane;
-                int ea = 0, eb = 0, eid = 0, ecmax = 0;
-                bool touches = false;
-                if (k < kept) {
-                    ea = t_a[k];
-                    eb = t_b[k];
-                    eid = t_id[k];
-                    ecmax = t_cmax[k];
-                    const int reach = eid < P.L ? P.reach : P.radius;
-                    touches = !(strip_y0 + kStripH - 1 < min(py_of(ea), py_of(eb)) - reach ||
-                                strip_y0 > max(py_of(ea), py_of(eb)) + reach) &&
-                              !(eid < P.L && far_from_line(ea, eb, ecmax, 2 * tile_x0 + kTileW - 1,
-                                                           2 * strip_y0 + kStripH - 1, kTileW - 1, kStripH - 1));
-                }
-                unsigned long long m = __ballot(touches);
-                while (m) {
-                    const int from_lane = 63 - __builtin_clzll(m);
-                    m &= ~(1ull << from_lane);
-                    const int a = __builtin_amdgcn_readlane(ea, from_lane), b = __builtin_amdgcn_readlane(eb, from_lane);
-                    const int cid = __builtin_amdgcn_readlane(eid, from_lane);
-                    const int cmax = __builtin_amdgcn_readlane(ecmax, from_lane);
-                    const int ax = px_of(a), ay = py_of(a), bx = px_of(b), by = py_of(b);
-                    const bool limb = cid < P.L;
-                    const int reach = limb ? P.reach : P.radius;
-                    // the lane's four pixels
-                    if (!open || x0 + 3 < min(ax, bx) - reach || x0 > max(ax, bx) + reach) continue;
-                    const int ux = x0 - ax, uy = y - ay;
-                    // squared distances of the lane's first pixel to the end points; pixel j adds j (2 u + j)
-                    const int dA = __mul24(ux, ux) + __mul24(uy, uy);
-                    if (limb) {
-                        // exact, in 32 bits: t = (P - A).(B - A) selects an end cap or the middle, where the pixel is
-                        // inside when |(P - A) x (B - A)| <= cmax
-                        const int dx = bx - ax, dy = by - ay, L2 = __mul24(dx, dx) + __mul24(dy, dy);
-                        const int vx = x0 - bx, vy = y - by;
-                        const int dB = __mul24(vx, vx) + __mul24(vy, vy);
-                        const int t0 = __mul24(ux, dx) + __mul24(uy, dy), c0 = __mul24(ux, dy) - __mul24(uy, dx);
-                        if (abs(2 * c0 + 3 * dy) > 2 * cmax + 3 * abs(dy) && t0 > 0 && t0 + 3 * dx > 0 && t0 < L2 &&
-                            t0 + 3 * dx < L2)
-                            continue;   // all four lie beside the middle part and too far from the line
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int t = t0 + j * dx, c = c0 + j * dy;
-                            const bool in = (t <= 0) & (dA + j * (2 * ux + j) <= P.th2_quarter) |
-                                            (t >= L2) & (dB + j * (2 * vx + j) <= P.th2_quarter) |
-                                            (t > 0) & (t < L2) & (abs(c) <= cmax);
-                            const int take = (int)in & (open >> j);   // bit 0: covered and not decided yet
-                            best[i][j] = (take & 1) ? cid : best[i][j];
-                            open &= ~((take & 1) << j);
-                        }
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int take = (int)(dA + j * (2 * ux + j) <= r2) & (open >> j);
-                            best[i][j] = (take & 1) ? cid : best[i][j];
-                            open &= ~((take & 1) << j);
-                        }
-                    }
-                }
-            }
-        }
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int i = 0; i < kStrips; ++i) {
-        if (!inside[i]) continue;
-        const int y = tile_y0 + (wv * kStrips + i) * kStripH + (lane >> 4);
-        const size_t row = ((size_t)n * P.Hf + y) * P.Wf;
-        if (VEC) {
-            // four whole pixels: 12 or 16 bytes at a 4-byte (C = 3) or 16-byte (C = 4) aligned address
-            if (C == 3) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (best[i][j] < 0) continue;
-                    const uint32_t rgb = s_rgb[best[i][j]];
-#pragma unroll
-                    for (int ch = 0; ch < 3; ++ch) {
-                        const int byte = 3 * j + ch;
-                        w[i][byte >> 2] = (w[i][byte >> 2] & ~(0xFFu << (8 * (byte & 3)))) |
-                                          (((rgb >> (8 * ch)) & 0xFFu) << (8 * (byte & 3)));
-                    }
-                }
-                uint32_t *d = (uint32_t *)(dst + (row + x0) * 3);
-                __builtin_nontemporal_store(w[i][0], d);
-                __builtin_nontemporal_store(w[i][1], d + 1);
-                __builtin_nontemporal_store(w[i][2], d + 2);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (best[i][j] >= 0) w[i][j] = (w[i][j] & 0xFF000000u) | s_rgb[best[i][j]];
-                v4u v = {w[i][0], w[i][1], w[i][2], w[i][3]};
-                __builtin_nontemporal_store(v, (v4u *)(dst + (row + x0) * 4));
-            }
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (VEC && inside) {
+        if (C == 3) {
+            const uint32_t *s = (const uint32_t *)(src + (row + x0) * 3);
+            w[0] = __builtin_nontemporal_load(s);
+            w[1] = __builtin_nontemporal_load(s + 1);
+            w[2] = __builtin_nontemporal_load(s + 2);
         } else {
-            for (int j = 0; j < 4 && x0 + j < P.Wf; ++j) {
-                const uint8_t *s = src + (row + x0 + j) * C;
-                uint8_t *d = dst + (row + x0 + j) * C;
-                uint8_t v[C];
+            const v4u v = __builtin_nontemporal_load((const v4u *)(src + (row + x0) * 4));
+            w[0] = v[0];
+            w[1] = v[1];
+            w[2] = v[2];
+            w[3] = v[3];
+        }
+    }
+
+    if (count > 0) {   // the same for every thread
+        if (tid == 0) {
+            // colours by id; tab is a kernel argument, so the copy goes through constant indices
 #pragma unroll
-                for (int ch = 0; ch < C; ++ch) v[ch] = s[ch];
-                if (best[i][j] >= 0) {
-                    const uint32_t rgb = s_rgb[best[i][j]];
+            for (int i = 0; i < HP_MAX_LIMBS + HP_MAX_PARTS; ++i) s_rgb[i] = tab.rgb[i];
+        }
 #pragma unroll
-                    for (int ch = 0; ch < 3; ++ch) v[ch] = (uint8_t)(rgb >> (8 * ch));
+        for (int j = 0; j < 4; ++j) s_owner[4 * tid + j] = 0;
+        for (int base = 0; base < count; base += kRound) {
+            if (tid == 0) s_kept = 0;
+            __syncthreads();
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int q = base + half * kBlock + tid;
+                if (q < count) {
+                    const DrawRecord rec = list[q];
+                    const bool limb = rec.id < P.L;
+                    if (box_meets(rec.a, rec.b, limb ? P.reach : P.radius, tile_x0, tile_y0, kTileW, kTileH) &&
+                        !(limb && far_from_line(rec.a, rec.b, rec.cmax, 2 * tile_x0 + kTileW - 1,
+                                                2 * tile_y0 + kTileH - 1, kTileW - 1, kTileH - 1))) {
+                        const int pos = atomicAdd(&s_kept, 1);
+                        s_rec[pos] = rec;
+                        s_rank[pos] = q;
+                    }
                 }
-#pragma unroll
-                for (int ch = 0; ch < C; ++ch) d[ch] = v[ch];
             }
+            __syncthreads();
+            // (record, row) pairs: the covered interval of the row, clipped to the tile, raises the owners
+            const int pairs = s_kept * kTileH;
+            for (int task = tid; task < pairs; task += kBlock) {
+                const int k = task / kTileH, r = task - k * kTileH;
+                const DrawRecord rec = s_rec[k];
+                int xl, xr;
+                row_interval(rec, rec.id < P.L, tile_y0 + r, P.th2_quarter, r2, xl, xr);
+                xl = max(xl, tile_x0);
+                xr = min(xr, tile_x0 + kTileW - 1);
+                const int value = ((s_rank[k] + 1) << 7) | rec.id;
+                for (int x = xl; x <= xr; ++x) atomicMax(&s_owner[r * kTileW + x - tile_x0], value);
+            }
+            __syncthreads();
+        }
+    }
+
+    if (!inside) return;
+    int best[4] = {-1, -1, -1, -1};   // colour id per pixel
+    if (count > 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int o = s_owner[4 * tid + j];
+            best[j] = o ? (o & 127) : -1;
+        }
+    }
+    if (VEC) {
+        // four whole pixels: 12 or 16 bytes at a 4-byte (C = 3) or 16-byte (C = 4) aligned address
+        if (C == 3) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (best[j] < 0) continue;
+                const uint32_t rgb = s_rgb[best[j]];
+#pragma unroll
+                for (int ch = 0; ch < 3; ++ch) {
+                    const int byte = 3 * j + ch;
+                    w[byte >> 2] = (w[byte >> 2] & ~(0xFFu << (8 * (byte & 3)))) |
+                                   (((rgb >> (8 * ch)) & 0xFFu) << (8 * (byte & 3)));
+                }
+            }
+            uint32_t *d = (uint32_t *)(dst + (row + x0) * 3);
+            __builtin_nontemporal_store(w[0], d);
+            __builtin_nontemporal_store(w[1], d + 1);
+            __builtin_nontemporal_store(w[2], d + 2);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (best[j] >= 0) w[j] = (w[j] & 0xFF000000u) | s_rgb[best[j]];
+            v4u v = {w[0], w[1], w[2], w[3]};
+            __builtin_nontemporal_store(v, (v4u *)(dst + (row + x0) * 4));
+        }
+    } else {
+        for (int j = 0; j < 4 && x0 + j < P.Wf; ++j) {
+            const uint8_t *s = src + (row + x0 + j) * C;
+            uint8_t *d = dst + (row + x0 + j) * C;
+            uint8_t v[C];
+#pragma unroll
+            for (int ch = 0; ch < C; ++ch) v[ch] = s[ch];
+            if (best[j] >= 0) {
+                const uint32_t rgb = s_rgb[best[j]];
+#pragma unroll
+                for (int ch = 0; ch < 3; ++ch) v[ch] = (uint8_t)(rgb >> (8 * ch));
+            }
+#pragma unroll
+            for (int ch = 0; ch < C; ++ch) d[ch] = v[ch];
         }
     }
 }
@@ -425,7 +421,7 @@ hipError_t launch_draw_list(int N, int Hf, int Wf, int H, int W, const LimbTable
     DrawParams P;
     const uint8_t none[3 * (HP_MAX_LIMBS + HP_MAX_PARTS)] = {0};   // the list holds no colours
     draw_setup(Hf, Wf, H, W, T, K, L, pk, poses, none, none, thickness, radius, tab, P);
-    HP_KERNEL(k_draw_list, dim3(N), dim3(kBlock), P.mask_words * sizeof(uint32_t), s, pk.x, pk.y, poses.slots, poses.count, tab, P,
+    HP_KERNEL(k_draw_list, dim3(N), dim3(kListBlock), P.mask_words * sizeof(uint32_t), s, pk.x, pk.y, poses.slots, poses.count, tab, P,
               records_of(workspace, N, P.mask_words), (int32_t *)workspace, mask_of(workspace, N));
     return hipGetLastError();
 }
