@@ -286,6 +286,46 @@ def main():
                   "parity_with_oracle": pre_ok}
     del pre_src, pre_dst
 
+    # the operator after post-processing (poses drawn on the original frames), on the same 64 frames of the benchmark
+    # video's size, with the poses of this workload's batch repeated
+    reps = pre_frames // N
+    vbuf = hp.Buffers(reps * N, K, L, h, w, cap, ccap, pcap, dev)
+    hp.hp_postprocess(cm.repeat(reps, 1, 1, 1), paf.repeat(reps, 1, 1, 1), skel, prm, vbuf)
+    vis_src = torch.randint(0, 256, (reps * N, 360, 640, 3), dtype=torch.uint8, device=dev)
+    vis_dst = torch.empty_like(vis_src)
+    vrng = np.random.default_rng(7)
+    limb_rgb, part_rgb = vrng.integers(0, 256, (L, 3), dtype=np.uint8), vrng.integers(0, 256, (K, 3), dtype=np.uint8)
+    for _ in range(3):
+        hp.hp_draw_poses(vis_src, cfg.H, cfg.W, skel, vbuf, limb_rgb, part_rgb, 4, 4, out=vis_dst)
+    torch.cuda.synchronize()
+    hp.hp_profile_begin(64)
+    for _ in range(20):
+        hp.hp_draw_poses(vis_src, cfg.H, cfg.W, skel, vbuf, limb_rgb, part_rgb, 4, 4, out=vis_dst)
+    torch.cuda.synchronize()
+    pr = hp.hp_profile_end()
+    list_us, tiles_us = 1e3 * pr["draw_list"][0] / pr["draw_list"][1], 1e3 * pr["draw"][0] / pr["draw"][1]
+    vis_bytes = 2 * vis_src.numel()
+    vpeaks, _ = vbuf.host_peaks()
+    vposes, _ = vbuf.host_poses()
+    vpx, vpy = np.zeros((1, K, cap), np.int32), np.zeros((1, K, cap), np.int32)
+    for c in range(K):
+        vpx[0, c, :len(vpeaks[N - 1][c][0])], vpy[0, c, :len(vpeaks[N - 1][c][1])] = vpeaks[N - 1][c][0], vpeaks[N - 1][c][1]
+    vis_ok = bool(np.array_equal(vis_dst[N - 1].cpu().numpy(),
+                                 oracle.draw_poses(vis_src[N - 1:N].cpu().numpy(), cfg.H, cfg.W, sk.limb_a, sk.limb_b, vpx, vpy,
+                                                   [vposes[N - 1][0]], limb_rgb, part_rgb, 4, 4)[0]))
+    parity = parity and vis_ok
+    visualise = {"kernel": "k_draw_list + k_draw_tiles (hp_draw_poses: the batch's poses drawn on 640x360 8-bit frames, "
+                           "thickness 4, radius 4)",
+                 "frames_per_launch": reps * N, "persons_per_frame": round(float(vbuf.pose_count.float().mean()), 1),
+                 "us_per_call": round(list_us + tiles_us, 2), "us_list": round(list_us, 2), "us_tiles": round(tiles_us, 2),
+                 "frames_per_s": round(reps * N / ((list_us + tiles_us) * 1e-6), 1),
+                 "roofline": {"kernel": "k_draw_tiles", "bound": "hbm", "achieved": round(vis_bytes / (tiles_us * 1e-6) / 1e9, 1),
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": round(vis_bytes / (tiles_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                              "bytes_per_launch": vis_bytes},
+                 "parity_with_oracle": vis_ok}
+    del vis_src, vis_dst, vbuf
+
     # the streaming front: frames arrive one at a time, the batch slot grows only while batches are running
     streaming = None if args.no_streaming else {
         "what": "hp_batcher_* (dynamic batch slot in front of hp_postprocess, Section 2.2.2): frames of this workload handed "
@@ -336,6 +376,7 @@ def main():
         "roofline": roofline, "roofline_fused": roofline_fused, "roofline_nms_hi": roofline_nms_hi,
         "roofline_scoring": roofline_scoring,
         "preprocess": preprocess,
+        "visualise": visualise,
         "streaming": streaming,
         "cpu_baseline": cpu,
     }
