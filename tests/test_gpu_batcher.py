@@ -248,3 +248,62 @@ def test_load_generator(copy):
         assert r.submit(tag)
         assert r.take()["n_frames"] == 1
     r.close()
+
+
+def test_producer_and_consumer_threads_with_random_pauses():
+    # two host threads, as the front is meant to be used: one hands frames in (copied or written in place, at random
+    # paces, flushing now and then), one takes batches, checks every frame against the oracle and releases lanes late
+    import threading
+    import time
+    m = hp()
+    r = Rig(SMALL3, n_lanes=4, max_batch=5, depth=2)
+    n_frames = 400
+    rng = np.random.default_rng(3)
+    pauses = rng.choice([0.0, 0.0, 0.0, 1e-4, 1e-3], n_frames)
+    in_place = rng.random(n_frames) < 0.3
+    errors = []
+
+    def produce():
+        try:
+            stream = torch.cuda.Stream()
+            for tag in range(n_frames):
+                if pauses[tag]:
+                    time.sleep(pauses[tag])
+                if in_place[tag]:
+                    place = None
+                    while place is None:
+                        place = m.hp_batcher_acquire(r.b, timeout_ms=50)
+                    lane, idx = r.lanes.slot_of(place[0])
+                    with torch.cuda.stream(stream):
+                        r.lanes.cm[lane][idx].copy_(r.cm[tag % r.n_img], non_blocking=True)
+                        r.lanes.paf[lane][idx].copy_(r.paf[tag % r.n_img], non_blocking=True)
+                    m.hp_batcher_commit(r.b, tag, producer_stream=stream, ready=False)
+                else:
+                    while not r.submit(tag, timeout_ms=50, ready=True):
+                        pass
+                if tag % 37 == 36:
+                    m.hp_batcher_flush(r.b)
+            m.hp_batcher_flush(r.b)
+        except Exception as e:      # surfaced by the main thread
+            errors.append(e)
+
+    t = threading.Thread(target=produce)
+    t.start()
+    deadline = time.time() + 60
+    held = []
+    while len(r.seen) < n_frames and time.time() < deadline and not errors:
+        info = r.take(timeout_ms=200, release=False)
+        if info is None:
+            continue
+        held.append(info["lane"])
+        if len(held) > 1 or rng.random() < 0.5:      # keep a lane for a while now and then
+            for lane in held:
+                m.hp_batcher_release(r.b, lane)
+            held = []
+    for lane in held:
+        m.hp_batcher_release(r.b, lane)
+    t.join(timeout=30)
+    assert not errors, errors
+    assert [tag for tag, _ in r.seen] == list(range(n_frames))
+    assert max(r.sizes) <= 5 and sum(r.sizes) == n_frames
+    r.close()
