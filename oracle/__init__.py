@@ -22,6 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hp_oracle.c")
 _SRC_PRE = os.path.join(_HERE, "hp_pre_oracle.c")
 _SRC_DRAW = os.path.join(_HERE, "hp_draw_oracle.c")
+_SRC_SMOOTH = os.path.join(_HERE, "hp_smooth_oracle.c")
 
 
 def _cpu_has_fma():
@@ -40,10 +41,10 @@ def build(force=False):
     out = []
     for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
         so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
-        newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_PRE), os.path.getmtime(_SRC_DRAW))
+        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH))
         if force or not os.path.exists(so) or os.path.getmtime(so) < newest:
             cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, "-o", so, "-lm"]
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
     return out
@@ -85,6 +86,8 @@ def lib():
         u8p = ctypes.POINTER(ctypes.c_uint8)
         L.hpq_preprocess.restype = None
         L.hpq_preprocess.argtypes = [u8p, ci, ci, ci, ci, ci, ci, ci, f32p, f32p, f32p]
+        L.hps_smooth.restype = ci
+        L.hps_smooth.argtypes = [f32p, f32p, ci, ci, ci, f32p, ci]
         L.hpv_in_capsule.restype = ci
         L.hpv_in_capsule.argtypes = [ci] * 7
         L.hpv_in_disc.restype = ci
@@ -133,6 +136,18 @@ def preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False):
     out = np.empty((N, C, Hd, Wd), np.float32)
     lib().hpq_preprocess(im.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), N, Hs, Ws, C, int(Hd), int(Wd),
                          1 if reverse_channels else 0, _f32(al), _f32(be), _f32(out))
+    return out
+
+
+def smooth(maps, taps):
+    """Separable correlation of fp32 maps [..., H, W] with an odd-length tap vector, edges repeated (hp_smooth_oracle.c)."""
+    m = np.ascontiguousarray(maps, np.float32)
+    t = np.ascontiguousarray(taps, np.float32)
+    assert t.ndim == 1 and len(t) % 2 == 1
+    H, W = m.shape[-2:]
+    out = np.empty_like(m)
+    rc = lib().hps_smooth(_f32(m), _f32(out), int(np.prod(m.shape[:-2], dtype=np.int64)), H, W, _f32(t), len(t))
+    assert rc == 0
     return out
 
 

@@ -229,3 +229,11 @@ def generate(cfg: SynthConfig, images=None) -> SynthBatch:
         paf[k] = p.astype(dt)
         people.append(pp)
     return SynthBatch(cfg, cm, paf, people)
+
+
+def gaussian_taps(sigma, radius):
+    """2 * radius + 1 samples of a Gaussian of standard deviation `sigma` (pixels), normalised to sum 1 in float64 and
+    rounded to fp32: the tap vector handed to the smoothing step by the tests and the benchmark (an input, like the maps)."""
+    k = np.arange(-radius, radius + 1, dtype=np.float64)
+    t = np.exp(-k * k / (2.0 * sigma * sigma))
+    return (t / t.sum()).astype(np.float32)
