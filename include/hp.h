@@ -69,7 +69,8 @@ enum {
     HP_MAX_LIMBS = 64,
     HP_MAX_CAP = 16384,    /* largest hp_peaks.cap */
     HP_MAX_CCAP = 1 << 20, /* largest candidate capacity */
-    HP_MAX_SAMPLES = 64
+    HP_MAX_SAMPLES = 64,
+    HP_MAX_TAPS = 65       /* longest tap vector of hp_smooth */
 };
 
 /* Skeleton: limb l joins part limb_a[l] to part limb_b[l] and owns PAF channels
@@ -151,6 +152,19 @@ int hp_resize(const void *src_lo, hp_dtype dt, int N, int C, int h, int w, int s
 int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
                   const hp_peaks *peaks, void *workspace, size_t ws_bytes,
                   int32_t *status, void *stream);
+
+/* Optional smoothing of materialised hi-res confidence maps before hp_find_peaks (the paper gives
+ * no arithmetic for the operator; implementations of the PAF family, Section 2.3, commonly smooth
+ * the upsampled maps with a small Gaussian first).  Channels 0..C-1 of every image are correlated
+ * with the tap vector along x and then along y, the edge pixel repeated beyond the borders:
+ *   t[y][x]   = sum_i taps[i] * src[y][clamp(x + i - r)]
+ *   dst[y][x] = sum_j taps[j] * t[clamp(y + j - r)][x],      r = (n_taps - 1) / 2,
+ * in fp32, each sum accumulated from 0 in ascending tap order with one fused multiply-add per
+ * tap.  src_hi, dst_hi: device fp32 [N][C_mem][H][W] (channels C..C_mem-1 of dst_hi are left
+ * untouched; the two tensors must not overlap); taps: DEVICE array of n_taps floats, n_taps odd,
+ * 1..HP_MAX_TAPS.  Allocates nothing; enqueues one kernel per 65535 planes on `stream`. */
+int hp_smooth(const float *src_hi, float *dst_hi, int N, int C, int C_mem, int H, int W,
+              const float *taps, int n_taps, void *stream);
 
 /* Limb scoring on materialised hi-res PAFs (Section 2.3, PAF family).  For
  * limb l = (a, b) and every pair (i in peaks[a], j in peaks[b]) with distinct
@@ -383,7 +397,8 @@ typedef enum {
     HP_K_PREPROCESS = 10,    /* hp_preprocess */
     HP_K_DRAW_LIST = 11,     /* hp_draw_poses: the images' primitives listed in painter's order */
     HP_K_DRAW = 12,          /* hp_draw_poses: the frames painted */
-    HP_K_COUNT = 13
+    HP_K_SMOOTH = 13,        /* hp_smooth */
+    HP_K_COUNT = 14
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

@@ -17,11 +17,11 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
-HP_K_COUNT = 13
+HP_K_COUNT = 14
 
 
 class HPError(RuntimeError):
@@ -105,6 +105,8 @@ def lib():
         L.hp_preprocess.restype = c_int
         L.hp_preprocess.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int,
                                     POINTER(c_float), POINTER(c_float), c_void_p]
+        L.hp_smooth.restype = c_int
+        L.hp_smooth.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_void_p]
         L.hp_draw_poses.restype = c_int
         L.hp_draw_poses.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
                                     POINTER(_Peaks), POINTER(_Poses), POINTER(ctypes.c_uint8), POINTER(ctypes.c_uint8),
@@ -340,6 +342,18 @@ def hp_preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False, out=None,
     be = (c_float * C)(*np.broadcast_to(np.asarray(beta, np.float32), (C,)).tolist())
     _check(lib().hp_preprocess(_dev(images, torch.uint8), N, Hs, Ws, C, _dtype_code(out), _dev(out), int(Hd), int(Wd),
                                1 if reverse_channels else 0, al, be, _stream()), "hp_preprocess")
+    return out
+
+
+def hp_smooth(maps_hi, taps, channels=None, out=None):
+    """maps_hi fp32 [N, C_mem, H, W] on the GPU -> the first `channels` channels (default: all) smoothed with `taps`
+    (a 1-D fp32 GPU tensor of odd length); other channels of `out` are left as they are."""
+    N, C_mem, H, W = maps_hi.shape
+    C = C_mem if channels is None else int(channels)
+    if out is None:
+        out = torch.empty_like(maps_hi)
+    _check(lib().hp_smooth(_dev(maps_hi, torch.float32), _dev(out, torch.float32), N, C, C_mem, H, W,
+                           _dev(taps, torch.float32), int(taps.numel()), _stream()), "hp_smooth")
     return out
 
 

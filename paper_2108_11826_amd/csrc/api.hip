@@ -337,6 +337,23 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
     return HP_OK;
 }
 
+int hp_smooth(const float *src_hi, float *dst_hi, int N, int C, int C_mem, int H, int W, const float *taps, int n_taps,
+              void *stream)
+{
+    if (!src_hi || !dst_hi || !taps) return HP_ERR_INVALID_ARG;
+    if (N <= 0 || C <= 0 || C_mem < C || H <= 0 || W <= 0 || n_taps <= 0 || (n_taps & 1) == 0) return HP_ERR_INVALID_ARG;
+    if (n_taps > HP_MAX_TAPS || C > 65535 || (long long)H * W >= (1LL << 31)) return HP_ERR_UNSUPPORTED;
+    {
+        // the filter reads neighbours that another workgroup may already have replaced: no smoothing in place
+        const size_t bytes = sizeof(float) * (size_t)N * C_mem * H * W;
+        const uintptr_t a = (uintptr_t)src_hi, b = (uintptr_t)dst_hi;
+        if (a < b + bytes && b < a + bytes) return HP_ERR_INVALID_ARG;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_SMOOTH, launch_smooth(src_hi, dst_hi, N, C, C_mem, H, W, taps, n_taps, s));
+    return HP_OK;
+}
+
 size_t hp_draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf)
 {
     if (N <= 0 || K <= 0 || L <= 0 || pcap <= 0 || K > HP_MAX_PARTS || L > HP_MAX_LIMBS) return 0;
@@ -427,6 +444,7 @@ const char *hp_kernel_name(int id)
     case HP_K_PREPROCESS: return "preprocess";
     case HP_K_DRAW_LIST: return "draw_list";
     case HP_K_DRAW: return "draw";
+    case HP_K_SMOOTH: return "smooth";
     default: return "unknown";
     }
 }

@@ -197,6 +197,10 @@ hipError_t launch_draw_tiles(const uint8_t *src, uint8_t *dst, int N, int Hf, in
                              const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
                              const void *workspace, hipStream_t s);
 
+// Separable smoothing of channels [0, C) of fp32 maps [N][C_mem][H][W]; taps is a device array of n_taps (odd) floats.
+hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, int H, int W, const float *taps,
+                         int n_taps, hipStream_t s);
+
 // hp_postprocess on the first N images of outputs and a workspace laid out for N_layout >= N images;
 // check_only: validate the arguments, enqueue nothing.
 int postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int N_layout, int h, int w,

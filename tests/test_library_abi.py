@@ -232,3 +232,19 @@ def test_draw_rejects_bad_calls(L):
     assert call(Wf=20000) == -5 and call(H=16385) == -5 and call(N=70000) == -5 and call(t=2000) == -5
     assert call(dst=c_void_p(0x100000 + 50)) == -1          # overlaps the source without being it
     assert call(ws=None) == -3 and call(ws=c_void_p(FAKE + 16)) == -3 and call(wsb=ctypes.c_size_t(need - 1)) == -3
+
+
+def test_smooth_rejects_bad_calls(L):
+    a, b, t = c_void_p(0x100000), c_void_p(0x9000000), c_void_p(0x2000)
+    ok = dict(src=a, dst=b, N=1, C=2, C_mem=3, H=16, W=16, taps=t, n=5, stream=None)
+
+    def call(**kw):
+        x = dict(ok)
+        x.update(kw)
+        return L.hp_smooth(*[x[k] for k in ("src", "dst", "N", "C", "C_mem", "H", "W", "taps", "n", "stream")])
+
+    assert call(src=None) == -1 and call(dst=None) == -1 and call(taps=None) == -1
+    assert call(N=0) == -1 and call(C=0) == -1 and call(C_mem=1) == -1 and call(H=0) == -1 and call(W=-4) == -1
+    assert call(n=0) == -1 and call(n=4) == -1             # the tap vector has odd length
+    assert call(n=67) == -5
+    assert call(dst=a) == -1 and call(dst=c_void_p(0x100000 + 64)) == -1      # no smoothing in place
