@@ -286,6 +286,35 @@ def main():
                   "parity_with_oracle": pre_ok}
     del pre_src, pre_dst
 
+    # the optional smoothing of the upsampled confidence maps (a 17-tap sampled Gaussian, sigma 3) on this workload's maps
+    from synth import gaussian_taps
+    taps_np = gaussian_taps(3.0, 8)
+    taps_dev = torch.from_numpy(taps_np).to(dev)
+    hp.hp_resize(cm, cm_hi)
+    sm_dst = torch.empty_like(cm_hi)
+    for _ in range(3):
+        hp.hp_smooth(cm_hi, taps_dev, channels=K, out=sm_dst)
+    torch.cuda.synchronize()
+    hp.hp_profile_begin(64)
+    for _ in range(20):
+        hp.hp_smooth(cm_hi, taps_dev, channels=K, out=sm_dst)
+    torch.cuda.synchronize()
+    ms, nl = hp.hp_profile_end()["smooth"]
+    sm_us = 1e3 * ms / nl
+    sm_px = N * K * cfg.H * cfg.W
+    sm_ok = bool(np.array_equal(sm_dst[N - 1, K - 1].cpu().numpy(),
+                                oracle.smooth(oracle.resize(batch.cm[N - 1, K - 1], 8), taps_np)))
+    parity = parity and sm_ok
+    sm_fma = sm_px * len(taps_np) * (1 + (64 + len(taps_np) - 1) / 64)
+    smooth = {"kernel": "k_smooth (hp_smooth: separable %d-tap smoothing of the %d part maps per image, %dx%d)" % (len(taps_np), K, cfg.W, cfg.H),
+              "us_per_launch": round(sm_us, 2),
+              "roofline": {"bound": "hbm", "achieved": round(8 * sm_px / (sm_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": round(8 * sm_px / (sm_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "bytes_per_launch": 8 * sm_px},
+              "alu": {"achieved": round(sm_fma / (sm_us * 1e-6) / 1e12, 2), "peak": round(ALU_PEAK_TLANEOPS, 1), "unit": "Tfma/s",
+                      "frac": round(sm_fma / (sm_us * 1e-6) / 1e12 / ALU_PEAK_TLANEOPS, 4)},
+              "parity_with_oracle": sm_ok}
+    del sm_dst
+
     # the operator after post-processing (poses drawn on the original frames), on the same 64 frames of the benchmark
     # video's size, with the poses of this workload's batch repeated
     reps = pre_frames // N
@@ -376,6 +405,7 @@ def main():
         "roofline": roofline, "roofline_fused": roofline_fused, "roofline_nms_hi": roofline_nms_hi,
         "roofline_scoring": roofline_scoring,
         "preprocess": preprocess,
+        "smooth": smooth,
         "visualise": visualise,
         "streaming": streaming,
         "cpu_baseline": cpu,

@@ -5,28 +5,40 @@
 //
 // One workgroup produces a tile of 64 x 64 outputs in one launch, the horizontally filtered rows
 // living only in LDS.  Horizontal pass: the tile's source rows (64 + 2r of them, 64 + 2r wide) are
-// staged 16 at a time, one coalesced row per wavefront load; a thread filters four neighbouring
+// staged in LDS, all at once when they fit 32 KB (up to 25 taps), so that every load of the tile is
+// in flight together, one coalesced row per wavefront load; a thread filters four neighbouring
 // outputs of a row from a sliding window held in registers (two 16-byte LDS reads per four taps,
 // sixteen multiply-adds).  Vertical pass: a thread walks down one column of the filtered rows,
 // four outputs at a time, with the same window scheme, and stores rows 256 bytes wide.  With 17
-// taps that is 38 multiply-adds and 8 bytes of memory traffic per output pixel: the kernel sits
-// near the balance of the vector ALUs and HBM.
+// taps that is 38 multiply-adds and 8 bytes of memory traffic per output pixel, which would put the
+// kernel near the balance of the vector ALUs and HBM; measured, it reaches a fifth of either: with
+// one phase switched off at a time, loading, the horizontal and the vertical pass each take a
+// quarter to a third of the time and hardly overlap, the three workgroups a compute unit holds
+// (46 KB of LDS each) being too few to hide one another's phases.
+#include <algorithm>
+
 #include "hp_dev.h"
 
 namespace hp {
 
-constexpr int kSmoothTile = 64;      // outputs per tile side
-constexpr int kSmoothStage = 16;     // source rows staged at a time: 16 rows x 16 threads x 4 outputs
+constexpr int kSmoothTile = 64;      // outputs per tile row: 16 threads x 4 (horizontal pass), 64 threads (vertical pass)
+constexpr int kSmoothTileH = 64;     // output rows per tile (measured at 17 taps, 8 x 18 maps of 368 x 656: tiles of
+                                     // 64 x 32, 64 x 64 and 64 x 128 rows with 256 to 1024 threads all within 165-180 us)
+constexpr int kSmoothBlock = 512;    // threads per workgroup
+constexpr int kSmoothWaves = kSmoothBlock / kWave;
+constexpr int kSmoothHRows = kSmoothBlock / 16;     // rows filtered per step of the horizontal pass (16 threads a row)
+constexpr int kSmoothVRows = kSmoothTileH / kSmoothWaves;   // output rows per thread in the vertical pass
+static_assert(kSmoothVRows % 4 == 0, "the vertical pass produces four outputs at a time");
 constexpr int kSmoothMaxR = 32;      // largest radius: 65 taps
-constexpr int kSmoothSrcW = kSmoothTile + 2 * kSmoothMaxR + 8;   // floats per staged row: a multiple of 4, with room
-                                                                 // for the last window's unused tail
+constexpr int kSmoothStageFloats = 8192;   // LDS given to the staged source rows
 
-__global__ __launch_bounds__(kBlock) void k_smooth(const float *__restrict__ src, float *__restrict__ dst, int C,
+__global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict__ src, float *__restrict__ dst, int C,
                                                    int C_mem, int H, int W, const float *__restrict__ taps, int T)
 {
-    __shared__ float s_taps[2 * kSmoothMaxR + 4];
-    __shared__ __attribute__((aligned(16))) float s_src[kSmoothStage][kSmoothSrcW];
-    extern __shared__ __attribute__((aligned(16))) float s_t[];   // [64 + 2r][64] horizontally filtered rows
+    __shared__ __attribute__((aligned(16))) float s_taps[2 * kSmoothMaxR + 4];   // read four at a time
+    extern __shared__ __attribute__((aligned(16))) float s_dyn[];
+    float *s_t = s_dyn;                                   // [tile rows + 2r][64] horizontally filtered rows
+    float *s_src = s_dyn + (kSmoothTileH + 2 * ((T - 1) >> 1)) * kSmoothTile;   // [stage rows][pitch] source rows (+ 8 floats)
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
     const int r = (T - 1) >> 1;
@@ -34,47 +46,72 @@ __global__ __launch_bounds__(kBlock) void k_smooth(const float *__restrict__ src
     const size_t plane_off = ((size_t)(plane / C) * C_mem + plane % C) * H * W;
     const float *s = src + plane_off;
     float *d = dst + plane_off;
-    const int x0 = blockIdx.x * kSmoothTile, y0 = blockIdx.y * kSmoothTile;
-    const int rows = kSmoothTile + 2 * r, cols = kSmoothTile + 2 * r;
+    const int x0 = blockIdx.x * kSmoothTile, y0 = blockIdx.y * kSmoothTileH;
+    const int rows = kSmoothTileH + 2 * r, cols = kSmoothTile + 2 * r;
 
-    if (tid < T) s_taps[tid] = taps[tid];
+    if (tid < 2 * kSmoothMaxR + 4) s_taps[tid] = tid < T ? taps[tid] : 0.0f;
 
     // ---- horizontal pass into s_t -------------------------------------------------------------
-    const int hr = tid >> 4, hx = 4 * (tid & 15);   // this thread's row of the stage and its four outputs
-    for (int rs = 0; rs < rows; rs += kSmoothStage) {
+    // rows staged at a time: a multiple of the rows filtered per step (16 threads x 4 outputs a row); the pitch is a multiple
+    // of 4 floats so that windows are read 16 bytes at a time, and the last window's unused tail (up to 7 floats
+    // beyond a row) stays inside the array
+    const int pitch = (cols + 3) & ~3;
+    const int stage = min((kSmoothStageFloats / pitch) & ~(kSmoothHRows - 1), (rows + kSmoothHRows - 1) & ~(kSmoothHRows - 1));
+    const int hr = tid >> 4, hx = 4 * (tid & 15);   // this thread's row of a step and its four outputs
+    for (int rs = 0; rs < rows; rs += stage) {
         __syncthreads();   // the previous stage has been consumed (and s_taps is in place)
-        for (int rr = wv; rr < kSmoothStage; rr += kBlock / kWave) {
-            const int y = min(max(y0 - r + rs + rr, 0), H - 1);
-            for (int c = lane; c < cols; c += kWave) s_src[rr][c] = s[(size_t)y * W + min(max(x0 - r + c, 0), W - 1)];
+        // a wavefront stages rows wv, wv + 4, ...: eight rows (sixteen loads per lane) are in flight at a time
+        const int xa = min(max(x0 - r + lane, 0), W - 1), xb = min(max(x0 - r + lane + kWave, 0), W - 1);
+        const bool second = lane + kWave < cols;   // a staged row is 64 + 2r <= 128 floats: at most two per lane
+        for (int rr0 = wv; rr0 < stage && rs + rr0 < rows; rr0 += 8 * kSmoothWaves) {
+            float va[8], vb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int rr = rr0 + u * kSmoothWaves;
+                const float *line = s + (size_t)min(max(y0 - r + rs + rr, 0), H - 1) * W;   // clamped: always readable
+                va[u] = line[xa];
+                vb[u] = second ? line[xb] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int rr = rr0 + u * kSmoothWaves;
+                if (rr < stage && rs + rr < rows) {
+                    s_src[rr * pitch + lane] = va[u];
+                    if (second) s_src[rr * pitch + lane + kWave] = vb[u];
+                }
+            }
         }
         __syncthreads();
-        if (rs + hr < rows) {
+        for (int row = hr; row < stage && rs + row < rows; row += kSmoothHRows) {
             float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            float4 lo = *(const float4 *)&s_src[hr][hx];
+            const float *win = &s_src[row * pitch + hx];
+            float4 lo = *(const float4 *)win;
             for (int i = 0; i < T; i += 4) {
-                const float4 hi = *(const float4 *)&s_src[hr][hx + i + 4];
+                const float4 hi = *(const float4 *)(win + i + 4);
+                const float4 t4 = *(const float4 *)&s_taps[i];
                 const float w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                const float tp[4] = {t4.x, t4.y, t4.z, t4.w};
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     if (i + m < T) {   // the same for every thread
-                        const float tap = s_taps[i + m];
+                        const float tap = tp[m];
 #pragma unroll
                         for (int o = 0; o < 4; ++o) acc[o] = __fmaf_rn(tap, w[o + m], acc[o]);
                     }
                 }
                 lo = hi;
             }
-            *(float4 *)&s_t[(rs + hr) * kSmoothTile + hx] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *(float4 *)&s_t[(rs + row) * kSmoothTile + hx] = make_float4(acc[0], acc[1], acc[2], acc[3]);
         }
     }
     __syncthreads();
 
     // ---- vertical pass out of s_t ----------------------------------------------------------------
-    const int vx = tid & (kSmoothTile - 1), vg = tid >> 6;   // this thread's column and its 16 rows
+    const int vx = tid & (kSmoothTile - 1), vg = tid >> 6;   // this thread's column and its rows
     if (x0 + vx >= W) return;
 #pragma unroll 1
-    for (int k = 0; k < 4; ++k) {
-        const int yo = 16 * vg + 4 * k;   // four outputs: tile rows yo .. yo + 3
+    for (int k = 0; k < kSmoothVRows / 4; ++k) {
+        const int yo = kSmoothVRows * vg + 4 * k;   // four outputs: tile rows yo .. yo + 3
         if (y0 + yo >= H) break;
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         float w[8];
@@ -83,10 +120,12 @@ __global__ __launch_bounds__(kBlock) void k_smooth(const float *__restrict__ src
         for (int i = 0; i < T; i += 4) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) w[4 + j] = (yo + i + 4 + j < rows) ? s_t[(yo + i + 4 + j) * kSmoothTile + vx] : 0.0f;
+            const float4 t4 = *(const float4 *)&s_taps[i];
+            const float tp[4] = {t4.x, t4.y, t4.z, t4.w};
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 if (i + m < T) {
-                    const float tap = s_taps[i + m];
+                    const float tap = tp[m];
 #pragma unroll
                     for (int o = 0; o < 4; ++o) acc[o] = __fmaf_rn(tap, w[o + m], acc[o]);
                 }
@@ -100,17 +139,27 @@ __global__ __launch_bounds__(kBlock) void k_smooth(const float *__restrict__ src
     }
 }
 
+// Rows staged at a time and the floats between staged rows, for radius r (the kernel derives the same two numbers).
+static void smooth_stage(int r, int &stage, int &pitch)
+{
+    const int rows = kSmoothTileH + 2 * r, cols = kSmoothTile + 2 * r;
+    pitch = (cols + 3) & ~3;
+    stage = std::min((kSmoothStageFloats / pitch) & ~(kSmoothHRows - 1), (rows + kSmoothHRows - 1) & ~(kSmoothHRows - 1));
+}
+
 hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, int H, int W, const float *taps,
                          int n_taps, hipStream_t s)
 {
     const int r = (n_taps - 1) / 2;
-    const size_t lds = sizeof(float) * (size_t)(kSmoothTile + 2 * r) * kSmoothTile;
+    int stage, pitch;
+    smooth_stage(r, stage, pitch);
+    const size_t lds = sizeof(float) * ((size_t)(kSmoothTileH + 2 * r) * kSmoothTile + (size_t)stage * pitch + 8);
     // grid.z carries the planes: at most 65535 per launch
     for (int p0 = 0; p0 < N * C; p0 += 65535 / C * C) {
-        const int planes = min(N * C - p0, 65535 / C * C);
+        const int planes = std::min(N * C - p0, 65535 / C * C);
         const size_t off = (size_t)(p0 / C) * C_mem * H * W;
-        const dim3 grid((W + kSmoothTile - 1) / kSmoothTile, (H + kSmoothTile - 1) / kSmoothTile, planes);
-        HP_KERNEL(k_smooth, grid, dim3(kBlock), lds, s, src + off, dst + off, C, C_mem, H, W, taps, n_taps);
+        const dim3 grid((W + kSmoothTile - 1) / kSmoothTile, (H + kSmoothTileH - 1) / kSmoothTileH, planes);
+        HP_KERNEL(k_smooth, grid, dim3(kSmoothBlock), lds, s, src + off, dst + off, C, C_mem, H, W, taps, n_taps);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
