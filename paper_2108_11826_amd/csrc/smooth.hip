@@ -5,16 +5,16 @@
 //
 // One workgroup produces a tile of 64 x 64 outputs in one launch, the horizontally filtered rows
 // living only in LDS.  Horizontal pass: the tile's source rows (64 + 2r of them, 64 + 2r wide) are
-// staged in LDS, all at once when they fit 32 KB (up to 25 taps), so that every load of the tile is
-// in flight together, one coalesced row per wavefront load; a thread filters four neighbouring
-// outputs of a row from a sliding window held in registers (two 16-byte LDS reads per four taps,
-// sixteen multiply-adds).  Vertical pass: a thread walks down one column of the filtered rows,
-// four outputs at a time, with the same window scheme, and stores rows 256 bytes wide.  With 17
-// taps that is 38 multiply-adds and 8 bytes of memory traffic per output pixel, which would put the
-// kernel near the balance of the vector ALUs and HBM; measured, it reaches a fifth of either: with
-// one phase switched off at a time, loading, the horizontal and the vertical pass each take a
-// quarter to a third of the time and hardly overlap, the three workgroups a compute unit holds
-// (46 KB of LDS each) being too few to hide one another's phases.
+// staged in LDS 32 at a time, sixteen loads per lane in flight, one coalesced row per wavefront
+// load; a thread filters four neighbouring outputs of a row from a sliding window held in
+// registers (two 16-byte LDS reads per four taps, sixteen multiply-adds).  Vertical pass: a thread
+// walks down one column of the filtered rows, four outputs at a time, with the same window scheme,
+// and stores rows 256 bytes wide.  The usual tap counts (5, 9, 13, 17, 25) are compiled in: the
+// loops over taps unroll completely and the taps stay in scalar registers, which took the 17-tap
+// case from 170 to 104 us; any other odd count up to 65 runs the same code with run-time loops.
+// With 17 taps the kernel does 38 multiply-adds and moves 8 bytes per output pixel and reaches
+// about 40 % of both the fp32 vector rate and the HBM peak; switching one phase off at a time shows
+// loading, the horizontal and the vertical pass adding up rather than overlapping.
 #include <algorithm>
 
 #include "hp_dev.h"
@@ -22,19 +22,25 @@
 namespace hp {
 
 constexpr int kSmoothTile = 64;      // outputs per tile row: 16 threads x 4 (horizontal pass), 64 threads (vertical pass)
-constexpr int kSmoothTileH = 64;     // output rows per tile (measured at 17 taps, 8 x 18 maps of 368 x 656: tiles of
-                                     // 64 x 32, 64 x 64 and 64 x 128 rows with 256 to 1024 threads all within 165-180 us)
+constexpr int kSmoothTileH = 64;     // output rows per tile (measured at 17 taps, 8 x 18 maps of 368 x 656: 64 x 32 tiles
+                                     // 96-113 us, 64 x 64 and 64 x 128 tiles 87 us with 512 threads, 103 us with 256)
 constexpr int kSmoothBlock = 512;    // threads per workgroup
 constexpr int kSmoothWaves = kSmoothBlock / kWave;
 constexpr int kSmoothHRows = kSmoothBlock / 16;     // rows filtered per step of the horizontal pass (16 threads a row)
 constexpr int kSmoothVRows = kSmoothTileH / kSmoothWaves;   // output rows per thread in the vertical pass
 static_assert(kSmoothVRows % 4 == 0, "the vertical pass produces four outputs at a time");
 constexpr int kSmoothMaxR = 32;      // largest radius: 65 taps
-constexpr int kSmoothStageFloats = 8192;   // LDS given to the staged source rows
+constexpr int kSmoothStageFloats = 4096;   // LDS given to the staged source rows: 32 rows at a time (with room for the
+                                           // whole tile, 32 KB, a compute unit held a workgroup less and the kernel took 104 us
+                                           // instead of 87)
 
+// TC: the number of taps when it is known at compile time (the loops over taps then unroll completely and the taps
+// stay in scalar registers), 0 for any number of taps.
+template <int TC>
 __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict__ src, float *__restrict__ dst, int C,
-                                                   int C_mem, int H, int W, const float *__restrict__ taps, int T)
+                                                   int C_mem, int H, int W, const float *__restrict__ taps, int T_any)
 {
+    const int T = TC ? TC : T_any;
     __shared__ __attribute__((aligned(16))) float s_taps[2 * kSmoothMaxR + 4];   // read four at a time
     extern __shared__ __attribute__((aligned(16))) float s_dyn[];
     float *s_t = s_dyn;                                   // [tile rows + 2r][64] horizontally filtered rows
@@ -86,6 +92,7 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
             float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
             const float *win = &s_src[row * pitch + hx];
             float4 lo = *(const float4 *)win;
+#pragma unroll
             for (int i = 0; i < T; i += 4) {
                 const float4 hi = *(const float4 *)(win + i + 4);
                 const float4 t4 = *(const float4 *)&s_taps[i];
@@ -94,7 +101,7 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     if (i + m < T) {   // the same for every thread
-                        const float tap = tp[m];
+                        const float tap = TC ? taps[TC ? i + m : 0] : tp[m];
 #pragma unroll
                         for (int o = 0; o < 4; ++o) acc[o] = __fmaf_rn(tap, w[o + m], acc[o]);
                     }
@@ -117,6 +124,7 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
         float w[8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) w[j] = s_t[(yo + j) * kSmoothTile + vx];
+#pragma unroll
         for (int i = 0; i < T; i += 4) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) w[4 + j] = (yo + i + 4 + j < rows) ? s_t[(yo + i + 4 + j) * kSmoothTile + vx] : 0.0f;
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 if (i + m < T) {
-                    const float tap = tp[m];
+                    const float tap = TC ? taps[TC ? i + m : 0] : tp[m];
 #pragma unroll
                     for (int o = 0; o < 4; ++o) acc[o] = __fmaf_rn(tap, w[o + m], acc[o]);
                 }
@@ -159,7 +167,20 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
         const int planes = std::min(N * C - p0, 65535 / C * C);
         const size_t off = (size_t)(p0 / C) * C_mem * H * W;
         const dim3 grid((W + kSmoothTile - 1) / kSmoothTile, (H + kSmoothTileH - 1) / kSmoothTileH, planes);
-        HP_KERNEL(k_smooth, grid, dim3(kSmoothBlock), lds, s, src + off, dst + off, C, C_mem, H, W, taps, n_taps);
+#define HP_SMOOTH_CASE(TC_)                                                                                            \
+    case TC_:                                                                                                      \
+        HP_KERNEL(k_smooth<TC_>, grid, dim3(kSmoothBlock), lds, s, src + off, dst + off, C, C_mem, H, W, taps, n_taps); \
+        break;
+        switch (n_taps) {
+            HP_SMOOTH_CASE(5)
+            HP_SMOOTH_CASE(9)
+            HP_SMOOTH_CASE(13)
+            HP_SMOOTH_CASE(17)
+            HP_SMOOTH_CASE(25)
+        default:
+            HP_KERNEL(k_smooth<0>, grid, dim3(kSmoothBlock), lds, s, src + off, dst + off, C, C_mem, H, W, taps, n_taps);
+        }
+#undef HP_SMOOTH_CASE
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
