@@ -23,6 +23,7 @@ _SRC = os.path.join(_HERE, "hp_oracle.c")
 _SRC_PRE = os.path.join(_HERE, "hp_pre_oracle.c")
 _SRC_DRAW = os.path.join(_HERE, "hp_draw_oracle.c")
 _SRC_SMOOTH = os.path.join(_HERE, "hp_smooth_oracle.c")
+_SRC_REFINE = os.path.join(_HERE, "hp_refine_oracle.c")
 
 
 def _cpu_has_fma():
@@ -41,10 +42,10 @@ def build(force=False):
     out = []
     for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
         so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
-        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH))
+        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE))
         if force or not os.path.exists(so) or os.path.getmtime(so) < newest:
             cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, "-o", so, "-lm"]
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
     return out
@@ -86,6 +87,8 @@ def lib():
         u8p = ctypes.POINTER(ctypes.c_uint8)
         L.hpq_preprocess.restype = None
         L.hpq_preprocess.argtypes = [u8p, ci, ci, ci, ci, ci, ci, ci, f32p, f32p, f32p]
+        L.hpf_refine.restype = None
+        L.hpf_refine.argtypes = [f32p, ci, ci, ci, i32p, i32p, f32p, f32p]
         L.hps_smooth.restype = ci
         L.hps_smooth.argtypes = [f32p, f32p, ci, ci, ci, f32p, ci]
         L.hpv_in_capsule.restype = ci
@@ -137,6 +140,15 @@ def preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False):
     lib().hpq_preprocess(im.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), N, Hs, Ws, C, int(Hd), int(Wd),
                          1 if reverse_channels else 0, _f32(al), _f32(be), _f32(out))
     return out
+
+
+def refine_peaks(plane_hi, px, py):
+    """Sub-pixel positions (xf, yf) of the peaks (px, py) of one fp32 plane (hp_refine_oracle.c)."""
+    u = np.ascontiguousarray(plane_hi, np.float32)
+    x, y = np.ascontiguousarray(px, np.int32), np.ascontiguousarray(py, np.int32)
+    xf, yf = np.empty(len(x), np.float32), np.empty(len(x), np.float32)
+    lib().hpf_refine(_f32(u), u.shape[0], u.shape[1], len(x), _i32(x), _i32(y), _f32(xf), _f32(yf))
+    return xf, yf
 
 
 def smooth(maps, taps):
