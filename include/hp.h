@@ -166,6 +166,16 @@ int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, floa
 int hp_smooth(const float *src_hi, float *dst_hi, int N, int C, int C_mem, int H, int W,
               const float *taps, int n_taps, void *stream);
 
+/* Optional sub-pixel refinement of the peaks hp_find_peaks stored (whole pixels, reading P4), on
+ * the maps they were found on (smoothed or not).  Per axis, with a, b, c the values at x-1, x, x+1:
+ *   den = (a + c) - (b + b),  off = (0.5f * (a - c)) / den   (fp32, IEEE divide),
+ * taken when den < 0 and clamped to [-0.5, 0.5]; off = 0 otherwise and on the first and last
+ * column; xf = (float)x + off; the same along y.  maps_hi: device fp32 [N][C_mem][H][W]; peaks: as
+ * written by hp_find_peaks for channels 0..K-1 (counts above cap are clamped); xf, yf: device fp32
+ * [N][K][cap], entries beyond a list's count are left untouched.  Allocates nothing; one kernel. */
+int hp_refine_peaks(const float *maps_hi, int N, int C_mem, int K, int H, int W, const hp_peaks *peaks,
+                    float *xf, float *yf, void *stream);
+
 /* Limb scoring on materialised hi-res PAFs (Section 2.3, PAF family).  For
  * limb l = (a, b) and every pair (i in peaks[a], j in peaks[b]) with distinct
  * pixels: unit direction u = (B - A)/|B - A|; S samples at
@@ -398,7 +408,8 @@ typedef enum {
     HP_K_DRAW_LIST = 11,     /* hp_draw_poses: the images' primitives listed in painter's order */
     HP_K_DRAW = 12,          /* hp_draw_poses: the frames painted */
     HP_K_SMOOTH = 13,        /* hp_smooth */
-    HP_K_COUNT = 14
+    HP_K_REFINE = 14,        /* hp_refine_peaks */
+    HP_K_COUNT = 15
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

@@ -17,11 +17,11 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
-HP_K_COUNT = 14
+HP_K_COUNT = 15
 
 
 class HPError(RuntimeError):
@@ -105,6 +105,8 @@ def lib():
         L.hp_preprocess.restype = c_int
         L.hp_preprocess.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int,
                                     POINTER(c_float), POINTER(c_float), c_void_p]
+        L.hp_refine_peaks.restype = c_int
+        L.hp_refine_peaks.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, POINTER(_Peaks), c_void_p, c_void_p, c_void_p]
         L.hp_smooth.restype = c_int
         L.hp_smooth.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_void_p]
         L.hp_draw_poses.restype = c_int
@@ -343,6 +345,16 @@ def hp_preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False, out=None,
     _check(lib().hp_preprocess(_dev(images, torch.uint8), N, Hs, Ws, C, _dtype_code(out), _dev(out), int(Hd), int(Wd),
                                1 if reverse_channels else 0, al, be, _stream()), "hp_preprocess")
     return out
+
+
+def hp_refine_peaks(maps_hi, K, buf):
+    """Sub-pixel positions of buf's peaks on maps_hi (fp32 [N, C_mem, H, W]): (xf, yf), fp32 [N, K, cap] on the GPU."""
+    N, C_mem, H, W = maps_hi.shape
+    xf = torch.zeros((N, K, buf.cap), dtype=torch.float32, device=maps_hi.device)
+    yf = torch.zeros_like(xf)
+    _check(lib().hp_refine_peaks(_dev(maps_hi, torch.float32), N, C_mem, int(K), H, W, ctypes.byref(buf.peaks),
+                                 _dev(xf), _dev(yf), _stream()), "hp_refine_peaks")
+    return xf, yf
 
 
 def hp_smooth(maps_hi, taps, channels=None, out=None):

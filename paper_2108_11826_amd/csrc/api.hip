@@ -337,6 +337,18 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
     return HP_OK;
 }
 
+int hp_refine_peaks(const float *maps_hi, int N, int C_mem, int K, int H, int W, const hp_peaks *peaks, float *xf, float *yf,
+                    void *stream)
+{
+    if (!maps_hi || !xf || !yf) return HP_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || C_mem < K || H <= 0 || W <= 0) return HP_ERR_INVALID_ARG;
+    if (K > HP_MAX_PARTS || (long long)H * W >= (1LL << 31)) return HP_ERR_UNSUPPORTED;
+    HP_TRY(check_peaks(peaks));
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_REFINE, launch_refine(maps_hi, N, C_mem, K, H, W, *peaks, xf, yf, s));
+    return HP_OK;
+}
+
 int hp_smooth(const float *src_hi, float *dst_hi, int N, int C, int C_mem, int H, int W, const float *taps, int n_taps,
               void *stream)
 {
@@ -445,6 +457,7 @@ const char *hp_kernel_name(int id)
     case HP_K_DRAW_LIST: return "draw_list";
     case HP_K_DRAW: return "draw";
     case HP_K_SMOOTH: return "smooth";
+    case HP_K_REFINE: return "refine";
     default: return "unknown";
     }
 }

@@ -201,6 +201,10 @@ hipError_t launch_draw_tiles(const uint8_t *src, uint8_t *dst, int N, int Hf, in
 hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, int H, int W, const float *taps,
                          int n_taps, hipStream_t s);
 
+// Sub-pixel positions of the stored peaks of channels [0, K) on fp32 maps [N][C_mem][H][W]; xf, yf: [N][K][cap].
+hipError_t launch_refine(const float *maps, int N, int C_mem, int K, int H, int W, const hp_peaks &pk, float *xf, float *yf,
+                         hipStream_t s);
+
 // hp_postprocess on the first N images of outputs and a workspace laid out for N_layout >= N images;
 // check_only: validate the arguments, enqueue nothing.
 int postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int N_layout, int h, int w,

@@ -68,3 +68,36 @@ def test_smoothed_peaks_of_a_full_workload():
     raw = sum(len(oracle.find_peaks(oracle.resize(b.cm[0, c], 8), DEFAULT_PARAMS.peak_thr)[0]) for c in range(sk.n_parts))
     smooth = sum(len(peaks[0][c][0]) for c in range(sk.n_parts))
     assert 0 < smooth <= raw
+
+
+@pytest.mark.parametrize("smoothed", [False, True], ids=["raw", "smoothed"])
+def test_refined_peak_positions(smoothed):
+    # the staged route with the optional steps: upsample, (smooth,) find peaks, refine; every float against the oracle
+    m = hp()
+    cfg = CONFIGS[1]
+    sk = cfg.skeleton
+    b = generate(cfg)
+    taps = gaussian_taps(3.0, 8)
+    maps = m.hp_resize(torch.from_numpy(b.cm).to(DEV))
+    if smoothed:
+        maps = m.hp_smooth(maps, torch.from_numpy(taps).to(DEV), channels=sk.n_parts)
+    cap, ccap, pcap = BENCH_CAPS[1]
+    buf = m.Buffers(cfg.batch, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, cap, ccap, pcap, DEV)
+    m.hp_find_peaks(maps, sk.n_parts, DEFAULT_PARAMS.peak_thr, buf)
+    xf, yf = m.hp_refine_peaks(maps, sk.n_parts, buf)
+    xf, yf = xf.cpu().numpy(), yf.cpu().numpy()
+    peaks, _ = buf.host_peaks()
+    moved = 0
+    for c in range(sk.n_parts):
+        plane = oracle.resize(b.cm[0, c], 8)
+        if smoothed:
+            plane = oracle.smooth(plane, taps)
+        ox, oy, _ = oracle.find_peaks(plane, DEFAULT_PARAMS.peak_thr)
+        assert np.array_equal(peaks[0][c][0], ox) and np.array_equal(peaks[0][c][1], oy)
+        wx, wy = oracle.refine_peaks(plane, ox, oy)
+        k = len(ox)
+        assert np.array_equal(xf[0, c, :k].view(np.uint32), wx.view(np.uint32))
+        assert np.array_equal(yf[0, c, :k].view(np.uint32), wy.view(np.uint32))
+        assert np.all(xf[0, c, k:] == 0) and np.all(yf[0, c, k:] == 0)      # entries beyond the count are untouched
+        moved += int(np.count_nonzero(wx != ox) + np.count_nonzero(wy != oy))
+    assert moved > 0

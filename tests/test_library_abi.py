@@ -248,3 +248,14 @@ def test_smooth_rejects_bad_calls(L):
     assert call(n=0) == -1 and call(n=4) == -1             # the tap vector has odd length
     assert call(n=67) == -5
     assert call(dst=a) == -1 and call(dst=c_void_p(0x100000 + 64)) == -1      # no smoothing in place
+
+
+def test_refine_rejects_bad_calls(L):
+    sk, prm, pk, cd, cn, ps = descriptors()
+    a, x, y = c_void_p(0x100000), c_void_p(0x200000), c_void_p(0x300000)
+    assert L.hp_refine_peaks(None, 1, 4, 3, 16, 16, byref(pk), x, y, None) == -1
+    assert L.hp_refine_peaks(a, 1, 4, 3, 16, 16, byref(pk), None, y, None) == -1
+    assert L.hp_refine_peaks(a, 1, 4, 3, 16, 16, None, x, y, None) == -1
+    assert L.hp_refine_peaks(a, 0, 4, 3, 16, 16, byref(pk), x, y, None) == -1
+    assert L.hp_refine_peaks(a, 1, 2, 3, 16, 16, byref(pk), x, y, None) == -1       # fewer channels than parts
+    assert L.hp_refine_peaks(a, 1, 99, 99, 16, 16, byref(pk), x, y, None) == -5
