@@ -24,6 +24,7 @@ _SRC_PRE = os.path.join(_HERE, "hp_pre_oracle.c")
 _SRC_DRAW = os.path.join(_HERE, "hp_draw_oracle.c")
 _SRC_SMOOTH = os.path.join(_HERE, "hp_smooth_oracle.c")
 _SRC_REFINE = os.path.join(_HERE, "hp_refine_oracle.c")
+_SRC_PP = os.path.join(_HERE, "hp_pp_oracle.c")
 
 
 def _cpu_has_fma():
@@ -42,10 +43,10 @@ def build(force=False):
     out = []
     for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
         so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
-        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE))
+        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP))
         if force or not os.path.exists(so) or os.path.getmtime(so) < newest:
             cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, "-o", so, "-lm"]
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
     return out
@@ -87,6 +88,12 @@ def lib():
         u8p = ctypes.POINTER(ctypes.c_uint8)
         L.hpq_preprocess.restype = None
         L.hpq_preprocess.argtypes = [u8p, ci, ci, ci, ci, ci, ci, ci, f32p, f32p, f32p]
+        L.hpp_iou.restype = cf
+        L.hpp_iou.argtypes = [f32p, f32p]
+        L.hpp_detect.restype = ci
+        L.hpp_detect.argtypes = [f32p, f32p, f32p, ci, ci, cf, cf, cf, cf, ci, i32p, f32p, f32p]
+        L.hpp_parse.restype = ci
+        L.hpp_parse.argtypes = [ci, ci, i32p, i32p, i32p, f32p, i32p, ci, f32p, ci, ci, ci, ci, cf, ci, ci, i32p, i32p, f32p]
         L.hpf_refine.restype = None
         L.hpf_refine.argtypes = [f32p, ci, ci, ci, i32p, i32p, f32p, f32p]
         L.hps_smooth.restype = ci
@@ -140,6 +147,49 @@ def preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False):
     lib().hpq_preprocess(im.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), N, Hs, Ws, C, int(Hd), int(Wd),
                          1 if reverse_channels else 0, _f32(al), _f32(be), _f32(out))
     return out
+
+
+def pp_iou(a, b):
+    a, b = np.ascontiguousarray(a, np.float32), np.ascontiguousarray(b, np.float32)
+    return float(lib().hpp_iou(_f32(a), _f32(b)))
+
+
+def pp_detect(resp, conf, box, img_w, img_h, det_thr, nms_thr):
+    """Pose-proposal detections of one (image, part): resp, conf [Gh, Gw], box [4, Gh, Gw] ->
+    (cell int32[], score fp32[], corners fp32[n, 4]) in the order kept (hp_pp_oracle.c, D1-D3)."""
+    r, c, b = (np.ascontiguousarray(v, np.float32) for v in (resp, conf, box))
+    Gh, Gw = r.shape
+    cap = Gh * Gw
+    cell, score, corners = np.zeros(cap, np.int32), np.zeros(cap, np.float32), np.zeros((cap, 4), np.float32)
+    n = lib().hpp_detect(_f32(r), _f32(c), _f32(b), Gh, Gw, float(img_w), float(img_h), float(det_thr), float(nms_thr), cap,
+                         _i32(cell), _f32(score), _f32(corners))
+    return cell[:n].copy(), score[:n].copy(), corners[:n].copy()
+
+
+def pp_decode(resp, conf, box, edge, limb_a, limb_b, img_w, img_h, det_thr, nms_thr, edge_thr, min_parts):
+    """Whole pose-proposal post-processing of a batch (D1-D5): resp, conf [N, K, Gh, Gw]; box [N, K, 4, Gh, Gw];
+    edge [N, L, Nh, Nw, Gh, Gw].  Returns {"dets": [n][k] -> (cell, score, corners), "poses": [n] -> (slots, nparts, score)}."""
+    resp, conf, box, edge = (np.ascontiguousarray(v, np.float32) for v in (resp, conf, box, edge))
+    N, K, Gh, Gw = resp.shape
+    L, Nh, Nw = edge.shape[1:4]
+    la, lb = np.ascontiguousarray(limb_a, np.int32), np.ascontiguousarray(limb_b, np.int32)
+    cap = Gh * Gw
+    dets, poses = [], []
+    for n in range(N):
+        per_part = [pp_detect(resp[n, k], conf[n, k], box[n, k], img_w, img_h, det_thr, nms_thr) for k in range(K)]
+        dets.append(per_part)
+        cell, score = np.zeros((K, cap), np.int32), np.zeros((K, cap), np.float32)
+        count = np.zeros(K, np.int32)
+        for k in range(K):
+            m = len(per_part[k][0])
+            cell[k, :m], score[k, :m], count[k] = per_part[k][0], per_part[k][1], m
+        pcap = max(1, int(count[la[0]]))
+        slots, nparts, pscore = np.zeros((pcap, K), np.int32), np.zeros(pcap, np.int32), np.zeros(pcap, np.float32)
+        e = np.ascontiguousarray(edge[n])
+        m = lib().hpp_parse(K, L, _i32(la), _i32(lb), _i32(cell), _f32(score), _i32(count), cap, _f32(e), Gh, Gw, Nh, Nw,
+                            float(edge_thr), int(min_parts), pcap, _i32(slots), _i32(nparts), _f32(pscore))
+        poses.append((slots[:m].copy(), nparts[:m].copy(), pscore[:m].copy()))
+    return {"dets": dets, "poses": poses}
 
 
 def refine_peaks(plane_hi, px, py):

@@ -8,7 +8,8 @@ consumes (Section 2.2.1, operator 4).  None of the post-processing arithmetic
 lives here.
 """
 from .skeletons import Skeleton, COCO18, BODY25
+from .pose_proposal import PPConfig, PP_CONFIGS, PP_COCO19, generate_pp
 from .generate import SynthConfig, CONFIGS, generate, Params, DEFAULT_PARAMS, BENCH_CAPS, gaussian_taps
 
-__all__ = ["gaussian_taps", "Skeleton", "COCO18", "BODY25", "SynthConfig", "CONFIGS", "generate",
+__all__ = ["PPConfig", "PP_CONFIGS", "PP_COCO19", "generate_pp", "gaussian_taps", "Skeleton", "COCO18", "BODY25", "SynthConfig", "CONFIGS", "generate",
            "Params", "DEFAULT_PARAMS", "BENCH_CAPS"]
