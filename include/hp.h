@@ -70,7 +70,8 @@ enum {
     HP_MAX_CAP = 16384,    /* largest hp_peaks.cap */
     HP_MAX_CCAP = 1 << 20, /* largest candidate capacity */
     HP_MAX_SAMPLES = 64,
-    HP_MAX_TAPS = 65       /* longest tap vector of hp_smooth */
+    HP_MAX_TAPS = 65,      /* longest tap vector of hp_smooth */
+    HP_PP_MAX_CELLS = 1024 /* most grid cells (Gh * Gw) of hp_pp_decode */
 };
 
 /* Skeleton: limb l joins part limb_a[l] to part limb_b[l] and owns PAF channels
@@ -267,6 +268,58 @@ int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C
                   const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
                   void *workspace, size_t ws_bytes, void *stream);
 
+/* ---- Post-processing of the pose-proposal family -------------------------------------------
+ * Section 2.3 lists PoseProposal as the second algorithm class the engine post-processes and gives
+ * no arithmetic.  The cited method detects every part (and a whole-person "instance") as a box on
+ * a coarse grid and predicts, per limb and grid cell, how likely the parent part in that cell
+ * connects to the child part in each cell of a small neighbourhood.  Inputs, all device fp32:
+ *   resp, conf [N][K][Gh][Gw]   (their product is the detection score);
+ *   box [N][K][4][Gh][Gw]       (ox, oy: centre offset inside the cell; bw, bh: fractions of the image);
+ *   edge [N][L][Nh][Nw][Gh][Gw] (connection value from the parent in cell i to the child in cell
+ *                                i + (dy - (Nh-1)/2, dx - (Nw-1)/2)).
+ * The skeleton's limbs are parent -> child in table order: the parent of limb 0 is the root part,
+ * every other parent is the root or the child of an earlier limb, a part is a child at most once.
+ * Rules (fp32, one operation per step as written):
+ *   D1 score = resp * conf; a cell is a candidate when score > det_thr;
+ *   D2 box: cx = ((float)gx + ox) * cell_w, cy = ((float)gy + oy) * cell_h, w = bw * img_w,
+ *      h = bh * img_h, corners cx -/+ 0.5f * w, cy -/+ 0.5f * h; cell_w = img_w / (float)Gw, cell_h likewise;
+ *   D3 per part, candidates in (score descending, cell index ascending) order are kept when their
+ *      IoU with every box kept before is at most nms_thr; IoU = inter / ((area_a + area_b) - inter),
+ *      inter = iw * ih when both overlaps are positive, else 0; IoU = 0 when the denominator is not
+ *      positive.  `dets` receives the kept detections in that order (corners x0, y0, x1, y1);
+ *   D4 every kept root detection starts a person, in order; limbs in table order; for a limb whose
+ *      parent the person holds in cell i, the child detection, among those no earlier person took
+ *      (dropped persons included) and whose cell lies in the Nh x Nw neighbourhood of i, with the
+ *      largest connection value is attached when that value exceeds edge_thr (ties: the earlier);
+ *   D5 person score = root score, then per attached limb in table order + connection value,
+ *      + child score; persons with >= min_parts parts are written in root order: slots = rank in
+ *      the part's detection list or -1.
+ * `status` (device int32, overwritten): HP_STATUS_PEAK_OVERFLOW when a detection list needs more
+ * than dets->cap entries, HP_STATUS_POSE_OVERFLOW for persons; counts are always the required ones.
+ * Limits: Gh * Gw <= HP_PP_MAX_CELLS, Nh and Nw odd and at most 31, dets->cap <= 1024 and
+ * n_parts * dets->cap <= 4096.  Allocates nothing; enqueues three kernels on `stream`. */
+typedef struct {
+    float det_thr;
+    float nms_thr;
+    float edge_thr;
+    int32_t min_parts;
+    float img_w;
+    float img_h;
+} hp_pp_params;
+
+typedef struct {
+    int32_t *cell;    /* device [N][K][cap], gy * Gw + gx */
+    float *score;     /* device [N][K][cap] */
+    float *box;       /* device [N][K][cap][4] */
+    int32_t *count;   /* device [N][K] */
+    int32_t cap;
+} hp_pp_dets;
+
+int hp_pp_decode(const float *resp, const float *conf, const float *box, const float *edge,
+                 int N, int Gh, int Gw, int Nh, int Nw, const hp_skeleton *skel,
+                 const hp_pp_params *prm, const hp_pp_dets *dets, const hp_poses *poses,
+                 int32_t *status, void *stream);
+
 /* ---- Streaming front with a dynamic batch slot ---------------------------------------------
  * Section 2.2.1 runs the operators asynchronously, a FIFO between each pair; Section 2.2.2 puts a
  * batch slot in front of the GPU operator that collects more input tensors only while the GPU is
@@ -409,7 +462,9 @@ typedef enum {
     HP_K_DRAW = 12,          /* hp_draw_poses: the frames painted */
     HP_K_SMOOTH = 13,        /* hp_smooth */
     HP_K_REFINE = 14,        /* hp_refine_peaks */
-    HP_K_COUNT = 15
+    HP_K_PP_DETECT = 15,     /* hp_pp_decode: scores, boxes and suppression per (image, part) */
+    HP_K_PP_PARSE = 16,      /* hp_pp_decode: the limb tree walked per image */
+    HP_K_COUNT = 17
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

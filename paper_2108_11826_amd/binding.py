@@ -17,11 +17,11 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_pp_decode", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
-HP_K_COUNT = 15
+HP_K_COUNT = 17
 
 
 class HPError(RuntimeError):
@@ -51,6 +51,15 @@ class _Pairs(Structure):
 class _Poses(Structure):
     _fields_ = [("slots", c_void_p), ("nparts", c_void_p), ("score", c_void_p), ("count", c_void_p),
                 ("cap", c_int32)]
+
+
+class _PPParams(Structure):
+    _fields_ = [("det_thr", c_float), ("nms_thr", c_float), ("edge_thr", c_float), ("min_parts", c_int32),
+                ("img_w", c_float), ("img_h", c_float)]
+
+
+class _PPDets(Structure):
+    _fields_ = [("cell", c_void_p), ("score", c_void_p), ("box", c_void_p), ("count", c_void_p), ("cap", c_int32)]
 
 
 class _Lane(Structure):
@@ -105,6 +114,9 @@ def lib():
         L.hp_preprocess.restype = c_int
         L.hp_preprocess.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int,
                                     POINTER(c_float), POINTER(c_float), c_void_p]
+        L.hp_pp_decode.restype = c_int
+        L.hp_pp_decode.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
+                                   POINTER(_PPParams), POINTER(_PPDets), POINTER(_Poses), c_void_p, c_void_p]
         L.hp_refine_peaks.restype = c_int
         L.hp_refine_peaks.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, POINTER(_Peaks), c_void_p, c_void_p, c_void_p]
         L.hp_smooth.restype = c_int
@@ -345,6 +357,44 @@ def hp_preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False, out=None,
     _check(lib().hp_preprocess(_dev(images, torch.uint8), N, Hs, Ws, C, _dtype_code(out), _dev(out), int(Hd), int(Wd),
                                1 if reverse_channels else 0, al, be, _stream()), "hp_preprocess")
     return out
+
+
+class PPBuffers:
+    """Caller-owned outputs of hp_pp_decode: detection lists per (image, part) and persons per image."""
+
+    def __init__(self, N, K, cap, pcap, device="cuda:0"):
+        self.N, self.K, self.cap, self.pcap = N, K, cap, pcap
+        i32, f32 = dict(dtype=torch.int32, device=device), dict(dtype=torch.float32, device=device)
+        self.cell, self.score = torch.zeros((N, K, cap), **i32), torch.zeros((N, K, cap), **f32)
+        self.box, self.count = torch.zeros((N, K, cap, 4), **f32), torch.zeros((N, K), **i32)
+        self.slots, self.nparts = torch.zeros((N, pcap, K), **i32), torch.zeros((N, pcap), **i32)
+        self.pscore, self.pose_count = torch.zeros((N, pcap), **f32), torch.zeros((N,), **i32)
+        self.status = torch.zeros((1,), **i32)
+        self.dets = _PPDets(self.cell.data_ptr(), self.score.data_ptr(), self.box.data_ptr(), self.count.data_ptr(), cap)
+        self.poses = _Poses(self.slots.data_ptr(), self.nparts.data_ptr(), self.pscore.data_ptr(),
+                            self.pose_count.data_ptr(), pcap)
+
+    def host(self):
+        """{"dets": [n][k] -> (cell, score, corners), "poses": [n] -> (slots, nparts, score), "status": int}."""
+        cnt, pc = self.count.cpu().numpy(), self.pose_count.cpu().numpy()
+        cell, score, box = self.cell.cpu().numpy(), self.score.cpu().numpy(), self.box.cpu().numpy()
+        sl, npt, ps = self.slots.cpu().numpy(), self.nparts.cpu().numpy(), self.pscore.cpu().numpy()
+        dets = [[(cell[n, k, :min(cnt[n, k], self.cap)].copy(), score[n, k, :min(cnt[n, k], self.cap)].copy(),
+                  box[n, k, :min(cnt[n, k], self.cap)].copy()) for k in range(self.K)] for n in range(self.N)]
+        poses = [(sl[n, :min(pc[n], self.pcap)].copy(), npt[n, :min(pc[n], self.pcap)].copy(),
+                  ps[n, :min(pc[n], self.pcap)].copy()) for n in range(self.N)]
+        return {"dets": dets, "poses": poses, "det_counts": cnt, "pose_counts": pc, "status": int(self.status.cpu()[0])}
+
+
+def hp_pp_decode(resp, conf, box, edge, skel, buf, img_w, img_h, det_thr, nms_thr, edge_thr, min_parts):
+    """Pose-proposal post-processing: resp, conf [N, K, Gh, Gw]; box [N, K, 4, Gh, Gw]; edge [N, L, Nh, Nw, Gh, Gw]
+    (fp32 on the GPU) -> buf (a PPBuffers)."""
+    N, K, Gh, Gw = resp.shape
+    Nh, Nw = edge.shape[2], edge.shape[3]
+    prm = _PPParams(det_thr, nms_thr, edge_thr, int(min_parts), img_w, img_h)
+    _check(lib().hp_pp_decode(_dev(resp, torch.float32), _dev(conf, torch.float32), _dev(box, torch.float32),
+                              _dev(edge, torch.float32), N, Gh, Gw, Nh, Nw, ctypes.byref(skel.c), ctypes.byref(prm),
+                              ctypes.byref(buf.dets), ctypes.byref(buf.poses), _dev(buf.status), _stream()), "hp_pp_decode")
 
 
 def hp_refine_peaks(maps_hi, K, buf):

@@ -337,6 +337,39 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
     return HP_OK;
 }
 
+int hp_pp_decode(const float *resp, const float *conf, const float *box, const float *edge, int N, int Gh, int Gw, int Nh,
+                 int Nw, const hp_skeleton *skel, const hp_pp_params *prm, const hp_pp_dets *dets, const hp_poses *poses,
+                 int32_t *status, void *stream)
+{
+    if (!resp || !conf || !box || !edge || !prm || !status) return HP_ERR_INVALID_ARG;
+    LimbTable tab;
+    HP_TRY(check_skeleton(skel, tab));
+    const int K = skel->n_parts, L = skel->n_limbs;
+    // the limbs must form a tree walked from the root in table order
+    {
+        bool reached[HP_MAX_PARTS] = {false};
+        reached[tab.a[0]] = true;
+        for (int l = 0; l < L; ++l) {
+            if (!reached[tab.a[l]] || reached[tab.b[l]]) return HP_ERR_INVALID_ARG;
+            reached[tab.b[l]] = true;
+        }
+    }
+    if (N <= 0 || Gh <= 0 || Gw <= 0 || Nh <= 0 || Nw <= 0 || (Nh & 1) == 0 || (Nw & 1) == 0) return HP_ERR_INVALID_ARG;
+    if (prm->min_parts < 0 || !(prm->img_w > 0.0f) || !(prm->img_h > 0.0f)) return HP_ERR_INVALID_ARG;
+    if (!(prm->det_thr == prm->det_thr) || !(prm->nms_thr == prm->nms_thr) || !(prm->edge_thr == prm->edge_thr))
+        return HP_ERR_INVALID_ARG;
+    if (!dets || !dets->cell || !dets->score || !dets->box || !dets->count || dets->cap <= 0) return HP_ERR_INVALID_ARG;
+    HP_TRY(check_poses(poses));
+    if ((long long)Gh * Gw > HP_PP_MAX_CELLS || Nh > 31 || Nw > 31 || N > 65535 || dets->cap > 1024 ||
+        (long long)K * dets->cap > 4096)
+        return HP_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
+    HP_LAUNCH(HP_K_PP_DETECT, launch_pp_detect(resp, conf, box, N, Gh, Gw, K, *prm, *dets, status, s));
+    HP_LAUNCH(HP_K_PP_PARSE, launch_pp_parse(edge, N, Gh, Gw, Nh, Nw, tab, K, L, *prm, *dets, *poses, status, s));
+    return HP_OK;
+}
+
 int hp_refine_peaks(const float *maps_hi, int N, int C_mem, int K, int H, int W, const hp_peaks *peaks, float *xf, float *yf,
                     void *stream)
 {
@@ -458,6 +491,8 @@ const char *hp_kernel_name(int id)
     case HP_K_DRAW: return "draw";
     case HP_K_SMOOTH: return "smooth";
     case HP_K_REFINE: return "refine";
+    case HP_K_PP_DETECT: return "pp_detect";
+    case HP_K_PP_PARSE: return "pp_parse";
     default: return "unknown";
     }
 }

@@ -205,6 +205,14 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
 hipError_t launch_refine(const float *maps, int N, int C_mem, int K, int H, int W, const hp_peaks &pk, float *xf, float *yf,
                          hipStream_t s);
 
+// Pose-proposal post-processing: the status word cleared, detections per (image, part), persons per image.
+hipError_t launch_pp_clear(int32_t *status, hipStream_t s);
+hipError_t launch_pp_detect(const float *resp, const float *conf, const float *box, int N, int Gh, int Gw, int K,
+                            const hp_pp_params &prm, const hp_pp_dets &dets, int32_t *status, hipStream_t s);
+hipError_t launch_pp_parse(const float *edge, int N, int Gh, int Gw, int Nh, int Nw, const LimbTable &T, int K, int L,
+                           const hp_pp_params &prm, const hp_pp_dets &dets, const hp_poses &poses, int32_t *status,
+                           hipStream_t s);
+
 // hp_postprocess on the first N images of outputs and a workspace laid out for N_layout >= N images;
 // check_only: validate the arguments, enqueue nothing.
 int postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int N_layout, int h, int w,

@@ -259,3 +259,32 @@ def test_refine_rejects_bad_calls(L):
     assert L.hp_refine_peaks(a, 0, 4, 3, 16, 16, byref(pk), x, y, None) == -1
     assert L.hp_refine_peaks(a, 1, 2, 3, 16, 16, byref(pk), x, y, None) == -1       # fewer channels than parts
     assert L.hp_refine_peaks(a, 1, 99, 99, 16, 16, byref(pk), x, y, None) == -5
+
+
+def test_pp_decode_rejects_bad_calls(L):
+    from paper_2108_11826_amd import binding as B
+    sk = B.Skeleton(3, np.array([0, 1], np.int32), np.array([1, 2], np.int32))
+    prm = B._PPParams(0.3, 0.3, 0.3, 1, 64.0, 64.0)
+    dets = B._PPDets(FAKE, FAKE, FAKE, FAKE, 8)
+    ps = B._Poses(FAKE, FAKE, FAKE, FAKE, 4)
+    a = c_void_p(FAKE)
+    ok = dict(resp=a, conf=a, box=a, edge=a, N=1, Gh=4, Gw=4, Nh=3, Nw=3, skel=byref(sk.c), prm=byref(prm), dets=byref(dets),
+              poses=byref(ps), status=a, stream=None)
+
+    def call(**kw):
+        x = dict(ok)
+        x.update(kw)
+        return L.hp_pp_decode(*[x[k] for k in ("resp", "conf", "box", "edge", "N", "Gh", "Gw", "Nh", "Nw", "skel", "prm", "dets",
+                                                "poses", "status", "stream")])
+
+    assert call(resp=None) == -1 and call(edge=None) == -1 and call(status=None) == -1 and call(prm=None) == -1
+    assert call(dets=None) == -1 and call(poses=None) == -1 and call(skel=None) == -1
+    assert call(N=0) == -1 and call(Gh=0) == -1 and call(Nh=4) == -1 and call(Nw=0) == -1       # neighbourhoods are odd
+    assert call(Gh=40, Gw=40) == -5 and call(Nh=33) == -5
+    assert call(dets=byref(B._PPDets(FAKE, FAKE, FAKE, FAKE, 2048))) == -5
+    # limbs that do not form a tree walked from the root: a child reached twice, a parent never reached
+    twice = B.Skeleton(3, np.array([0, 0, 1], np.int32), np.array([1, 2, 2], np.int32))
+    orphan = B.Skeleton(4, np.array([0, 2], np.int32), np.array([1, 3], np.int32))
+    assert call(skel=byref(twice.c)) == -1 and call(skel=byref(orphan.c)) == -1
+    assert call(prm=byref(B._PPParams(0.3, float("nan"), 0.3, 1, 64.0, 64.0))) == -1
+    assert call(prm=byref(B._PPParams(0.3, 0.3, 0.3, 1, 0.0, 64.0))) == -1
