@@ -355,6 +355,44 @@ def main():
                  "parity_with_oracle": vis_ok}
     del vis_src, vis_dst, vbuf
 
+    # the second algorithm class: pose-proposal post-processing on a synthetic batch (12 x 12 grid, 19 parts, 9 x 9 neighbourhood)
+    from synth import PPConfig, PP_COCO19, generate_pp
+    pp_cfg = PPConfig(101, PP_COCO19, 8, 12, 12, 4, dropout=0.1)
+    pp_in = generate_pp(pp_cfg)
+    pp_sk = pp_cfg.skeleton
+    pp_t = [torch.from_numpy(np.ascontiguousarray(pp_in[k])).to(dev) for k in ("resp", "conf", "box", "edge")]
+    pp_buf = hp.PPBuffers(pp_cfg.batch, pp_sk.n_parts, 64, 32, dev)
+    pp_skel = hp.Skeleton(pp_sk.n_parts, pp_sk.limb_a, pp_sk.limb_b)
+    pp_call = lambda: hp.hp_pp_decode(*pp_t, pp_skel, pp_buf, pp_cfg.img_w, pp_cfg.img_h, pp_cfg.det_thr, pp_cfg.nms_thr,
+                                      pp_cfg.edge_thr, pp_cfg.min_parts)
+    for _ in range(3):
+        pp_call()
+    torch.cuda.synchronize()
+    hp.hp_profile_begin(256)
+    for _ in range(20):
+        pp_call()
+    torch.cuda.synchronize()
+    pr = hp.hp_profile_end()
+    t0 = time.perf_counter()
+    for _ in range(200):
+        pp_call()
+    torch.cuda.synchronize()
+    pp_us = (time.perf_counter() - t0) / 200 * 1e6
+    pp_got = pp_buf.host()
+    pp_ora = oracle.pp_decode(pp_in["resp"], pp_in["conf"], pp_in["box"], pp_in["edge"], pp_sk.limb_a, pp_sk.limb_b, pp_cfg.img_w,
+                              pp_cfg.img_h, pp_cfg.det_thr, pp_cfg.nms_thr, pp_cfg.edge_thr, pp_cfg.min_parts)
+    pp_ok = pp_got["status"] == 0 and all(
+        np.array_equal(pp_got["poses"][n][0], pp_ora["poses"][n][0]) and np.array_equal(pp_got["poses"][n][2], pp_ora["poses"][n][2])
+        and all(np.array_equal(pp_got["dets"][n][k][0], pp_ora["dets"][n][k][0]) for k in range(pp_sk.n_parts))
+        for n in range(pp_cfg.batch))
+    parity = parity and bool(pp_ok)
+    pose_proposal = {"what": "hp_pp_decode: batch %d, %dx%d grid, %d parts, %dx%d neighbourhood, %d planted persons per image"
+                             % (pp_cfg.batch, pp_cfg.Gh, pp_cfg.Gw, pp_sk.n_parts, pp_cfg.Nh, pp_cfg.Nw, pp_cfg.n_people),
+                     "us_per_call": round(pp_us, 2), "frames_per_s": round(pp_cfg.batch / (pp_us * 1e-6), 1),
+                     "kernel_us": {k: round(1e3 * ms / nl, 2) for k, (ms, nl) in sorted(pr.items())},
+                     "bound": "latency (a few KB per image: one wavefront walks the limb tree of an image)",
+                     "parity_with_oracle": bool(pp_ok)}
+
     # the streaming front: frames arrive one at a time, the batch slot grows only while batches are running
     streaming = None if args.no_streaming else {
         "what": "hp_batcher_* (dynamic batch slot in front of hp_postprocess, Section 2.2.2): frames of this workload handed "
@@ -405,6 +443,7 @@ def main():
         "roofline": roofline, "roofline_fused": roofline_fused, "roofline_nms_hi": roofline_nms_hi,
         "roofline_scoring": roofline_scoring,
         "preprocess": preprocess,
+        "pose_proposal": pose_proposal,
         "smooth": smooth,
         "visualise": visualise,
         "streaming": streaming,
