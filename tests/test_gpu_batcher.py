@@ -236,7 +236,8 @@ def test_load_generator(copy):
     src = (r.cm, r.paf) if copy else (None, None)
     # one frame every 2 ms: the GPU is idle at every arrival
     lat, size, elapsed = m.hp_batcher_drive(r.b, 50, 2_000_000, *src)
-    assert np.all(size == 1) and np.all(lat > 0) and np.median(lat) < 1_000_000
+    # (a stall of the host thread for more than one period would pair two frames: allow a few)
+    assert np.count_nonzero(size == 1) >= 45 and size.max() <= 2 and np.all(lat > 0) and np.median(lat) < 1_000_000
     assert elapsed >= 49 * 2_000_000
     # as fast as the frames are taken: batches form
     lat, size, elapsed = m.hp_batcher_drive(r.b, 2000, 0, *src)
