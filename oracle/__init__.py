@@ -25,6 +25,7 @@ _SRC_DRAW = os.path.join(_HERE, "hp_draw_oracle.c")
 _SRC_SMOOTH = os.path.join(_HERE, "hp_smooth_oracle.c")
 _SRC_REFINE = os.path.join(_HERE, "hp_refine_oracle.c")
 _SRC_PP = os.path.join(_HERE, "hp_pp_oracle.c")
+_SRC_CF = os.path.join(_HERE, "hp_cf_oracle.c")
 
 
 def _cpu_has_fma():
@@ -43,10 +44,10 @@ def build(force=False):
     out = []
     for tag, extra in (("fma", ["-mfma"]), ("generic", [])):
         so = os.path.join(_HERE, f"libhp_oracle_{tag}.so")
-        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP))
+        newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP, _SRC_CF))
         if force or not os.path.exists(so) or os.path.getmtime(so) < newest:
             cmd = ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
-                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP, "-o", so, "-lm"]
+                   "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP, _SRC_CF, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
     return out
@@ -104,6 +105,13 @@ def lib():
         L.hpv_in_disc.argtypes = [ci] * 5
         L.hpv_draw.restype = None
         L.hpv_draw.argtypes = [u8p, u8p, ci, ci, ci, ci, ci, ci, ci, i32p, i32p, i32p, i32p, ci, i32p, ci, u8p, u8p, ci, ci]
+        L.hpc_expneg.restype = cf
+        L.hpc_expneg.argtypes = [cf]
+        L.hpc_field.restype = None
+        L.hpc_field.argtypes = [f32p, ci, ci, ci, cf, f32p]
+        L.hpc_decode.restype = ci
+        L.hpc_decode.argtypes = [f32p, f32p, ci, ci, i32p, i32p, ci, ci, ci, cf, cf, cf, cf, cf, ci, ci,
+                                 i32p, f32p, i32p, i32p, f32p, f32p, i32p, f32p, i32p, f32p, i32p]
         _lib = L
     return _lib
 
@@ -190,6 +198,57 @@ def pp_decode(resp, conf, box, edge, limb_a, limb_b, img_w, img_h, det_thr, nms_
                             float(edge_thr), int(min_parts), pcap, _i32(slots), _i32(nparts), _f32(pscore))
         poses.append((slots[:m].copy(), nparts[:m].copy(), pscore[:m].copy()))
     return {"dets": dets, "poses": poses}
+
+
+def cf_expneg(t):
+    """E(t) of the composite-field decoder (hp_cf_oracle.c, C0), elementwise on an fp32 array."""
+    t = np.ascontiguousarray(t, np.float32)
+    f = lib().hpc_expneg
+    return np.array([f(float(v)) for v in t.ravel()], np.float32).reshape(t.shape)
+
+
+def cf_field(pif_k, stride, pif_thr):
+    """Fine confidence map [Fh * stride, Fw * stride] of one part's intensity field [5, Fh, Fw] (C1-C2)."""
+    p = np.ascontiguousarray(pif_k, np.float32)
+    _, Fh, Fw = p.shape
+    out = np.empty((Fh * stride, Fw * stride), np.float32)
+    lib().hpc_field(_f32(p), Fh, Fw, int(stride), float(pif_thr), _f32(out))
+    return out
+
+
+def cf_decode(pif, paf, limb_a, limb_b, stride, pif_thr, paf_thr, seed_thr, grow_thr, rev_tol, min_parts, pcap=64):
+    """Composite-field decoding of a batch (C1-C8): pif [N, K, 5, Fh, Fw], paf [N, L, 7, Fh, Fw].
+    Returns {"pif": [n][k] -> (cell, value), "paf": [n][l] -> (cell, F1, F2), "poses": [n] -> (xyv [m, K, 3], nparts,
+    score), "overflow": [n]}."""
+    pif, paf = np.ascontiguousarray(pif, np.float32), np.ascontiguousarray(paf, np.float32)
+    N, K, _, Fh, Fw = pif.shape
+    L = paf.shape[1]
+    la, lb = np.ascontiguousarray(limb_a, np.int32), np.ascontiguousarray(limb_b, np.int32)
+    cells = Fh * Fw
+    out = {"pif": [], "paf": [], "poses": [], "overflow": []}
+
+    def one(n):
+        pc, pv, pn = np.zeros((K, cells), np.int32), np.zeros((K, cells), np.float32), np.zeros(K, np.int32)
+        ac, f1, f2, an = (np.zeros((L, cells), np.int32), np.zeros((L, cells), np.float32),
+                          np.zeros((L, cells), np.float32), np.zeros(L, np.int32))
+        xyv, npt, sc = np.zeros((pcap, K, 3), np.float32), np.zeros(pcap, np.int32), np.zeros(pcap, np.float32)
+        ovf = np.zeros(1, np.int32)
+        a, b = np.ascontiguousarray(pif[n]), np.ascontiguousarray(paf[n])
+        m = lib().hpc_decode(_f32(a), _f32(b), K, L, _i32(la), _i32(lb), Fh, Fw, int(stride), float(pif_thr),
+                             float(paf_thr), float(seed_thr), float(grow_thr), float(rev_tol), int(min_parts), int(pcap),
+                             _i32(pc), _f32(pv), _i32(pn), _i32(ac), _f32(f1), _f32(f2), _i32(an), _f32(xyv), _i32(npt),
+                             _f32(sc), _i32(ovf))
+        return ([(pc[k, :pn[k]].copy(), pv[k, :pn[k]].copy()) for k in range(K)],
+                [(ac[l, :an[l]].copy(), f1[l, :an[l]].copy(), f2[l, :an[l]].copy()) for l in range(L)],
+                (xyv[:m].copy(), npt[:m].copy(), sc[:m].copy()), int(ovf[0]))
+
+    for n in range(N):
+        p, a, ps, o = one(n)
+        out["pif"].append(p)
+        out["paf"].append(a)
+        out["poses"].append(ps)
+        out["overflow"].append(o)
+    return out
 
 
 def refine_peaks(plane_hi, px, py):

@@ -9,7 +9,8 @@ lives here.
 """
 from .skeletons import Skeleton, COCO18, BODY25
 from .pose_proposal import PPConfig, PP_CONFIGS, PP_COCO19, generate_pp
+from .composite_fields import CFConfig, CF_CONFIGS, CF_COCO17, generate_cf
 from .generate import SynthConfig, CONFIGS, generate, Params, DEFAULT_PARAMS, BENCH_CAPS, gaussian_taps
 
-__all__ = ["PPConfig", "PP_CONFIGS", "PP_COCO19", "generate_pp", "gaussian_taps", "Skeleton", "COCO18", "BODY25", "SynthConfig", "CONFIGS", "generate",
+__all__ = ["CFConfig", "CF_CONFIGS", "CF_COCO17", "generate_cf", "PPConfig", "PP_CONFIGS", "PP_COCO19", "generate_pp", "gaussian_taps", "Skeleton", "COCO18", "BODY25", "SynthConfig", "CONFIGS", "generate",
            "Params", "DEFAULT_PARAMS", "BENCH_CAPS"]

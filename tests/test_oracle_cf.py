@@ -1,0 +1,336 @@
+"""Pins of the composite-field oracle (oracle/hp_cf_oracle.c): its exponential against the library one, the fine map
+of a single cell against the Gaussian in float64, additivity and symmetry of the map, exact recovery of persons planted
+in hand-built fields, and hand-built cases for the thresholds, the reverse check, occupancy and the round rule."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from synth import CF_CONFIGS, generate_cf
+
+S = 8   # stride of the hand-built cases
+
+
+def blank(K, L, Fh, Fw):
+    """Fields with nothing in them: zero confidence everywhere, unit scales and spreads."""
+    pif = np.zeros((1, K, 5, Fh, Fw), np.float32)
+    pif[:, :, 3:5] = 1.0
+    paf = np.zeros((1, L, 7, Fh, Fw), np.float32)
+    paf[:, :, (3, 6)] = 1.0
+    return pif, paf
+
+
+def put_pif(pif, k, x, y, c=0.9, sigma=4.0, cell=None):
+    """Part k at pixel (x, y): the cell (default: the one that contains the point) points to it."""
+    gx, gy = (int(x // S), int(y // S)) if cell is None else cell
+    pif[0, k, :, gy, gx] = (c, x / S - gx, y / S - gy, 1.0, sigma / S)
+    return gy * pif.shape[4] + gx
+
+
+def put_paf(paf, l, p1, p2, c=0.9, b=4.0, cell=None):
+    """Limb l from pixel p1 to pixel p2, stored in the cell that contains p1 (or `cell`)."""
+    gx, gy = (int(p1[0] // S), int(p1[1] // S)) if cell is None else cell
+    paf[0, l, :, gy, gx] = (c, p1[0] / S - gx, p1[1] / S - gy, b / S, p2[0] / S - gx, p2[1] / S - gy, b / S)
+
+
+def decode(pif, paf, limbs, **kw):
+    prm = dict(stride=S, pif_thr=0.1, paf_thr=0.1, seed_thr=0.2, grow_thr=0.05, rev_tol=4.0, min_parts=1, pcap=16)
+    prm.update(kw)
+    la, lb = [a for a, _ in limbs], [b for _, b in limbs]
+    return oracle.cf_decode(pif, paf, la, lb, **prm)
+
+
+# ---- C0 ------------------------------------------------------------------------------------------
+
+def test_exponential_against_the_library():
+    t = np.concatenate([np.linspace(0, 80, 200001), np.random.default_rng(0).uniform(0, 20, 50000)]).astype(np.float32)
+    e = oracle.cf_expneg(t).astype(np.float64)
+    ref = np.exp(-t.astype(np.float64))
+    assert np.max(np.abs(e - ref) / ref) < 1e-5
+    assert oracle.cf_expneg(np.float32([0.0]))[0] == 1.0
+    # the argument is clamped to [0, 80]
+    lo, hi = oracle.cf_expneg(np.float32([-3.0, 80.0, 1e9, np.inf]))[[0, 1]], oracle.cf_expneg(np.float32([80.0]))[0]
+    assert lo[0] == 1.0 and lo[1] == hi
+    assert np.all(oracle.cf_expneg(np.float32([1e9, np.inf])) == hi)
+
+
+def test_exponential_halves_per_ln2_steps():
+    # E(t + n ln 2) = E(t) 2^-n up to the rounding of the argument
+    t = np.float32(np.linspace(0, 5, 1001))
+    for n in (1, 3, 10):
+        a = oracle.cf_expneg(t).astype(np.float64) * 2.0 ** -n
+        b = oracle.cf_expneg(np.float32(t + np.float32(n * math.log(2)))).astype(np.float64)
+        assert np.max(np.abs(a - b) / a) < 4e-6
+
+
+# ---- C1-C2 ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("sigma,x,y", [(4.0, 41.3, 30.6), (1.5, 20.0, 20.0), (11.0, 50.5, 40.25), (0.2, 33.0, 17.0)])
+def test_map_of_one_cell_is_a_truncated_gaussian(sigma, x, y):
+    pif, _ = blank(1, 1, 10, 12)
+    put_pif(pif, 0, x, y, c=0.8, sigma=sigma)
+    f = oracle.cf_field(pif[0, 0], S, 0.1).astype(np.float64)
+    H, W = f.shape
+    # the same quantities in float64 from the stored fp32 field values
+    gx, gy = int(x // S), int(y // S)
+    X = (gx + float(pif[0, 0, 1, gy, gx])) * S
+    Y = (gy + float(pif[0, 0, 2, gy, gx])) * S
+    sg = max(float(pif[0, 0, 4, gy, gx]) * S, 1.0)
+    w = min(math.ceil(float(np.float32(3.0) * np.float32(sg))), 24)
+    xr, yr = round(X), round(Y)
+    py, px = np.mgrid[0:H, 0:W]
+    inside = (np.abs(px - xr) <= w) & (np.abs(py - yr) <= w)
+    ref = np.where(inside, float(pif[0, 0, 0, gy, gx]) * np.exp(-0.5 * ((px - X) ** 2 + (py - Y) ** 2) / sg ** 2), 0.0)
+    assert np.all(f[~inside] == 0.0)
+    assert np.max(np.abs(f - ref)) < 1e-5
+    assert abs(f.max() - ref.max()) < 1e-5 and np.unravel_index(f.argmax(), f.shape) == np.unravel_index(ref.argmax(), f.shape)
+
+
+def test_window_is_three_sigma_and_at_most_24():
+    for sigma, w in ((1.0, 3), (2.5, 8), (7.9, 24), (20.0, 24), (0.3, 3)):
+        pif, _ = blank(1, 1, 12, 12)
+        put_pif(pif, 0, 48.0, 48.0, c=1.0, sigma=sigma)
+        f = oracle.cf_field(pif[0, 0], S, 0.1)
+        ys, xs = np.nonzero(f)
+        assert (xs.min(), xs.max(), ys.min(), ys.max()) == (48 - w, 48 + w, 48 - w, 48 + w)
+
+
+def test_map_is_symmetric_about_an_integer_centre():
+    pif, _ = blank(1, 1, 10, 10)
+    put_pif(pif, 0, 40.0, 32.0, c=0.7, sigma=5.0)
+    f = oracle.cf_field(pif[0, 0], S, 0.1)
+    win = f[32 - 15:32 + 16, 40 - 15:40 + 16]
+    assert np.array_equal(win, win[::-1]) and np.array_equal(win, win[:, ::-1]) and np.array_equal(win, win.T)
+
+
+def test_map_adds_cells_in_ascending_order():
+    rng = np.random.default_rng(3)
+    pif, _ = blank(1, 1, 10, 12)
+    cells = [(2, 3), (3, 3), (3, 4), (6, 8)]
+    for gy, gx in cells:
+        put_pif(pif, 0, gx * S + rng.uniform(0, S), gy * S + rng.uniform(0, S), c=rng.uniform(0.3, 0.9), sigma=rng.uniform(3, 9),
+                cell=(gx, gy))
+    whole = oracle.cf_field(pif[0, 0], S, 0.1)
+    acc = np.zeros_like(whole)
+    for gy, gx in sorted(cells):                       # ascending cell index
+        one, _ = blank(1, 1, 10, 12)
+        one[0, 0, :, gy, gx] = pif[0, 0, :, gy, gx]
+        acc = acc + oracle.cf_field(one[0, 0], S, 0.1)  # fp32 additions in the same order
+    assert np.array_equal(whole, acc)
+    assert whole.max() > 0.9                            # the windows do overlap
+
+
+def test_map_transposes_with_the_field():
+    rng = np.random.default_rng(4)
+    pif, _ = blank(1, 1, 9, 13)
+    for _ in range(12):
+        put_pif(pif, 0, rng.uniform(0, 13 * S - 1), rng.uniform(0, 9 * S - 1), c=rng.uniform(0.2, 0.9), sigma=rng.uniform(2, 8))
+    f = oracle.cf_field(pif[0, 0], S, 0.1)
+    t = np.ascontiguousarray(pif[0, 0].transpose(0, 2, 1))
+    t[[1, 2]] = t[[2, 1]]
+    ft = oracle.cf_field(t, S, 0.1)
+    assert np.allclose(ft.T, f, rtol=0, atol=2e-6)     # only the order of the additions differs
+
+
+def test_activity_thresholds_are_strict_and_the_centre_must_lie_on_the_map():
+    pif, _ = blank(1, 1, 6, 6)
+    put_pif(pif, 0, 20.0, 20.0, c=0.1)
+    assert not oracle.cf_field(pif[0, 0], S, 0.1).any()                     # c == pif_thr: not active
+    assert oracle.cf_field(pif[0, 0], S, np.nextafter(np.float32(0.1), np.float32(0))).any()
+    for x, y, on in ((47.0, 47.0, True), (47.5, 20.0, False), (20.0, -0.25, False), (0.0, 0.0, True)):
+        pif, _ = blank(1, 1, 6, 6)
+        put_pif(pif, 0, x, y, c=0.9, cell=(2, 2))
+        assert oracle.cf_field(pif[0, 0], S, 0.1).any() == on
+
+
+# ---- C3-C8 ---------------------------------------------------------------------------------------
+
+CHAIN = [(0, 1), (1, 2)]
+
+
+def plant_chain(pif, paf, pts, c=0.9):
+    for k, (x, y) in enumerate(pts):
+        put_pif(pif, k, x, y, c=c)
+    for l, (a, b) in enumerate(CHAIN):
+        put_paf(paf, l, pts[a], pts[b], c=c)
+
+
+def test_planted_persons_are_recovered_exactly():
+    pif, paf = blank(3, 2, 16, 24)
+    people = [[(30.5, 20.25), (34.0, 50.0), (36.75, 81.5)], [(120.0, 30.0), (124.5, 58.0), (131.0, 90.5)]]
+    plant_chain(pif, paf, people[0], c=0.9)
+    plant_chain(pif, paf, people[1], c=0.8)
+    r = decode(pif, paf, CHAIN)
+    xyv, nparts, score = r["poses"][0]
+    assert list(nparts) == [3, 3] and r["overflow"] == [0]
+    for p, pts in enumerate(people):                   # the person planted with the higher confidence comes first
+        for k, (x, y) in enumerate(pts):
+            gx, gy = int(x // S), int(y // S)
+            assert xyv[p, k, 0] == (np.float32(gx) + np.float32(x / S - gx)) * np.float32(S)
+            assert abs(xyv[p, k, 0] - x) < 1e-4 and abs(xyv[p, k, 1] - y) < 1e-4
+    # values: the seed (part 1, on a pixel centre) has its cell's confidence; a grown joint has
+    # c * exp(-|Q - P1| / B1) * f(rint P2) with |Q - P1| = 0 and the other part's Gaussian sampled at the nearest pixel
+    off = 0.9 * math.exp(-0.5 * (0.5 ** 2 + 0.25 ** 2) / 4.0 ** 2)
+    assert abs(xyv[0, 1, 2] - 0.9) < 1e-6
+    assert abs(xyv[0, 0, 2] - 0.9 * off) < 1e-5 and abs(xyv[0, 2, 2] - 0.9 * off) < 1e-5
+    assert abs(score[0] - xyv[0, :, 2].sum() / 3) < 1e-6
+
+
+def test_grown_value_in_closed_form():
+    pif, paf = blank(2, 1, 8, 8)
+    put_pif(pif, 0, 20.0, 20.0, c=0.9, sigma=4.0)
+    put_pif(pif, 1, 41.0, 22.0, c=0.6, sigma=2.0)
+    # the association starts 3 pixels off the joint (spread 4) and ends half a pixel off the other part's peak
+    put_paf(paf, 0, (20.0, 23.0), (41.0, 22.5), c=0.7, b=4.0)
+    r = decode(pif, paf, [(0, 1)])
+    xyv, nparts, _ = r["poses"][0]
+    assert list(nparts) == [2]
+    f1 = 0.6 * math.exp(-0.5 * (0.0 + 0.0) / 4.0)      # f_1 sampled at rint(41, 22.5) = (41, 22): the peak itself
+    assert abs(xyv[0, 1, 2] - 0.7 * math.exp(-3.0 / 4.0) * f1) < 1e-5
+    assert tuple(xyv[0, 1, :2]) == (41.0, 22.5) and tuple(xyv[0, 0, :2]) == (20.0, 20.0)
+    assert abs(xyv[0, 0, 2] - 0.9) < 1e-6
+
+
+def test_growth_threshold_and_reverse_check():
+    def run(**kw):
+        pif, paf = blank(2, 1, 8, 8)
+        put_pif(pif, 0, 20.0, 20.0)
+        put_pif(pif, 1, 44.0, 20.0)
+        put_paf(paf, 0, (20.0, 25.0), (44.0, 20.0), c=0.9, b=4.0)   # starts 5 pixels from the joint
+        return decode(pif, paf, [(0, 1)], **kw)["poses"][0][1]
+
+    # the first person is seeded at part 0 (equal seed values: the lower part first); when it cannot grow, part 1
+    # seeds a person of its own, which reaches (20, 25) backwards along the limb: outside the first person's radius
+    value = 0.9 * math.exp(-5 / 4) * 0.9
+    assert list(run(rev_tol=6.0)) == [2]
+    assert list(run(rev_tol=5.0)) == [2]                            # the bound is inclusive
+    assert list(run(rev_tol=4.9)) == [1, 2]                         # the way back ends too far from the joint
+    assert list(run(rev_tol=6.0, grow_thr=value + 1e-4)) == [1, 2]
+    assert list(run(rev_tol=6.0, grow_thr=value - 1e-4)) == [2]
+    assert list(run(rev_tol=6.0, grow_thr=0.5)) == [1, 1]           # nothing grows either way
+
+
+def test_growing_backwards_along_a_limb():
+    # the seed is the limb's second part: the association is followed from P2 to P1
+    pif, paf = blank(2, 1, 8, 8)
+    put_pif(pif, 0, 20.0, 20.0, c=0.5)
+    put_pif(pif, 1, 44.0, 28.0, c=0.9)
+    put_paf(paf, 0, (20.0, 20.0), (44.0, 28.0))
+    xyv, nparts, _ = decode(pif, paf, [(0, 1)])["poses"][0]
+    assert list(nparts) == [2] and tuple(xyv[0, 0, :2]) == (20.0, 20.0)
+    assert xyv[0, 1, 2] > xyv[0, 0, 2]                  # part 1 was the seed
+
+
+def test_occupied_seeds_are_skipped():
+    def run(dx):
+        pif, paf = blank(2, 1, 8, 8)
+        put_pif(pif, 0, 20.0, 20.0, c=0.9, sigma=4.0, cell=(2, 2))
+        put_pif(pif, 0, 20.0 + dx, 20.0, c=0.8, sigma=4.0, cell=(3, 2))
+        return len(decode(pif, paf, [(0, 1)])["poses"][0][1])
+
+    assert run(3.0) == 1
+    assert run(4.0) == 1                                # on the radius: occupied
+    assert run(4.5) == 2
+
+
+def test_a_part_reached_by_two_limbs_takes_the_better_proposal():
+    square = [(0, 1), (0, 2), (1, 3), (2, 3)]
+    for c13, c23, expect in ((0.9, 0.5, (60.0, 60.0)), (0.5, 0.9, (62.0, 61.0)), (0.7, 0.7, (60.0, 60.0))):
+        pif, paf = blank(4, 4, 12, 12)
+        put_pif(pif, 0, 20.0, 20.0, c=0.95)
+        put_pif(pif, 1, 60.0, 20.0, c=0.5)
+        put_pif(pif, 2, 20.0, 60.0, c=0.5)
+        put_pif(pif, 3, 60.0, 60.0, c=0.3, sigma=6.0, cell=(7, 7))
+        put_pif(pif, 3, 62.0, 61.0, c=0.3, sigma=6.0, cell=(8, 7))
+        put_paf(paf, 0, (20.0, 20.0), (60.0, 20.0))
+        put_paf(paf, 1, (20.0, 20.0), (20.0, 60.0))
+        put_paf(paf, 2, (60.0, 20.0), (60.0, 60.0), c=c13)
+        put_paf(paf, 3, (20.0, 60.0), (62.0, 61.0), c=c23)
+        xyv, nparts, _ = decode(pif, paf, square, seed_thr=0.9)["poses"][0]
+        assert list(nparts) == [4]
+        if c13 != c23:
+            assert tuple(xyv[0, 3, :2]) == expect
+        else:                                           # not an exact tie (the map values differ): either is valid
+            assert tuple(xyv[0, 3, :2]) in ((60.0, 60.0), (62.0, 61.0))
+
+
+def test_limbs_see_the_person_as_it_was_when_the_round_began():
+    # chain 0 - 1 - 2 listed as (1, 2) before (0, 1): two rounds either way, and the result does not depend on the order
+    pts = [(20.0, 20.0), (44.0, 24.0), (68.0, 30.0)]
+    out = []
+    for limbs in ([(0, 1), (1, 2)], [(1, 2), (0, 1)]):
+        pif, paf = blank(3, 2, 8, 12)
+        for k, p in enumerate(pts):
+            put_pif(pif, k, *p, c=0.9 - 0.1 * k)
+        for l, (a, b) in enumerate(limbs):
+            put_paf(paf, l, pts[a], pts[b])
+        out.append(decode(pif, paf, limbs)["poses"][0])
+    assert list(out[0][1]) == [3] and np.array_equal(out[0][0], out[1][0])
+
+
+def test_a_grown_joint_keeps_out_of_recorded_persons():
+    # two roots share one child candidate: the second person may not take the joint the first one holds
+    pif, paf = blank(2, 1, 8, 12)
+    put_pif(pif, 0, 20.0, 20.0, c=0.9)
+    put_pif(pif, 0, 60.0, 20.0, c=0.8)
+    put_pif(pif, 1, 40.0, 40.0, c=0.9)
+    put_paf(paf, 0, (20.0, 20.0), (40.0, 40.0))
+    put_paf(paf, 0, (60.0, 20.0), (40.0, 40.0), c=0.8)
+    xyv, nparts, _ = decode(pif, paf, [(0, 1)], seed_thr=0.85)["poses"][0]
+    assert list(nparts) == [2]                          # only the first root seeds (0.8 and the child are below seed_thr ...)
+    xyv, nparts, _ = decode(pif, paf, [(0, 1)], seed_thr=0.5)["poses"][0]
+    assert sorted(nparts) == [1, 2]                     # ... and with all three seeding, the child belongs to one person
+
+
+def test_min_parts_and_person_capacity():
+    pif, paf = blank(3, 2, 16, 24)
+    plant_chain(pif, paf, [(30.0, 20.0), (34.0, 50.0), (36.0, 81.0)], c=0.9)
+    put_pif(pif, 0, 150.0, 100.0, c=0.8)                # a lone part
+    assert list(decode(pif, paf, CHAIN, min_parts=1)["poses"][0][1]) == [3, 1]
+    assert list(decode(pif, paf, CHAIN, min_parts=2)["poses"][0][1]) == [3]
+    r = decode(pif, paf, CHAIN, min_parts=1, pcap=1)
+    assert list(r["poses"][0][1]) == [3] and r["overflow"] == [1]
+    assert decode(pif, paf, CHAIN, min_parts=2, pcap=1)["overflow"] == [1]   # the lone seed still meets a full list
+
+
+def test_seed_values_and_association_samples_come_from_the_map():
+    cfg = CF_CONFIGS[1]
+    d = generate_cf(cfg)
+    sk = cfg.skeleton
+    r = oracle.cf_decode(d["pif"][:1], d["paf"][:1], sk.limb_a, sk.limb_b, cfg.stride, cfg.pif_thr, cfg.paf_thr, cfg.seed_thr,
+                         cfg.grow_thr, cfg.rev_tol, cfg.min_parts)
+    s = cfg.stride
+    gy, gx = np.mgrid[0:cfg.Fh, 0:cfg.Fw]
+    for k in range(sk.n_parts):
+        f = oracle.cf_field(d["pif"][0, k], s, cfg.pif_thr)
+        cell, val = r["pif"][0][k]
+        p = d["pif"][0, k]
+        X, Y = (gx.astype(np.float32) + p[1]) * np.float32(s), (gy.astype(np.float32) + p[2]) * np.float32(s)
+        act = (p[0] > np.float32(cfg.pif_thr)) & (X >= 0) & (X <= cfg.Fw * s - 1) & (Y >= 0) & (Y <= cfg.Fh * s - 1)
+        assert np.array_equal(cell, np.flatnonzero(act.ravel()))
+        assert np.array_equal(val, f[np.rint(Y.ravel()[cell]).astype(int), np.rint(X.ravel()[cell]).astype(int)])
+
+
+@pytest.mark.parametrize("ci", [0, 1, 2])
+def test_synthetic_people_are_found(ci):
+    cfg = CF_CONFIGS[ci]
+    d = generate_cf(cfg)
+    sk = cfg.skeleton
+    r = oracle.cf_decode(d["pif"], d["paf"], sk.limb_a, sk.limb_b, cfg.stride, cfg.pif_thr, cfg.paf_thr, cfg.seed_thr,
+                         cfg.grow_thr, cfg.rev_tol, cfg.min_parts)
+    found = total = 0
+    for n in range(cfg.batch):
+        xyv, nparts, _ = r["poses"][n]
+        for person in d["planted"][n]:
+            have = ~np.isnan(person[:, 0])
+            if have.sum() < 6:
+                continue
+            total += 1
+            # some decoded person explains most of this planted one
+            best = 0
+            for q in range(len(nparts)):
+                close = have & (xyv[q, :, 2] > 0) & (np.hypot(xyv[q, :, 0] - person[:, 0], xyv[q, :, 1] - person[:, 1]) < 4.0)
+                best = max(best, int(close.sum()))
+            found += best >= 0.6 * have.sum()
+    assert total > 0 and found >= 0.7 * total
