@@ -71,7 +71,8 @@ enum {
     HP_MAX_CCAP = 1 << 20, /* largest candidate capacity */
     HP_MAX_SAMPLES = 64,
     HP_MAX_TAPS = 65,      /* longest tap vector of hp_smooth */
-    HP_PP_MAX_CELLS = 1024 /* most grid cells (Gh * Gw) of hp_pp_decode */
+    HP_PP_MAX_CELLS = 1024, /* most grid cells (Gh * Gw) of hp_pp_decode */
+    HP_CF_MAX_SEEDS = 4096  /* most seeds per image of hp_cf_decode: n_parts * lists->cap may not exceed it */
 };
 
 /* Skeleton: limb l joins part limb_a[l] to part limb_b[l] and owns PAF channels
@@ -320,6 +321,105 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
                  const hp_pp_params *prm, const hp_pp_dets *dets, const hp_poses *poses,
                  int32_t *status, void *stream);
 
+/* ---- Decoder of the composite-field family ----------------------------------------------------
+ * Section 2.3 lists PifPaf as the third algorithm class the engine post-processes and gives no
+ * arithmetic.  The cited method predicts, on an Fh x Fw grid of cells `stride` pixels apart, a part
+ * intensity field per part (confidence c, a vector to the part, a spread unused by decoding, a
+ * scale sigma) and a part association field per limb (confidence c and, for each of the limb's two
+ * parts, a vector and a spread); its decoder builds a fine confidence map per part (one Gaussian of
+ * width sigma per cell, placed where the cell's vector points), seeds persons at the cells with
+ * the highest map values and grows them along the association fields, an association a scoring
+ * c * exp(-|x - a1| / b1) * f2(a2) for a joint at x, each step confirmed by the reverse search,
+ * found joints suppressing later seeds.  Inputs, device fp32, vectors, spreads and scales in cell units:
+ *   pif [N][K][5][Fh][Fw]   (c, x, y, b, sigma);
+ *   paf [N][L][7][Fh][Fw]   (c, x1, y1, b1, x2, y2, b2), limb l joining parts (limb_a[l], limb_b[l]).
+ * The limb table may hold cycles.  Rules (fp32, one operation per step as written; s = stride,
+ * the map is H = Fh * s by W = Fw * s):
+ *   C0 E(t) ~ exp(-t) in fixed arithmetic: tc = max(min(t, 80), 0); y = tc * 0x1.715476p+0f;
+ *      n = rint(y); z = (y - n) * -0x1.62e430p-1f; p = 0x1.6c16c2p-10f, then p = fma(p, z, q) for
+ *      q = 0x1.111112p-7f, 0x1.555556p-5f, 0x1.555556p-3f, 0.5f, 1.0f, 1.0f; E = ldexp(p, -n);
+ *   C1 cell (gy, gx) of part k points to X = ((float)gx + x) * s, Y = ((float)gy + y) * s and is
+ *      active when c > pif_thr, 0 <= X <= W - 1 and 0 <= Y <= H - 1; sg = max(sigma * s, 1);
+ *      window w = (int)min(ceil(3 * sg), 24); nearest pixel (xr, yr) = (rint X, rint Y), ties to even;
+ *   C2 map: f_k(px, py) = sum over the active cells of k, ascending cell index, with
+ *      |px - xr| <= w and |py - yr| <= w, of c * E(d2 * inv); d2 = dx * dx + dy * dy,
+ *      dx = (float)px - X, inv = 0.5f / (sg * sg);
+ *   C3 an active cell's value is v = f_k(xr, yr); it is a seed when v > seed_thr; seeds are taken by
+ *      (v descending, part ascending, cell ascending);
+ *   C4 cell (gy, gx) of limb l: P1 = (((float)gx + x1) * s, ((float)gy + y1) * s), P2 likewise; active
+ *      when c > paf_thr and both points lie on the map (as in C1); B1 = max(b1 * s, 1), B2 likewise;
+ *      F1 = f_a(rint P1), F2 = f_b(rint P2).  For a joint of part a at Q the cell scores
+ *      (c * E(|Q - P1| / B1)) * F2 and proposes P2 for part b; for a joint of part b it scores
+ *      (c * E(|Q - P2| / B2)) * F1 and proposes P1; |.| = sqrt(dx * dx + dy * dy).  A search takes
+ *      the active cell with the largest score (ties: the lowest cell);
+ *   C5 a person starts as the seed's joint (position (X, Y), value v, radius sg) and grows in
+ *      rounds.  A round looks at every limb of which the person held exactly one part when the
+ *      round began: the search from that joint must score above grow_thr; the search back from the
+ *      proposed point T over the same limb in the other direction must find a cell (score above 0)
+ *      whose proposal lies within rev_tol of the joint (dx * dx + dy * dy <= rev_tol * rev_tol); T
+ *      must not be occupied (C7) for its part.  Of a round's proposals for one part the highest
+ *      score wins (ties: the earlier limb); the part is then held at T, its value that score, its
+ *      radius max(sigma * s, 1) of the part's intensity cell ((int)rint(T.y) / s, (int)rint(T.x) / s).
+ *      Growing ends with the first round that adds nothing;
+ *   C6 a person with at least min_parts parts is recorded: score = (sum of the held values in part
+ *      order, from 0) / (float)K;
+ *   C7 (x, y) is occupied for part k when a recorded person holds k at (xj, yj) with radius r and
+ *      (x - xj)^2 + (y - yj)^2 <= r * r; a seed occupied for its part is skipped;
+ *   C8 decoding of an image stops when a seed passes C7 while poses->cap persons are recorded;
+ *      HP_STATUS_POSE_OVERFLOW is then set.
+ * `lists` receives, in ascending cell order, the active cells of every (image, part) with their
+ * values and the active cells of every (image, limb) with F1 and F2; counts are the required ones,
+ * HP_STATUS_PEAK_OVERFLOW / HP_STATUS_CAND_OVERFLOW tell that a list needed more than cap / acap
+ * entries (everything computed from it is then incomplete).  `poses`: xyv holds (x, y, value) per
+ * part, zeros for a part not held.  `status`: device int32, overwritten.
+ * Limits: 1 <= lists->cap <= 512, n_parts * lists->cap <= HP_CF_MAX_SEEDS, lists->acap >= 1,
+ * n_parts * poses->cap <= 1536, Fw * stride and Fh * stride below 2^23, thresholds not negative.
+ * `workspace`: hp_cf_workspace_bytes(N, n_parts, n_limbs, cap, acap) bytes of device memory, no
+ * initialisation needed.  Allocates nothing; enqueues four kernels on `stream`. */
+typedef struct {
+    float pif_thr;
+    float paf_thr;
+    float seed_thr;
+    float grow_thr;
+    float rev_tol;
+    int32_t min_parts;
+    int32_t stride;
+} hp_cf_params;
+
+typedef struct {
+    int32_t *pif_cell;    /* device [N][K][cap], gy * Fw + gx */
+    float *pif_val;       /* device [N][K][cap] */
+    int32_t *pif_count;   /* device [N][K] */
+    int32_t *paf_cell;    /* device [N][L][acap] */
+    float *paf_f1;        /* device [N][L][acap] */
+    float *paf_f2;        /* device [N][L][acap] */
+    int32_t *paf_count;   /* device [N][L] */
+    int32_t cap;
+    int32_t acap;
+} hp_cf_lists;
+
+typedef struct {
+    float *xyv;           /* device [N][cap][K][3] */
+    int32_t *nparts;      /* device [N][cap] */
+    float *score;         /* device [N][cap] */
+    int32_t *count;       /* device [N] */
+    int32_t cap;
+} hp_cf_poses;
+
+size_t hp_cf_workspace_bytes(int N, int n_parts, int n_limbs, int cap, int acap);
+
+int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, const hp_skeleton *skel,
+                 const hp_cf_params *prm, const hp_cf_lists *lists, const hp_cf_poses *poses,
+                 void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
+/* The fine confidence maps of rule C2 as arrays: out device fp32 [N][K][Fh * stride][Fw * stride].
+ * Uses pif_thr and stride of `prm`; cell, val and count as in hp_cf_lists ([N][K][cap], [N][K]);
+ * `workspace`: hp_cf_workspace_bytes(N, K, 0, cap, 0); cap <= 512, N * K <= 65535.
+ * HP_STATUS_PEAK_OVERFLOW as above. */
+int hp_cf_field(const float *pif, int N, int K, int Fh, int Fw, const hp_cf_params *prm, int32_t *cell,
+                float *val, int32_t *count, int cap, float *out, void *workspace, size_t ws_bytes,
+                int32_t *status, void *stream);
+
 /* ---- Streaming front with a dynamic batch slot ---------------------------------------------
  * Section 2.2.1 runs the operators asynchronously, a FIFO between each pair; Section 2.2.2 puts a
  * batch slot in front of the GPU operator that collects more input tensors only while the GPU is
@@ -464,7 +564,11 @@ typedef enum {
     HP_K_REFINE = 14,        /* hp_refine_peaks */
     HP_K_PP_DETECT = 15,     /* hp_pp_decode: scores, boxes and suppression per (image, part) */
     HP_K_PP_PARSE = 16,      /* hp_pp_decode: the limb tree walked per image */
-    HP_K_COUNT = 17
+    HP_K_CF_PIF = 17,        /* hp_cf_decode, hp_cf_field: active intensity cells and their map values */
+    HP_K_CF_PAF = 18,        /* hp_cf_decode: active associations and their map samples */
+    HP_K_CF_GROW = 19,       /* hp_cf_decode: seeds and persons per image */
+    HP_K_CF_FIELD = 20,      /* hp_cf_field: the fine maps written out */
+    HP_K_COUNT = 21
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

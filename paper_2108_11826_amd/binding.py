@@ -17,11 +17,11 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_pp_decode", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_pp_decode", "hp_cf_decode", "hp_cf_field", "hp_cf_workspace_bytes", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
-HP_K_COUNT = 17
+HP_K_COUNT = 21
 
 
 class HPError(RuntimeError):
@@ -56,6 +56,20 @@ class _Poses(Structure):
 class _PPParams(Structure):
     _fields_ = [("det_thr", c_float), ("nms_thr", c_float), ("edge_thr", c_float), ("min_parts", c_int32),
                 ("img_w", c_float), ("img_h", c_float)]
+
+
+class _CFParams(Structure):
+    _fields_ = [("pif_thr", c_float), ("paf_thr", c_float), ("seed_thr", c_float), ("grow_thr", c_float),
+                ("rev_tol", c_float), ("min_parts", c_int32), ("stride", c_int32)]
+
+
+class _CFLists(Structure):
+    _fields_ = [("pif_cell", c_void_p), ("pif_val", c_void_p), ("pif_count", c_void_p), ("paf_cell", c_void_p),
+                ("paf_f1", c_void_p), ("paf_f2", c_void_p), ("paf_count", c_void_p), ("cap", c_int32), ("acap", c_int32)]
+
+
+class _CFPoses(Structure):
+    _fields_ = [("xyv", c_void_p), ("nparts", c_void_p), ("score", c_void_p), ("count", c_void_p), ("cap", c_int32)]
 
 
 class _PPDets(Structure):
@@ -125,6 +139,14 @@ def lib():
         L.hp_draw_poses.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
                                     POINTER(_Peaks), POINTER(_Poses), POINTER(ctypes.c_uint8), POINTER(ctypes.c_uint8),
                                     c_int, c_int, c_void_p, c_size_t, c_void_p]
+        L.hp_cf_workspace_bytes.restype = c_size_t
+        L.hp_cf_workspace_bytes.argtypes = [c_int] * 5
+        L.hp_cf_decode.restype = c_int
+        L.hp_cf_decode.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, POINTER(_Skeleton), POINTER(_CFParams),
+                                   POINTER(_CFLists), POINTER(_CFPoses), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_cf_field.restype = c_int
+        L.hp_cf_field.argtypes = [c_void_p, c_int, c_int, c_int, c_int, POINTER(_CFParams), c_void_p, c_void_p, c_void_p,
+                                  c_int, c_void_p, c_void_p, c_size_t, c_void_p, c_void_p]
         L.hp_draw_workspace_bytes.restype = c_size_t
         L.hp_draw_workspace_bytes.argtypes = [c_int] * 6
         L.hp_batcher_create.restype = c_int
@@ -395,6 +417,75 @@ def hp_pp_decode(resp, conf, box, edge, skel, buf, img_w, img_h, det_thr, nms_th
     _check(lib().hp_pp_decode(_dev(resp, torch.float32), _dev(conf, torch.float32), _dev(box, torch.float32),
                               _dev(edge, torch.float32), N, Gh, Gw, Nh, Nw, ctypes.byref(skel.c), ctypes.byref(prm),
                               ctypes.byref(buf.dets), ctypes.byref(buf.poses), _dev(buf.status), _stream()), "hp_pp_decode")
+
+
+class CFBuffers:
+    """Caller-owned outputs and workspace of hp_cf_decode: the active cells per (image, part) and (image, limb), and the
+    persons per image."""
+
+    def __init__(self, N, K, L, cap, acap, pcap, device="cuda:0"):
+        self.N, self.K, self.L, self.cap, self.acap, self.pcap = N, K, L, cap, acap, pcap
+        i32, f32 = dict(dtype=torch.int32, device=device), dict(dtype=torch.float32, device=device)
+        self.pif_cell, self.pif_val = torch.zeros((N, K, cap), **i32), torch.zeros((N, K, cap), **f32)
+        self.pif_count = torch.zeros((N, K), **i32)
+        self.paf_cell, self.paf_count = torch.zeros((N, L, acap), **i32), torch.zeros((N, L), **i32)
+        self.paf_f1, self.paf_f2 = torch.zeros((N, L, acap), **f32), torch.zeros((N, L, acap), **f32)
+        self.xyv, self.nparts = torch.zeros((N, pcap, K, 3), **f32), torch.zeros((N, pcap), **i32)
+        self.pscore, self.pose_count = torch.zeros((N, pcap), **f32), torch.zeros((N,), **i32)
+        self.status = torch.zeros((1,), **i32)
+        self.workspace = torch.empty((hp_cf_workspace_bytes(N, K, L, cap, acap),), dtype=torch.uint8, device=device)
+        self.lists = _CFLists(self.pif_cell.data_ptr(), self.pif_val.data_ptr(), self.pif_count.data_ptr(),
+                              self.paf_cell.data_ptr(), self.paf_f1.data_ptr(), self.paf_f2.data_ptr(),
+                              self.paf_count.data_ptr(), cap, acap)
+        self.poses = _CFPoses(self.xyv.data_ptr(), self.nparts.data_ptr(), self.pscore.data_ptr(),
+                              self.pose_count.data_ptr(), pcap)
+
+    def host(self):
+        """{"pif": [n][k] -> (cell, value), "paf": [n][l] -> (cell, F1, F2), "poses": [n] -> (xyv, nparts, score), ...}."""
+        pn, an, pc = self.pif_count.cpu().numpy(), self.paf_count.cpu().numpy(), self.pose_count.cpu().numpy()
+        pcell, pval = self.pif_cell.cpu().numpy(), self.pif_val.cpu().numpy()
+        acell, f1, f2 = self.paf_cell.cpu().numpy(), self.paf_f1.cpu().numpy(), self.paf_f2.cpu().numpy()
+        xyv, npt, ps = self.xyv.cpu().numpy(), self.nparts.cpu().numpy(), self.pscore.cpu().numpy()
+        pif = [[(pcell[n, k, :min(pn[n, k], self.cap)].copy(), pval[n, k, :min(pn[n, k], self.cap)].copy())
+                for k in range(self.K)] for n in range(self.N)]
+        paf = [[tuple(a[n, l, :min(an[n, l], self.acap)].copy() for a in (acell, f1, f2)) for l in range(self.L)]
+               for n in range(self.N)]
+        poses = [(xyv[n, :pc[n]].copy(), npt[n, :pc[n]].copy(), ps[n, :pc[n]].copy()) for n in range(self.N)]
+        return {"pif": pif, "paf": paf, "poses": poses, "pif_counts": pn, "paf_counts": an, "pose_counts": pc,
+                "status": int(self.status.cpu()[0])}
+
+
+def hp_cf_workspace_bytes(N, K, L, cap, acap):
+    return int(lib().hp_cf_workspace_bytes(int(N), int(K), int(L), int(cap), int(acap)))
+
+
+def hp_cf_decode(pif, paf, skel, buf, stride, pif_thr, paf_thr, seed_thr, grow_thr, rev_tol, min_parts):
+    """Composite-field decoding: pif [N, K, 5, Fh, Fw], paf [N, L, 7, Fh, Fw] (fp32 on the GPU) -> buf (a CFBuffers)."""
+    N, K, _, Fh, Fw = pif.shape
+    prm = _CFParams(pif_thr, paf_thr, seed_thr, grow_thr, rev_tol, int(min_parts), int(stride))
+    _check(lib().hp_cf_decode(_dev(pif, torch.float32), _dev(paf, torch.float32), N, Fh, Fw, ctypes.byref(skel.c),
+                              ctypes.byref(prm), ctypes.byref(buf.lists), ctypes.byref(buf.poses),
+                              _dev(buf.workspace, torch.uint8), c_size_t(buf.workspace.numel()), _dev(buf.status), _stream()),
+           "hp_cf_decode")
+
+
+def hp_cf_field(pif, stride, pif_thr, cap=256, out=None):
+    """The fine confidence maps [N, K, Fh * stride, Fw * stride] of intensity fields pif [N, K, 5, Fh, Fw] (fp32 on the
+    GPU); returns (maps, status) with status a one-element int32 GPU tensor."""
+    N, K, _, Fh, Fw = pif.shape
+    dev = pif.device
+    if out is None:
+        out = torch.empty((N, K, Fh * stride, Fw * stride), dtype=torch.float32, device=dev)
+    cell = torch.empty((N, K, cap), dtype=torch.int32, device=dev)
+    val = torch.empty((N, K, cap), dtype=torch.float32, device=dev)
+    count = torch.empty((N, K), dtype=torch.int32, device=dev)
+    status = torch.zeros((1,), dtype=torch.int32, device=dev)
+    ws = torch.empty((hp_cf_workspace_bytes(N, K, 0, cap, 0),), dtype=torch.uint8, device=dev)
+    prm = _CFParams(pif_thr, 0.0, 0.0, 0.0, 0.0, 0, int(stride))
+    _check(lib().hp_cf_field(_dev(pif, torch.float32), N, K, Fh, Fw, ctypes.byref(prm), _dev(cell), _dev(val), _dev(count),
+                             int(cap), _dev(out, torch.float32), _dev(ws, torch.uint8), c_size_t(ws.numel()), _dev(status),
+                             _stream()), "hp_cf_field")
+    return out, status
 
 
 def hp_refine_peaks(maps_hi, K, buf):

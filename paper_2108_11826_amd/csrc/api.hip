@@ -370,6 +370,67 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
     return HP_OK;
 }
 
+static int check_cf_params(const hp_cf_params *prm, int Fh, int Fw)
+{
+    if (!prm) return HP_ERR_INVALID_ARG;
+    if (Fh <= 0 || Fw <= 0 || prm->stride <= 0 || prm->min_parts < 0) return HP_ERR_INVALID_ARG;
+    if (!(prm->pif_thr >= 0.0f) || !(prm->paf_thr >= 0.0f) || !(prm->seed_thr >= 0.0f) || !(prm->grow_thr >= 0.0f) ||
+        !(prm->rev_tol >= 0.0f))
+        return HP_ERR_INVALID_ARG;
+    if ((long long)Fh * prm->stride >= (1 << 23) || (long long)Fw * prm->stride >= (1 << 23) ||
+        (long long)Fh * Fw >= (1LL << 27))
+        return HP_ERR_UNSUPPORTED;
+    return HP_OK;
+}
+
+size_t hp_cf_workspace_bytes(int N, int n_parts, int n_limbs, int cap, int acap)
+{
+    if (N <= 0 || n_parts <= 0 || n_limbs < 0 || cap <= 0 || acap < 0) return 0;
+    return cf_workspace_bytes(N, n_parts, n_limbs, cap, acap);
+}
+
+int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, const hp_skeleton *skel, const hp_cf_params *prm,
+                 const hp_cf_lists *lists, const hp_cf_poses *poses, void *workspace, size_t ws_bytes, int32_t *status,
+                 void *stream)
+{
+    if (!pif || !paf || !status || !workspace) return HP_ERR_INVALID_ARG;
+    LimbTable tab;
+    HP_TRY(check_skeleton(skel, tab));
+    const int K = skel->n_parts, L = skel->n_limbs;
+    HP_TRY(check_cf_params(prm, Fh, Fw));
+    if (N <= 0) return HP_ERR_INVALID_ARG;
+    if (!lists || !lists->pif_cell || !lists->pif_val || !lists->pif_count || !lists->paf_cell || !lists->paf_f1 ||
+        !lists->paf_f2 || !lists->paf_count || lists->cap <= 0 || lists->acap <= 0)
+        return HP_ERR_INVALID_ARG;
+    if (!poses || !poses->xyv || !poses->nparts || !poses->score || !poses->count || poses->cap <= 0) return HP_ERR_INVALID_ARG;
+    if (N > 65535 || lists->cap > 512 || (long long)K * lists->cap > HP_CF_MAX_SEEDS || lists->acap > (1 << 24) ||
+        (long long)K * poses->cap > 1536)
+        return HP_ERR_UNSUPPORTED;
+    if (ws_bytes < cf_workspace_bytes(N, K, L, lists->cap, lists->acap) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
+    HP_LAUNCH(HP_K_CF_PIF, launch_cf_pif(pif, N, Fh, Fw, K, *prm, lists->cap, lists->pif_cell, lists->pif_val, lists->pif_count,
+                                         workspace, L, lists->acap, status, s));
+    HP_LAUNCH(HP_K_CF_PAF, launch_cf_paf(paf, N, Fh, Fw, tab, K, L, *prm, *lists, workspace, status, s));
+    HP_LAUNCH(HP_K_CF_GROW, launch_cf_grow(pif, N, Fh, Fw, tab, K, L, *prm, *lists, *poses, workspace, status, s));
+    return HP_OK;
+}
+
+int hp_cf_field(const float *pif, int N, int K, int Fh, int Fw, const hp_cf_params *prm, int32_t *cell, float *val,
+                int32_t *count, int cap, float *out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!pif || !cell || !val || !count || !out || !status || !workspace) return HP_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || cap <= 0) return HP_ERR_INVALID_ARG;
+    HP_TRY(check_cf_params(prm, Fh, Fw));
+    if (K > HP_MAX_PARTS || cap > 512 || (long long)N * K > 65535) return HP_ERR_UNSUPPORTED;
+    if (ws_bytes < cf_workspace_bytes(N, K, 0, cap, 0) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
+    HP_LAUNCH(HP_K_CF_PIF, launch_cf_pif(pif, N, Fh, Fw, K, *prm, cap, cell, val, count, workspace, 0, 0, status, s));
+    HP_LAUNCH(HP_K_CF_FIELD, launch_cf_field(N, Fh, Fw, K, *prm, cap, count, out, workspace, s));
+    return HP_OK;
+}
+
 int hp_refine_peaks(const float *maps_hi, int N, int C_mem, int K, int H, int W, const hp_peaks *peaks, float *xf, float *yf,
                     void *stream)
 {
@@ -493,6 +554,10 @@ const char *hp_kernel_name(int id)
     case HP_K_REFINE: return "refine";
     case HP_K_PP_DETECT: return "pp_detect";
     case HP_K_PP_PARSE: return "pp_parse";
+    case HP_K_CF_PIF: return "cf_pif";
+    case HP_K_CF_PAF: return "cf_paf";
+    case HP_K_CF_GROW: return "cf_grow";
+    case HP_K_CF_FIELD: return "cf_field";
     default: return "unknown";
     }
 }
@@ -521,6 +586,6 @@ const char *hp_strerror(int code)
     }
 }
 
-int hp_version(void) { return 300; }
+int hp_version(void) { return 400; }
 
 }  // extern "C"

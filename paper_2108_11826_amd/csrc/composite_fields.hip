@@ -1,0 +1,573 @@
+// Decoder of the composite-field family (Section 2.3 names PifPaf as the engine's third algorithm class): the fine
+// confidence map of the part intensity fields, seeds, and persons grown along the part association fields.  The
+// rules (C0-C8) are written at hp_cf_decode in hp.h; every float operation below is one of theirs, in their order.
+//
+// The method's own description builds the fine map of every part (one Gaussian per grid cell, summed at image
+// resolution) and then reads it at a few hundred points: the seeds and the two end points of every association.
+// At 368 x 656 and 17 parts that map is 16 MB per image to fill and throw away.  Here the map is a function, not an
+// array: k_cf_pif lists the active cells of a part in ascending cell order (the order the sum is defined in), and
+// whoever needs a map value sums, in that order, the listed cells whose window holds the pixel: the same additions,
+// bit for bit, as reading the filled array.  hp_cf_field still fills the array for callers who want to look at it.
+//   k_cf_pif   one workgroup per (image, part): ordered compaction of the active cells, then every listed cell's
+//              own map value (its seed value);
+//   k_cf_paf   one workgroup per (image, limb): ordered compaction of the active associations, then the two map
+//              samples of each, the two parts' cell lists held in LDS;
+//   k_cf_grow  one workgroup per image: seeds sorted in LDS; the occupancy test of up to 512 seeds at a time is
+//              one test per thread, repeated only against each newly recorded person; a person grows in rounds, a
+//              wavefront per frontier limb (forward search, reverse search, occupancy, 64 associations at a time);
+//   k_cf_field one workgroup per 64 x 32 pixel tile: the part's listed cells whose window meets the tile, then the
+//              sum per pixel.
+#include <limits.h>
+#include <string.h>
+
+#include "hp_dev.h"
+
+namespace hp {
+
+constexpr int kCfBlock = 256;       // k_cf_pif, k_cf_paf, k_cf_field
+constexpr int kCfGrowBlock = 512;   // k_cf_grow: eight wavefronts, one per frontier limb of a round
+constexpr int kCfMaxSeeds = HP_CF_MAX_SEEDS;
+constexpr int kCfTileW = 64, kCfTileH = 32;
+
+struct CFParams {
+    float pif_thr, paf_thr, seed_thr, grow_thr, rev_tol;
+    int min_parts, stride, Fh, Fw, K, L, cap, acap, pcap;
+};
+
+// Records of the active cells, in the caller's workspace.
+struct CFWork {
+    float4 *pif_a;   // [N][K][cap]   X, Y, inv, c
+    int4 *pif_b;     // [N][K][cap]   xr, yr, bits of sg, cell
+    float4 *paf_a;   // [N][L][acap]  c, x1, y1, B1
+    float4 *paf_b;   // [N][L][acap]  x2, y2, B2, unused
+    size_t bytes;
+};
+
+static CFWork cf_layout(void *base, int N, int K, int L, int cap, int acap)
+{
+    CFWork w;
+    char *p = (char *)base;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *q = p ? p + off : nullptr;
+        off += (bytes + 255) & ~(size_t)255;
+        return q;
+    };
+    w.pif_a = (float4 *)take(sizeof(float4) * (size_t)N * K * cap);
+    w.pif_b = (int4 *)take(sizeof(int4) * (size_t)N * K * cap);
+    w.paf_a = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.paf_b = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.bytes = off;
+    return w;
+}
+
+size_t cf_workspace_bytes(int N, int K, int L, int cap, int acap) { return cf_layout(nullptr, N, K, L, cap, acap).bytes; }
+
+// C0: exp(-t) with fixed arithmetic.
+__device__ __forceinline__ float cf_expneg(float t)
+{
+    const float tc = fmaxf(fminf(t, 80.0f), 0.0f);
+    const float y = tc * 0x1.715476p+0f;
+    const float n = rintf(y);
+    const float z = (y - n) * -0x1.62e430p-1f;
+    float p = 0x1.6c16c2p-10f;
+    p = __fmaf_rn(p, z, 0x1.111112p-7f);
+    p = __fmaf_rn(p, z, 0x1.555556p-5f);
+    p = __fmaf_rn(p, z, 0x1.555556p-3f);
+    p = __fmaf_rn(p, z, 0.5f);
+    p = __fmaf_rn(p, z, 1.0f);
+    p = __fmaf_rn(p, z, 1.0f);
+    return ldexpf(p, -(int)n);
+}
+
+__device__ __forceinline__ bool cf_on_map(float X, float Y, int H, int W)
+{
+    return X >= 0.0f && X <= (float)(W - 1) && Y >= 0.0f && Y <= (float)(H - 1);
+}
+
+__device__ __forceinline__ int cf_window(float sg) { return (int)fminf(ceilf(3.0f * sg), 24.0f); }
+
+// C2 at one pixel: the listed cells of a part, in list (ascending cell) order.
+__device__ __forceinline__ float cf_sample(const float4 *ra, const int4 *rb, int n, int px, int py)
+{
+    float f = 0.0f;
+    for (int j = 0; j < n; ++j) {
+        const int4 b = rb[j];
+        const int w = cf_window(__int_as_float(b.z));
+        if (abs(px - b.x) > w || abs(py - b.y) > w) continue;
+        const float4 a = ra[j];
+        const float dx = (float)px - a.x, dy = (float)py - a.y;
+        const float d2 = dx * dx + dy * dy;
+        f = f + a.w * cf_expneg(d2 * a.z);
+    }
+    return f;
+}
+
+// ---- C1, C3: active cells of a part and their map values ---------------------------------------------------------
+__global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ pif, CFParams P, CFWork ws,
+                                                     int32_t *__restrict__ out_cell, float *__restrict__ out_val,
+                                                     int32_t *__restrict__ out_count, int32_t *__restrict__ status)
+{
+    extern __shared__ float4 s_dyn4[];
+    float4 *s_a = s_dyn4;                     // [cap]
+    int4 *s_b = (int4 *)(s_dyn4 + P.cap);     // [cap]
+    __shared__ int s_scan[kCfBlock / kWave + 1];
+
+    const int k = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
+    const int cells = P.Fh * P.Fw, H = P.Fh * P.stride, W = P.Fw * P.stride;
+    const float *f = pif + ((size_t)n * P.K + k) * 5 * cells;
+    const size_t list = ((size_t)n * P.K + k) * P.cap;
+    const float s = (float)P.stride;
+
+    int count = 0;
+    for (int c0 = 0; c0 < cells; c0 += kCfBlock) {
+        const int cell = c0 + tid;
+        bool act = false;
+        float X = 0.0f, Y = 0.0f, c = 0.0f;
+        if (cell < cells) {
+            const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
+            c = f[cell];
+            X = ((float)gx + f[1 * cells + cell]) * s;
+            Y = ((float)gy + f[2 * cells + cell]) * s;
+            act = c > P.pif_thr && cf_on_map(X, Y, H, W);
+        }
+        int total;
+        const int at = count + block_flag_scan(act, s_scan, total);
+        if (act && at < P.cap) {
+            const float sg = fmaxf(f[4 * cells + cell] * s, 1.0f);
+            const float4 a = make_float4(X, Y, 0.5f / (sg * sg), c);
+            const int4 b = make_int4((int)rintf(X), (int)rintf(Y), __float_as_int(sg), cell);
+            s_a[at] = a;
+            s_b[at] = b;
+            ws.pif_a[list + at] = a;
+            ws.pif_b[list + at] = b;
+            out_cell[list + at] = cell;
+        }
+        count += total;
+    }
+    __syncthreads();
+    const int m = min(count, P.cap);
+    for (int i = tid; i < m; i += kCfBlock) out_val[list + i] = cf_sample(s_a, s_b, m, s_b[i].x, s_b[i].y);
+    if (tid == 0) {
+        out_count[(size_t)n * P.K + k] = count;
+        if (count > P.cap) atomicOr(status, HP_STATUS_PEAK_OVERFLOW);
+    }
+}
+
+// ---- C4: active associations of a limb and their two map samples --------------------------------------------------
+struct CFLimbs {
+    uint8_t a[HP_MAX_LIMBS], b[HP_MAX_LIMBS];
+};
+
+__global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ paf, CFParams P, CFWork ws, CFLimbs limbs,
+                                                         const int32_t *__restrict__ pif_count,
+                                                         int32_t *__restrict__ out_cell, float *__restrict__ out_f1,
+                                                         float *__restrict__ out_f2, int32_t *__restrict__ out_count,
+                                                         int32_t *__restrict__ status)
+{
+    extern __shared__ float4 s_dyn4[];
+    float4 *s_aa = s_dyn4;                        // part a: [cap] X, Y, inv, c
+    int4 *s_ab = (int4 *)(s_dyn4 + P.cap);        //         [cap] xr, yr, sg, cell
+    float4 *s_ba = s_dyn4 + 2 * P.cap;            // part b
+    int4 *s_bb = (int4 *)(s_dyn4 + 3 * P.cap);
+    __shared__ int s_scan[kCfBlock / kWave + 1];
+    __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
+
+    const int l = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
+    if (tid == 0) {
+#pragma unroll
+        for (int i = 0; i < HP_MAX_LIMBS; ++i) {
+            s_la[i] = limbs.a[i];
+            s_lb[i] = limbs.b[i];
+        }
+    }
+    __syncthreads();
+    const int pa = s_la[l], pb = s_lb[l];
+    const int na = min(pif_count[(size_t)n * P.K + pa], P.cap), nb = min(pif_count[(size_t)n * P.K + pb], P.cap);
+    for (int i = tid; i < na; i += kCfBlock) {
+        s_aa[i] = ws.pif_a[((size_t)n * P.K + pa) * P.cap + i];
+        s_ab[i] = ws.pif_b[((size_t)n * P.K + pa) * P.cap + i];
+    }
+    for (int i = tid; i < nb; i += kCfBlock) {
+        s_ba[i] = ws.pif_a[((size_t)n * P.K + pb) * P.cap + i];
+        s_bb[i] = ws.pif_b[((size_t)n * P.K + pb) * P.cap + i];
+    }
+
+    const int cells = P.Fh * P.Fw, H = P.Fh * P.stride, W = P.Fw * P.stride;
+    const float *f = paf + ((size_t)n * P.L + l) * 7 * cells;
+    const size_t list = ((size_t)n * P.L + l) * P.acap;
+    const float s = (float)P.stride;
+
+    int count = 0;
+    for (int c0 = 0; c0 < cells; c0 += kCfBlock) {
+        const int cell = c0 + tid;
+        bool act = false;
+        float c = 0.0f, x1 = 0.0f, y1 = 0.0f, x2 = 0.0f, y2 = 0.0f;
+        if (cell < cells) {
+            const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
+            c = f[cell];
+            x1 = ((float)gx + f[1 * cells + cell]) * s;
+            y1 = ((float)gy + f[2 * cells + cell]) * s;
+            x2 = ((float)gx + f[4 * cells + cell]) * s;
+            y2 = ((float)gy + f[5 * cells + cell]) * s;
+            act = c > P.paf_thr && cf_on_map(x1, y1, H, W) && cf_on_map(x2, y2, H, W);
+        }
+        int total;
+        const int at = count + block_flag_scan(act, s_scan, total);   // its first barrier also covers the lists above
+        if (act && at < P.acap) {
+            const float B1 = fmaxf(f[3 * cells + cell] * s, 1.0f), B2 = fmaxf(f[6 * cells + cell] * s, 1.0f);
+            ws.paf_a[list + at] = make_float4(c, x1, y1, B1);
+            ws.paf_b[list + at] = make_float4(x2, y2, B2, 0.0f);
+            out_cell[list + at] = cell;
+        }
+        count += total;
+    }
+    __syncthreads();   // the records written above are read back by other threads of this workgroup
+    const int m = min(count, P.acap);
+    for (int i = tid; i < m; i += kCfBlock) {
+        const float4 ra = ws.paf_a[list + i], rb = ws.paf_b[list + i];
+        out_f1[list + i] = cf_sample(s_aa, s_ab, na, (int)rintf(ra.y), (int)rintf(ra.z));
+        out_f2[list + i] = cf_sample(s_ba, s_bb, nb, (int)rintf(rb.x), (int)rintf(rb.y));
+    }
+    if (tid == 0) {
+        out_count[(size_t)n * P.L + l] = count;
+        if (count > P.acap) atomicOr(status, HP_STATUS_CAND_OVERFLOW);
+    }
+}
+
+// ---- C3, C5-C8: seeds and persons of one image -----------------------------------------------------------------
+// C7 for one joint of a recorded person (x, y, radius, value; value 0 = part not held)
+__device__ __forceinline__ bool cf_covers(const float4 j, float x, float y)
+{
+    if (!(j.w > 0.0f)) return false;
+    const float dx = x - j.x, dy = y - j.y;
+    return dx * dx + dy * dy <= j.z * j.z;
+}
+
+// C4: the best association of a limb's list for a joint at (qx, qy), searched by one wavefront.  Returns
+// (score order) << 32 | (0xFFFFFFFF - index), the same in every lane, or 0 when no score exceeds `above`.
+__device__ __forceinline__ uint64_t cf_search(const float4 *__restrict__ pa, const float4 *__restrict__ pb,
+                                              const float *__restrict__ fother, int cnt, bool forward, float qx,
+                                              float qy, float above, int lane)
+{
+    uint64_t key = 0ull;
+    for (int i = lane; i < cnt; i += kWave) {
+        const float4 ra = pa[i], rb = pb[i];
+        const float dx = qx - (forward ? ra.y : rb.x), dy = qy - (forward ? ra.z : rb.y);
+        const float d = sqrtf(dx * dx + dy * dy);
+        const float e = cf_expneg(d / (forward ? ra.w : rb.z));
+        const float sc = (ra.x * e) * fother[i];
+        if (sc > above) {
+            const uint64_t mine = ((uint64_t)float_order(sc) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)i);
+            key = mine > key ? mine : key;
+        }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        const uint64_t other = __shfl_xor(key, off);
+        key = other > key ? other : key;
+    }
+    return key;
+}
+
+__global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(const float *__restrict__ pif, CFParams P, CFWork ws,
+                                                          CFLimbs limbs, const int32_t *__restrict__ pif_count,
+                                                          const float *__restrict__ pif_val,
+                                                          const int32_t *__restrict__ paf_count,
+                                                          const float *__restrict__ paf_f1,
+                                                          const float *__restrict__ paf_f2, float *__restrict__ xyv,
+                                                          int32_t *__restrict__ nparts, float *__restrict__ score,
+                                                          int32_t *__restrict__ pcount, int32_t *__restrict__ status)
+{
+    extern __shared__ uint64_t s_dyn8[];
+    uint64_t *s_key = s_dyn8;                                  // [seed capacity] (inverted value order) << 32 | part << 16 | rank
+    float4 *s_person = (float4 *)(s_dyn8 + kCfMaxSeeds);       // [pcap][K] x, y, radius, value of the recorded persons
+    __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
+    __shared__ int s_cnt[HP_MAX_PARTS], s_acnt[HP_MAX_LIMBS];
+    __shared__ int s_held[HP_MAX_PARTS], s_was[HP_MAX_PARTS];
+    __shared__ float4 s_joint[HP_MAX_PARTS];                   // x, y, radius, value of the growing person
+    __shared__ float4 s_prop[HP_MAX_LIMBS];                    // a round's proposals: score, x, y, 1 (0 = none)
+    __shared__ int s_front[HP_MAX_LIMBS];
+    __shared__ int s_nfront, s_nseeds, s_next, s_added[2];
+
+    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+    const int K = P.K, L = P.L, cells = P.Fh * P.Fw;
+    if (tid == 0) {
+#pragma unroll
+        for (int i = 0; i < HP_MAX_LIMBS; ++i) {
+            s_la[i] = limbs.a[i];
+            s_lb[i] = limbs.b[i];
+        }
+        s_nseeds = 0;
+    }
+    if (tid < K) s_cnt[tid] = min(pif_count[(size_t)n * K + tid], P.cap);
+    if (tid < L) s_acnt[tid] = min(paf_count[(size_t)n * L + tid], P.acap);
+    __syncthreads();
+
+    // C3: the seeds, sorted by (value descending, part ascending, cell ascending)
+    for (int k = 0; k < K; ++k)
+        for (int q = tid; q < s_cnt[k]; q += kCfGrowBlock) {
+            const float v = pif_val[((size_t)n * K + k) * P.cap + q];
+            if (v > P.seed_thr)
+                s_key[atomicAdd(&s_nseeds, 1)] = ((uint64_t)(~float_order(v)) << 32) | (uint32_t)((k << 16) | q);
+        }
+    __syncthreads();
+    const int ns = s_nseeds;                                   // at most K * cap <= the seed capacity
+    int n2 = 1;
+    while (n2 < ns) n2 <<= 1;
+    for (int i = ns + tid; i < n2; i += kCfGrowBlock) s_key[i] = ~0ull;
+    __syncthreads();
+    block_bitonic_sort(s_key, n2);
+
+    int np = 0;          // persons recorded so far (the same in every thread)
+    bool stop = false;   // C8
+    for (int base = 0; base < ns && !stop; base += kCfGrowBlock) {
+        // this thread's seed of the batch, tested against everyone recorded so far
+        const int mine = base + tid;
+        bool occ = true;
+        int sk = 0;
+        float sx = 0.0f, sy = 0.0f;
+        if (mine < ns) {
+            const uint32_t id = (uint32_t)s_key[mine];
+            sk = (int)(id >> 16);
+            const float4 ra = ws.pif_a[((size_t)n * K + sk) * P.cap + (id & 0xFFFFu)];
+            sx = ra.x;
+            sy = ra.y;
+            occ = false;
+            for (int p = 0; p < np && !occ; ++p) occ = cf_covers(s_person[p * K + sk], sx, sy);
+        }
+        for (;;) {
+            __syncthreads();
+            if (tid == 0) s_next = INT_MAX;
+            __syncthreads();
+            if (!occ) atomicMin(&s_next, mine);
+            __syncthreads();
+            const int cur = s_next;
+            if (cur == INT_MAX) break;
+            if (np >= P.pcap) {
+                if (tid == 0) atomicOr(status, HP_STATUS_POSE_OVERFLOW);
+                stop = true;
+                break;
+            }
+            if (mine == cur) occ = true;                       // taken
+
+            // ---- C5: the person of seed `cur` ----
+            if (tid < K) s_held[tid] = 0;
+            __syncthreads();
+            if (tid == 0) {
+                const uint64_t key = s_key[cur];
+                const int k0 = (int)((uint32_t)key >> 16), rank = (int)((uint32_t)key & 0xFFFFu);
+                const float4 ra = ws.pif_a[((size_t)n * K + k0) * P.cap + rank];
+                const int4 rb = ws.pif_b[((size_t)n * K + k0) * P.cap + rank];
+                s_held[k0] = 1;
+                s_joint[k0] = make_float4(ra.x, ra.y, __int_as_float(rb.z), float_unorder(~(uint32_t)(key >> 32)));
+            }
+            __syncthreads();
+            for (int round = 0;; ++round) {
+                if (wv == 0) {                                 // the limbs with exactly one part held, in table order
+                    const bool fr = lane < L && (s_held[s_la[lane < L ? lane : 0]] != s_held[s_lb[lane < L ? lane : 0]]);
+                    const uint64_t m = __ballot(fr);
+                    if (fr) s_front[__popcll(m & ((1ull << lane) - 1ull))] = lane;
+                    if (lane == 0) {
+                        s_nfront = __popcll(m);
+                        s_added[round & 1] = 0;
+                    }
+                }
+                if (tid >= kWave && tid < kWave + K) s_was[tid - kWave] = s_held[tid - kWave];
+                if (tid >= 2 * kWave && tid < 2 * kWave + L) s_prop[tid - 2 * kWave].w = 0.0f;
+                __syncthreads();
+                const int nf = s_nfront;
+                if (nf == 0) break;
+                for (int fi = wv; fi < nf; fi += kCfGrowBlock / kWave) {
+                    const int l = s_front[fi], a = s_la[l], b = s_lb[l];
+                    const bool forward = s_was[a] != 0;
+                    const int src = forward ? a : b, dst = forward ? b : a;
+                    const float qx = s_joint[src].x, qy = s_joint[src].y;
+                    const size_t list = ((size_t)n * L + l) * P.acap;
+                    const float4 *pa = ws.paf_a + list, *pb = ws.paf_b + list;
+                    const float *f1 = paf_f1 + list, *f2 = paf_f2 + list;
+                    const int cnt = s_acnt[l];
+                    const uint64_t found = cf_search(pa, pb, forward ? f2 : f1, cnt, forward, qx, qy, P.grow_thr, lane);
+                    if (found == 0ull) continue;
+                    const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
+                    const float sc = float_unorder((uint32_t)(found >> 32));
+                    const float tx = forward ? pb[i].x : pa[i].y, ty = forward ? pb[i].y : pa[i].z;
+                    const uint64_t back = cf_search(pa, pb, forward ? f1 : f2, cnt, !forward, tx, ty, 0.0f, lane);
+                    if (back == 0ull) continue;
+                    const int r = (int)(0xFFFFFFFFu - (uint32_t)back);
+                    const float dx = (forward ? pa[r].y : pb[r].x) - qx, dy = (forward ? pa[r].z : pb[r].y) - qy;
+                    if (!(dx * dx + dy * dy <= P.rev_tol * P.rev_tol)) continue;
+                    bool taken = false;
+                    for (int p = lane; p < np; p += kWave) taken = taken || cf_covers(s_person[p * K + dst], tx, ty);
+                    if (__ballot(taken) != 0ull) continue;
+                    if (lane == 0) s_prop[l] = make_float4(sc, tx, ty, 1.0f);
+                }
+                __syncthreads();
+                if (tid < K && !s_was[tid]) {                  // the best proposal for part `tid`, the earlier limb on ties
+                    bool have = false;
+                    float4 best = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    for (int l = 0; l < L; ++l) {
+                        const float4 pr = s_prop[l];
+                        if (pr.w == 0.0f) continue;
+                        const int a = s_la[l], b = s_lb[l];
+                        if ((s_was[a] ? b : a) != tid) continue;
+                        if (!have || pr.x > best.x) {
+                            best = pr;
+                            have = true;
+                        }
+                    }
+                    if (have) {
+                        const int cy = (int)rintf(best.z) / P.stride, cx = (int)rintf(best.y) / P.stride;
+                        const float sig = pif[(((size_t)n * K + tid) * 5 + 4) * cells + (size_t)cy * P.Fw + cx];
+                        s_held[tid] = 1;
+                        s_joint[tid] = make_float4(best.y, best.z, fmaxf(sig * (float)P.stride, 1.0f), best.x);
+                        s_added[round & 1] = 1;
+                    }
+                }
+                __syncthreads();
+                if (!s_added[round & 1]) break;
+            }
+
+            // ---- C6: record ----
+            int parts = 0;
+            for (int k = 0; k < K; ++k) parts += s_held[k];
+            if (parts >= P.min_parts) {
+                if (tid < K) {
+                    const float4 j = s_held[tid] ? s_joint[tid] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    s_person[np * K + tid] = j;
+                    float *o = xyv + (((size_t)n * P.pcap + np) * K + tid) * 3;
+                    o[0] = j.x;
+                    o[1] = j.y;
+                    o[2] = j.w;
+                }
+                if (tid == 0) {
+                    float sum = 0.0f;
+                    for (int k = 0; k < K; ++k)
+                        if (s_held[k]) sum = sum + s_joint[k].w;
+                    nparts[(size_t)n * P.pcap + np] = parts;
+                    score[(size_t)n * P.pcap + np] = sum / (float)K;
+                }
+                __syncthreads();
+                if (!occ) occ = cf_covers(s_person[np * K + sk], sx, sy);
+                ++np;
+            }
+        }
+    }
+    if (tid == 0) pcount[n] = np;
+}
+
+// ---- C2 as an array ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kCfBlock) void k_cf_field(CFParams P, CFWork ws, const int32_t *__restrict__ pif_count,
+                                                       float *__restrict__ out)
+{
+    extern __shared__ float4 s_dyn4[];
+    float4 *s_a = s_dyn4;                     // [cap] the listed cells whose window meets this tile, in list order
+    int4 *s_b = (int4 *)(s_dyn4 + P.cap);
+    __shared__ int s_scan[kCfBlock / kWave + 1];
+
+    const int plane = blockIdx.z, tid = threadIdx.x;
+    const int H = P.Fh * P.stride, W = P.Fw * P.stride;
+    const int x0 = blockIdx.x * kCfTileW, y0 = blockIdx.y * kCfTileH;
+    const size_t list = (size_t)plane * P.cap;
+    const int m = min(pif_count[plane], P.cap);
+    int cnt = 0;
+    for (int j0 = 0; j0 < m; j0 += kCfBlock) {
+        const int j = j0 + tid;
+        bool meets = false;
+        int4 b = make_int4(0, 0, 0, 0);
+        if (j < m) {
+            b = ws.pif_b[list + j];
+            const int w = cf_window(__int_as_float(b.z));
+            meets = b.x + w >= x0 && b.x - w < x0 + kCfTileW && b.y + w >= y0 && b.y - w < y0 + kCfTileH;
+        }
+        int total;
+        const int at = cnt + block_flag_scan(meets, s_scan, total);
+        if (meets) {
+            s_a[at] = ws.pif_a[list + j];
+            s_b[at] = b;
+        }
+        cnt += total;
+    }
+    __syncthreads();
+    const int px = x0 + (tid & (kCfTileW - 1));
+    if (px >= W) return;
+    for (int r = tid / kCfTileW; r < kCfTileH; r += kCfBlock / kCfTileW) {
+        const int py = y0 + r;
+        if (py >= H) break;
+        __builtin_nontemporal_store(cf_sample(s_a, s_b, cnt, px, py), &out[((size_t)plane * H + py) * W + px]);
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------------------------
+static CFParams cf_params(const hp_cf_params &prm, int Fh, int Fw, int K, int L, int cap, int acap, int pcap)
+{
+    CFParams P;
+    P.pif_thr = prm.pif_thr;
+    P.paf_thr = prm.paf_thr;
+    P.seed_thr = prm.seed_thr;
+    P.grow_thr = prm.grow_thr;
+    P.rev_tol = prm.rev_tol;
+    P.min_parts = prm.min_parts;
+    P.stride = prm.stride;
+    P.Fh = Fh;
+    P.Fw = Fw;
+    P.K = K;
+    P.L = L;
+    P.cap = cap;
+    P.acap = acap;
+    P.pcap = pcap;
+    return P;
+}
+
+hipError_t launch_cf_pif(const float *pif, int N, int Fh, int Fw, int K, const hp_cf_params &prm, int cap, int32_t *cell,
+                         float *val, int32_t *count, void *workspace, int L, int acap, int32_t *status, hipStream_t s)
+{
+    const CFParams P = cf_params(prm, Fh, Fw, K, L, cap, acap, 0);
+    const CFWork ws = cf_layout(workspace, N, K, L, cap, acap);
+    HP_KERNEL(k_cf_pif, dim3(K, N), dim3(kCfBlock), sizeof(float4) * 2 * (size_t)cap, s, pif, P, ws, cell, val, count, status);
+    return hipGetLastError();
+}
+
+static CFLimbs cf_limbs(const LimbTable &T, int L)
+{
+    CFLimbs limbs = {};
+    for (int l = 0; l < L; ++l) {
+        limbs.a[l] = (uint8_t)T.a[l];
+        limbs.b[l] = (uint8_t)T.b[l];
+    }
+    return limbs;
+}
+
+hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+                         const hp_cf_lists &lists, void *workspace, int32_t *status, hipStream_t s)
+{
+    const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, 0);
+    const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
+    HP_KERNEL(k_cf_paf, dim3(L, N), dim3(kCfBlock), sizeof(float4) * 4 * (size_t)lists.cap, s, paf, P, ws, cf_limbs(T, L),
+              lists.pif_count, lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_cf_grow(const float *pif, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+                          const hp_cf_lists &lists, const hp_cf_poses &poses, void *workspace, int32_t *status, hipStream_t s)
+{
+    const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, poses.cap);
+    const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
+    const size_t lds = sizeof(uint64_t) * kCfMaxSeeds + sizeof(float4) * (size_t)poses.cap * K;
+    HP_KERNEL(k_cf_grow, dim3(N), dim3(kCfGrowBlock), lds, s, pif, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
+              lists.paf_count, lists.paf_f1, lists.paf_f2, poses.xyv, poses.nparts, poses.score, poses.count, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_cf_field(int N, int Fh, int Fw, int K, const hp_cf_params &prm, int cap, const int32_t *count, float *out,
+                           void *workspace, hipStream_t s)
+{
+    const CFParams P = cf_params(prm, Fh, Fw, K, 0, cap, 0, 0);
+    const CFWork ws = cf_layout(workspace, N, K, 0, cap, 0);
+    const int H = Fh * prm.stride, W = Fw * prm.stride;
+    const dim3 grid((W + kCfTileW - 1) / kCfTileW, (H + kCfTileH - 1) / kCfTileH, N * K);
+    HP_KERNEL(k_cf_field, grid, dim3(kCfBlock), sizeof(float4) * 2 * (size_t)cap, s, P, ws, count, out);
+    return hipGetLastError();
+}
+
+}  // namespace hp

@@ -74,6 +74,17 @@ __device__ __forceinline__ float up_lo(const T *lo, int h, int w, int Y, int X)
     return __fmaf_rn(g, r1, (1.0f - g) * r0);
 }
 
+// Monotone map of a float to an unsigned integer (larger float, larger integer), and back.
+__device__ __forceinline__ uint32_t float_order(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_unorder(uint32_t o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+
 // Ascending bitonic sort of n2 (a power of two) 64-bit keys by the whole workgroup.
 // `a` may be LDS or global memory; ends with a barrier.
 __device__ __forceinline__ void block_bitonic_sort(uint64_t *a, int n2)
@@ -212,6 +223,18 @@ hipError_t launch_pp_detect(const float *resp, const float *conf, const float *b
 hipError_t launch_pp_parse(const float *edge, int N, int Gh, int Gw, int Nh, int Nw, const LimbTable &T, int K, int L,
                            const hp_pp_params &prm, const hp_pp_dets &dets, const hp_poses &poses, int32_t *status,
                            hipStream_t s);
+
+// Composite-field decoding: active cells and seed values per (image, part), active associations and their map
+// samples per (image, limb), persons per image; the fine map as an array.  `workspace`: cf_workspace_bytes.
+size_t cf_workspace_bytes(int N, int K, int L, int cap, int acap);
+hipError_t launch_cf_pif(const float *pif, int N, int Fh, int Fw, int K, const hp_cf_params &prm, int cap, int32_t *cell,
+                         float *val, int32_t *count, void *workspace, int L, int acap, int32_t *status, hipStream_t s);
+hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+                         const hp_cf_lists &lists, void *workspace, int32_t *status, hipStream_t s);
+hipError_t launch_cf_grow(const float *pif, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+                          const hp_cf_lists &lists, const hp_cf_poses &poses, void *workspace, int32_t *status, hipStream_t s);
+hipError_t launch_cf_field(int N, int Fh, int Fw, int K, const hp_cf_params &prm, int cap, const int32_t *count, float *out,
+                           void *workspace, hipStream_t s);
 
 // hp_postprocess on the first N images of outputs and a workspace laid out for N_layout >= N images;
 // check_only: validate the arguments, enqueue nothing.

@@ -23,17 +23,6 @@ struct PPParams {
     int min_parts, Gh, Gw, Nh, Nw, K, L, cap, pcap;
 };
 
-// Monotone map of a float to an unsigned integer (larger float, larger integer), and back.
-__device__ __forceinline__ uint32_t float_order(float v)
-{
-    const uint32_t u = __float_as_uint(v);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float float_unorder(uint32_t o)
-{
-    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
-}
-
 __device__ __forceinline__ float box_iou(const float4 a, const float4 b)
 {
     const float iw = fminf(a.z, b.z) - fmaxf(a.x, b.x);
