@@ -347,10 +347,10 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
  *   C3 an active cell's value is v = f_k(xr, yr); it is a seed when v > seed_thr; seeds are taken by
  *      (v descending, part ascending, cell ascending);
  *   C4 cell (gy, gx) of limb l: P1 = (((float)gx + x1) * s, ((float)gy + y1) * s), P2 likewise; active
- *      when c > paf_thr and both points lie on the map (as in C1); B1 = max(b1 * s, 1), B2 likewise;
- *      F1 = f_a(rint P1), F2 = f_b(rint P2).  For a joint of part a at Q the cell scores
- *      (c * E(|Q - P1| / B1)) * F2 and proposes P2 for part b; for a joint of part b it scores
- *      (c * E(|Q - P2| / B2)) * F1 and proposes P1; |.| = sqrt(dx * dx + dy * dy).  A search takes
+ *      when c > paf_thr and both points lie on the map (as in C1); iB1 = 1 / max(b1 * s, 1), iB2
+ *      likewise; F1 = f_a(rint P1), F2 = f_b(rint P2).  For a joint of part a at Q the cell scores
+ *      (c * F2) * E(|Q - P1| * iB1) and proposes P2 for part b; for a joint of part b it scores
+ *      (c * F1) * E(|Q - P2| * iB2) and proposes P1; |.| = sqrt(dx * dx + dy * dy).  A search takes
  *      the active cell with the largest score (ties: the lowest cell);
  *   C5 a person starts as the seed's joint (position (X, Y), value v, radius sg) and grows in
  *      rounds.  A round looks at every limb of which the person held exactly one part when the
@@ -364,7 +364,9 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
  *   C6 a person with at least min_parts parts is recorded: score = (sum of the held values in part
  *      order, from 0) / (float)K;
  *   C7 (x, y) is occupied for part k when a recorded person holds k at (xj, yj) with radius r and
- *      (x - xj)^2 + (y - yj)^2 <= r * r; a seed occupied for its part is skipped;
+ *      (x - xj)^2 + (y - yj)^2 <= r * r; a seed occupied for its part is skipped, and so is a seed
+ *      within the radius of an earlier seed of its part whose person was grown and not recorded
+ *      (the same test with that seed's position and radius);
  *   C8 decoding of an image stops when a seed passes C7 while poses->cap persons are recorded;
  *      HP_STATUS_POSE_OVERFLOW is then set.
  * `lists` receives, in ascending cell order, the active cells of every (image, part) with their

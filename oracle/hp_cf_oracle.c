@@ -34,9 +34,9 @@
  *      seeds are taken by (v descending, part ascending, cell ascending);
  *   C4 cell (gy, gx) of limb l (a -> b) has the end points P1 = ((gx + x1) s, (gy + y1) s)
  *      and P2 likewise; it is active when c > paf_thr and both end points lie on the map
- *      (as in C1).  B1 = max(b1 * s, 1), B2 likewise; F1 = f_a(rint P1), F2 = f_b(rint P2).
- *      For a joint of part a at Q the cell scores (c * E(|Q - P1| / B1)) * F2 and proposes
- *      P2 for part b; for a joint of part b at Q it scores (c * E(|Q - P2| / B2)) * F1 and
+ *      (as in C1).  iB1 = 1 / max(b1 * s, 1), iB2 likewise; F1 = f_a(rint P1), F2 = f_b(rint P2).
+ *      For a joint of part a at Q the cell scores (c * F2) * E(|Q - P1| * iB1) and proposes
+ *      P2 for part b; for a joint of part b at Q it scores (c * F1) * E(|Q - P2| * iB2) and
  *      proposes P1.  |.| = sqrt(dx * dx + dy * dy).  A search takes the active cell with the
  *      largest score (ties: the lowest cell);
  *   C5 a person starts as the seed's joint (position (X, Y), value v, radius sg) and grows
@@ -53,7 +53,10 @@
  *      values in part order, from 0) / (float)K;
  *   C7 a point (x, y) is occupied for part k when a recorded person holds k at (xj, yj)
  *      with radius r and (x - xj)^2 + (y - yj)^2 <= r * r.  A seed that is occupied
- *      for its part is skipped;
+ *      for its part is skipped, and so is a seed that lies within the radius of an earlier
+ *      seed of its part whose person was grown and not recorded (the same test with that
+ *      seed's position and radius): suppression at the level of a part applies to every
+ *      person the decoder finished, kept or not;
  *   C8 decoding of an image stops when a seed passes C7 while pcap persons are recorded
  *      (the caller is told).
  *
@@ -138,7 +141,7 @@ void hpc_field(const float *pif, int Fh, int Fw, int s, float pif_thr, float *f)
 
 typedef struct {
     int cell;
-    float c, x1, y1, B1, x2, y2, B2, F1, F2;
+    float c, x1, y1, iB1, x2, y2, iB2, F1, F2;
 } hpc_paf;
 
 typedef struct {
@@ -163,8 +166,8 @@ static int hpc_search(const hpc_paf *list, int n, int forward, float qx, float q
         const hpc_paf *a = &list[i];
         const float dx = qx - (forward ? a->x1 : a->x2), dy = qy - (forward ? a->y1 : a->y2);
         const float d = sqrtf(dx * dx + dy * dy);
-        const float e = hpc_expneg(d / (forward ? a->B1 : a->B2));
-        const float sc = (a->c * e) * (forward ? a->F2 : a->F1);
+        const float e = hpc_expneg(d * (forward ? a->iB1 : a->iB2));
+        const float sc = (a->c * (forward ? a->F2 : a->F1)) * e;
         if (sc > bs) {
             bs = sc;
             best = i;
@@ -204,6 +207,8 @@ int hpc_decode(const float *pif, const float *paf, int K, int L, const int32_t *
     hpc_paf *al = (hpc_paf *)malloc(sizeof(hpc_paf) * (size_t)L * cells);
     hpc_seed *seeds = (hpc_seed *)malloc(sizeof(hpc_seed) * (size_t)K * cells);
     float *rad = (float *)malloc(sizeof(float) * (size_t)(pcap > 0 ? pcap : 1) * K);
+    float *ghost = (float *)malloc(sizeof(float) * 4 * (size_t)K * cells);   /* x, y, radius, part of the seeds grown in vain */
+    int ng = 0;
     int ns = 0, np = 0;
     *overflow = 0;
 
@@ -246,8 +251,8 @@ int hpc_decode(const float *pif, const float *paf, int K, int L, const int32_t *
             q.x2 = ((float)gx + pl7[4 * cells + cell]) * (float)s;
             q.y2 = ((float)gy + pl7[5 * cells + cell]) * (float)s;
             if (!(q.c > paf_thr) || !hpc_on_map(q.x1, q.y1, H, W) || !hpc_on_map(q.x2, q.y2, H, W)) continue;
-            q.B1 = fmaxf(pl7[3 * cells + cell] * (float)s, 1.0f);
-            q.B2 = fmaxf(pl7[6 * cells + cell] * (float)s, 1.0f);
+            q.iB1 = 1.0f / fmaxf(pl7[3 * cells + cell] * (float)s, 1.0f);
+            q.iB2 = 1.0f / fmaxf(pl7[6 * cells + cell] * (float)s, 1.0f);
             q.F1 = f[((size_t)a * H + (int)rintf(q.y1)) * W + (int)rintf(q.x1)];
             q.F2 = f[((size_t)b * H + (int)rintf(q.y2)) * W + (int)rintf(q.x2)];
             al[(size_t)l * cells + n] = q;
@@ -267,6 +272,12 @@ int hpc_decode(const float *pif, const float *paf, int K, int L, const int32_t *
         const int k0 = seeds[t].k;
         const hpc_pif *q0 = &pl[(size_t)k0 * cells + seeds[t].rank];
         if (hpc_occupied(xyv, rad, np, K, k0, q0->X, q0->Y)) continue;
+        int shadowed = 0;
+        for (int g = 0; g < ng && !shadowed; ++g) {
+            const float dx = q0->X - ghost[4 * g + 0], dy = q0->Y - ghost[4 * g + 1], r = ghost[4 * g + 2];
+            shadowed = (int)ghost[4 * g + 3] == k0 && dx * dx + dy * dy <= r * r;
+        }
+        if (shadowed) continue;
         if (np >= pcap) {
             *overflow = 1;
             break;
@@ -322,7 +333,14 @@ int hpc_decode(const float *pif, const float *paf, int K, int L, const int32_t *
                 ++parts;
                 sum = sum + jv[k];
             }
-        if (parts < min_parts) continue;
+        if (parts < min_parts) {
+            ghost[4 * ng + 0] = q0->X;
+            ghost[4 * ng + 1] = q0->Y;
+            ghost[4 * ng + 2] = q0->sg;
+            ghost[4 * ng + 3] = (float)k0;
+            ++ng;
+            continue;
+        }
         for (int k = 0; k < K; ++k) {
             float *j = xyv + ((size_t)np * K + k) * 3;
             j[0] = held[k] ? jx[k] : 0.0f;
@@ -343,5 +361,6 @@ int hpc_decode(const float *pif, const float *paf, int K, int L, const int32_t *
     free(al);
     free(seeds);
     free(rad);
+    free(ghost);
     return np;
 }

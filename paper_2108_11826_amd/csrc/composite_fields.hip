@@ -10,23 +10,26 @@
 // bit for bit, as reading the filled array.  hp_cf_field still fills the array for callers who want to look at it.
 //   k_cf_pif   one workgroup per (image, part): ordered compaction of the active cells, then every listed cell's
 //              own map value (its seed value);
-//   k_cf_paf   one workgroup per (image, limb): ordered compaction of the active associations, then the two map
-//              samples of each, the two parts' cell lists held in LDS;
-//   k_cf_grow  one workgroup per image: seeds sorted in LDS; the occupancy test of up to 512 seeds at a time is
-//              one test per thread, repeated only against each newly recorded person; a person grows in rounds, a
-//              wavefront per frontier limb (forward search, reverse search, occupancy, 64 associations at a time);
+//   k_cf_paf   one workgroup per (image, limb): ordered compaction of the active associations, the two map
+//              samples of each (the two parts' cell lists held in LDS), and what each would propose if it won a
+//              search: the target's radius and the point the reverse search leads back to, neither of which
+//              depends on the person; one more workgroup per image sorts the seeds;
+//   k_cf_grow  one workgroup per image: the occupancy test of up to 256 seeds at a time is one test per thread,
+//              repeated only against each newly finished person; a person grows in rounds, a wavefront per
+//              frontier limb (the search, 64 associations at a time, over records held in LDS);
 //   k_cf_field one workgroup per 64 x 32 pixel tile: the part's listed cells whose window meets the tile, then the
 //              sum per pixel.
 #include <limits.h>
 #include <string.h>
+
+#include <algorithm>
 
 #include "hp_dev.h"
 
 namespace hp {
 
 constexpr int kCfBlock = 256;       // k_cf_pif, k_cf_paf, k_cf_field
-constexpr int kCfGrowBlock = 512;   // k_cf_grow: eight wavefronts, one per frontier limb of a round
-constexpr int kCfMaxSeeds = HP_CF_MAX_SEEDS;
+constexpr int kCfGrowBlock = 256;   // k_cf_grow: four wavefronts, one per frontier limb of a round
 constexpr int kCfTileW = 64, kCfTileH = 32;
 
 struct CFParams {
@@ -36,10 +39,16 @@ struct CFParams {
 
 // Records of the active cells, in the caller's workspace.
 struct CFWork {
-    float4 *pif_a;   // [N][K][cap]   X, Y, inv, c
-    int4 *pif_b;     // [N][K][cap]   xr, yr, bits of sg, cell
-    float4 *paf_a;   // [N][L][acap]  c, x1, y1, B1
-    float4 *paf_b;   // [N][L][acap]  x2, y2, B2, unused
+    float4 *pif_a;        // [N][K][cap]   X, Y, inv, c
+    int4 *pif_b;          // [N][K][cap]   xr, yr, bits of sg, cell
+    float4 *fwd_s;        // [N][L][acap]  searched from part a: P1.x, P1.y, 1 / B1, c * F2
+    float4 *bwd_s;        // [N][L][acap]  searched from part b: P2.x, P2.y, 1 / B2, c * F1
+    float4 *fwd_r;        // [N][L][acap]  followed forwards: radius at P2, the point the reverse search leads back to, 1 (0: none)
+    float4 *bwd_r;        // [N][L][acap]  followed backwards
+    float4 *seed;         // [N][K * cap]  the seeds in the order they are taken: X, Y, sg, value
+    float4 *ghost;        // [N][K * cap]  the seeds grown in vain: X, Y, sg, bits of the part
+    int32_t *seed_part;   // [N][K * cap]
+    int32_t *seed_count;  // [N]
     size_t bytes;
 };
 
@@ -55,8 +64,14 @@ static CFWork cf_layout(void *base, int N, int K, int L, int cap, int acap)
     };
     w.pif_a = (float4 *)take(sizeof(float4) * (size_t)N * K * cap);
     w.pif_b = (int4 *)take(sizeof(int4) * (size_t)N * K * cap);
-    w.paf_a = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
-    w.paf_b = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.fwd_s = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.bwd_s = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.fwd_r = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.bwd_r = (float4 *)take(sizeof(float4) * (size_t)N * L * acap);
+    w.seed = (float4 *)take(sizeof(float4) * (size_t)N * K * cap);
+    w.ghost = (float4 *)take(sizeof(float4) * (size_t)N * K * cap);
+    w.seed_part = (int32_t *)take(sizeof(int32_t) * (size_t)N * K * cap);
+    w.seed_count = (int32_t *)take(sizeof(int32_t) * (size_t)N);
     w.bytes = off;
     return w;
 }
@@ -154,18 +169,68 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
     }
 }
 
-// ---- C4: active associations of a limb and their two map samples --------------------------------------------------
+// ---- C4: active associations of a limb, their map samples, and what each would propose ---------------------------
 struct CFLimbs {
     uint8_t a[HP_MAX_LIMBS], b[HP_MAX_LIMBS];
 };
 
-__global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ paf, CFParams P, CFWork ws, CFLimbs limbs,
-                                                         const int32_t *__restrict__ pif_count,
-                                                         int32_t *__restrict__ out_cell, float *__restrict__ out_f1,
-                                                         float *__restrict__ out_f2, int32_t *__restrict__ out_count,
-                                                         int32_t *__restrict__ status)
+// C4 score of one search record (source point x, y; 1 / spread; c * F of the other end) for a joint at (qx, qy)
+__device__ __forceinline__ float cf_score(const float4 r, float qx, float qy)
+{
+    const float dx = qx - r.x, dy = qy - r.y;
+    const float d = sqrtf(dx * dx + dy * dy);
+    return r.w * cf_expneg(d * r.z);
+}
+
+// C3 for one image: the seeds sorted by (value descending, part ascending, cell ascending), written to the workspace.
+__device__ void cf_sort_seeds(const CFParams &P, const CFWork &ws, int n, const int32_t *__restrict__ pif_count,
+                              const float *__restrict__ pif_val, uint64_t *s_key)
+{
+    __shared__ int s_nseeds;
+    const int tid = threadIdx.x, K = P.K;
+    if (tid == 0) s_nseeds = 0;
+    __syncthreads();
+    for (int k = 0; k < K; ++k) {
+        const int cnt = min(pif_count[(size_t)n * K + k], P.cap);
+        for (int q = tid; q < cnt; q += kCfBlock) {
+            const float v = pif_val[((size_t)n * K + k) * P.cap + q];
+            if (v > P.seed_thr)
+                s_key[atomicAdd(&s_nseeds, 1)] = ((uint64_t)(~float_order(v)) << 32) | (uint32_t)((k << 16) | q);
+        }
+    }
+    __syncthreads();
+    const int ns = s_nseeds;                                   // at most K * cap <= the seed capacity
+    int n2 = 1;
+    while (n2 < ns) n2 <<= 1;
+    for (int i = ns + tid; i < n2; i += kCfBlock) s_key[i] = ~0ull;
+    __syncthreads();
+    block_bitonic_sort(s_key, n2);
+    __syncthreads();
+    const size_t base = (size_t)n * K * P.cap;
+    for (int i = tid; i < ns; i += kCfBlock) {
+        const uint64_t key = s_key[i];
+        const int k = (int)((uint32_t)key >> 16), rank = (int)((uint32_t)key & 0xFFFFu);
+        const float4 ra = ws.pif_a[((size_t)n * K + k) * P.cap + rank];
+        const int4 rb = ws.pif_b[((size_t)n * K + k) * P.cap + rank];
+        ws.seed[base + i] = make_float4(ra.x, ra.y, __int_as_float(rb.z), float_unorder(~(uint32_t)(key >> 32)));
+        ws.seed_part[base + i] = k;
+    }
+    if (tid == 0) ws.seed_count[n] = ns;
+}
+
+// Workgroups (l < L, n): limb l of image n.  Workgroups (L, n): the seeds of image n.
+__global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ pif, const float *__restrict__ paf, CFParams P,
+                                                     CFWork ws, CFLimbs limbs, const int32_t *__restrict__ pif_count,
+                                                     const float *__restrict__ pif_val, int32_t *__restrict__ out_cell,
+                                                     float *__restrict__ out_f1, float *__restrict__ out_f2,
+                                                     int32_t *__restrict__ out_count, int32_t *__restrict__ status)
 {
     extern __shared__ float4 s_dyn4[];
+    const int l = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
+    if (l == P.L) {
+        cf_sort_seeds(P, ws, n, pif_count, pif_val, (uint64_t *)s_dyn4);
+        return;
+    }
     float4 *s_aa = s_dyn4;                        // part a: [cap] X, Y, inv, c
     int4 *s_ab = (int4 *)(s_dyn4 + P.cap);        //         [cap] xr, yr, sg, cell
     float4 *s_ba = s_dyn4 + 2 * P.cap;            // part b
@@ -173,7 +238,6 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     __shared__ int s_scan[kCfBlock / kWave + 1];
     __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
 
-    const int l = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
     if (tid == 0) {
 #pragma unroll
         for (int i = 0; i < HP_MAX_LIMBS; ++i) {
@@ -197,6 +261,7 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     const float *f = paf + ((size_t)n * P.L + l) * 7 * cells;
     const size_t list = ((size_t)n * P.L + l) * P.acap;
     const float s = (float)P.stride;
+    float4 *fs = ws.fwd_s + list, *bs = ws.bwd_s + list;
 
     int count = 0;
     for (int c0 = 0; c0 < cells; c0 += kCfBlock) {
@@ -215,9 +280,9 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
         int total;
         const int at = count + block_flag_scan(act, s_scan, total);   // its first barrier also covers the lists above
         if (act && at < P.acap) {
-            const float B1 = fmaxf(f[3 * cells + cell] * s, 1.0f), B2 = fmaxf(f[6 * cells + cell] * s, 1.0f);
-            ws.paf_a[list + at] = make_float4(c, x1, y1, B1);
-            ws.paf_b[list + at] = make_float4(x2, y2, B2, 0.0f);
+            const float iB1 = 1.0f / fmaxf(f[3 * cells + cell] * s, 1.0f), iB2 = 1.0f / fmaxf(f[6 * cells + cell] * s, 1.0f);
+            fs[at] = make_float4(x1, y1, iB1, c);         // c is replaced by c * F2 below
+            bs[at] = make_float4(x2, y2, iB2, c);
             out_cell[list + at] = cell;
         }
         count += total;
@@ -225,9 +290,38 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     __syncthreads();   // the records written above are read back by other threads of this workgroup
     const int m = min(count, P.acap);
     for (int i = tid; i < m; i += kCfBlock) {
-        const float4 ra = ws.paf_a[list + i], rb = ws.paf_b[list + i];
-        out_f1[list + i] = cf_sample(s_aa, s_ab, na, (int)rintf(ra.y), (int)rintf(ra.z));
-        out_f2[list + i] = cf_sample(s_ba, s_bb, nb, (int)rintf(rb.x), (int)rintf(rb.y));
+        float4 ra = fs[i], rb = bs[i];
+        const float F1 = cf_sample(s_aa, s_ab, na, (int)rintf(ra.x), (int)rintf(ra.y));
+        const float F2 = cf_sample(s_ba, s_bb, nb, (int)rintf(rb.x), (int)rintf(rb.y));
+        out_f1[list + i] = F1;
+        out_f2[list + i] = F2;
+        ra.w = ra.w * F2;
+        rb.w = rb.w * F1;
+        fs[i] = ra;
+        bs[i] = rb;
+    }
+    __syncthreads();
+    // What a search's winner proposes does not depend on the person: the target's radius (C5) and the point the
+    // reverse search (C5) leads back to.  Task 2 i: association i followed forwards; task 2 i + 1: backwards.
+    const float *sig_a = pif + (((size_t)n * P.K + pa) * 5 + 4) * cells, *sig_b = pif + (((size_t)n * P.K + pb) * 5 + 4) * cells;
+    for (int t = tid; t < 2 * m; t += kCfBlock) {
+        const int i = t >> 1;
+        const bool forward = (t & 1) == 0;
+        const float4 *back = forward ? bs : fs, *from = forward ? fs : bs;   // searched on the way back; holds the points led back to
+        const float tx = back[i].x, ty = back[i].y;
+        float best = 0.0f;
+        int r = -1;
+        for (int j = 0; j < m; ++j) {
+            const float sc = cf_score(back[j], tx, ty);
+            if (sc > best) {
+                best = sc;
+                r = j;
+            }
+        }
+        const int cy = (int)rintf(ty) / P.stride, cx = (int)rintf(tx) / P.stride;
+        const float rad = fmaxf((forward ? sig_b : sig_a)[(size_t)cy * P.Fw + cx] * s, 1.0f);
+        const float4 res = r >= 0 ? make_float4(rad, from[r].x, from[r].y, 1.0f) : make_float4(rad, 0.0f, 0.0f, 0.0f);
+        (forward ? ws.fwd_r : ws.bwd_r)[list + i] = res;
     }
     if (tid == 0) {
         out_count[(size_t)n * P.L + l] = count;
@@ -235,7 +329,7 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     }
 }
 
-// ---- C3, C5-C8: seeds and persons of one image -----------------------------------------------------------------
+// ---- C5-C8: persons of one image ---------------------------------------------------------------------------------
 // C7 for one joint of a recorded person (x, y, radius, value; value 0 = part not held)
 __device__ __forceinline__ bool cf_covers(const float4 j, float x, float y)
 {
@@ -244,19 +338,13 @@ __device__ __forceinline__ bool cf_covers(const float4 j, float x, float y)
     return dx * dx + dy * dy <= j.z * j.z;
 }
 
-// C4: the best association of a limb's list for a joint at (qx, qy), searched by one wavefront.  Returns
+// C4: the best record of a list for a joint at (qx, qy), searched by one wavefront.  Returns
 // (score order) << 32 | (0xFFFFFFFF - index), the same in every lane, or 0 when no score exceeds `above`.
-__device__ __forceinline__ uint64_t cf_search(const float4 *__restrict__ pa, const float4 *__restrict__ pb,
-                                              const float *__restrict__ fother, int cnt, bool forward, float qx,
-                                              float qy, float above, int lane)
+__device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx, float qy, float above, int lane)
 {
     uint64_t key = 0ull;
     for (int i = lane; i < cnt; i += kWave) {
-        const float4 ra = pa[i], rb = pb[i];
-        const float dx = qx - (forward ? ra.y : rb.x), dy = qy - (forward ? ra.z : rb.y);
-        const float d = sqrtf(dx * dx + dy * dy);
-        const float e = cf_expneg(d / (forward ? ra.w : rb.z));
-        const float sc = (ra.x * e) * fother[i];
+        const float sc = cf_score(S[i], qx, qy);
         if (sc > above) {
             const uint64_t mine = ((uint64_t)float_order(sc) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)i);
             key = mine > key ? mine : key;
@@ -270,165 +358,170 @@ __device__ __forceinline__ uint64_t cf_search(const float4 *__restrict__ pa, con
     return key;
 }
 
-__global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(const float *__restrict__ pif, CFParams P, CFWork ws,
-                                                          CFLimbs limbs, const int32_t *__restrict__ pif_count,
-                                                          const float *__restrict__ pif_val,
-                                                          const int32_t *__restrict__ paf_count,
-                                                          const float *__restrict__ paf_f1,
-                                                          const float *__restrict__ paf_f2, float *__restrict__ xyv,
+// One workgroup per image.  A barrier costs about as much as a search here, so the loop is built to need few:
+// one to pick the next seed, one to set its person up, two per round of growth, one when a person is recorded.
+__global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws, CFLimbs limbs, int lds_cells,
+                                                          const int32_t *__restrict__ paf_count, float *__restrict__ xyv,
                                                           int32_t *__restrict__ nparts, float *__restrict__ score,
                                                           int32_t *__restrict__ pcount, int32_t *__restrict__ status)
 {
-    extern __shared__ uint64_t s_dyn8[];
-    uint64_t *s_key = s_dyn8;                                  // [seed capacity] (inverted value order) << 32 | part << 16 | rank
-    float4 *s_person = (float4 *)(s_dyn8 + kCfMaxSeeds);       // [pcap][K] x, y, radius, value of the recorded persons
+    extern __shared__ float4 s_dyn4[];
+    float4 *s_person = s_dyn4;                                 // [pcap][K] x, y, radius, value of the recorded persons
+    float4 *s_rec = s_dyn4 + P.pcap * P.K;                     // [4][lds_cells] records of the limbs that fit: searched
+                                                               // forwards, backwards; proposed forwards, backwards
     __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
-    __shared__ int s_cnt[HP_MAX_PARTS], s_acnt[HP_MAX_LIMBS];
-    __shared__ int s_held[HP_MAX_PARTS], s_was[HP_MAX_PARTS];
+    __shared__ int s_acnt[HP_MAX_LIMBS], s_off[HP_MAX_LIMBS];  // associations of a limb; where its records start in LDS, -1 = not there
+    __shared__ int s_held[HP_MAX_PARTS];
     __shared__ float4 s_joint[HP_MAX_PARTS];                   // x, y, radius, value of the growing person
-    __shared__ float4 s_prop[HP_MAX_LIMBS];                    // a round's proposals: score, x, y, 1 (0 = none)
-    __shared__ int s_front[HP_MAX_LIMBS];
-    __shared__ int s_nfront, s_nseeds, s_next, s_added[2];
+    __shared__ float4 s_prop[HP_MAX_LIMBS];                    // a round's proposals: score, x, y, radius
+    __shared__ int s_dst[HP_MAX_LIMBS];                        // the part a proposal is for, -1 = the limb proposes nothing
+    __shared__ int s_first[2][kCfGrowBlock / kWave], s_added[2];
+    __shared__ float4 s_seed;                                  // the seed being grown: x, y, radius, part
+    constexpr int kWaves = kCfGrowBlock / kWave;
 
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-    const int K = P.K, L = P.L, cells = P.Fh * P.Fw;
+    const int K = P.K, L = P.L;
     if (tid == 0) {
 #pragma unroll
         for (int i = 0; i < HP_MAX_LIMBS; ++i) {
             s_la[i] = limbs.a[i];
             s_lb[i] = limbs.b[i];
         }
-        s_nseeds = 0;
-    }
-    if (tid < K) s_cnt[tid] = min(pif_count[(size_t)n * K + tid], P.cap);
-    if (tid < L) s_acnt[tid] = min(paf_count[(size_t)n * L + tid], P.acap);
-    __syncthreads();
-
-    // C3: the seeds, sorted by (value descending, part ascending, cell ascending)
-    for (int k = 0; k < K; ++k)
-        for (int q = tid; q < s_cnt[k]; q += kCfGrowBlock) {
-            const float v = pif_val[((size_t)n * K + k) * P.cap + q];
-            if (v > P.seed_thr)
-                s_key[atomicAdd(&s_nseeds, 1)] = ((uint64_t)(~float_order(v)) << 32) | (uint32_t)((k << 16) | q);
+        int off = 0;
+        for (int l = 0; l < L; ++l) {
+            const int c = min(paf_count[(size_t)n * L + l], P.acap);
+            s_acnt[l] = c;
+            s_off[l] = off + c <= lds_cells ? off : -1;
+            if (s_off[l] >= 0) off += c;
         }
+        s_added[0] = s_added[1] = 0;
+    }
     __syncthreads();
-    const int ns = s_nseeds;                                   // at most K * cap <= the seed capacity
-    int n2 = 1;
-    while (n2 < ns) n2 <<= 1;
-    for (int i = ns + tid; i < n2; i += kCfGrowBlock) s_key[i] = ~0ull;
-    __syncthreads();
-    block_bitonic_sort(s_key, n2);
+    for (int l = 0; l < L; ++l) {
+        if (s_off[l] < 0) continue;
+        const size_t list = ((size_t)n * L + l) * P.acap;
+        for (int i = tid; i < s_acnt[l]; i += kCfGrowBlock) {
+            s_rec[0 * lds_cells + s_off[l] + i] = ws.fwd_s[list + i];
+            s_rec[1 * lds_cells + s_off[l] + i] = ws.bwd_s[list + i];
+            s_rec[2 * lds_cells + s_off[l] + i] = ws.fwd_r[list + i];
+            s_rec[3 * lds_cells + s_off[l] + i] = ws.bwd_r[list + i];
+        }
+    }
+    const int ns = ws.seed_count[n];
+    const size_t seed0 = (size_t)n * K * P.cap;
+    float4 *ghost = ws.ghost + seed0;
 
-    int np = 0;          // persons recorded so far (the same in every thread)
+    int np = 0, ng = 0;  // persons recorded, seeds grown in vain (the same in every thread)
+    int it = 0, rounds = 0;
     bool stop = false;   // C8
     for (int base = 0; base < ns && !stop; base += kCfGrowBlock) {
-        // this thread's seed of the batch, tested against everyone recorded so far
+        // this thread's seed of the batch, tested against everything found so far
         const int mine = base + tid;
         bool occ = true;
         int sk = 0;
-        float sx = 0.0f, sy = 0.0f;
+        float4 sd = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (mine < ns) {
-            const uint32_t id = (uint32_t)s_key[mine];
-            sk = (int)(id >> 16);
-            const float4 ra = ws.pif_a[((size_t)n * K + sk) * P.cap + (id & 0xFFFFu)];
-            sx = ra.x;
-            sy = ra.y;
+            sd = ws.seed[seed0 + mine];
+            sk = ws.seed_part[seed0 + mine];
             occ = false;
-            for (int p = 0; p < np && !occ; ++p) occ = cf_covers(s_person[p * K + sk], sx, sy);
+            for (int p = 0; p < np && !occ; ++p) occ = cf_covers(s_person[p * K + sk], sd.x, sd.y);
+            for (int g = 0; g < ng && !occ; ++g) {
+                const float4 gh = ghost[g];
+                occ = __float_as_int(gh.w) == sk && cf_covers(make_float4(gh.x, gh.y, gh.z, 1.0f), sd.x, sd.y);
+            }
         }
         for (;;) {
+            // the first seed of the batch that is still free
+            const uint64_t free_mask = __ballot(!occ);
+            if (lane == 0) s_first[it & 1][wv] = free_mask ? base + wv * kWave + __ffsll((long long)free_mask) - 1 : INT_MAX;
             __syncthreads();
-            if (tid == 0) s_next = INT_MAX;
-            __syncthreads();
-            if (!occ) atomicMin(&s_next, mine);
-            __syncthreads();
-            const int cur = s_next;
+            int cur = INT_MAX;
+#pragma unroll
+            for (int u = 0; u < kWaves; ++u) cur = min(cur, s_first[it & 1][u]);
+            ++it;
             if (cur == INT_MAX) break;
             if (np >= P.pcap) {
                 if (tid == 0) atomicOr(status, HP_STATUS_POSE_OVERFLOW);
                 stop = true;
                 break;
             }
-            if (mine == cur) occ = true;                       // taken
-
-            // ---- C5: the person of seed `cur` ----
-            if (tid < K) s_held[tid] = 0;
-            __syncthreads();
-            if (tid == 0) {
-                const uint64_t key = s_key[cur];
-                const int k0 = (int)((uint32_t)key >> 16), rank = (int)((uint32_t)key & 0xFFFFu);
-                const float4 ra = ws.pif_a[((size_t)n * K + k0) * P.cap + rank];
-                const int4 rb = ws.pif_b[((size_t)n * K + k0) * P.cap + rank];
-                s_held[k0] = 1;
-                s_joint[k0] = make_float4(ra.x, ra.y, __int_as_float(rb.z), float_unorder(~(uint32_t)(key >> 32)));
+            // ---- C5: the person of seed `cur`, set up by the thread that holds the seed ----
+            if (mine == cur) {
+                occ = true;
+                for (int k = 0; k < K; ++k) s_held[k] = k == sk;
+                s_joint[sk] = sd;
+                s_seed = make_float4(sd.x, sd.y, sd.z, __int_as_float(sk));
             }
             __syncthreads();
-            for (int round = 0;; ++round) {
-                if (wv == 0) {                                 // the limbs with exactly one part held, in table order
-                    const bool fr = lane < L && (s_held[s_la[lane < L ? lane : 0]] != s_held[s_lb[lane < L ? lane : 0]]);
-                    const uint64_t m = __ballot(fr);
-                    if (fr) s_front[__popcll(m & ((1ull << lane) - 1ull))] = lane;
-                    if (lane == 0) {
-                        s_nfront = __popcll(m);
-                        s_added[round & 1] = 0;
-                    }
-                }
-                if (tid >= kWave && tid < kWave + K) s_was[tid - kWave] = s_held[tid - kWave];
-                if (tid >= 2 * kWave && tid < 2 * kWave + L) s_prop[tid - 2 * kWave].w = 0.0f;
-                __syncthreads();
-                const int nf = s_nfront;
-                if (nf == 0) break;
-                for (int fi = wv; fi < nf; fi += kCfGrowBlock / kWave) {
-                    const int l = s_front[fi], a = s_la[l], b = s_lb[l];
-                    const bool forward = s_was[a] != 0;
+            for (;; ++rounds) {
+                // the limbs with exactly one part held, in table order (every wavefront computes the same mask)
+                const int ll = lane < L ? lane : 0;
+                const int ha = s_held[s_la[ll]], hb = s_held[s_lb[ll]];
+                const uint64_t front = __ballot(lane < L && ha != hb);
+                if (front == 0ull) break;
+                int nth = 0;
+                for (uint64_t rest = front; rest; rest &= rest - 1, ++nth) {
+                    if ((nth & (kWaves - 1)) != wv) continue;
+                    const int l = __ffsll((long long)rest) - 1, a = s_la[l], b = s_lb[l];
+                    const bool forward = s_held[a] != 0;
                     const int src = forward ? a : b, dst = forward ? b : a;
                     const float qx = s_joint[src].x, qy = s_joint[src].y;
                     const size_t list = ((size_t)n * L + l) * P.acap;
-                    const float4 *pa = ws.paf_a + list, *pb = ws.paf_b + list;
-                    const float *f1 = paf_f1 + list, *f2 = paf_f2 + list;
-                    const int cnt = s_acnt[l];
-                    const uint64_t found = cf_search(pa, pb, forward ? f2 : f1, cnt, forward, qx, qy, P.grow_thr, lane);
-                    if (found == 0ull) continue;
-                    const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
-                    const float sc = float_unorder((uint32_t)(found >> 32));
-                    const float tx = forward ? pb[i].x : pa[i].y, ty = forward ? pb[i].y : pa[i].z;
-                    const uint64_t back = cf_search(pa, pb, forward ? f1 : f2, cnt, !forward, tx, ty, 0.0f, lane);
-                    if (back == 0ull) continue;
-                    const int r = (int)(0xFFFFFFFFu - (uint32_t)back);
-                    const float dx = (forward ? pa[r].y : pb[r].x) - qx, dy = (forward ? pa[r].z : pb[r].y) - qy;
-                    if (!(dx * dx + dy * dy <= P.rev_tol * P.rev_tol)) continue;
-                    bool taken = false;
-                    for (int p = lane; p < np; p += kWave) taken = taken || cf_covers(s_person[p * K + dst], tx, ty);
-                    if (__ballot(taken) != 0ull) continue;
-                    if (lane == 0) s_prop[l] = make_float4(sc, tx, ty, 1.0f);
+                    const int off = s_off[l];
+                    // searched records; the records whose points the winner proposes; what else the winner proposes
+                    const float4 *S = off >= 0 ? s_rec + (forward ? 0 : 1) * lds_cells + off : (forward ? ws.fwd_s : ws.bwd_s) + list;
+                    const float4 *T = off >= 0 ? s_rec + (forward ? 1 : 0) * lds_cells + off : (forward ? ws.bwd_s : ws.fwd_s) + list;
+                    const float4 *R = off >= 0 ? s_rec + (forward ? 2 : 3) * lds_cells + off : (forward ? ws.fwd_r : ws.bwd_r) + list;
+                    int proposes = -1;
+                    float4 prop = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    const uint64_t found = cf_search(S, s_acnt[l], qx, qy, P.grow_thr, lane);
+                    if (found != 0ull) {
+                        const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
+                        const float4 res = R[i];               // radius, point led back to, found
+                        const float tx = T[i].x, ty = T[i].y;
+                        const float dx = res.y - qx, dy = res.z - qy;
+                        if (res.w != 0.0f && dx * dx + dy * dy <= P.rev_tol * P.rev_tol) {
+                            bool taken = false;
+                            for (int p = lane; p < np; p += kWave) taken = taken || cf_covers(s_person[p * K + dst], tx, ty);
+                            if (__ballot(taken) == 0ull) {
+                                proposes = dst;
+                                prop = make_float4(float_unorder((uint32_t)(found >> 32)), tx, ty, res.x);
+                            }
+                        }
+                    }
+                    if (lane == 0) {
+                        s_dst[l] = proposes;
+                        s_prop[l] = prop;
+                    }
                 }
                 __syncthreads();
-                if (tid < K && !s_was[tid]) {                  // the best proposal for part `tid`, the earlier limb on ties
+                if (tid == 0) s_added[(rounds + 1) & 1] = 0;   // the next round's flag; everyone has read it for the last time
+                if (tid < K && !s_held[tid]) {                 // the best proposal for part `tid`, the earlier limb on ties
                     bool have = false;
                     float4 best = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                    for (int l = 0; l < L; ++l) {
+                    for (uint64_t rest = front; rest; rest &= rest - 1) {
+                        const int l = __ffsll((long long)rest) - 1;
+                        if (s_dst[l] != tid) continue;
                         const float4 pr = s_prop[l];
-                        if (pr.w == 0.0f) continue;
-                        const int a = s_la[l], b = s_lb[l];
-                        if ((s_was[a] ? b : a) != tid) continue;
                         if (!have || pr.x > best.x) {
                             best = pr;
                             have = true;
                         }
                     }
                     if (have) {
-                        const int cy = (int)rintf(best.z) / P.stride, cx = (int)rintf(best.y) / P.stride;
-                        const float sig = pif[(((size_t)n * K + tid) * 5 + 4) * cells + (size_t)cy * P.Fw + cx];
                         s_held[tid] = 1;
-                        s_joint[tid] = make_float4(best.y, best.z, fmaxf(sig * (float)P.stride, 1.0f), best.x);
-                        s_added[round & 1] = 1;
+                        s_joint[tid] = make_float4(best.y, best.z, best.w, best.x);
+                        s_added[rounds & 1] = 1;
                     }
                 }
                 __syncthreads();
-                if (!s_added[round & 1]) break;
+                if (!s_added[rounds & 1]) {
+                    ++rounds;
+                    break;
+                }
             }
 
-            // ---- C6: record ----
+            // ---- C6: record, or remember the seed as grown in vain (C7) ----
             int parts = 0;
             for (int k = 0; k < K; ++k) parts += s_held[k];
             if (parts >= P.min_parts) {
@@ -440,7 +533,7 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(const float *__restric
                     o[1] = j.y;
                     o[2] = j.w;
                 }
-                if (tid == 0) {
+                if (tid == kWave) {
                     float sum = 0.0f;
                     for (int k = 0; k < K; ++k)
                         if (s_held[k]) sum = sum + s_joint[k].w;
@@ -448,8 +541,13 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(const float *__restric
                     score[(size_t)n * P.pcap + np] = sum / (float)K;
                 }
                 __syncthreads();
-                if (!occ) occ = cf_covers(s_person[np * K + sk], sx, sy);
+                if (!occ) occ = cf_covers(s_person[np * K + sk], sd.x, sd.y);
                 ++np;
+            } else {
+                const float4 gh = s_seed;
+                if (tid == 0) ghost[ng] = gh;
+                if (!occ) occ = __float_as_int(gh.w) == sk && cf_covers(make_float4(gh.x, gh.y, gh.z, 1.0f), sd.x, sd.y);
+                ++ng;
             }
         }
     }
@@ -538,24 +636,37 @@ static CFLimbs cf_limbs(const LimbTable &T, int L)
     return limbs;
 }
 
-hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
-                         const hp_cf_lists &lists, void *workspace, int32_t *status, hipStream_t s)
+hipError_t launch_cf_paf(const float *pif, const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L,
+                         const hp_cf_params &prm, const hp_cf_lists &lists, void *workspace, int32_t *status, hipStream_t s)
 {
     const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, 0);
     const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
-    HP_KERNEL(k_cf_paf, dim3(L, N), dim3(kCfBlock), sizeof(float4) * 4 * (size_t)lists.cap, s, paf, P, ws, cf_limbs(T, L),
-              lists.pif_count, lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
+    // the limb workgroups hold two parts' cell lists, the seed workgroups the keys they sort
+    const size_t lds = std::max(sizeof(float4) * 4 * (size_t)lists.cap, sizeof(uint64_t) * (size_t)next_pow2(K * lists.cap));
+    HP_KERNEL(k_cf_paf, dim3(L + 1, N), dim3(kCfBlock), lds, s, pif, paf, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
+              lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
     return hipGetLastError();
 }
 
-hipError_t launch_cf_grow(const float *pif, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+// LDS the persons kernel may use: the device allows 160 KB a workgroup; 144 KB leaves room for the static arrays.
+constexpr size_t kCfGrowLds = 144 * 1024;
+
+hipError_t launch_cf_grow(int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
                           const hp_cf_lists &lists, const hp_cf_poses &poses, void *workspace, int32_t *status, hipStream_t s)
 {
     const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, poses.cap);
     const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
-    const size_t lds = sizeof(uint64_t) * kCfMaxSeeds + sizeof(float4) * (size_t)poses.cap * K;
-    HP_KERNEL(k_cf_grow, dim3(N), dim3(kCfGrowBlock), lds, s, pif, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
-              lists.paf_count, lists.paf_f1, lists.paf_f2, poses.xyv, poses.nparts, poses.score, poses.count, status);
+    const size_t persons = sizeof(float4) * (size_t)poses.cap * K;
+    // search records kept in LDS: all of them when the lists' capacity fits, else the limbs that fit in table order
+    const size_t room = (kCfGrowLds - persons) / (4 * sizeof(float4));
+    const int lds_cells = (int)std::min(room, (size_t)L * lists.acap);
+    const size_t lds = persons + 4 * sizeof(float4) * (size_t)lds_cells;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_cf_grow, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCfGrowLds);
+        if (e != hipSuccess) return e;
+    }
+    HP_KERNEL(k_cf_grow, dim3(N), dim3(kCfGrowBlock), lds, s, P, ws, cf_limbs(T, L), lds_cells, lists.paf_count, poses.xyv,
+              poses.nparts, poses.score, poses.count, status);
     return hipGetLastError();
 }
 

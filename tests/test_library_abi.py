@@ -288,3 +288,58 @@ def test_pp_decode_rejects_bad_calls(L):
     assert call(skel=byref(twice.c)) == -1 and call(skel=byref(orphan.c)) == -1
     assert call(prm=byref(B._PPParams(0.3, float("nan"), 0.3, 1, 64.0, 64.0))) == -1
     assert call(prm=byref(B._PPParams(0.3, 0.3, 0.3, 1, 0.0, 64.0))) == -1
+
+
+def test_cf_decode_rejects_bad_calls(L):
+    from paper_2108_11826_amd import binding as B
+    sk = B.Skeleton(3, np.array([0, 1, 2], np.int32), np.array([1, 2, 0], np.int32))      # a cycle is a valid table
+    prm = B._CFParams(0.1, 0.1, 0.2, 0.05, 4.0, 1, 8)
+    lists = B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 128)
+    ps = B._CFPoses(FAKE, FAKE, FAKE, FAKE, 16)
+    a = c_void_p(FAKE)
+    need = L.hp_cf_workspace_bytes(2, 3, 3, 64, 128)
+    assert need >= 2 * 3 * (64 + 128) * 32 and L.hp_cf_workspace_bytes(0, 3, 3, 64, 128) == 0
+    ok = dict(pif=a, paf=a, N=2, Fh=10, Fw=12, skel=byref(sk.c), prm=byref(prm), lists=byref(lists), poses=byref(ps), ws=a,
+              wsb=ctypes.c_size_t(need), status=a, stream=None)
+
+    def call(**kw):
+        x = dict(ok)
+        x.update(kw)
+        return L.hp_cf_decode(*[x[k] for k in ("pif", "paf", "N", "Fh", "Fw", "skel", "prm", "lists", "poses", "ws", "wsb",
+                                                "status", "stream")])
+
+    assert call(pif=None) == -1 and call(paf=None) == -1 and call(status=None) == -1 and call(ws=None) == -1
+    assert call(prm=None) == -1 and call(lists=None) == -1 and call(poses=None) == -1 and call(skel=None) == -1
+    assert call(N=0) == -1 and call(Fh=0) == -1 and call(Fw=-3) == -1
+    assert call(wsb=ctypes.c_size_t(need - 1)) == -3 and call(ws=c_void_p(FAKE + 4)) == -3
+    for bad in (B._CFParams(-0.1, 0.1, 0.2, 0.05, 4.0, 1, 8), B._CFParams(0.1, float("nan"), 0.2, 0.05, 4.0, 1, 8),
+                B._CFParams(0.1, 0.1, 0.2, -1.0, 4.0, 1, 8), B._CFParams(0.1, 0.1, 0.2, 0.05, 4.0, -1, 8),
+                B._CFParams(0.1, 0.1, 0.2, 0.05, 4.0, 1, 0)):
+        assert call(prm=byref(bad)) == -1
+    assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 128))) == -1
+    assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 64, 128))) == -1
+    big = L.hp_cf_workspace_bytes(2, 3, 3, 513, 128)
+    assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 513, 128)), wsb=ctypes.c_size_t(big)) == -5
+    assert call(poses=byref(B._CFPoses(FAKE, FAKE, FAKE, FAKE, 513))) == -5               # 3 * 513 > 1536 joints in LDS
+    assert call(prm=byref(B._CFParams(0.1, 0.1, 0.2, 0.05, 4.0, 1, 1 << 22))) == -5        # the map would pass 2^23 pixels a side
+
+
+def test_cf_field_rejects_bad_calls(L):
+    from paper_2108_11826_amd import binding as B
+    prm = B._CFParams(0.1, 0.0, 0.0, 0.0, 0.0, 0, 8)
+    a = c_void_p(FAKE)
+    need = L.hp_cf_workspace_bytes(2, 5, 0, 64, 0)
+    assert need >= 2 * 5 * 64 * 32
+    ok = dict(pif=a, N=2, K=5, Fh=10, Fw=12, prm=byref(prm), cell=a, val=a, count=a, cap=64, out=a, ws=a,
+              wsb=ctypes.c_size_t(need), status=a, stream=None)
+
+    def call(**kw):
+        x = dict(ok)
+        x.update(kw)
+        return L.hp_cf_field(*[x[k] for k in ("pif", "N", "K", "Fh", "Fw", "prm", "cell", "val", "count", "cap", "out", "ws",
+                                               "wsb", "status", "stream")])
+
+    assert call(pif=None) == -1 and call(out=None) == -1 and call(count=None) == -1 and call(prm=None) == -1
+    assert call(N=0) == -1 and call(K=0) == -1 and call(cap=0) == -1 and call(Fh=0) == -1
+    assert call(K=33) == -5 and call(cap=513) == -5
+    assert call(wsb=ctypes.c_size_t(need - 1)) == -3

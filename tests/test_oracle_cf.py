@@ -234,6 +234,20 @@ def test_occupied_seeds_are_skipped():
     assert run(4.5) == 2
 
 
+def test_a_seed_grown_in_vain_still_suppresses_its_neighbours():
+    def run(bx):
+        pif, paf = blank(2, 1, 8, 10)
+        put_pif(pif, 0, 20.0, 20.0, c=0.9, sigma=4.0, cell=(2, 2))          # taken first; the association starts too far from it
+        put_pif(pif, 0, bx, 20.0, c=0.6, sigma=4.0, cell=(3, 2))
+        put_pif(pif, 1, 60.0, 20.0, c=0.3)                                   # too weak to seed
+        put_paf(paf, 0, (bx + 2.0, 20.0), (60.0, 20.0), cell=(4, 2))
+        return list(decode(pif, paf, [(0, 1)], min_parts=2, seed_thr=0.5)["poses"][0][1])
+
+    assert run(23.0) == []            # 3 pixels from the first seed (radius 4): never tried
+    assert run(24.0) == []            # on the radius
+    assert run(26.0) == [2]           # outside: it seeds, and the association is within rev_tol of it
+
+
 def test_a_part_reached_by_two_limbs_takes_the_better_proposal():
     square = [(0, 1), (0, 2), (1, 3), (2, 3)]
     for c13, c23, expect in ((0.9, 0.5, (60.0, 60.0)), (0.5, 0.9, (62.0, 61.0)), (0.7, 0.7, (60.0, 60.0))):
