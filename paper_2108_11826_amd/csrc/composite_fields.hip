@@ -358,8 +358,13 @@ __device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx
     return key;
 }
 
-// One workgroup per image.  A barrier costs about as much as a search here, so the loop is built to need few:
-// one to pick the next seed, one to set its person up, two per round of growth, one when a person is recorded.
+// One workgroup per image.  The loop is a chain of short dependent steps, so it is built around what a step costs
+// here: a barrier waits for the workgroup's outstanding global stores, so nothing is stored to global memory before
+// the end (persons, their part counts and scores, and the seeds grown in vain live in LDS); there is one barrier to
+// pick the next seed, one to set its person up and one per round of growth (every wavefront folds the round's
+// proposals into the person by itself, all writing the same values), one more when a person is recorded.
+constexpr int kCfGhostLds = 256;   // seeds grown in vain that are remembered in LDS; later ones go to the workspace
+
 __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws, CFLimbs limbs, int lds_cells,
                                                           const int32_t *__restrict__ paf_count, float *__restrict__ xyv,
                                                           int32_t *__restrict__ nparts, float *__restrict__ score,
@@ -367,16 +372,19 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
 {
     extern __shared__ float4 s_dyn4[];
     float4 *s_person = s_dyn4;                                 // [pcap][K] x, y, radius, value of the recorded persons
-    float4 *s_rec = s_dyn4 + P.pcap * P.K;                     // [4][lds_cells] records of the limbs that fit: searched
+    float *s_pscore = (float *)(s_dyn4 + P.pcap * P.K);        // [pcap]
+    int *s_pparts = (int *)(s_pscore + P.pcap);                // [pcap]
+    float4 *s_rec = s_dyn4 + P.pcap * P.K + (P.pcap + 1) / 2;  // [4][lds_cells] records of the limbs that fit: searched
                                                                // forwards, backwards; proposed forwards, backwards
     __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
     __shared__ int s_acnt[HP_MAX_LIMBS], s_off[HP_MAX_LIMBS];  // associations of a limb; where its records start in LDS, -1 = not there
     __shared__ int s_held[HP_MAX_PARTS];
     __shared__ float4 s_joint[HP_MAX_PARTS];                   // x, y, radius, value of the growing person
-    __shared__ float4 s_prop[HP_MAX_LIMBS];                    // a round's proposals: score, x, y, radius
-    __shared__ int s_dst[HP_MAX_LIMBS];                        // the part a proposal is for, -1 = the limb proposes nothing
-    __shared__ int s_first[2][kCfGrowBlock / kWave], s_added[2];
+    __shared__ float4 s_prop[2][HP_MAX_LIMBS];                 // a round's proposals (rounds alternate): score, x, y, radius
+    __shared__ int s_dst[2][HP_MAX_LIMBS];                     // the part a proposal is for, -1 = the limb proposes nothing
+    __shared__ int s_first[2][kCfGrowBlock / kWave];
     __shared__ float4 s_seed;                                  // the seed being grown: x, y, radius, part
+    __shared__ float4 s_ghost[kCfGhostLds];                    // seeds grown in vain: x, y, radius, part
     constexpr int kWaves = kCfGrowBlock / kWave;
 
     const int n = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
@@ -394,7 +402,6 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
             s_off[l] = off + c <= lds_cells ? off : -1;
             if (s_off[l] >= 0) off += c;
         }
-        s_added[0] = s_added[1] = 0;
     }
     __syncthreads();
     for (int l = 0; l < L; ++l) {
@@ -426,31 +433,35 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
             occ = false;
             for (int p = 0; p < np && !occ; ++p) occ = cf_covers(s_person[p * K + sk], sd.x, sd.y);
             for (int g = 0; g < ng && !occ; ++g) {
-                const float4 gh = ghost[g];
+                const float4 gh = g < kCfGhostLds ? s_ghost[g] : ghost[g];
                 occ = __float_as_int(gh.w) == sk && cf_covers(make_float4(gh.x, gh.y, gh.z, 1.0f), sd.x, sd.y);
             }
         }
         for (;;) {
-            // the first seed of the batch that is still free
+            // the first seed of the batch that is still free, and its part: index << 5 | part
             const uint64_t free_mask = __ballot(!occ);
-            if (lane == 0) s_first[it & 1][wv] = free_mask ? base + wv * kWave + __ffsll((long long)free_mask) - 1 : INT_MAX;
+            const int first_lane = free_mask ? __ffsll((long long)free_mask) - 1 : 0;
+            const int first_part = __shfl(sk, first_lane);
+            if (lane == 0) s_first[it & 1][wv] = free_mask ? ((base + wv * kWave + first_lane) << 5) | first_part : INT_MAX;
             __syncthreads();
-            int cur = INT_MAX;
+            int cur_key = INT_MAX;
 #pragma unroll
-            for (int u = 0; u < kWaves; ++u) cur = min(cur, s_first[it & 1][u]);
+            for (int u = 0; u < kWaves; ++u) cur_key = min(cur_key, s_first[it & 1][u]);
             ++it;
-            if (cur == INT_MAX) break;
+            if (cur_key == INT_MAX) break;
             if (np >= P.pcap) {
                 if (tid == 0) atomicOr(status, HP_STATUS_POSE_OVERFLOW);
                 stop = true;
                 break;
             }
-            // ---- C5: the person of seed `cur`, set up by the thread that holds the seed ----
-            if (mine == cur) {
+            // ---- C5: the person of seed `cur` ----
+            const int cur = cur_key >> 5, k0 = cur_key & 31;
+            const bool owner = mine == cur;
+            if (tid < K) s_held[tid] = tid == k0;
+            if (owner) {
                 occ = true;
-                for (int k = 0; k < K; ++k) s_held[k] = k == sk;
-                s_joint[sk] = sd;
-                s_seed = make_float4(sd.x, sd.y, sd.z, __int_as_float(sk));
+                s_joint[k0] = sd;
+                s_seed = make_float4(sd.x, sd.y, sd.z, __int_as_float(k0));
             }
             __syncthreads();
             for (;; ++rounds) {
@@ -459,6 +470,7 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                 const int ha = s_held[s_la[ll]], hb = s_held[s_lb[ll]];
                 const uint64_t front = __ballot(lane < L && ha != hb);
                 if (front == 0ull) break;
+                const int par = rounds & 1;
                 int nth = 0;
                 for (uint64_t rest = front; rest; rest &= rest - 1, ++nth) {
                     if ((nth & (kWaves - 1)) != wv) continue;
@@ -490,32 +502,31 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                         }
                     }
                     if (lane == 0) {
-                        s_dst[l] = proposes;
-                        s_prop[l] = prop;
+                        s_dst[par][l] = proposes;
+                        s_prop[par][l] = prop;
                     }
                 }
                 __syncthreads();
-                if (tid == 0) s_added[(rounds + 1) & 1] = 0;   // the next round's flag; everyone has read it for the last time
-                if (tid < K && !s_held[tid]) {                 // the best proposal for part `tid`, the earlier limb on ties
-                    bool have = false;
+                // every wavefront folds the proposals in: lane k takes the best one for part k, the earlier limb on
+                // ties.  (Only parts not held are proposed for; what a lane decides depends on the proposals alone.)
+                bool have = false;
+                if (lane < K) {
                     float4 best = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
                     for (uint64_t rest = front; rest; rest &= rest - 1) {
                         const int l = __ffsll((long long)rest) - 1;
-                        if (s_dst[l] != tid) continue;
-                        const float4 pr = s_prop[l];
+                        if (s_dst[par][l] != lane) continue;
+                        const float4 pr = s_prop[par][l];
                         if (!have || pr.x > best.x) {
                             best = pr;
                             have = true;
                         }
                     }
                     if (have) {
-                        s_held[tid] = 1;
-                        s_joint[tid] = make_float4(best.y, best.z, best.w, best.x);
-                        s_added[rounds & 1] = 1;
+                        s_held[lane] = 1;
+                        s_joint[lane] = make_float4(best.y, best.z, best.w, best.x);
                     }
                 }
-                __syncthreads();
-                if (!s_added[rounds & 1]) {
+                if (__ballot(have) == 0ull) {
                     ++rounds;
                     break;
                 }
@@ -525,31 +536,41 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
             int parts = 0;
             for (int k = 0; k < K; ++k) parts += s_held[k];
             if (parts >= P.min_parts) {
-                if (tid < K) {
-                    const float4 j = s_held[tid] ? s_joint[tid] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                    s_person[np * K + tid] = j;
-                    float *o = xyv + (((size_t)n * P.pcap + np) * K + tid) * 3;
-                    o[0] = j.x;
-                    o[1] = j.y;
-                    o[2] = j.w;
-                }
+                if (tid < K) s_person[np * K + tid] = s_held[tid] ? s_joint[tid] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
                 if (tid == kWave) {
                     float sum = 0.0f;
                     for (int k = 0; k < K; ++k)
                         if (s_held[k]) sum = sum + s_joint[k].w;
-                    nparts[(size_t)n * P.pcap + np] = parts;
-                    score[(size_t)n * P.pcap + np] = sum / (float)K;
+                    s_pparts[np] = parts;
+                    s_pscore[np] = sum / (float)K;
                 }
                 __syncthreads();
                 if (!occ) occ = cf_covers(s_person[np * K + sk], sd.x, sd.y);
                 ++np;
             } else {
                 const float4 gh = s_seed;
-                if (tid == 0) ghost[ng] = gh;
+                if (owner) {
+                    if (ng < kCfGhostLds)
+                        s_ghost[ng] = gh;
+                    else
+                        ghost[ng] = gh;
+                }
                 if (!occ) occ = __float_as_int(gh.w) == sk && cf_covers(make_float4(gh.x, gh.y, gh.z, 1.0f), sd.x, sd.y);
                 ++ng;
             }
         }
+    }
+    __syncthreads();
+    for (int i = tid; i < np * K; i += kCfGrowBlock) {
+        const float4 j = s_person[i];
+        float *o = xyv + ((size_t)n * P.pcap * K + i) * 3;
+        o[0] = j.x;
+        o[1] = j.y;
+        o[2] = j.w;
+    }
+    for (int p = tid; p < np; p += kCfGrowBlock) {
+        nparts[(size_t)n * P.pcap + p] = s_pparts[p];
+        score[(size_t)n * P.pcap + p] = s_pscore[p];
     }
     if (tid == 0) pcount[n] = np;
 }
@@ -656,7 +677,7 @@ hipError_t launch_cf_grow(int N, int Fh, int Fw, const LimbTable &T, int K, int 
 {
     const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, poses.cap);
     const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
-    const size_t persons = sizeof(float4) * (size_t)poses.cap * K;
+    const size_t persons = sizeof(float4) * ((size_t)poses.cap * K + (poses.cap + 1) / 2);   // joints, part counts, scores
     // search records kept in LDS: all of them when the lists' capacity fits, else the limbs that fit in table order
     const size_t room = (kCfGrowLds - persons) / (4 * sizeof(float4));
     const int lds_cells = (int)std::min(room, (size_t)L * lists.acap);
