@@ -340,22 +340,25 @@ __device__ __forceinline__ bool cf_covers(const float4 j, float x, float y)
 
 // C4: the best record of a list for a joint at (qx, qy), searched by one wavefront.  Returns
 // (score order) << 32 | (0xFFFFFFFF - index), the same in every lane, or 0 when no score exceeds `above`.
-__device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx, float qy, float above, int lane)
+// The lanes' candidates meet in `slot`, an LDS word of this wavefront's own: LDS serves one wavefront's requests in
+// the order they were issued, so the clearing store, the maxima and the final load need no barrier between them
+// (and cost about a quarter of a butterfly of twelve cross-lane moves).
+__device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx, float qy, float above, int lane,
+                                              unsigned long long *slot)
 {
-    uint64_t key = 0ull;
+    unsigned long long key = 0ull;
     for (int i = lane; i < cnt; i += kWave) {
         const float sc = cf_score(S[i], qx, qy);
         if (sc > above) {
-            const uint64_t mine = ((uint64_t)float_order(sc) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)i);
+            const unsigned long long mine = ((unsigned long long)float_order(sc) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)i);
             key = mine > key ? mine : key;
         }
     }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        const uint64_t other = __shfl_xor(key, off);
-        key = other > key ? other : key;
-    }
-    return key;
+    if (lane == 0) *(volatile unsigned long long *)slot = 0ull;
+    __builtin_amdgcn_wave_barrier();
+    if (key != 0ull) atomicMax(slot, key);
+    __builtin_amdgcn_wave_barrier();
+    return *(volatile unsigned long long *)slot;
 }
 
 // One workgroup per image.  The loop is a chain of short dependent steps, so it is built around what a step costs
@@ -378,12 +381,11 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                                                                // forwards, backwards; proposed forwards, backwards
     __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
     __shared__ int s_acnt[HP_MAX_LIMBS], s_off[HP_MAX_LIMBS];  // associations of a limb; where its records start in LDS, -1 = not there
-    __shared__ int s_held[HP_MAX_PARTS];
-    __shared__ float4 s_joint[HP_MAX_PARTS];                   // x, y, radius, value of the growing person
     __shared__ float4 s_prop[2][HP_MAX_LIMBS];                 // a round's proposals (rounds alternate): score, x, y, radius
     __shared__ int s_dst[2][HP_MAX_LIMBS];                     // the part a proposal is for, -1 = the limb proposes nothing
     __shared__ int s_first[2][kCfGrowBlock / kWave];
-    __shared__ float4 s_seed;                                  // the seed being grown: x, y, radius, part
+    __shared__ unsigned long long s_best[kCfGrowBlock / kWave];   // where a wavefront's search candidates meet
+    __shared__ float4 s_seed;                                  // the seed being grown: x, y, radius, value
     __shared__ float4 s_ghost[kCfGhostLds];                    // seeds grown in vain: x, y, radius, part
     constexpr int kWaves = kCfGrowBlock / kWave;
 
@@ -414,6 +416,13 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
             s_rec[3 * lds_cells + s_off[l] + i] = ws.bwd_r[list + i];
         }
     }
+    // Every wavefront keeps the whole state of the growing person in registers: lane l holds limb l's table entry,
+    // lane k the person's joint k, and the set of held parts is a bit mask; all wavefronts update them alike.
+    const int ll = lane < L ? lane : 0;
+    const int la = s_la[ll], lb = s_lb[ll], lcnt = s_acnt[ll], loff = s_off[ll];
+    float jx = 0.0f, jy = 0.0f, jr = 0.0f, jv = 0.0f;
+    uint32_t held = 0u;
+
     const int ns = ws.seed_count[n];
     const size_t seed0 = (size_t)n * K * P.cap;
     float4 *ghost = ws.ghost + seed0;
@@ -441,7 +450,7 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
             // the first seed of the batch that is still free, and its part: index << 5 | part
             const uint64_t free_mask = __ballot(!occ);
             const int first_lane = free_mask ? __ffsll((long long)free_mask) - 1 : 0;
-            const int first_part = __shfl(sk, first_lane);
+            const int first_part = __builtin_amdgcn_readlane(sk, first_lane);
             if (lane == 0) s_first[it & 1][wv] = free_mask ? ((base + wv * kWave + first_lane) << 5) | first_part : INT_MAX;
             __syncthreads();
             int cur_key = INT_MAX;
@@ -457,36 +466,42 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
             // ---- C5: the person of seed `cur` ----
             const int cur = cur_key >> 5, k0 = cur_key & 31;
             const bool owner = mine == cur;
-            if (tid < K) s_held[tid] = tid == k0;
             if (owner) {
                 occ = true;
-                s_joint[k0] = sd;
-                s_seed = make_float4(sd.x, sd.y, sd.z, __int_as_float(k0));
+                s_seed = sd;
             }
             __syncthreads();
+            const float4 seed = s_seed;
+            held = 1u << k0;
+            if (lane == k0) {
+                jx = seed.x;
+                jy = seed.y;
+                jr = seed.z;
+                jv = seed.w;
+            }
             for (;; ++rounds) {
-                // the limbs with exactly one part held, in table order (every wavefront computes the same mask)
-                const int ll = lane < L ? lane : 0;
-                const int ha = s_held[s_la[ll]], hb = s_held[s_lb[ll]];
-                const uint64_t front = __ballot(lane < L && ha != hb);
+                // the limbs with exactly one part held, in table order
+                const uint64_t front = __ballot(lane < L && (((held >> la) ^ (held >> lb)) & 1u));
                 if (front == 0ull) break;
                 const int par = rounds & 1;
                 int nth = 0;
                 for (uint64_t rest = front; rest; rest &= rest - 1, ++nth) {
                     if ((nth & (kWaves - 1)) != wv) continue;
-                    const int l = __ffsll((long long)rest) - 1, a = s_la[l], b = s_lb[l];
-                    const bool forward = s_held[a] != 0;
+                    const int l = __ffsll((long long)rest) - 1;
+                    const int a = __builtin_amdgcn_readlane(la, l), b = __builtin_amdgcn_readlane(lb, l);
+                    const bool forward = (held >> a) & 1u;
                     const int src = forward ? a : b, dst = forward ? b : a;
-                    const float qx = s_joint[src].x, qy = s_joint[src].y;
+                    const float qx = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(jx), src));
+                    const float qy = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(jy), src));
                     const size_t list = ((size_t)n * L + l) * P.acap;
-                    const int off = s_off[l];
+                    const int off = __builtin_amdgcn_readlane(loff, l), cnt = __builtin_amdgcn_readlane(lcnt, l);
                     // searched records; the records whose points the winner proposes; what else the winner proposes
                     const float4 *S = off >= 0 ? s_rec + (forward ? 0 : 1) * lds_cells + off : (forward ? ws.fwd_s : ws.bwd_s) + list;
                     const float4 *T = off >= 0 ? s_rec + (forward ? 1 : 0) * lds_cells + off : (forward ? ws.bwd_s : ws.fwd_s) + list;
                     const float4 *R = off >= 0 ? s_rec + (forward ? 2 : 3) * lds_cells + off : (forward ? ws.fwd_r : ws.bwd_r) + list;
                     int proposes = -1;
                     float4 prop = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                    const uint64_t found = cf_search(S, s_acnt[l], qx, qy, P.grow_thr, lane);
+                    const uint64_t found = cf_search(S, cnt, qx, qy, P.grow_thr, lane, &s_best[wv]);
                     if (found != 0ull) {
                         const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
                         const float4 res = R[i];               // radius, point led back to, found
@@ -507,8 +522,7 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                     }
                 }
                 __syncthreads();
-                // every wavefront folds the proposals in: lane k takes the best one for part k, the earlier limb on
-                // ties.  (Only parts not held are proposed for; what a lane decides depends on the proposals alone.)
+                // every wavefront folds the proposals in: lane k takes the best one for part k, the earlier limb on ties
                 bool have = false;
                 if (lane < K) {
                     float4 best = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -522,40 +536,45 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                         }
                     }
                     if (have) {
-                        s_held[lane] = 1;
-                        s_joint[lane] = make_float4(best.y, best.z, best.w, best.x);
+                        jx = best.y;
+                        jy = best.z;
+                        jr = best.w;
+                        jv = best.x;
                     }
                 }
-                if (__ballot(have) == 0ull) {
+                const uint32_t added = (uint32_t)__ballot(have);   // lanes below K <= 32: one bit per part
+                held |= added;
+                if (added == 0u) {
                     ++rounds;
                     break;
                 }
             }
 
             // ---- C6: record, or remember the seed as grown in vain (C7) ----
-            int parts = 0;
-            for (int k = 0; k < K; ++k) parts += s_held[k];
+            const int parts = __popc(held);
             if (parts >= P.min_parts) {
-                if (tid < K) s_person[np * K + tid] = s_held[tid] ? s_joint[tid] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if (tid == kWave) {
+                if (tid < K) s_person[np * K + tid] = ((held >> tid) & 1u) ? make_float4(jx, jy, jr, jv) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (wv == 1) {
                     float sum = 0.0f;
                     for (int k = 0; k < K; ++k)
-                        if (s_held[k]) sum = sum + s_joint[k].w;
-                    s_pparts[np] = parts;
-                    s_pscore[np] = sum / (float)K;
+                        if ((held >> k) & 1u) sum = sum + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(jv), k));
+                    if (lane == 0) {
+                        s_pparts[np] = parts;
+                        s_pscore[np] = sum / (float)K;
+                    }
                 }
                 __syncthreads();
                 if (!occ) occ = cf_covers(s_person[np * K + sk], sd.x, sd.y);
                 ++np;
             } else {
-                const float4 gh = s_seed;
                 if (owner) {
+                    const float4 gh = make_float4(sd.x, sd.y, sd.z, __int_as_float(sk));
                     if (ng < kCfGhostLds)
                         s_ghost[ng] = gh;
                     else
                         ghost[ng] = gh;
                 }
-                if (!occ) occ = __float_as_int(gh.w) == sk && cf_covers(make_float4(gh.x, gh.y, gh.z, 1.0f), sd.x, sd.y);
+                if (!occ) occ = k0 == sk && cf_covers(make_float4(seed.x, seed.y, seed.z, 1.0f), sd.x, sd.y);
                 ++ng;
             }
         }
