@@ -377,7 +377,7 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
  * Limits: 1 <= lists->cap <= 512, n_parts * lists->cap <= HP_CF_MAX_SEEDS, lists->acap >= 1,
  * n_parts * poses->cap <= 1536, Fw * stride and Fh * stride below 2^23, thresholds not negative.
  * `workspace`: hp_cf_workspace_bytes(N, n_parts, n_limbs, cap, acap) bytes of device memory, no
- * initialisation needed.  Allocates nothing; enqueues four kernels on `stream`. */
+ * initialisation needed.  Allocates nothing; enqueues five kernels on `stream`. */
 typedef struct {
     float pif_thr;
     float paf_thr;
@@ -567,10 +567,11 @@ typedef enum {
     HP_K_PP_DETECT = 15,     /* hp_pp_decode: scores, boxes and suppression per (image, part) */
     HP_K_PP_PARSE = 16,      /* hp_pp_decode: the limb tree walked per image */
     HP_K_CF_PIF = 17,        /* hp_cf_decode, hp_cf_field: active intensity cells and their map values */
-    HP_K_CF_PAF = 18,        /* hp_cf_decode: active associations and their map samples */
-    HP_K_CF_GROW = 19,       /* hp_cf_decode: seeds and persons per image */
+    HP_K_CF_PAF = 18,        /* hp_cf_decode: active associations and their map samples; the seeds sorted */
+    HP_K_CF_GROW = 19,       /* hp_cf_decode: persons per image */
     HP_K_CF_FIELD = 20,      /* hp_cf_field: the fine maps written out */
-    HP_K_COUNT = 21
+    HP_K_CF_LINK = 21,       /* hp_cf_decode: what every association would propose if it won a search */
+    HP_K_COUNT = 22
 } hp_kernel_id;
 int hp_profile_begin(int max_launches);
 int hp_profile_end(float *total_ms, int32_t *launches);

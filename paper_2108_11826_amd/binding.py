@@ -21,7 +21,7 @@ EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peak
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
-HP_K_COUNT = 21
+HP_K_COUNT = 22
 
 
 class HPError(RuntimeError):

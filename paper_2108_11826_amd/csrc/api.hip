@@ -411,7 +411,8 @@ int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, cons
     HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
     HP_LAUNCH(HP_K_CF_PIF, launch_cf_pif(pif, N, Fh, Fw, K, *prm, lists->cap, lists->pif_cell, lists->pif_val, lists->pif_count,
                                          workspace, L, lists->acap, status, s));
-    HP_LAUNCH(HP_K_CF_PAF, launch_cf_paf(pif, paf, N, Fh, Fw, tab, K, L, *prm, *lists, workspace, status, s));
+    HP_LAUNCH(HP_K_CF_PAF, launch_cf_paf(paf, N, Fh, Fw, tab, K, L, *prm, *lists, workspace, status, s));
+    HP_LAUNCH(HP_K_CF_LINK, launch_cf_link(pif, N, Fh, Fw, tab, K, L, *prm, *lists, workspace, s));
     HP_LAUNCH(HP_K_CF_GROW, launch_cf_grow(N, Fh, Fw, tab, K, L, *prm, *lists, *poses, workspace, status, s));
     return HP_OK;
 }
@@ -556,6 +557,7 @@ const char *hp_kernel_name(int id)
     case HP_K_PP_PARSE: return "pp_parse";
     case HP_K_CF_PIF: return "cf_pif";
     case HP_K_CF_PAF: return "cf_paf";
+    case HP_K_CF_LINK: return "cf_link";
     case HP_K_CF_GROW: return "cf_grow";
     case HP_K_CF_FIELD: return "cf_field";
     default: return "unknown";

@@ -10,10 +10,11 @@
 // bit for bit, as reading the filled array.  hp_cf_field still fills the array for callers who want to look at it.
 //   k_cf_pif   one workgroup per (image, part): ordered compaction of the active cells, then every listed cell's
 //              own map value (its seed value);
-//   k_cf_paf   one workgroup per (image, limb): ordered compaction of the active associations, the two map
-//              samples of each (the two parts' cell lists held in LDS), and what each would propose if it won a
-//              search: the target's radius and the point the reverse search leads back to, neither of which
-//              depends on the person; one more workgroup per image sorts the seeds;
+//   k_cf_paf   one workgroup per (image, limb): ordered compaction of the active associations and the two map
+//              samples of each (the two parts' cell lists held in LDS); one more workgroup per image sorts the seeds;
+//   k_cf_link  what each association would propose if it won a search: the target's radius and the point the reverse
+//              search leads back to, neither of which depends on the person (a wavefront per association and
+//              direction);
 //   k_cf_grow  one workgroup per image: the occupancy test of up to 256 seeds at a time is one test per thread,
 //              repeated only against each newly finished person; a person grows in rounds, a wavefront per
 //              frontier limb (the search, 64 associations at a time, over records held in LDS);
@@ -118,6 +119,34 @@ __device__ __forceinline__ float cf_sample(const float4 *ra, const int4 *rb, int
     return f;
 }
 
+// Ordered compaction of kCfPer * 256 items a step: flag u of thread t stands for item u * 256 + t of the step (so that
+// a wavefront's loads stay contiguous); returns where each flagged item goes, counting from the step's first one, and
+// the step's total.  `scratch` holds kCfPer * 4 ints of LDS.  Contains two barriers.
+constexpr int kCfPer = 8;
+__device__ __forceinline__ void cf_scan(const bool (&flag)[kCfPer], int *scratch, int (&at)[kCfPer], int &total)
+{
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+    int within[kCfPer];
+#pragma unroll
+    for (int u = 0; u < kCfPer; ++u) {
+        const unsigned long long m = __ballot(flag[u]);
+        within[u] = __popcll(m & ((1ull << lane) - 1ull));
+        if (lane == 0) scratch[u * 4 + wv] = __popcll(m);
+    }
+    __syncthreads();
+    int run = 0;
+#pragma unroll
+    for (int u = 0; u < kCfPer; ++u) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w == wv) at[u] = run + within[u];
+            run += scratch[u * 4 + w];
+        }
+    }
+    total = run;
+    __syncthreads();
+}
+
 // ---- C1, C3: active cells of a part and their map values ---------------------------------------------------------
 __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ pif, CFParams P, CFWork ws,
                                                      int32_t *__restrict__ out_cell, float *__restrict__ out_val,
@@ -126,7 +155,7 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
     extern __shared__ float4 s_dyn4[];
     float4 *s_a = s_dyn4;                     // [cap]
     int4 *s_b = (int4 *)(s_dyn4 + P.cap);     // [cap]
-    __shared__ int s_scan[kCfBlock / kWave + 1];
+    __shared__ int s_scan[kCfPer * 4];
 
     const int k = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
     const int cells = P.Fh * P.Fw, H = P.Fh * P.stride, W = P.Fw * P.stride;
@@ -135,28 +164,37 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
     const float s = (float)P.stride;
 
     int count = 0;
-    for (int c0 = 0; c0 < cells; c0 += kCfBlock) {
-        const int cell = c0 + tid;
-        bool act = false;
-        float X = 0.0f, Y = 0.0f, c = 0.0f;
-        if (cell < cells) {
-            const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
-            c = f[cell];
-            X = ((float)gx + f[1 * cells + cell]) * s;
-            Y = ((float)gy + f[2 * cells + cell]) * s;
-            act = c > P.pif_thr && cf_on_map(X, Y, H, W);
+    for (int c0 = 0; c0 < cells; c0 += kCfPer * kCfBlock) {
+        bool act[kCfPer];
+        float X[kCfPer], Y[kCfPer], c[kCfPer];
+#pragma unroll
+        for (int u = 0; u < kCfPer; ++u) {
+            const int cell = c0 + u * kCfBlock + tid;
+            act[u] = false;
+            X[u] = Y[u] = c[u] = 0.0f;
+            if (cell < cells) {
+                const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
+                c[u] = f[cell];
+                X[u] = ((float)gx + f[1 * cells + cell]) * s;
+                Y[u] = ((float)gy + f[2 * cells + cell]) * s;
+                act[u] = c[u] > P.pif_thr && cf_on_map(X[u], Y[u], H, W);
+            }
         }
-        int total;
-        const int at = count + block_flag_scan(act, s_scan, total);
-        if (act && at < P.cap) {
-            const float sg = fmaxf(f[4 * cells + cell] * s, 1.0f);
-            const float4 a = make_float4(X, Y, 0.5f / (sg * sg), c);
-            const int4 b = make_int4((int)rintf(X), (int)rintf(Y), __float_as_int(sg), cell);
-            s_a[at] = a;
-            s_b[at] = b;
-            ws.pif_a[list + at] = a;
-            ws.pif_b[list + at] = b;
-            out_cell[list + at] = cell;
+        int at[kCfPer], total;
+        cf_scan(act, s_scan, at, total);
+#pragma unroll
+        for (int u = 0; u < kCfPer; ++u) {
+            const int cell = c0 + u * kCfBlock + tid, to = count + at[u];
+            if (act[u] && to < P.cap) {
+                const float sg = fmaxf(f[4 * cells + cell] * s, 1.0f);
+                const float4 a = make_float4(X[u], Y[u], 0.5f / (sg * sg), c[u]);
+                const int4 b = make_int4((int)rintf(X[u]), (int)rintf(Y[u]), __float_as_int(sg), cell);
+                s_a[to] = a;
+                s_b[to] = b;
+                ws.pif_a[list + to] = a;
+                ws.pif_b[list + to] = b;
+                out_cell[list + to] = cell;
+            }
         }
         count += total;
     }
@@ -219,7 +257,7 @@ __device__ void cf_sort_seeds(const CFParams &P, const CFWork &ws, int n, const 
 }
 
 // Workgroups (l < L, n): limb l of image n.  Workgroups (L, n): the seeds of image n.
-__global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ pif, const float *__restrict__ paf, CFParams P,
+__global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ paf, CFParams P,
                                                      CFWork ws, CFLimbs limbs, const int32_t *__restrict__ pif_count,
                                                      const float *__restrict__ pif_val, int32_t *__restrict__ out_cell,
                                                      float *__restrict__ out_f1, float *__restrict__ out_f2,
@@ -235,7 +273,7 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     int4 *s_ab = (int4 *)(s_dyn4 + P.cap);        //         [cap] xr, yr, sg, cell
     float4 *s_ba = s_dyn4 + 2 * P.cap;            // part b
     int4 *s_bb = (int4 *)(s_dyn4 + 3 * P.cap);
-    __shared__ int s_scan[kCfBlock / kWave + 1];
+    __shared__ int s_scan[kCfPer * 4];
     __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
 
     if (tid == 0) {
@@ -264,26 +302,35 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     float4 *fs = ws.fwd_s + list, *bs = ws.bwd_s + list;
 
     int count = 0;
-    for (int c0 = 0; c0 < cells; c0 += kCfBlock) {
-        const int cell = c0 + tid;
-        bool act = false;
-        float c = 0.0f, x1 = 0.0f, y1 = 0.0f, x2 = 0.0f, y2 = 0.0f;
-        if (cell < cells) {
-            const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
-            c = f[cell];
-            x1 = ((float)gx + f[1 * cells + cell]) * s;
-            y1 = ((float)gy + f[2 * cells + cell]) * s;
-            x2 = ((float)gx + f[4 * cells + cell]) * s;
-            y2 = ((float)gy + f[5 * cells + cell]) * s;
-            act = c > P.paf_thr && cf_on_map(x1, y1, H, W) && cf_on_map(x2, y2, H, W);
+    for (int c0 = 0; c0 < cells; c0 += kCfPer * kCfBlock) {
+        bool act[kCfPer];
+        float c[kCfPer], x1[kCfPer], y1[kCfPer], x2[kCfPer], y2[kCfPer];
+#pragma unroll
+        for (int u = 0; u < kCfPer; ++u) {
+            const int cell = c0 + u * kCfBlock + tid;
+            act[u] = false;
+            c[u] = x1[u] = y1[u] = x2[u] = y2[u] = 0.0f;
+            if (cell < cells) {
+                const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
+                c[u] = f[cell];
+                x1[u] = ((float)gx + f[1 * cells + cell]) * s;
+                y1[u] = ((float)gy + f[2 * cells + cell]) * s;
+                x2[u] = ((float)gx + f[4 * cells + cell]) * s;
+                y2[u] = ((float)gy + f[5 * cells + cell]) * s;
+                act[u] = c[u] > P.paf_thr && cf_on_map(x1[u], y1[u], H, W) && cf_on_map(x2[u], y2[u], H, W);
+            }
         }
-        int total;
-        const int at = count + block_flag_scan(act, s_scan, total);   // its first barrier also covers the lists above
-        if (act && at < P.acap) {
-            const float iB1 = 1.0f / fmaxf(f[3 * cells + cell] * s, 1.0f), iB2 = 1.0f / fmaxf(f[6 * cells + cell] * s, 1.0f);
-            fs[at] = make_float4(x1, y1, iB1, c);         // c is replaced by c * F2 below
-            bs[at] = make_float4(x2, y2, iB2, c);
-            out_cell[list + at] = cell;
+        int at[kCfPer], total;
+        cf_scan(act, s_scan, at, total);   // its first barrier also covers the lists above
+#pragma unroll
+        for (int u = 0; u < kCfPer; ++u) {
+            const int cell = c0 + u * kCfBlock + tid, to = count + at[u];
+            if (act[u] && to < P.acap) {
+                const float iB1 = 1.0f / fmaxf(f[3 * cells + cell] * s, 1.0f), iB2 = 1.0f / fmaxf(f[6 * cells + cell] * s, 1.0f);
+                fs[to] = make_float4(x1[u], y1[u], iB1, c[u]);   // c is replaced by c * F2 below
+                bs[to] = make_float4(x2[u], y2[u], iB2, c[u]);
+                out_cell[list + to] = cell;
+            }
         }
         count += total;
     }
@@ -299,29 +346,6 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
         rb.w = rb.w * F1;
         fs[i] = ra;
         bs[i] = rb;
-    }
-    __syncthreads();
-    // What a search's winner proposes does not depend on the person: the target's radius (C5) and the point the
-    // reverse search (C5) leads back to.  Task 2 i: association i followed forwards; task 2 i + 1: backwards.
-    const float *sig_a = pif + (((size_t)n * P.K + pa) * 5 + 4) * cells, *sig_b = pif + (((size_t)n * P.K + pb) * 5 + 4) * cells;
-    for (int t = tid; t < 2 * m; t += kCfBlock) {
-        const int i = t >> 1;
-        const bool forward = (t & 1) == 0;
-        const float4 *back = forward ? bs : fs, *from = forward ? fs : bs;   // searched on the way back; holds the points led back to
-        const float tx = back[i].x, ty = back[i].y;
-        float best = 0.0f;
-        int r = -1;
-        for (int j = 0; j < m; ++j) {
-            const float sc = cf_score(back[j], tx, ty);
-            if (sc > best) {
-                best = sc;
-                r = j;
-            }
-        }
-        const int cy = (int)rintf(ty) / P.stride, cx = (int)rintf(tx) / P.stride;
-        const float rad = fmaxf((forward ? sig_b : sig_a)[(size_t)cy * P.Fw + cx] * s, 1.0f);
-        const float4 res = r >= 0 ? make_float4(rad, from[r].x, from[r].y, 1.0f) : make_float4(rad, 0.0f, 0.0f, 0.0f);
-        (forward ? ws.fwd_r : ws.bwd_r)[list + i] = res;
     }
     if (tid == 0) {
         out_count[(size_t)n * P.L + l] = count;
@@ -359,6 +383,51 @@ __device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx
     if (key != 0ull) atomicMax(slot, key);
     __builtin_amdgcn_wave_barrier();
     return *(volatile unsigned long long *)slot;
+}
+
+// ---- C5, the part that does not depend on the person ------------------------------------------------------------
+// What the winner of a search proposes besides its point: the target's radius and the point the reverse search
+// leads back to.  Task 2 i: association i followed forwards; task 2 i + 1: backwards.  A wavefront per task, the
+// tasks of a limb dealt to the 32 wavefronts of eight workgroups (one workgroup a limb took 60 us at 140 associations).
+constexpr int kCfLinkSlices = 8, kCfLinkStage = 2048;
+__global__ __launch_bounds__(kCfBlock) void k_cf_link(const float *__restrict__ pif, CFParams P, CFWork ws, CFLimbs limbs,
+                                                      const int32_t *__restrict__ paf_count)
+{
+    extern __shared__ float4 s_dyn4[];                      // [2][staged] the limb's search records, when they fit
+    __shared__ unsigned long long s_best[kCfBlock / kWave];
+    const int l = blockIdx.x, n = blockIdx.y, z = blockIdx.z, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+    const int m = min(paf_count[(size_t)n * P.L + l], P.acap);
+    if (z * (kCfBlock / kWave) >= 2 * m) return;            // the same for the whole workgroup
+    const size_t list = ((size_t)n * P.L + l) * P.acap;
+    const float4 *fs = ws.fwd_s + list, *bs = ws.bwd_s + list;
+    if (m <= kCfLinkStage) {
+        for (int i = tid; i < m; i += kCfBlock) {
+            s_dyn4[i] = fs[i];
+            s_dyn4[m + i] = bs[i];
+        }
+        __syncthreads();
+        fs = s_dyn4;
+        bs = s_dyn4 + m;
+    }
+    const int pa = limbs.a[l], pb = limbs.b[l], cells = P.Fh * P.Fw;
+    const float *sig_a = pif + (((size_t)n * P.K + pa) * 5 + 4) * cells, *sig_b = pif + (((size_t)n * P.K + pb) * 5 + 4) * cells;
+    for (int t = z * (kCfBlock / kWave) + wv; t < 2 * m; t += kCfLinkSlices * (kCfBlock / kWave)) {
+        const int i = t >> 1;
+        const bool forward = (t & 1) == 0;
+        const float4 *back = forward ? bs : fs, *from = forward ? fs : bs;   // searched on the way back; holds the points led back to
+        const float tx = back[i].x, ty = back[i].y;
+        const uint64_t found = cf_search(back, m, tx, ty, 0.0f, lane, &s_best[wv]);
+        if (lane == 0) {
+            const int cy = (int)rintf(ty) / P.stride, cx = (int)rintf(tx) / P.stride;
+            const float rad = fmaxf((forward ? sig_b : sig_a)[(size_t)cy * P.Fw + cx] * (float)P.stride, 1.0f);
+            float4 res = make_float4(rad, 0.0f, 0.0f, 0.0f);
+            if (found != 0ull) {
+                const float4 rr = from[(int)(0xFFFFFFFFu - (uint32_t)found)];
+                res = make_float4(rad, rr.x, rr.y, 1.0f);
+            }
+            (forward ? ws.fwd_r : ws.bwd_r)[list + i] = res;
+        }
+    }
 }
 
 // One workgroup per image.  The loop is a chain of short dependent steps, so it is built around what a step costs
@@ -676,15 +745,25 @@ static CFLimbs cf_limbs(const LimbTable &T, int L)
     return limbs;
 }
 
-hipError_t launch_cf_paf(const float *pif, const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L,
+hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L,
                          const hp_cf_params &prm, const hp_cf_lists &lists, void *workspace, int32_t *status, hipStream_t s)
 {
     const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, 0);
     const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
     // the limb workgroups hold two parts' cell lists, the seed workgroups the keys they sort
     const size_t lds = std::max(sizeof(float4) * 4 * (size_t)lists.cap, sizeof(uint64_t) * (size_t)next_pow2(K * lists.cap));
-    HP_KERNEL(k_cf_paf, dim3(L + 1, N), dim3(kCfBlock), lds, s, pif, paf, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
+    HP_KERNEL(k_cf_paf, dim3(L + 1, N), dim3(kCfBlock), lds, s, paf, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
               lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_cf_link(const float *pif, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+                          const hp_cf_lists &lists, void *workspace, hipStream_t s)
+{
+    const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, 0);
+    const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
+    const size_t lds = sizeof(float4) * 2 * (size_t)std::min(lists.acap, kCfLinkStage);
+    HP_KERNEL(k_cf_link, dim3(L, N, kCfLinkSlices), dim3(kCfBlock), lds, s, pif, P, ws, cf_limbs(T, L), lists.paf_count);
     return hipGetLastError();
 }
 

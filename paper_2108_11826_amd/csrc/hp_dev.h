@@ -229,8 +229,10 @@ hipError_t launch_pp_parse(const float *edge, int N, int Gh, int Gw, int Nh, int
 size_t cf_workspace_bytes(int N, int K, int L, int cap, int acap);
 hipError_t launch_cf_pif(const float *pif, int N, int Fh, int Fw, int K, const hp_cf_params &prm, int cap, int32_t *cell,
                          float *val, int32_t *count, void *workspace, int L, int acap, int32_t *status, hipStream_t s);
-hipError_t launch_cf_paf(const float *pif, const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L,
+hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTable &T, int K, int L,
                          const hp_cf_params &prm, const hp_cf_lists &lists, void *workspace, int32_t *status, hipStream_t s);
+hipError_t launch_cf_link(const float *pif, int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
+                          const hp_cf_lists &lists, void *workspace, hipStream_t s);
 hipError_t launch_cf_grow(int N, int Fh, int Fw, const LimbTable &T, int K, int L, const hp_cf_params &prm,
                           const hp_cf_lists &lists, const hp_cf_poses &poses, void *workspace, int32_t *status, hipStream_t s);
 hipError_t launch_cf_field(int N, int Fh, int Fw, int K, const hp_cf_params &prm, int cap, const int32_t *count, float *out,
