@@ -393,6 +393,59 @@ def main():
                      "bound": "latency (a few KB per image: one wavefront walks the limb tree of an image)",
                      "parity_with_oracle": bool(pp_ok)}
 
+    # the third algorithm class: composite-field decoding on a synthetic batch (46 x 82 grid, stride 8, 17 parts, 19 limbs)
+    from synth import CF_CONFIGS, generate_cf
+    cf_cfg = CF_CONFIGS[2]
+    cf_in = generate_cf(cf_cfg)
+    cf_sk = cf_cfg.skeleton
+    cf_pif, cf_paf = (torch.from_numpy(cf_in[k]).to(dev) for k in ("pif", "paf"))
+    cf_buf = hp.CFBuffers(cf_cfg.batch, cf_sk.n_parts, cf_sk.n_limbs, 128, 256, 32, dev)
+    cf_skel = hp.Skeleton(cf_sk.n_parts, cf_sk.limb_a, cf_sk.limb_b)
+    cf_prm = (cf_cfg.stride, cf_cfg.pif_thr, cf_cfg.paf_thr, cf_cfg.seed_thr, cf_cfg.grow_thr, cf_cfg.rev_tol, cf_cfg.min_parts)
+    cf_call = lambda: hp.hp_cf_decode(cf_pif, cf_paf, cf_skel, cf_buf, *cf_prm)
+    for _ in range(3):
+        cf_call()
+    torch.cuda.synchronize()
+    hp.hp_profile_begin(256)
+    for _ in range(20):
+        cf_call()
+    torch.cuda.synchronize()
+    pr = hp.hp_profile_end()
+    t0 = time.perf_counter()
+    for _ in range(100):
+        cf_call()
+    torch.cuda.synchronize()
+    cf_us = (time.perf_counter() - t0) / 100 * 1e6
+    cf_got = cf_buf.host()
+    cf_ora = oracle.cf_decode(cf_in["pif"], cf_in["paf"], cf_sk.limb_a, cf_sk.limb_b, *cf_prm, pcap=32)
+    same = lambda a, b: np.array_equal(np.ascontiguousarray(a).view(np.uint32), np.ascontiguousarray(b).view(np.uint32))
+    cf_ok = cf_got["status"] == 0 and all(
+        np.array_equal(cf_got["poses"][n][1], cf_ora["poses"][n][1]) and same(cf_got["poses"][n][0], cf_ora["poses"][n][0])
+        and same(cf_got["poses"][n][2], cf_ora["poses"][n][2])
+        and all(same(cf_got["pif"][n][k][1], cf_ora["pif"][n][k][1]) for k in range(cf_sk.n_parts))
+        for n in range(cf_cfg.batch))
+    parity = parity and bool(cf_ok)
+    hp.hp_profile_begin(64)
+    for _ in range(5):
+        cf_maps, _ = hp.hp_cf_field(cf_pif, cf_cfg.stride, cf_cfg.pif_thr, cap=128)
+    torch.cuda.synchronize()
+    prf = hp.hp_profile_end()
+    cf_field_us = 1e3 * prf["cf_field"][0] / prf["cf_field"][1]
+    cf_field_bytes = cf_maps.numel() * 4
+    del cf_maps
+    composite_fields = {"what": "hp_cf_decode: batch %d, %dx%d grid, stride %d, %d parts, %d limbs, %d planted persons per image"
+                                % (cf_cfg.batch, cf_cfg.Fh, cf_cfg.Fw, cf_cfg.stride, cf_sk.n_parts, cf_sk.n_limbs, cf_cfg.n_people),
+                        "us_per_call": round(cf_us, 2), "frames_per_s": round(cf_cfg.batch / (cf_us * 1e-6), 1),
+                        "kernel_us": {k: round(1e3 * ms / nl, 2) for k, (ms, nl) in sorted(pr.items())},
+                        "bound": "latency (persons of an image grow one after the other, a round of growth at a time; the fine "
+                                 "confidence maps are never written: their values are summed where they are needed)",
+                        "field": {"what": "hp_cf_field: the fine maps of the same batch written out (fp32, %d MB)"
+                                          % (cf_field_bytes // 2**20),
+                                  "kernel": "k_cf_field", "us": round(cf_field_us, 2), "bound": "hbm",
+                                  "achieved": round(cf_field_bytes / (cf_field_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                                  "unit": "GB/s", "frac": round(cf_field_bytes / (cf_field_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+                        "parity_with_oracle": bool(cf_ok)}
+
     # the streaming front: frames arrive one at a time, the batch slot grows only while batches are running
     streaming = None if args.no_streaming else {
         "what": "hp_batcher_* (dynamic batch slot in front of hp_postprocess, Section 2.2.2): frames of this workload handed "
@@ -444,6 +497,7 @@ def main():
         "roofline_scoring": roofline_scoring,
         "preprocess": preprocess,
         "pose_proposal": pose_proposal,
+        "composite_fields": composite_fields,
         "smooth": smooth,
         "visualise": visualise,
         "streaming": streaming,

@@ -18,8 +18,8 @@
 //   k_cf_grow  one workgroup per image: the occupancy test of up to 256 seeds at a time is one test per thread,
 //              repeated only against each newly finished person; a person grows in rounds, a wavefront per
 //              frontier limb (the search, 64 associations at a time, over records held in LDS);
-//   k_cf_field one workgroup per 64 x 32 pixel tile: the part's listed cells whose window meets the tile, then the
-//              sum per pixel.
+//   k_cf_field one wavefront per strip of 64 x 8 pixels: the part's listed cells whose window meets the strip, then
+//              the sum per pixel.
 #include <limits.h>
 #include <string.h>
 
@@ -41,7 +41,7 @@ struct CFParams {
 // Records of the active cells, in the caller's workspace.
 struct CFWork {
     float4 *pif_a;        // [N][K][cap]   X, Y, inv, c
-    int4 *pif_b;          // [N][K][cap]   xr, yr, bits of sg, cell
+    int4 *pif_b;          // [N][K][cap]   xr, yr, bits of sg, window
     float4 *fwd_s;        // [N][L][acap]  searched from part a: P1.x, P1.y, 1 / B1, c * F2
     float4 *bwd_s;        // [N][L][acap]  searched from part b: P2.x, P2.y, 1 / B2, c * F1
     float4 *fwd_r;        // [N][L][acap]  followed forwards: radius at P2, the point the reverse search leads back to, 1 (0: none)
@@ -109,8 +109,7 @@ __device__ __forceinline__ float cf_sample(const float4 *ra, const int4 *rb, int
     float f = 0.0f;
     for (int j = 0; j < n; ++j) {
         const int4 b = rb[j];
-        const int w = cf_window(__int_as_float(b.z));
-        if (abs(px - b.x) > w || abs(py - b.y) > w) continue;
+        if (abs(px - b.x) > b.w || abs(py - b.y) > b.w) continue;
         const float4 a = ra[j];
         const float dx = (float)px - a.x, dy = (float)py - a.y;
         const float d2 = dx * dx + dy * dy;
@@ -188,7 +187,7 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
             if (act[u] && to < P.cap) {
                 const float sg = fmaxf(f[4 * cells + cell] * s, 1.0f);
                 const float4 a = make_float4(X[u], Y[u], 0.5f / (sg * sg), c[u]);
-                const int4 b = make_int4((int)rintf(X[u]), (int)rintf(Y[u]), __float_as_int(sg), cell);
+                const int4 b = make_int4((int)rintf(X[u]), (int)rintf(Y[u]), __float_as_int(sg), cf_window(sg));
                 s_a[to] = a;
                 s_b[to] = b;
                 ws.pif_a[list + to] = a;
@@ -664,45 +663,71 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
 }
 
 // ---- C2 as an array ----------------------------------------------------------------------------------------------
+// A wavefront fills a strip of 64 x 8 pixels on its own (four strips a workgroup, no barrier): it picks, in list order,
+// the part's listed cells whose window meets the strip (most strips meet none and are plain zero stores), then sums
+// per pixel.  The first 64 records are fetched together with the list's length, so that one memory round trip
+// separates a strip's start from its first store.
+constexpr int kCfStripH = 8;
 __global__ __launch_bounds__(kCfBlock) void k_cf_field(CFParams P, CFWork ws, const int32_t *__restrict__ pif_count,
                                                        float *__restrict__ out)
 {
     extern __shared__ float4 s_dyn4[];
-    float4 *s_a = s_dyn4;                     // [cap] the listed cells whose window meets this tile, in list order
-    int4 *s_b = (int4 *)(s_dyn4 + P.cap);
-    __shared__ int s_scan[kCfBlock / kWave + 1];
+    const int plane = blockIdx.z, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+    float4 *s_a = s_dyn4 + (size_t)wv * 2 * P.cap;   // [cap] this wavefront's cells, in list order
+    int4 *s_b = (int4 *)(s_a + P.cap);
 
-    const int plane = blockIdx.z, tid = threadIdx.x;
     const int H = P.Fh * P.stride, W = P.Fw * P.stride;
-    const int x0 = blockIdx.x * kCfTileW, y0 = blockIdx.y * kCfTileH;
+    const int x0 = blockIdx.x * kCfTileW, y0 = blockIdx.y * kCfTileH + wv * kCfStripH;
+    if (y0 >= H) return;
     const size_t list = (size_t)plane * P.cap;
+    // records beyond the list's end are never used: the first fetch only may not wait for the length
+    int4 b = lane < P.cap ? ws.pif_b[list + lane] : make_int4(0, 0, 0, 0);
+    float4 a = lane < P.cap ? ws.pif_a[list + lane] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     const int m = min(pif_count[plane], P.cap);
     int cnt = 0;
-    for (int j0 = 0; j0 < m; j0 += kCfBlock) {
-        const int j = j0 + tid;
-        bool meets = false;
-        int4 b = make_int4(0, 0, 0, 0);
-        if (j < m) {
+    for (int j0 = 0; j0 < m; j0 += kWave) {
+        const int j = j0 + lane;
+        if (j0 > 0 && j < m) {
             b = ws.pif_b[list + j];
-            const int w = cf_window(__int_as_float(b.z));
-            meets = b.x + w >= x0 && b.x - w < x0 + kCfTileW && b.y + w >= y0 && b.y - w < y0 + kCfTileH;
+            a = ws.pif_a[list + j];
         }
-        int total;
-        const int at = cnt + block_flag_scan(meets, s_scan, total);
+        bool meets = false;
+        if (j < m) meets = b.x + b.w >= x0 && b.x - b.w < x0 + kCfTileW && b.y + b.w >= y0 && b.y - b.w < y0 + kCfStripH;
+        const unsigned long long mask = __ballot(meets);
         if (meets) {
-            s_a[at] = ws.pif_a[list + j];
+            const int at = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+            s_a[at] = a;
             s_b[at] = b;
         }
-        cnt += total;
+        cnt += __popcll(mask);
     }
-    __syncthreads();
-    const int px = x0 + (tid & (kCfTileW - 1));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the records above are read by the other lanes below
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int px = x0 + lane;
     if (px >= W) return;
-    for (int r = tid / kCfTileW; r < kCfTileH; r += kCfBlock / kCfTileW) {
-        const int py = y0 + r;
-        if (py >= H) break;
-        __builtin_nontemporal_store(cf_sample(s_a, s_b, cnt, px, py), &out[((size_t)plane * H + py) * W + px]);
+    // the cells outermost, the strip's rows innermost: a pixel still adds its cells in list order
+    float f[kCfStripH];
+#pragma unroll
+    for (int r = 0; r < kCfStripH; ++r) f[r] = 0.0f;
+    for (int j = 0; j < cnt; ++j) {
+        const int4 bj = s_b[j];
+        if (abs(px - bj.x) > bj.w) continue;
+        const float4 aj = s_a[j];
+        const float dx = (float)px - aj.x;
+        const float dx2 = dx * dx;
+#pragma unroll
+        for (int r = 0; r < kCfStripH; ++r) {
+            const int py = y0 + r;
+            if (abs(py - bj.y) > bj.w) continue;              // the same for the whole wavefront
+            const float dy = (float)py - aj.y;
+            const float d2 = dx2 + dy * dy;
+            f[r] = f[r] + aj.w * cf_expneg(d2 * aj.z);
+        }
     }
+#pragma unroll
+    for (int r = 0; r < kCfStripH; ++r)
+        if (y0 + r < H) __builtin_nontemporal_store(f[r], &out[((size_t)plane * H + y0 + r) * W + px]);
 }
 
 // ---- host side ---------------------------------------------------------------------------------------------------
@@ -796,7 +821,7 @@ hipError_t launch_cf_field(int N, int Fh, int Fw, int K, const hp_cf_params &prm
     const CFWork ws = cf_layout(workspace, N, K, 0, cap, 0);
     const int H = Fh * prm.stride, W = Fw * prm.stride;
     const dim3 grid((W + kCfTileW - 1) / kCfTileW, (H + kCfTileH - 1) / kCfTileH, N * K);
-    HP_KERNEL(k_cf_field, grid, dim3(kCfBlock), sizeof(float4) * 2 * (size_t)cap, s, P, ws, count, out);
+    HP_KERNEL(k_cf_field, grid, dim3(kCfBlock), sizeof(float4) * 2 * (size_t)cap * (kCfBlock / kWave), s, P, ws, count, out);
     return hipGetLastError();
 }
 
