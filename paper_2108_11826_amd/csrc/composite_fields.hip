@@ -370,8 +370,12 @@ __device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx
                                               unsigned long long *slot)
 {
     unsigned long long key = 0ull;
+    // the next record is on its way while this one is scored
+    float4 next = lane < cnt ? S[lane] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     for (int i = lane; i < cnt; i += kWave) {
-        const float sc = cf_score(S[i], qx, qy);
+        const float4 rec = next;
+        if (i + kWave < cnt) next = S[i + kWave];
+        const float sc = cf_score(rec, qx, qy);
         if (sc > above) {
             const unsigned long long mine = ((unsigned long long)float_order(sc) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)i);
             key = mine > key ? mine : key;
@@ -592,22 +596,33 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                 __syncthreads();
                 // every wavefront folds the proposals in: lane k takes the best one for part k, the earlier limb on ties
                 bool have = false;
-                if (lane < K) {
-                    float4 best = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                {
+                    // lane l fetches limb l's proposal (one LDS round trip for all of them); the frontier limbs are
+                    // then read across lanes, by the whole wavefront
+                    const int my_dst = s_dst[par][ll];
+                    const float4 my_prop = s_prop[par][ll];
+                    float bsc = 0.0f, bx = 0.0f, by = 0.0f, br = 0.0f;
                     for (uint64_t rest = front; rest; rest &= rest - 1) {
                         const int l = __ffsll((long long)rest) - 1;
-                        if (s_dst[par][l] != lane) continue;
-                        const float4 pr = s_prop[par][l];
-                        if (!have || pr.x > best.x) {
-                            best = pr;
+                        const int d = __builtin_amdgcn_readlane(my_dst, l);
+                        if (d < 0) continue;                                   // the same for the whole wavefront
+                        const float sc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_prop.x), l));
+                        const float lx = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_prop.y), l));
+                        const float ly = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_prop.z), l));
+                        const float lr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_prop.w), l));
+                        if (d == lane && (!have || sc > bsc)) {
                             have = true;
+                            bsc = sc;
+                            bx = lx;
+                            by = ly;
+                            br = lr;
                         }
                     }
                     if (have) {
-                        jx = best.y;
-                        jy = best.z;
-                        jr = best.w;
-                        jv = best.x;
+                        jx = bx;
+                        jy = by;
+                        jr = br;
+                        jv = bsc;
                     }
                 }
                 const uint32_t added = (uint32_t)__ballot(have);   // lanes below K <= 32: one bit per part
