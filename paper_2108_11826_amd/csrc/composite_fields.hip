@@ -365,7 +365,8 @@ __device__ __forceinline__ bool cf_covers(const float4 j, float x, float y)
 // (score order) << 32 | (0xFFFFFFFF - index), the same in every lane, or 0 when no score exceeds `above`.
 // The lanes' candidates meet in `slot`, an LDS word of this wavefront's own: LDS serves one wavefront's requests in
 // the order they were issued, so the clearing store, the maxima and the final load need no barrier between them
-// (and cost about a quarter of a butterfly of twelve cross-lane moves).
+// (and cost about a quarter of a butterfly of twelve cross-lane moves).  Callers pass pointers whose memory (LDS or
+// global) the compiler can see: a pointer that may be either compiles to flat loads, several times slower on LDS.
 __device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx, float qy, float above, int lane,
                                               unsigned long long *slot)
 {
@@ -381,11 +382,11 @@ __device__ __forceinline__ uint64_t cf_search(const float4 *S, int cnt, float qx
             key = mine > key ? mine : key;
         }
     }
-    if (lane == 0) *(volatile unsigned long long *)slot = 0ull;
+    if (lane == 0) __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     __builtin_amdgcn_wave_barrier();
-    if (key != 0ull) atomicMax(slot, key);
+    if (key != 0ull) __hip_atomic_fetch_max(slot, key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     __builtin_amdgcn_wave_barrier();
-    return *(volatile unsigned long long *)slot;
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
 // ---- C5, the part that does not depend on the person ------------------------------------------------------------
@@ -402,34 +403,37 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_link(const float *__restrict__ 
     const int m = min(paf_count[(size_t)n * P.L + l], P.acap);
     if (z * (kCfBlock / kWave) >= 2 * m) return;            // the same for the whole workgroup
     const size_t list = ((size_t)n * P.L + l) * P.acap;
-    const float4 *fs = ws.fwd_s + list, *bs = ws.bwd_s + list;
-    if (m <= kCfLinkStage) {
-        for (int i = tid; i < m; i += kCfBlock) {
-            s_dyn4[i] = fs[i];
-            s_dyn4[m + i] = bs[i];
-        }
-        __syncthreads();
-        fs = s_dyn4;
-        bs = s_dyn4 + m;
-    }
     const int pa = limbs.a[l], pb = limbs.b[l], cells = P.Fh * P.Fw;
     const float *sig_a = pif + (((size_t)n * P.K + pa) * 5 + 4) * cells, *sig_b = pif + (((size_t)n * P.K + pb) * 5 + 4) * cells;
-    for (int t = z * (kCfBlock / kWave) + wv; t < 2 * m; t += kCfLinkSlices * (kCfBlock / kWave)) {
-        const int i = t >> 1;
-        const bool forward = (t & 1) == 0;
-        const float4 *back = forward ? bs : fs, *from = forward ? fs : bs;   // searched on the way back; holds the points led back to
-        const float tx = back[i].x, ty = back[i].y;
-        const uint64_t found = cf_search(back, m, tx, ty, 0.0f, lane, &s_best[wv]);
-        if (lane == 0) {
-            const int cy = (int)rintf(ty) / P.stride, cx = (int)rintf(tx) / P.stride;
-            const float rad = fmaxf((forward ? sig_b : sig_a)[(size_t)cy * P.Fw + cx] * (float)P.stride, 1.0f);
-            float4 res = make_float4(rad, 0.0f, 0.0f, 0.0f);
-            if (found != 0ull) {
-                const float4 rr = from[(int)(0xFFFFFFFFu - (uint32_t)found)];
-                res = make_float4(rad, rr.x, rr.y, 1.0f);
+    // fs, bs: the limb's search records, forwards and backwards (in LDS or in the workspace: one copy of the loop each)
+    auto tasks = [&](const float4 *fs, const float4 *bs) {
+        for (int t = z * (kCfBlock / kWave) + wv; t < 2 * m; t += kCfLinkSlices * (kCfBlock / kWave)) {
+            const int i = t >> 1;
+            const bool forward = (t & 1) == 0;
+            const float4 *back = forward ? bs : fs, *from = forward ? fs : bs;   // searched on the way back; holds the points led back to
+            const float tx = back[i].x, ty = back[i].y;
+            const uint64_t found = cf_search(back, m, tx, ty, 0.0f, lane, &s_best[wv]);
+            if (lane == 0) {
+                const int cy = (int)rintf(ty) / P.stride, cx = (int)rintf(tx) / P.stride;
+                const float rad = fmaxf((forward ? sig_b : sig_a)[(size_t)cy * P.Fw + cx] * (float)P.stride, 1.0f);
+                float4 res = make_float4(rad, 0.0f, 0.0f, 0.0f);
+                if (found != 0ull) {
+                    const float4 rr = from[(int)(0xFFFFFFFFu - (uint32_t)found)];
+                    res = make_float4(rad, rr.x, rr.y, 1.0f);
+                }
+                (forward ? ws.fwd_r : ws.bwd_r)[list + i] = res;
             }
-            (forward ? ws.fwd_r : ws.bwd_r)[list + i] = res;
         }
+    };
+    if (m <= kCfLinkStage) {
+        for (int i = tid; i < m; i += kCfBlock) {
+            s_dyn4[i] = ws.fwd_s[list + i];
+            s_dyn4[m + i] = ws.bwd_s[list + i];
+        }
+        __syncthreads();
+        tasks(s_dyn4, s_dyn4 + m);
+    } else {
+        tasks(ws.fwd_s + list, ws.bwd_s + list);
     }
 }
 
@@ -567,17 +571,30 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
                     const float qy = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(jy), src));
                     const size_t list = ((size_t)n * L + l) * P.acap;
                     const int off = __builtin_amdgcn_readlane(loff, l), cnt = __builtin_amdgcn_readlane(lcnt, l);
-                    // searched records; the records whose points the winner proposes; what else the winner proposes
-                    const float4 *S = off >= 0 ? s_rec + (forward ? 0 : 1) * lds_cells + off : (forward ? ws.fwd_s : ws.bwd_s) + list;
-                    const float4 *T = off >= 0 ? s_rec + (forward ? 1 : 0) * lds_cells + off : (forward ? ws.bwd_s : ws.fwd_s) + list;
-                    const float4 *R = off >= 0 ? s_rec + (forward ? 2 : 3) * lds_cells + off : (forward ? ws.fwd_r : ws.bwd_r) + list;
+                    // the searched records (array 0 or 1), the records whose points the winner proposes (the other of the
+                    // two), and what else the winner proposes (array 2 or 3): in LDS, or else in the workspace
                     int proposes = -1;
                     float4 prop = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                    const uint64_t found = cf_search(S, cnt, qx, qy, P.grow_thr, lane, &s_best[wv]);
+                    uint64_t found;
+                    float4 res = make_float4(0.0f, 0.0f, 0.0f, 0.0f), tgt = res;
+                    if (off >= 0) {
+                        const float4 *rec = s_rec + off;
+                        found = cf_search(rec + (forward ? 0 : 1) * lds_cells, cnt, qx, qy, P.grow_thr, lane, &s_best[wv]);
+                        if (found != 0ull) {
+                            const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
+                            res = rec[(forward ? 2 : 3) * lds_cells + i];
+                            tgt = rec[(forward ? 1 : 0) * lds_cells + i];
+                        }
+                    } else {
+                        found = cf_search((forward ? ws.fwd_s : ws.bwd_s) + list, cnt, qx, qy, P.grow_thr, lane, &s_best[wv]);
+                        if (found != 0ull) {
+                            const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
+                            res = (forward ? ws.fwd_r : ws.bwd_r)[list + i];
+                            tgt = (forward ? ws.bwd_s : ws.fwd_s)[list + i];
+                        }
+                    }
                     if (found != 0ull) {
-                        const int i = (int)(0xFFFFFFFFu - (uint32_t)found);
-                        const float4 res = R[i];               // radius, point led back to, found
-                        const float tx = T[i].x, ty = T[i].y;
+                        const float tx = tgt.x, ty = tgt.y;      // res: radius, point led back to, found
                         const float dx = res.y - qx, dy = res.z - qy;
                         if (res.w != 0.0f && dx * dx + dy * dy <= P.rev_tol * P.rev_tol) {
                             bool taken = false;
