@@ -74,6 +74,13 @@ def test_decode_matches_oracle(cfg):
         assert sum(len(p[1]) for p in ora["poses"]) > 0
 
 
+def test_benchmark_configuration():
+    # the batch, the capacities and hence the launch shapes that bench.py times
+    got, ora = run_both(CF_CONFIGS[2], cap=128, acap=256, pcap=32)
+    assert_same(got, ora)
+    assert min(len(p[1]) for p in ora["poses"]) >= 8
+
+
 @pytest.mark.parametrize("over", [dict(pif_thr=0.0, paf_thr=0.0), dict(seed_thr=0.0, min_parts=1), dict(grow_thr=0.0),
                                   dict(rev_tol=0.0), dict(rev_tol=1e6), dict(min_parts=17), dict(seed_thr=2.5),
                                   dict(grow_thr=0.6), dict(pif_thr=0.5, paf_thr=0.5)],
