@@ -28,10 +28,10 @@ def put_pif(pif, k, x, y, c=0.9, sigma=4.0, cell=None):
     return gy * pif.shape[4] + gx
 
 
-def put_paf(paf, l, p1, p2, c=0.9, b=4.0, cell=None):
-    """Limb l from pixel p1 to pixel p2, stored in the cell that contains p1 (or `cell`)."""
+def put_paf(paf, l, p1, p2, c=0.9, b=4.0, cell=None, b2=None):
+    """Limb l from pixel p1 to pixel p2 (spreads b and b2, default the same), stored in the cell that contains p1 (or `cell`)."""
     gx, gy = (int(p1[0] // S), int(p1[1] // S)) if cell is None else cell
-    paf[0, l, :, gy, gx] = (c, p1[0] / S - gx, p1[1] / S - gy, b / S, p2[0] / S - gx, p2[1] / S - gy, b / S)
+    paf[0, l, :, gy, gx] = (c, p1[0] / S - gx, p1[1] / S - gy, b / S, p2[0] / S - gx, p2[1] / S - gy, (b if b2 is None else b2) / S)
 
 
 def decode(pif, paf, limbs, **kw):
@@ -182,7 +182,7 @@ def test_grown_value_in_closed_form():
     put_pif(pif, 0, 20.0, 20.0, c=0.9, sigma=4.0)
     put_pif(pif, 1, 41.0, 22.0, c=0.6, sigma=2.0)
     # the association starts 3 pixels off the joint (spread 4) and ends half a pixel off the other part's peak
-    put_paf(paf, 0, (20.0, 23.0), (41.0, 22.5), c=0.7, b=4.0)
+    put_paf(paf, 0, (20.0, 23.0), (41.0, 22.5), c=0.7, b=4.0, b2=1.5)     # the far end's spread plays no part forwards
     r = decode(pif, paf, [(0, 1)])
     xyv, nparts, _ = r["poses"][0]
     assert list(nparts) == [2]
@@ -246,6 +246,79 @@ def test_a_seed_grown_in_vain_still_suppresses_its_neighbours():
     assert run(23.0) == []            # 3 pixels from the first seed (radius 4): never tried
     assert run(24.0) == []            # on the radius
     assert run(26.0) == [2]           # outside: it seeds, and the association is within rev_tol of it
+
+
+def test_growing_backwards_uses_the_far_ends_spread_and_sample():
+    pif, paf = blank(2, 1, 8, 8)
+    put_pif(pif, 0, 20.0, 20.0, c=0.4, sigma=4.0)
+    put_pif(pif, 1, 44.0, 28.0, c=0.9, sigma=2.0)
+    put_paf(paf, 0, (20.0, 20.0), (44.0, 25.0), c=0.7, b=4.0, b2=1.5)     # ends 3 pixels off the seed, spread 1.5 there
+    xyv, nparts, _ = decode(pif, paf, [(0, 1)], seed_thr=0.5, grow_thr=0.01)["poses"][0]
+    assert list(nparts) == [2] and tuple(xyv[0, 0, :2]) == (20.0, 20.0)
+    assert abs(xyv[0, 0, 2] - (0.7 * 0.4) * math.exp(-3.0 / 1.5)) < 1e-6   # (c * f_0(P1)) * E(|Q - P2| / B2)
+
+
+def test_a_value_equal_to_the_seed_threshold_does_not_seed():
+    pif, paf = blank(2, 1, 8, 8)
+    put_pif(pif, 0, 24.0, 24.0, c=0.5)                                     # on a pixel centre: its value is 0.5 exactly
+    assert list(decode(pif, paf, [(0, 1)], seed_thr=0.5)["poses"][0][1]) == []
+    assert list(decode(pif, paf, [(0, 1)], seed_thr=float(np.nextafter(np.float32(0.5), np.float32(0))))["poses"][0][1]) == [1]
+
+
+def test_equal_scores_go_to_the_lower_cell():
+    pif, paf = blank(2, 1, 8, 10)
+    put_pif(pif, 0, 20.0, 20.0, c=0.9)
+    put_pif(pif, 1, 52.0, 20.0, c=0.5, sigma=4.0, cell=(6, 2))
+    put_pif(pif, 1, 52.0, 28.0, c=0.5, sigma=4.0, cell=(6, 3))            # the two map values are equal by symmetry
+    put_paf(paf, 0, (20.0, 20.0), (52.0, 28.0), cell=(1, 2))               # the lower cell proposes the lower point
+    put_paf(paf, 0, (20.0, 20.0), (52.0, 20.0), cell=(2, 2))
+    r = decode(pif, paf, [(0, 1)], seed_thr=0.8)
+    f2 = r["paf"][0][0][2]
+    assert len(f2) == 2 and f2[0] == f2[1]                                 # hence two equal scores
+    assert tuple(r["poses"][0][0][0, 1, :2]) == (52.0, 28.0)
+
+
+def test_an_association_with_an_end_off_the_map_is_ignored():
+    for p2 in ((-3.0, 20.0), (20.0, 64.5), (79.5, 20.0)):
+        pif, paf = blank(2, 1, 8, 10)
+        put_pif(pif, 0, 20.0, 20.0)
+        put_paf(paf, 0, (20.0, 20.0), p2)
+        r = decode(pif, paf, [(0, 1)])
+        assert len(r["paf"][0][0][0]) == 0 and list(r["poses"][0][1]) == [1]
+
+
+def test_a_proposal_inside_a_recorded_joint_is_dropped():
+    # the second root's association ends 2 pixels from the joint the first person holds (radius 4), and its way back is fine
+    def run(x2):
+        pif, paf = blank(2, 1, 8, 12)
+        put_pif(pif, 0, 20.0, 20.0, c=0.9)
+        put_pif(pif, 0, 68.0, 20.0, c=0.8)
+        put_pif(pif, 1, 40.0, 40.0, c=0.9, sigma=4.0)
+        put_paf(paf, 0, (20.0, 20.0), (40.0, 40.0))
+        put_paf(paf, 0, (68.0, 20.0), (x2, 40.0), c=0.8)
+        return list(decode(pif, paf, [(0, 1)], seed_thr=0.5)["poses"][0][1])
+
+    assert run(42.0) == [2, 1]
+    assert run(44.0) == [2, 1]        # on the radius
+    assert run(45.0) == [2, 2]        # outside: the second person takes its own point
+
+
+def test_a_grown_joint_has_the_radius_of_its_own_part():
+    pif, paf = blank(2, 1, 8, 12)
+    put_pif(pif, 0, 20.0, 20.0, c=0.9, sigma=2.0)
+    put_pif(pif, 1, 44.0, 20.0, c=0.5, sigma=6.0)
+    put_pif(pif, 1, 49.0, 20.0, c=0.45, sigma=6.0)                         # 5 pixels from the joint: inside 6, outside 2
+    put_paf(paf, 0, (20.0, 20.0), (44.0, 20.0))
+    assert list(decode(pif, paf, [(0, 1)])["poses"][0][1]) == [2]
+
+
+def test_a_seed_grown_in_vain_suppresses_its_own_part_only():
+    pif, paf = blank(3, 1, 8, 12)
+    put_pif(pif, 0, 20.0, 20.0, c=0.9)                                     # part 0 is in no limb: grown in vain
+    put_pif(pif, 1, 21.0, 20.0, c=0.8, cell=(3, 2))                        # one pixel away, another part
+    put_pif(pif, 2, 60.0, 20.0, c=0.3)
+    put_paf(paf, 0, (21.0, 20.0), (60.0, 20.0))
+    assert list(decode(pif, paf, [(1, 2)], min_parts=2, seed_thr=0.5)["poses"][0][1]) == [2]
 
 
 def test_a_part_reached_by_two_limbs_takes_the_better_proposal():
