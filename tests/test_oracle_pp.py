@@ -164,3 +164,76 @@ def test_detections_taken_by_a_dropped_person_stay_taken():
     assert len(slots) == 0
     dets, (slots, nparts, score) = decode(resp, conf, box, edge, limbs, min_parts=2)
     assert slots.tolist() == [[0, 0]]
+
+
+def boxes_1d(xs, w, scores, img_w=64.0):
+    """A 1 x n grid (cells 64 / n wide, image 64 x 16) with a box of width w centred at xs[i] in cell i."""
+    n = len(xs)
+    cw = img_w / n
+    resp = np.array([scores], np.float32)
+    conf = np.ones((1, n), np.float32)
+    box = np.zeros((4, 1, n), np.float32)
+    for i, x in enumerate(xs):
+        box[:, 0, i] = (x / cw - i, 0.5, w / img_w, 0.5)
+    return resp, conf, box
+
+
+def test_equal_scores_are_taken_in_cell_order():
+    resp, conf, box = boxes_1d([24.0, 24.0, 50.0], 8.0, [0.0, 0.0, 0.0])
+    resp[0, :2] = 0.75                                  # two identical boxes with equal scores
+    cell, score, corners = oracle.pp_detect(resp, conf, box, 64.0, 16.0, 0.5, 0.5)
+    assert cell.tolist() == [0]
+    resp[0, 2] = 0.75                                   # and a third, apart: listed after the first
+    cell, score, corners = oracle.pp_detect(resp, conf, box, 64.0, 16.0, 0.5, 0.5)
+    assert cell.tolist() == [0, 2]
+
+
+def test_an_overlap_equal_to_the_threshold_is_allowed():
+    # [0, 4] x [0, 4] and [1, 3] x [1, 3]: IoU = 4 / 16 exactly
+    resp = np.array([[0.9, 0.8]], np.float32)
+    conf = np.ones((1, 2), np.float32)
+    box = np.zeros((4, 1, 2), np.float32)
+    box[:, 0, 0] = (0.5, 0.5, 0.5, 1.0)
+    box[:, 0, 1] = (-0.5, 0.5, 0.25, 0.5)
+    cell, score, corners = oracle.pp_detect(resp, conf, box, 8.0, 4.0, 0.5, 0.25)
+    assert corners.tolist() == [[0, 0, 4, 4], [1, 1, 3, 3]] and oracle.pp_iou(corners[0], corners[1]) == 0.25
+    cell, _, _ = oracle.pp_detect(resp, conf, box, 8.0, 4.0, 0.5, float(np.nextafter(np.float32(0.25), np.float32(0))))
+    assert cell.tolist() == [0]
+
+
+def test_a_suppressed_box_suppresses_nothing():
+    # A (0.9) overlaps B (0.8), B overlaps C (0.7), A and C are apart: B goes, C stays
+    resp, conf, box = boxes_1d([10.0, 16.0, 22.0], 10.0, [0.9, 0.8, 0.7])
+    cell, _, _ = oracle.pp_detect(resp, conf, box, 64.0, 16.0, 0.5, 0.2)
+    assert cell.tolist() == [0, 2]
+
+
+def test_the_neighbourhood_ends_where_it_says():
+    # the child lies one column beyond a 3 x 3 neighbourhood; the value an index running over would find is set high
+    limbs = ((0, 1),)
+    resp, conf, box, edge = tiny(K=2, Gh=4, Gw=5)
+    resp[0, 0, 1, 1] = 0.9
+    resp[0, 1, 1, 3] = 0.8                              # dy = 0, dx = +2
+    edge[0, 0, :, :, 1, 1] = 0.0
+    edge[0, 0, 2, 0, 1, 1] = 0.9                        # offset (+1, -1): the entry right after (0, +1) in memory
+    dets, (slots, nparts, score) = decode(resp, conf, box, edge, limbs)
+    assert slots.tolist() == [[0, -1]]
+    resp[0, 1, 1, 3], resp[0, 1, 1, 2] = 0.0, 0.8       # one column closer: inside, at offset (0, +1)
+    edge[0, 0, 1, 2, 1, 1] = 0.6
+    dets, (slots, nparts, score) = decode(resp, conf, box, edge, limbs)
+    assert slots.tolist() == [[0, 0]]
+
+
+def test_a_dropped_person_keeps_what_it_took_from_a_person_that_would_have_been_kept():
+    limbs = ((0, 1), (0, 2))
+    resp, conf, box, edge = tiny(K=3)
+    resp[0, 0, 1, 1], resp[0, 0, 1, 2] = 0.9, 0.8       # two roots
+    resp[0, 1, 2, 1] = 0.7                              # X, reachable from both
+    resp[0, 2, 2, 2] = 0.6                              # Y, reachable from the second root only
+    edge[0, 0, 2, 1, 1, 1] = 0.5
+    edge[0, 0, 2, 0, 1, 2] = 0.75
+    edge[0, 1, 2, 1, 1, 2] = 0.75
+    dets, (slots, nparts, score) = decode(resp, conf, box, edge, limbs, min_parts=3)
+    assert len(slots) == 0                              # the first root takes X and is dropped; the second is left with Y
+    dets, (slots, nparts, score) = decode(resp, conf, box, edge, limbs, min_parts=2)
+    assert slots.tolist() == [[0, 0, -1], [1, -1, 0]]
