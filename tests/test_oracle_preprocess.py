@@ -77,6 +77,11 @@ def test_scale_and_offset_per_channel():
     want = raw * alpha.astype(np.float64)[None, :, None, None] + beta.astype(np.float64)[None, :, None, None]
     assert np.abs(out - want).max() <= 1e-5
     assert not np.allclose(out[0, 0], out[0, 1])
+    # with the colour order reversed, scale and offset still go with the OUTPUT channel
+    const = np.empty((1, 4, 4, 3), np.uint8)
+    const[..., 0], const[..., 1], const[..., 2] = 10, 20, 30
+    rev = oracle.preprocess(const, 4, 4, np.float32([1.0, 2.0, 4.0]), np.float32([0.5, 0.25, 0.125]), reverse_channels=True)
+    assert rev[0, :, 0, 0].tolist() == [30.5, 40.25, 40.125]
 
 
 @pytest.mark.parametrize("hs,ws,hd,wd", [(10, 14, 25, 31), (30, 40, 12, 17)])

@@ -29,7 +29,7 @@ def test_hand_values_symmetry_plateaus_and_borders():
     ramp = np.tile(np.arange(6, dtype=np.float32), (6, 1))     # first / last column and row: no neighbours, no offset
     xf, yf = oracle.refine_peaks(ramp, [0, 5, 3], [0, 5, 0])
     assert xf.tolist() == [0.0, 5.0, 3.0] and yf.tolist() == [0.0, 5.0, 0.0]
-    valley = np.array([[3, 1, 3]], np.float32).repeat(3, axis=0)   # den > 0: not a maximum of the parabola
+    valley = np.array([[4, 1, 3]], np.float32).repeat(3, axis=0)   # den = 5 > 0: not a maximum of the parabola
     assert oracle.refine_peaks(valley, [1], [1])[0][0] == 1.0
 
 
