@@ -72,7 +72,7 @@ enum {
     HP_MAX_SAMPLES = 64,
     HP_MAX_TAPS = 65,      /* longest tap vector of hp_smooth */
     HP_PP_MAX_CELLS = 1024, /* most grid cells (Gh * Gw) of hp_pp_decode */
-    HP_CF_MAX_SEEDS = 4096  /* most seeds per image of hp_cf_decode: n_parts * lists->cap may not exceed it */
+    HP_CF_MAX_SEEDS = 16384 /* most seeds per image of hp_cf_decode: n_parts * lists->cap may not exceed it */
 };
 
 /* Skeleton: limb l joins part limb_a[l] to part limb_b[l] and owns PAF channels
@@ -374,7 +374,7 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
  * HP_STATUS_PEAK_OVERFLOW / HP_STATUS_CAND_OVERFLOW tell that a list needed more than cap / acap
  * entries (everything computed from it is then incomplete).  `poses`: xyv holds (x, y, value) per
  * part, zeros for a part not held.  `status`: device int32, overwritten.
- * Limits: 1 <= lists->cap <= 512, n_parts * lists->cap <= HP_CF_MAX_SEEDS, lists->acap >= 1,
+ * Limits: 1 <= lists->cap <= 1024, n_parts * lists->cap <= HP_CF_MAX_SEEDS, lists->acap >= 1,
  * n_parts * poses->cap <= 1536, Fw * stride and Fh * stride below 2^23, thresholds not negative.
  * `workspace`: hp_cf_workspace_bytes(N, n_parts, n_limbs, cap, acap) bytes of device memory, no
  * initialisation needed.  Allocates nothing; enqueues five kernels on `stream`. */
@@ -416,7 +416,7 @@ int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, cons
 
 /* The fine confidence maps of rule C2 as arrays: out device fp32 [N][K][Fh * stride][Fw * stride].
  * Uses pif_thr and stride of `prm`; cell, val and count as in hp_cf_lists ([N][K][cap], [N][K]);
- * `workspace`: hp_cf_workspace_bytes(N, K, 0, cap, 0); cap <= 512, N * K <= 65535.
+ * `workspace`: hp_cf_workspace_bytes(N, K, 0, cap, 0); cap <= 1024, N * K <= 65535.
  * HP_STATUS_PEAK_OVERFLOW as above. */
 int hp_cf_field(const float *pif, int N, int K, int Fh, int Fw, const hp_cf_params *prm, int32_t *cell,
                 float *val, int32_t *count, int cap, float *out, void *workspace, size_t ws_bytes,

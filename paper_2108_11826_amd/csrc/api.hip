@@ -403,7 +403,7 @@ int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, cons
         !lists->paf_f2 || !lists->paf_count || lists->cap <= 0 || lists->acap <= 0)
         return HP_ERR_INVALID_ARG;
     if (!poses || !poses->xyv || !poses->nparts || !poses->score || !poses->count || poses->cap <= 0) return HP_ERR_INVALID_ARG;
-    if (N > 65535 || lists->cap > 512 || (long long)K * lists->cap > HP_CF_MAX_SEEDS || lists->acap > (1 << 24) ||
+    if (N > 65535 || lists->cap > 1024 || (long long)K * lists->cap > HP_CF_MAX_SEEDS || lists->acap > (1 << 24) ||
         (long long)K * poses->cap > 1536)
         return HP_ERR_UNSUPPORTED;
     if (ws_bytes < cf_workspace_bytes(N, K, L, lists->cap, lists->acap) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
@@ -423,7 +423,7 @@ int hp_cf_field(const float *pif, int N, int K, int Fh, int Fw, const hp_cf_para
     if (!pif || !cell || !val || !count || !out || !status || !workspace) return HP_ERR_INVALID_ARG;
     if (N <= 0 || K <= 0 || cap <= 0) return HP_ERR_INVALID_ARG;
     HP_TRY(check_cf_params(prm, Fh, Fw));
-    if (K > HP_MAX_PARTS || cap > 512 || (long long)N * K > 65535) return HP_ERR_UNSUPPORTED;
+    if (K > HP_MAX_PARTS || cap > 1024 || (long long)N * K > 65535) return HP_ERR_UNSUPPORTED;
     if (ws_bytes < cf_workspace_bytes(N, K, 0, cap, 0) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));

@@ -763,6 +763,14 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_field(CFParams P, CFWork ws, co
 }
 
 // ---- host side ---------------------------------------------------------------------------------------------------
+// A workgroup may use up to 160 KB of LDS on this device; beyond 64 KB the kernel has to be told.
+template <typename Kern>
+static hipError_t allow_lds(Kern kern, size_t bytes)
+{
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+}
+
 static CFParams cf_params(const hp_cf_params &prm, int Fh, int Fw, int K, int L, int cap, int acap, int pcap)
 {
     CFParams P;
@@ -809,6 +817,7 @@ hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTabl
     const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
     // the limb workgroups hold two parts' cell lists, the seed workgroups the keys they sort
     const size_t lds = std::max(sizeof(float4) * 4 * (size_t)lists.cap, sizeof(uint64_t) * (size_t)next_pow2(K * lists.cap));
+    if (hipError_t e = allow_lds(k_cf_paf, lds)) return e;
     HP_KERNEL(k_cf_paf, dim3(L + 1, N), dim3(kCfBlock), lds, s, paf, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
               lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
     return hipGetLastError();
@@ -837,10 +846,7 @@ hipError_t launch_cf_grow(int N, int Fh, int Fw, const LimbTable &T, int K, int 
     const size_t room = (kCfGrowLds - persons) / (4 * sizeof(float4));
     const int lds_cells = (int)std::min(room, (size_t)L * lists.acap);
     const size_t lds = persons + 4 * sizeof(float4) * (size_t)lds_cells;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_cf_grow, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCfGrowLds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_lds(k_cf_grow, lds)) return e;
     HP_KERNEL(k_cf_grow, dim3(N), dim3(kCfGrowBlock), lds, s, P, ws, cf_limbs(T, L), lds_cells, lists.paf_count, poses.xyv,
               poses.nparts, poses.score, poses.count, status);
     return hipGetLastError();
@@ -853,7 +859,9 @@ hipError_t launch_cf_field(int N, int Fh, int Fw, int K, const hp_cf_params &prm
     const CFWork ws = cf_layout(workspace, N, K, 0, cap, 0);
     const int H = Fh * prm.stride, W = Fw * prm.stride;
     const dim3 grid((W + kCfTileW - 1) / kCfTileW, (H + kCfTileH - 1) / kCfTileH, N * K);
-    HP_KERNEL(k_cf_field, grid, dim3(kCfBlock), sizeof(float4) * 2 * (size_t)cap * (kCfBlock / kWave), s, P, ws, count, out);
+    const size_t lds = sizeof(float4) * 2 * (size_t)cap * (kCfBlock / kWave);
+    if (hipError_t e = allow_lds(k_cf_field, lds)) return e;
+    HP_KERNEL(k_cf_field, grid, dim3(kCfBlock), lds, s, P, ws, count, out);
     return hipGetLastError();
 }
 

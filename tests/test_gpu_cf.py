@@ -74,6 +74,14 @@ def test_decode_matches_oracle(cfg):
         assert sum(len(p[1]) for p in ora["poses"]) > 0
 
 
+def test_a_crowd_at_full_hd():
+    # 135 x 240 cells, 40 large persons: lists of 500 cells per part (8700 seeds to sort), 550 associations per limb
+    cfg = CFConfig(250, CF_COCO17, 2, 135, 240, 40, stride=8, scale_lo=150.0, scale_hi=420.0, dropout=0.1, clutter=150)
+    got, ora = run_both(cfg, pcap=90)
+    assert_same(got, ora)
+    assert max(got["pif_counts"].max(), 0) > 400 and min(len(p[1]) for p in ora["poses"]) >= 35
+
+
 def test_benchmark_configuration():
     # the batch, the capacities and hence the launch shapes that bench.py times
     got, ora = run_both(CF_CONFIGS[2], cap=128, acap=256, pcap=32)

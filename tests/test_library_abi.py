@@ -318,8 +318,8 @@ def test_cf_decode_rejects_bad_calls(L):
         assert call(prm=byref(bad)) == -1
     assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 128))) == -1
     assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 64, 128))) == -1
-    big = L.hp_cf_workspace_bytes(2, 3, 3, 513, 128)
-    assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 513, 128)), wsb=ctypes.c_size_t(big)) == -5
+    big = L.hp_cf_workspace_bytes(2, 3, 3, 1025, 128)
+    assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1025, 128)), wsb=ctypes.c_size_t(big)) == -5
     assert call(poses=byref(B._CFPoses(FAKE, FAKE, FAKE, FAKE, 513))) == -5               # 3 * 513 > 1536 joints in LDS
     assert call(prm=byref(B._CFParams(0.1, 0.1, 0.2, 0.05, 4.0, 1, 1 << 22))) == -5        # the map would pass 2^23 pixels a side
 
@@ -341,5 +341,5 @@ def test_cf_field_rejects_bad_calls(L):
 
     assert call(pif=None) == -1 and call(out=None) == -1 and call(count=None) == -1 and call(prm=None) == -1
     assert call(N=0) == -1 and call(K=0) == -1 and call(cap=0) == -1 and call(Fh=0) == -1
-    assert call(K=33) == -5 and call(cap=513) == -5
+    assert call(K=33) == -5 and call(cap=1025) == -5
     assert call(wsb=ctypes.c_size_t(need - 1)) == -3
