@@ -74,6 +74,31 @@ def test_decode_matches_oracle(cfg):
         assert sum(len(p[1]) for p in ora["poses"]) > 0
 
 
+def test_lists_near_the_capacity_limit():
+    # 800 active cells per part and 1000-entry lists: the kernels that keep lists in LDS ask for more than 64 KB of it
+    m = hp()
+    rng = np.random.default_rng(21)
+    N, K, L, Fh, Fw = 1, 3, 2, 40, 40
+    pif = np.empty((N, K, 5, Fh, Fw), np.float32)
+    pif[:, :, 0] = rng.random((N, K, Fh, Fw))
+    pif[:, :, 1:3] = rng.normal(0, 0.6, (N, K, 2, Fh, Fw))
+    pif[:, :, 3] = 1.0
+    pif[:, :, 4] = rng.uniform(0.1, 0.6, (N, K, Fh, Fw))
+    paf = np.empty((N, L, 7, Fh, Fw), np.float32)
+    paf[:, :, 0] = rng.random((N, L, Fh, Fw))
+    paf[:, :, (1, 2, 4, 5)] = rng.normal(0, 1.0, (N, L, 4, Fh, Fw))
+    paf[:, :, (3, 6)] = rng.uniform(0.1, 0.8, (N, L, 2, Fh, Fw))
+    cfg = CFConfig(232, CF_COCO17, N, Fh, Fw, 0, stride=4, pif_thr=0.5, paf_thr=0.5, seed_thr=0.8, grow_thr=0.05, rev_tol=3.0,
+                   min_parts=2)
+    got, ora = run_both(cfg, dict(pif=pif, paf=paf), limbs=[(0, 1), (1, 2)], cap=1000, acap=1000, pcap=400)
+    assert_same(got, ora)
+    assert got["pif_counts"].max() > 700
+    maps, status = m.hp_cf_field(torch.from_numpy(pif).to(DEV), 4, 0.5, cap=1024)
+    assert int(status.cpu()[0]) == 0
+    for k in range(K):
+        assert np.array_equal(bits(maps[0, k].cpu().numpy()), bits(oracle.cf_field(pif[0, k], 4, 0.5))), k
+
+
 def test_a_crowd_at_full_hd():
     # 135 x 240 cells, 40 large persons: lists of 500 cells per part (8700 seeds to sort), 550 associations per limb
     cfg = CFConfig(250, CF_COCO17, 2, 135, 240, 40, stride=8, scale_lo=150.0, scale_hi=420.0, dropout=0.1, clutter=150)
