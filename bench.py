@@ -416,6 +416,23 @@ def main():
         cf_call()
     torch.cuda.synchronize()
     cf_us = (time.perf_counter() - t0) / 100 * 1e6
+    # the same call with three batches in flight on separate streams (own outputs and workspace each), as for the headline
+    cf_lanes = [(torch.cuda.Stream(), hp.CFBuffers(cf_cfg.batch, cf_sk.n_parts, cf_sk.n_limbs, 128, 256, 32, dev)) for _ in range(3)]
+    torch.cuda.synchronize()
+
+    def cf_round(reps):
+        for i in range(reps):
+            st, b = cf_lanes[i % 3]
+            with torch.cuda.stream(st):
+                hp.hp_cf_decode(cf_pif, cf_paf, cf_skel, b, *cf_prm)
+        torch.cuda.synchronize()
+
+    cf_round(6)
+    t0 = time.perf_counter()
+    cf_round(150)
+    cf_us3 = (time.perf_counter() - t0) / 150 * 1e6
+    cf_same_lanes = all(torch.equal(b.xyv, cf_buf.xyv) and torch.equal(b.pose_count, cf_buf.pose_count) for _, b in cf_lanes)
+    del cf_lanes
     cf_got = cf_buf.host()
     cf_ora = oracle.cf_decode(cf_in["pif"], cf_in["paf"], cf_sk.limb_a, cf_sk.limb_b, *cf_prm, pcap=32)
     same = lambda a, b: np.array_equal(np.ascontiguousarray(a).view(np.uint32), np.ascontiguousarray(b).view(np.uint32))
@@ -424,7 +441,8 @@ def main():
         and same(cf_got["poses"][n][2], cf_ora["poses"][n][2])
         and all(same(cf_got["pif"][n][k][1], cf_ora["pif"][n][k][1]) for k in range(cf_sk.n_parts))
         for n in range(cf_cfg.batch))
-    parity = parity and bool(cf_ok)
+    cf_ok = bool(cf_ok) and bool(cf_same_lanes)
+    parity = parity and cf_ok
     hp.hp_profile_begin(64)
     for _ in range(5):
         cf_maps, _ = hp.hp_cf_field(cf_pif, cf_cfg.stride, cf_cfg.pif_thr, cap=128)
@@ -436,6 +454,7 @@ def main():
     composite_fields = {"what": "hp_cf_decode: batch %d, %dx%d grid, stride %d, %d parts, %d limbs, %d planted persons per image"
                                 % (cf_cfg.batch, cf_cfg.Fh, cf_cfg.Fw, cf_cfg.stride, cf_sk.n_parts, cf_sk.n_limbs, cf_cfg.n_people),
                         "us_per_call": round(cf_us, 2), "frames_per_s": round(cf_cfg.batch / (cf_us * 1e-6), 1),
+                        "frames_per_s_three_streams": round(cf_cfg.batch / (cf_us3 * 1e-6), 1),
                         "kernel_us": {k: round(1e3 * ms / nl, 2) for k, (ms, nl) in sorted(pr.items())},
                         "bound": "latency (persons of an image grow one after the other, a round of growth at a time; the fine "
                                  "confidence maps are never written: their values are summed where they are needed)",
