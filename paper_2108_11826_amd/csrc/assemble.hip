@@ -173,6 +173,22 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
     const float *psc = pscore + (size_t)n * K * cap;
     const unsigned long long lt = (1ull << lane) - 1ull;
 
+    // The first limbs' connections are fetched before their counts are known (lane k reads entry k of each list, which
+    // exists whatever the count; entries beyond the count are never used): one memory round trip less before the fold.
+    constexpr int kGroup = 8;
+    int i0[kGroup], j0[kGroup];
+    float s0[kGroup];
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+        i0[u] = j0[u] = 0;
+        s0[u] = 0.0f;
+        if (u < L && lane < mcap) {
+            const size_t idx = (size_t)(n * L + u) * mcap + lane;
+            i0[u] = mi[idx];
+            j0[u] = mj[idx];
+            s0[u] = ms[idx];
+        }
+    }
     // connection counts -> offsets of each limb in the image's flat connection list
     const int mc = (lane < L) ? max(min(mcounts[n * L + lane], mcap), 0) : 0;
     int incl = mc;
@@ -207,7 +223,6 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
 
         for (int idx = lane; idx < K * cmax; idx += kWave) owner[idx] = -1;
         const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
-        constexpr int kGroup = 8;
         struct Group {
             int i[kGroup], j[kGroup];
             float s[kGroup], sa[kGroup], sb[kGroup];
@@ -324,7 +339,13 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
         };
         __syncthreads();                          // owner table initialised
         Group ga, gb;
-        fetch_conn(0, ga);
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const int cnt = u < L ? __builtin_amdgcn_readlane(mc, u) : 0;
+            ga.i[u] = lane < cnt ? i0[u] : 0;
+            ga.j[u] = lane < cnt ? j0[u] : 0;
+            ga.s[u] = lane < cnt ? s0[u] : 0.0f;
+        }
         fetch_peak(0, ga);
         for (int g = 0; g * kGroup < L; g += 2) {
             run_group(g, ga, gb);
