@@ -375,7 +375,7 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
  * entries (everything computed from it is then incomplete).  `poses`: xyv holds (x, y, value) per
  * part, zeros for a part not held.  `status`: device int32, overwritten.
  * Limits: 1 <= lists->cap <= 1024, n_parts * lists->cap <= HP_CF_MAX_SEEDS, lists->acap >= 1,
- * n_parts * poses->cap <= 1536, Fw * stride and Fh * stride below 2^23, thresholds not negative.
+ * n_parts * poses->cap <= 4096, Fw * stride and Fh * stride below 2^23, thresholds not negative.
  * `workspace`: hp_cf_workspace_bytes(N, n_parts, n_limbs, cap, acap) bytes of device memory, 16-byte
  * aligned, no initialisation needed (HP_ERR_WORKSPACE when too small or misaligned).  Every check
  * is made on the host before anything is enqueued.  Allocates nothing; enqueues five kernels on

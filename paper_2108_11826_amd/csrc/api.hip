@@ -404,7 +404,7 @@ int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, cons
         return HP_ERR_INVALID_ARG;
     if (!poses || !poses->xyv || !poses->nparts || !poses->score || !poses->count || poses->cap <= 0) return HP_ERR_INVALID_ARG;
     if (N > 65535 || lists->cap > 1024 || (long long)K * lists->cap > HP_CF_MAX_SEEDS || lists->acap > (1 << 24) ||
-        (long long)K * poses->cap > 1536)
+        (long long)K * poses->cap > 4096)
         return HP_ERR_UNSUPPORTED;
     if (ws_bytes < cf_workspace_bytes(N, K, L, lists->cap, lists->acap) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;

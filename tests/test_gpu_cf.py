@@ -144,7 +144,7 @@ def test_dense_random_fields():
     paf[:, :, (3, 6)] = rng.integers(1, 8, (N, L, 2, Fh, Fw)) / 8
     cfg = CFConfig(231, CF_COCO17, N, Fh, Fw, 0, stride=8, pif_thr=0.3, paf_thr=0.3, seed_thr=0.5, grow_thr=0.01, rev_tol=6.0,
                    min_parts=2)
-    got, ora = run_both(cfg, dict(pif=pif, paf=paf), limbs=limbs, pcap=250)
+    got, ora = run_both(cfg, dict(pif=pif, paf=paf), limbs=limbs, pcap=680)   # 6 x 680 joints: the most the persons kernel holds
     assert_same(got, ora)
     assert max(len(c) for c, _ in ora["pif"][0]) > 100 and sum(len(p[1]) for p in ora["poses"]) > 20
 

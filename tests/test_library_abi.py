@@ -320,7 +320,7 @@ def test_cf_decode_rejects_bad_calls(L):
     assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 64, 128))) == -1
     big = L.hp_cf_workspace_bytes(2, 3, 3, 1025, 128)
     assert call(lists=byref(B._CFLists(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1025, 128)), wsb=ctypes.c_size_t(big)) == -5
-    assert call(poses=byref(B._CFPoses(FAKE, FAKE, FAKE, FAKE, 513))) == -5               # 3 * 513 > 1536 joints in LDS
+    assert call(poses=byref(B._CFPoses(FAKE, FAKE, FAKE, FAKE, 1366))) == -5              # 3 * 1366 > 4096 joints in LDS
     assert call(prm=byref(B._CFParams(0.1, 0.1, 0.2, 0.05, 4.0, 1, 1 << 22))) == -5        # the map would pass 2^23 pixels a side
 
 
