@@ -364,7 +364,7 @@ int hp_pp_decode(const float *resp, const float *conf, const float *box, const f
         (long long)K * dets->cap > 4096)
         return HP_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
+    HP_LAUNCH(HP_K_INIT, launch_clear_status(status, s));
     HP_LAUNCH(HP_K_PP_DETECT, launch_pp_detect(resp, conf, box, N, Gh, Gw, K, *prm, *dets, status, s));
     HP_LAUNCH(HP_K_PP_PARSE, launch_pp_parse(edge, N, Gh, Gw, Nh, Nw, tab, K, L, *prm, *dets, *poses, status, s));
     return HP_OK;
@@ -408,7 +408,7 @@ int hp_cf_decode(const float *pif, const float *paf, int N, int Fh, int Fw, cons
         return HP_ERR_UNSUPPORTED;
     if (ws_bytes < cf_workspace_bytes(N, K, L, lists->cap, lists->acap) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
+    HP_LAUNCH(HP_K_INIT, launch_clear_status(status, s));
     HP_LAUNCH(HP_K_CF_PIF, launch_cf_pif(pif, N, Fh, Fw, K, *prm, lists->cap, lists->pif_cell, lists->pif_val, lists->pif_count,
                                          workspace, L, lists->acap, status, s));
     HP_LAUNCH(HP_K_CF_PAF, launch_cf_paf(paf, N, Fh, Fw, tab, K, L, *prm, *lists, workspace, status, s));
@@ -426,7 +426,7 @@ int hp_cf_field(const float *pif, int N, int K, int Fh, int Fw, const hp_cf_para
     if (K > HP_MAX_PARTS || cap > 1024 || (long long)N * K > 65535) return HP_ERR_UNSUPPORTED;
     if (ws_bytes < cf_workspace_bytes(N, K, 0, cap, 0) || ((uintptr_t)workspace & 15)) return HP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_INIT, launch_pp_clear(status, s));
+    HP_LAUNCH(HP_K_INIT, launch_clear_status(status, s));
     HP_LAUNCH(HP_K_CF_PIF, launch_cf_pif(pif, N, Fh, Fw, K, *prm, cap, cell, val, count, workspace, 0, 0, status, s));
     HP_LAUNCH(HP_K_CF_FIELD, launch_cf_field(N, Fh, Fw, K, *prm, cap, count, out, workspace, s));
     return HP_OK;

@@ -216,8 +216,9 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
 hipError_t launch_refine(const float *maps, int N, int C_mem, int K, int H, int W, const hp_peaks &pk, float *xf, float *yf,
                          hipStream_t s);
 
-// Pose-proposal post-processing: the status word cleared, detections per (image, part), persons per image.
-hipError_t launch_pp_clear(int32_t *status, hipStream_t s);
+// The status word cleared (first launch of hp_pp_decode, hp_cf_decode and hp_cf_field).
+hipError_t launch_clear_status(int32_t *status, hipStream_t s);
+// Pose-proposal post-processing: detections per (image, part), persons per image.
 hipError_t launch_pp_detect(const float *resp, const float *conf, const float *box, int N, int Gh, int Gw, int K,
                             const hp_pp_params &prm, const hp_pp_dets &dets, int32_t *status, hipStream_t s);
 hipError_t launch_pp_parse(const float *edge, int N, int Gh, int Gw, int Nh, int Nw, const LimbTable &T, int K, int L,

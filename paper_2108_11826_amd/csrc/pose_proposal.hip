@@ -234,7 +234,7 @@ __global__ __launch_bounds__(kWave) void k_pp_parse(const int32_t *__restrict__ 
     }
 }
 
-__global__ void k_pp_clear(int32_t *status) { *status = 0; }
+__global__ void k_clear_status(int32_t *status) { *status = 0; }
 
 static PPParams pp_params(int Gh, int Gw, int Nh, int Nw, int K, int L, const hp_pp_params &prm, int cap, int pcap)
 {
@@ -256,9 +256,9 @@ static PPParams pp_params(int Gh, int Gw, int Nh, int Nw, int K, int L, const hp
     return P;
 }
 
-hipError_t launch_pp_clear(int32_t *status, hipStream_t s)
+hipError_t launch_clear_status(int32_t *status, hipStream_t s)
 {
-    HP_KERNEL(k_pp_clear, dim3(1), dim3(1), 0, s, status);
+    HP_KERNEL(k_clear_status, dim3(1), dim3(1), 0, s, status);
     return hipGetLastError();
 }
 
