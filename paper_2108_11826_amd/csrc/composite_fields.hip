@@ -103,17 +103,30 @@ __device__ __forceinline__ bool cf_on_map(float X, float Y, int H, int W)
 
 __device__ __forceinline__ int cf_window(float sg) { return (int)fminf(ceilf(3.0f * sg), 24.0f); }
 
-// C2 at one pixel: the listed cells of a part, in list (ascending cell) order.
+// C2 at one pixel: the listed cells of a part, in list (ascending cell) order.  The list is walked 32 cells at a time
+// in two passes: the window tests first (independent LDS reads that go out together), then the cells whose window
+// holds the pixel, still in ascending order, each with its Gaussian (a thread working alone spends its time waiting
+// for LDS: one pass with the test and the sum interleaved took three times as long).
 __device__ __forceinline__ float cf_sample(const float4 *ra, const int4 *rb, int n, int px, int py)
 {
     float f = 0.0f;
-    for (int j = 0; j < n; ++j) {
-        const int4 b = rb[j];
-        if (abs(px - b.x) > b.w || abs(py - b.y) > b.w) continue;
-        const float4 a = ra[j];
-        const float dx = (float)px - a.x, dy = (float)py - a.y;
-        const float d2 = dx * dx + dy * dy;
-        f = f + a.w * cf_expneg(d2 * a.z);
+    for (int j0 = 0; j0 < n; j0 += 32) {
+        uint32_t in = 0u;
+#pragma unroll 8
+        for (int u = 0; u < 32; ++u) {
+            if (j0 + u < n) {
+                const int4 b = rb[j0 + u];
+                in |= (abs(px - b.x) <= b.w && abs(py - b.y) <= b.w) ? 1u << u : 0u;
+            }
+        }
+        while (in) {
+            const int u = __ffs((int)in) - 1;
+            in &= in - 1u;
+            const float4 a = ra[j0 + u];
+            const float dx = (float)px - a.x, dy = (float)py - a.y;
+            const float d2 = dx * dx + dy * dy;
+            f = f + a.w * cf_expneg(d2 * a.z);
+        }
     }
     return f;
 }
@@ -256,6 +269,10 @@ __device__ void cf_sort_seeds(const CFParams &P, const CFWork &ws, int n, const 
 }
 
 // Workgroups (l < L, n): limb l of image n.  Workgroups (L, n): the seeds of image n.
+// kStaged: the records stay in LDS until their map values are known and go to the lists once (a barrier also waits
+// for the global stores issued before it, and the records written early would be read back and written again).
+constexpr int kCfPafStage = 1024;   // records a list may hold for the staged form
+template <bool kStaged>
 __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ paf, CFParams P,
                                                      CFWork ws, CFLimbs limbs, const int32_t *__restrict__ pif_count,
                                                      const float *__restrict__ pif_val, int32_t *__restrict__ out_cell,
@@ -272,6 +289,9 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     int4 *s_ab = (int4 *)(s_dyn4 + P.cap);        //         [cap] xr, yr, sg, cell
     float4 *s_ba = s_dyn4 + 2 * P.cap;            // part b
     int4 *s_bb = (int4 *)(s_dyn4 + 3 * P.cap);
+    float4 *s_fs = s_dyn4 + 4 * P.cap;            // staged records: [acap] forwards, [acap] backwards, [acap] cells
+    float4 *s_bs = s_fs + P.acap;
+    int *s_cell = (int *)(s_bs + P.acap);
     __shared__ int s_scan[kCfPer * 4];
     __shared__ uint8_t s_la[HP_MAX_LIMBS], s_lb[HP_MAX_LIMBS];
 
@@ -303,12 +323,12 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
     int count = 0;
     for (int c0 = 0; c0 < cells; c0 += kCfPer * kCfBlock) {
         bool act[kCfPer];
-        float c[kCfPer], x1[kCfPer], y1[kCfPer], x2[kCfPer], y2[kCfPer];
+        float c[kCfPer], x1[kCfPer], y1[kCfPer], x2[kCfPer], y2[kCfPer], b1[kCfPer], b2[kCfPer];
 #pragma unroll
         for (int u = 0; u < kCfPer; ++u) {
             const int cell = c0 + u * kCfBlock + tid;
             act[u] = false;
-            c[u] = x1[u] = y1[u] = x2[u] = y2[u] = 0.0f;
+            c[u] = x1[u] = y1[u] = x2[u] = y2[u] = b1[u] = b2[u] = 0.0f;
             if (cell < cells) {
                 const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
                 c[u] = f[cell];
@@ -316,6 +336,8 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
                 y1[u] = ((float)gy + f[2 * cells + cell]) * s;
                 x2[u] = ((float)gx + f[4 * cells + cell]) * s;
                 y2[u] = ((float)gy + f[5 * cells + cell]) * s;
+                b1[u] = f[3 * cells + cell];   // fetched with the rest: a second round of loads would cost as much again
+                b2[u] = f[6 * cells + cell];
                 act[u] = c[u] > P.paf_thr && cf_on_map(x1[u], y1[u], H, W) && cf_on_map(x2[u], y2[u], H, W);
             }
         }
@@ -325,26 +347,48 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_paf(const float *__restrict__ p
         for (int u = 0; u < kCfPer; ++u) {
             const int cell = c0 + u * kCfBlock + tid, to = count + at[u];
             if (act[u] && to < P.acap) {
-                const float iB1 = 1.0f / fmaxf(f[3 * cells + cell] * s, 1.0f), iB2 = 1.0f / fmaxf(f[6 * cells + cell] * s, 1.0f);
-                fs[to] = make_float4(x1[u], y1[u], iB1, c[u]);   // c is replaced by c * F2 below
-                bs[to] = make_float4(x2[u], y2[u], iB2, c[u]);
-                out_cell[list + to] = cell;
+                const float iB1 = 1.0f / fmaxf(b1[u] * s, 1.0f), iB2 = 1.0f / fmaxf(b2[u] * s, 1.0f);
+                const float4 rf = make_float4(x1[u], y1[u], iB1, c[u]);   // c is replaced by c * F2 below
+                const float4 rb = make_float4(x2[u], y2[u], iB2, c[u]);
+                if constexpr (kStaged) {
+                    s_fs[to] = rf;
+                    s_bs[to] = rb;
+                    s_cell[to] = cell;
+                } else {
+                    fs[to] = rf;
+                    bs[to] = rb;
+                    out_cell[list + to] = cell;
+                }
             }
         }
         count += total;
     }
     __syncthreads();   // the records written above are read back by other threads of this workgroup
+    // one thread per sample: even lanes take F1 of a candidate, odd lanes its F2, and the pair swaps the results
     const int m = min(count, P.acap);
-    for (int i = tid; i < m; i += kCfBlock) {
-        float4 ra = fs[i], rb = bs[i];
-        const float F1 = cf_sample(s_aa, s_ab, na, (int)rintf(ra.x), (int)rintf(ra.y));
-        const float F2 = cf_sample(s_ba, s_bb, nb, (int)rintf(rb.x), (int)rintf(rb.y));
-        out_f1[list + i] = F1;
-        out_f2[list + i] = F2;
-        ra.w = ra.w * F2;
-        rb.w = rb.w * F1;
-        fs[i] = ra;
-        bs[i] = rb;
+    for (int j0 = 0; j0 < 2 * m; j0 += kCfBlock) {
+        const int j = j0 + tid, i = j >> 1;
+        const bool second = (j & 1) != 0, on = j < 2 * m;
+        float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if constexpr (kStaged) {
+            if (on) r = second ? s_bs[i] : s_fs[i];
+        } else {
+            if (on) r = second ? bs[i] : fs[i];
+        }
+        const float F = cf_sample(second ? s_ba : s_aa, second ? s_bb : s_ab, on ? (second ? nb : na) : 0,
+                                  (int)rintf(r.x), (int)rintf(r.y));
+        const float other = __shfl_xor(F, 1);
+        if (on) {
+            r.w = r.w * other;
+            if (second) {
+                out_f2[list + i] = F;
+                bs[i] = r;
+            } else {
+                out_f1[list + i] = F;
+                fs[i] = r;
+                if constexpr (kStaged) out_cell[list + i] = s_cell[i];
+            }
+        }
     }
     if (tid == 0) {
         out_count[(size_t)n * P.L + l] = count;
@@ -816,10 +860,18 @@ hipError_t launch_cf_paf(const float *paf, int N, int Fh, int Fw, const LimbTabl
     const CFParams P = cf_params(prm, Fh, Fw, K, L, lists.cap, lists.acap, 0);
     const CFWork ws = cf_layout(workspace, N, K, L, lists.cap, lists.acap);
     // the limb workgroups hold two parts' cell lists, the seed workgroups the keys they sort
-    const size_t lds = std::max(sizeof(float4) * 4 * (size_t)lists.cap, sizeof(uint64_t) * (size_t)next_pow2(K * lists.cap));
-    if (hipError_t e = allow_lds(k_cf_paf, lds)) return e;
-    HP_KERNEL(k_cf_paf, dim3(L + 1, N), dim3(kCfBlock), lds, s, paf, P, ws, cf_limbs(T, L), lists.pif_count, lists.pif_val,
-              lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
+    const bool staged = lists.acap <= kCfPafStage;
+    const size_t held = sizeof(float4) * 4 * (size_t)lists.cap + (staged ? (2 * sizeof(float4) + sizeof(int)) * (size_t)lists.acap : 0);
+    const size_t lds = std::max(held, sizeof(uint64_t) * (size_t)next_pow2(K * lists.cap));
+    if (staged) {
+        if (hipError_t e = allow_lds(k_cf_paf<true>, lds)) return e;
+        HP_KERNEL(k_cf_paf<true>, dim3(L + 1, N), dim3(kCfBlock), lds, s, paf, P, ws, cf_limbs(T, L), lists.pif_count,
+                  lists.pif_val, lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
+    } else {
+        if (hipError_t e = allow_lds(k_cf_paf<false>, lds)) return e;
+        HP_KERNEL(k_cf_paf<false>, dim3(L + 1, N), dim3(kCfBlock), lds, s, paf, P, ws, cf_limbs(T, L), lists.pif_count,
+                  lists.pif_val, lists.paf_cell, lists.paf_f1, lists.paf_f2, lists.paf_count, status);
+    }
     return hipGetLastError();
 }
 

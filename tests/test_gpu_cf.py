@@ -183,6 +183,18 @@ def test_list_capacity_overflow_is_reported():
     assert all(got["paf_counts"][n][l] == len(ora["paf"][n][l][0]) for n in range(cfg.batch) for l in range(L))
 
 
+def test_candidate_lists_beyond_the_staged_size():
+    # lists of more than 1024 candidates are written to the workspace as they are found, shorter ones are held in
+    # LDS first: both forms give the same lists and persons
+    cfg = CF_CONFIGS[1]
+    got, ora = run_both(cfg, acap=1500)
+    assert_same(got, ora)
+    got, ora = run_both(cfg, acap=1024)
+    assert_same(got, ora)
+    got, ora = run_both(CF_CONFIGS[2], cap=256, acap=1025, pcap=32)
+    assert_same(got, ora)
+
+
 def test_images_are_independent_and_calls_repeat():
     m = hp()
     cfg = CF_CONFIGS[2]
