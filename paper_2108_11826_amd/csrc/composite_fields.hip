@@ -236,16 +236,30 @@ __device__ __forceinline__ float cf_score(const float4 r, float qx, float qy)
 __device__ void cf_sort_seeds(const CFParams &P, const CFWork &ws, int n, const int32_t *__restrict__ pif_count,
                               const float *__restrict__ pif_val, uint64_t *s_key)
 {
-    __shared__ int s_nseeds;
+    __shared__ int s_nseeds, s_cnt[HP_MAX_PARTS];
     const int tid = threadIdx.x, K = P.K;
     if (tid == 0) s_nseeds = 0;
+    if (tid < K) s_cnt[tid] = min(pif_count[(size_t)n * K + tid], P.cap);
     __syncthreads();
-    for (int k = 0; k < K; ++k) {
-        const int cnt = min(pif_count[(size_t)n * K + k], P.cap);
-        for (int q = tid; q < cnt; q += kCfBlock) {
-            const float v = pif_val[((size_t)n * K + k) * P.cap + q];
-            if (v > P.seed_thr)
-                s_key[atomicAdd(&s_nseeds, 1)] = ((uint64_t)(~float_order(v)) << 32) | (uint32_t)((k << 16) | q);
+    // every (part, rank) slot of the image, four a thread at a time: the values are fetched before it is known which
+    // of them exist (a slot beyond its list's end lies inside the array and is not used), so that the loads of all
+    // parts go out together; the keys are unique, so the order they are appended in does not matter
+    constexpr int kPer = 4;
+    const int slots = K * P.cap;
+    for (int s0 = 0; s0 < slots; s0 += kPer * kCfBlock) {
+        float v[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int idx = s0 + u * kCfBlock + tid;
+            v[u] = idx < slots ? pif_val[(size_t)n * slots + idx] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int idx = s0 + u * kCfBlock + tid;
+            if (idx >= slots) continue;
+            const int k = idx / P.cap, q = idx - k * P.cap;
+            if (q < s_cnt[k] && v[u] > P.seed_thr)
+                s_key[atomicAdd(&s_nseeds, 1)] = ((uint64_t)(~float_order(v[u])) << 32) | (uint32_t)((k << 16) | q);
         }
     }
     __syncthreads();
@@ -254,8 +268,7 @@ __device__ void cf_sort_seeds(const CFParams &P, const CFWork &ws, int n, const 
     while (n2 < ns) n2 <<= 1;
     for (int i = ns + tid; i < n2; i += kCfBlock) s_key[i] = ~0ull;
     __syncthreads();
-    block_bitonic_sort(s_key, n2);
-    __syncthreads();
+    block_bitonic_sort(s_key, n2);   // ends with a barrier
     const size_t base = (size_t)n * K * P.cap;
     for (int i = tid; i < ns; i += kCfBlock) {
         const uint64_t key = s_key[i];
