@@ -167,6 +167,7 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
     extern __shared__ float4 s_dyn4[];
     float4 *s_a = s_dyn4;                     // [cap]
     int4 *s_b = (int4 *)(s_dyn4 + P.cap);     // [cap]
+    int *s_cell = (int *)(s_dyn4 + 2 * P.cap);  // [cap]
     __shared__ int s_scan[kCfPer * 4];
 
     const int k = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
@@ -178,17 +179,18 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
     int count = 0;
     for (int c0 = 0; c0 < cells; c0 += kCfPer * kCfBlock) {
         bool act[kCfPer];
-        float X[kCfPer], Y[kCfPer], c[kCfPer];
+        float X[kCfPer], Y[kCfPer], c[kCfPer], sig[kCfPer];
 #pragma unroll
         for (int u = 0; u < kCfPer; ++u) {
             const int cell = c0 + u * kCfBlock + tid;
             act[u] = false;
-            X[u] = Y[u] = c[u] = 0.0f;
+            X[u] = Y[u] = c[u] = sig[u] = 0.0f;
             if (cell < cells) {
                 const int gy = cell / P.Fw, gx = cell - gy * P.Fw;
                 c[u] = f[cell];
                 X[u] = ((float)gx + f[1 * cells + cell]) * s;
                 Y[u] = ((float)gy + f[2 * cells + cell]) * s;
+                sig[u] = f[4 * cells + cell];   // fetched with the rest: a second round of loads would cost as much again
                 act[u] = c[u] > P.pif_thr && cf_on_map(X[u], Y[u], H, W);
             }
         }
@@ -198,20 +200,22 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_pif(const float *__restrict__ p
         for (int u = 0; u < kCfPer; ++u) {
             const int cell = c0 + u * kCfBlock + tid, to = count + at[u];
             if (act[u] && to < P.cap) {
-                const float sg = fmaxf(f[4 * cells + cell] * s, 1.0f);
-                const float4 a = make_float4(X[u], Y[u], 0.5f / (sg * sg), c[u]);
-                const int4 b = make_int4((int)rintf(X[u]), (int)rintf(Y[u]), __float_as_int(sg), cf_window(sg));
-                s_a[to] = a;
-                s_b[to] = b;
-                ws.pif_a[list + to] = a;
-                ws.pif_b[list + to] = b;
-                out_cell[list + to] = cell;
+                const float sg = fmaxf(sig[u] * s, 1.0f);
+                s_a[to] = make_float4(X[u], Y[u], 0.5f / (sg * sg), c[u]);
+                s_b[to] = make_int4((int)rintf(X[u]), (int)rintf(Y[u]), __float_as_int(sg), cf_window(sg));
+                s_cell[to] = cell;
             }
         }
         count += total;
     }
     __syncthreads();
+    // the list leaves LDS once, after the last barrier (a barrier also waits for the stores issued before it)
     const int m = min(count, P.cap);
+    for (int i = tid; i < m; i += kCfBlock) {
+        ws.pif_a[list + i] = s_a[i];
+        ws.pif_b[list + i] = s_b[i];
+        out_cell[list + i] = s_cell[i];
+    }
     for (int i = tid; i < m; i += kCfBlock) out_val[list + i] = cf_sample(s_a, s_b, m, s_b[i].x, s_b[i].y);
     if (tid == 0) {
         out_count[(size_t)n * P.K + k] = count;
@@ -853,7 +857,7 @@ hipError_t launch_cf_pif(const float *pif, int N, int Fh, int Fw, int K, const h
 {
     const CFParams P = cf_params(prm, Fh, Fw, K, L, cap, acap, 0);
     const CFWork ws = cf_layout(workspace, N, K, L, cap, acap);
-    HP_KERNEL(k_cf_pif, dim3(K, N), dim3(kCfBlock), sizeof(float4) * 2 * (size_t)cap, s, pif, P, ws, cell, val, count, status);
+    HP_KERNEL(k_cf_pif, dim3(K, N), dim3(kCfBlock), (sizeof(float4) * 2 + sizeof(int)) * (size_t)cap, s, pif, P, ws, cell, val, count, status);
     return hipGetLastError();
 }
 
