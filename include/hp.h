@@ -227,6 +227,24 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
                    const hp_poses *poses,
                    void *workspace, size_t ws_bytes, int32_t *status, void *stream);
 
+/* hp_postprocess for callers that cannot allocate device memory and have no workspace to pass:
+ * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, checks, kernels and results as hp_postprocess, but the workspace is a fixed array of
+ * HP_STATIC_WS_BYTES inside the library's device image (every GPU the library runs on holds its
+ * own copy until the process ends; its address on the current device is looked up at the first
+ * call there).  The call allocates and frees nothing.  Sizes whose workspace
+ * (hp_workspace_bytes) exceeds HP_STATIC_WS_BYTES are rejected with HP_ERR_WORKSPACE before
+ * anything is enqueued.  The array keeps what the last call left in it; the call clears the list
+ * counters it needs with one small kernel of its own (four or more launches on `stream`, no
+ * memset).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two
+ * streams, two threads) race and give undefined results; order them on one stream or with events. */
+enum { HP_STATIC_WS_BYTES = 8 << 20 };
+int hp_postprocess_static(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                          const hp_skeleton *skel, const hp_params *prm,
+                          float *cm_hi, float *paf_hi,
+                          const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns,
+                          const hp_poses *poses, int32_t *status, void *stream);
+
 /* Pre-processing (Section 2.2.1, operator 2: decoded images are resized and switched to the
  * channel-first layout the network expects; Section 2.2 names "resizing and data layout
  * switching").  src: device uint8 [N][Hs][Ws][C], interleaved channels, C = 1..4; dst: device

@@ -17,7 +17,7 @@ HP_F32, HP_F16 = 0, 1
 STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
-           "hp_postprocess", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_pp_decode", "hp_cf_decode", "hp_cf_field", "hp_cf_workspace_bytes", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
+           "hp_postprocess", "hp_postprocess_static", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_pp_decode", "hp_cf_decode", "hp_cf_field", "hp_cf_workspace_bytes", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
            "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
@@ -125,6 +125,10 @@ def lib():
         L.hp_postprocess.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
                                      POINTER(_Params), c_void_p, c_void_p, POINTER(_Peaks), POINTER(_Pairs),
                                      POINTER(_Pairs), POINTER(_Poses), c_void_p, c_size_t, c_void_p, c_void_p]
+        L.hp_postprocess_static.restype = c_int
+        L.hp_postprocess_static.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, POINTER(_Skeleton),
+                                            POINTER(_Params), c_void_p, c_void_p, POINTER(_Peaks), POINTER(_Pairs),
+                                            POINTER(_Pairs), POINTER(_Poses), c_void_p, c_void_p]
         L.hp_preprocess.restype = c_int
         L.hp_preprocess.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int,
                                     POINTER(c_float), POINTER(c_float), c_void_p]
@@ -367,6 +371,20 @@ def hp_postprocess(cm_lo, paf_lo, skel, prm, buf, cm_hi=None, paf_hi=None):
                                 ctypes.byref(buf.peaks), ctypes.byref(buf.cands), ctypes.byref(buf.conns),
                                 ctypes.byref(buf.poses), wsp, wsb, _dev(buf.status), _stream()),
            "hp_postprocess")
+
+
+def hp_postprocess_static(cm_lo, paf_lo, skel, prm, buf, cm_hi=None, paf_hi=None):
+    """hp_postprocess on the library's own fixed workspace (buf's outputs are used, its workspace is not)."""
+    N, C_cm, h, w = cm_lo.shape
+    if cm_lo.dtype != paf_lo.dtype:
+        raise TypeError("cm_lo and paf_lo must share a dtype")
+    _check(lib().hp_postprocess_static(_dev(cm_lo), _dev(paf_lo), _dtype_code(cm_lo), N, h, w,
+                                       ctypes.byref(skel.c), ctypes.byref(prm.c),
+                                       _dev(cm_hi, torch.float32) if cm_hi is not None else None,
+                                       _dev(paf_hi, torch.float32) if paf_hi is not None else None,
+                                       ctypes.byref(buf.peaks), ctypes.byref(buf.cands), ctypes.byref(buf.conns),
+                                       ctypes.byref(buf.poses), _dev(buf.status), _stream()),
+           "hp_postprocess_static")
 
 
 def hp_preprocess(images, Hd, Wd, alpha, beta, reverse_channels=False, out=None, dtype=torch.float32):

@@ -267,6 +267,58 @@ int hp_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, in
 
 }  // extern "C"
 
+// Workspace of hp_postprocess_static: a fixed array in the library's device image.  Each GPU that
+// loads the library holds its own copy at its own address until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; the address it returns, looked up
+// once per device with that device current, is what kernels and launchers are given.
+static __device__ __align__(256) unsigned char scratch[HP_STATIC_WS_BYTES];
+
+namespace hp {
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];       // per device, null until the first call there
+
+static int static_workspace(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return HP_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return HP_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HP_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return HP_OK;
+}
+
+}  // namespace hp
+
+extern "C" int hp_postprocess_static(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w,
+                                     const hp_skeleton *skel, const hp_params *prm, float *cm_hi, float *paf_hi,
+                                     const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns,
+                                     const hp_poses *poses, int32_t *status, void *stream)
+{
+    // everything hp_postprocess checks, against a stand-in workspace address that is never used
+    HP_TRY(hp::postprocess(cm_lo, paf_lo, dt, N, N, h, w, skel, prm, cm_hi, paf_hi, peaks, cands, conns, poses,
+                           (void *)(uintptr_t)256, (size_t)-1, status, stream, true));
+    Workspace ws;
+    if (!layout(nullptr, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws)) return HP_ERR_INVALID_ARG;
+    if (ws.bytes > (size_t)HP_STATIC_WS_BYTES) return HP_ERR_WORKSPACE;
+    void *base = nullptr;
+    HP_TRY(static_workspace(&base));
+    layout(base, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws);
+    // the array keeps the last call's contents and its layout follows the sizes, so the append
+    // counters of this call may lie where an earlier call staged its lists: cleared by a kernel
+    // (not a memset node: the call may be recorded into a graph)
+    HP_LAUNCH(HP_K_INIT, launch_init(ws.peak_ctr, N * skel->n_parts * kCtrStride, ws.cand_ctr,
+                                     N * skel->n_limbs * kCtrStride, nullptr, (hipStream_t)stream));
+    return hp::postprocess(cm_lo, paf_lo, dt, N, N, h, w, skel, prm, cm_hi, paf_hi, peaks, cands, conns, poses, base,
+                           (size_t)HP_STATIC_WS_BYTES, status, stream, false);
+}
+
 // The operator on the first N images of buffers laid out for N_layout >= N images: every per-image
 // region of the workspace sits where a call on N_layout images puts it, so calls with different N
 // can share one workspace without clearing it in between (each call leaves its counters at zero).

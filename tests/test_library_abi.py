@@ -121,6 +121,29 @@ def test_postprocess_rejects_bad_calls(L):
     assert L.hp_postprocess(*args(pk=huge)) == -5
 
 
+def test_postprocess_static_rejects_on_the_host(L):
+    """The entry point that allocates nothing: what hp_postprocess rejects it rejects, and sizes whose
+    workspace does not fit its fixed array are refused before any GPU call is made."""
+    from paper_2108_11826_amd import binding as B
+    sk, prm, pk, cd, cn, ps = descriptors()
+    args = lambda **kw: [kw.get("cm", FAKE), FAKE, kw.get("dt", 0), kw.get("N", 1), 4, 4, byref(sk.c),
+                         byref(kw.get("prm", prm).c), kw.get("cm_hi", None), None,
+                         byref(kw.get("pk", pk)), byref(kw.get("cd", cd)), byref(kw.get("cn", cn)), byref(ps),
+                         kw.get("status", FAKE), None]
+    assert L.hp_postprocess_static(*args(cm=None)) == -1
+    assert L.hp_postprocess_static(*args(status=None)) == -1
+    assert L.hp_postprocess_static(*args(dt=3)) == -2
+    assert L.hp_postprocess_static(*args(cm_hi=FAKE)) == -1
+    assert L.hp_postprocess_static(*args(prm=B.Params(scale=4))) == -5
+    assert L.hp_postprocess_static(*args(pk=B._Peaks(FAKE, FAKE, FAKE, FAKE, 1 << 20))) == -5
+    # 64 images x 2 limbs x 2^16 candidates of staging alone is 64 MiB: beyond the 8 MiB array
+    big = B._Pairs(FAKE, FAKE, FAKE, FAKE, 1 << 16)
+    assert L.hp_workspace_bytes(64, 3, 2, 4, 4, 8, 64, 1 << 16, 16) > 8 << 20
+    assert L.hp_postprocess_static(*args(N=64, cd=big)) == -3
+    src = open(os.path.join(ROOT, "include", "hp.h")).read()
+    assert re.search(r"HP_STATIC_WS_BYTES\s*=\s*8\s*<<\s*20", src)
+
+
 def test_staged_calls_reject_bad_calls(L):
     sk, prm, pk, cd, cn, ps = descriptors()
     ws = L.hp_workspace_bytes(1, 3, 2, 4, 4, 8, 64, 64, 16)
