@@ -50,11 +50,44 @@ def build(force=False):
                    "-shared", "-Wall", "-Wextra", *extra, _SRC, _SRC_PRE, _SRC_DRAW, _SRC_SMOOTH, _SRC_REFINE, _SRC_PP, _SRC_CF, "-o", so, "-lm"]
             subprocess.check_call(cmd)
         out.append(so)
+    build_cf_libm(force)
     return out
 
 
+def build_cf_libm(force=False):
+    """The composite-field oracle alone, compiled with the C library's exponential in place of rule C0's fixed
+    arithmetic (-DHPC_LIBM_EXP): a checker of the oracle, used by tests/test_oracle_cf.py only."""
+    so = os.path.join(_HERE, "libhp_oracle_cf_libmexp.so")
+    if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(_SRC_CF):
+        subprocess.check_call(["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-Wall",
+                               "-Wextra", "-DHPC_LIBM_EXP", _SRC_CF, "-o", so, "-lm"])
+    return so
+
+
 _lib = None
+_lib_cf_libm = None
 _lock = threading.Lock()
+
+
+def _declare_cf(L):
+    i32p, f32p, ci, cf = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.c_float
+    L.hpc_expneg.restype = cf
+    L.hpc_expneg.argtypes = [cf]
+    L.hpc_field.restype = None
+    L.hpc_field.argtypes = [f32p, ci, ci, ci, cf, f32p]
+    L.hpc_decode.restype = ci
+    L.hpc_decode.argtypes = [f32p, f32p, ci, ci, i32p, i32p, ci, ci, ci, cf, cf, cf, cf, cf, ci, ci,
+                             i32p, f32p, i32p, i32p, f32p, f32p, i32p, f32p, i32p, f32p, i32p]
+
+
+def lib_cf_libm():
+    global _lib_cf_libm
+    with _lock:
+        if _lib_cf_libm is None:
+            L = ctypes.CDLL(build_cf_libm())
+            _declare_cf(L)
+            _lib_cf_libm = L
+    return _lib_cf_libm
 
 
 def lib():
@@ -105,13 +138,7 @@ def lib():
         L.hpv_in_disc.argtypes = [ci] * 5
         L.hpv_draw.restype = None
         L.hpv_draw.argtypes = [u8p, u8p, ci, ci, ci, ci, ci, ci, ci, i32p, i32p, i32p, i32p, ci, i32p, ci, u8p, u8p, ci, ci]
-        L.hpc_expneg.restype = cf
-        L.hpc_expneg.argtypes = [cf]
-        L.hpc_field.restype = None
-        L.hpc_field.argtypes = [f32p, ci, ci, ci, cf, f32p]
-        L.hpc_decode.restype = ci
-        L.hpc_decode.argtypes = [f32p, f32p, ci, ci, i32p, i32p, ci, ci, ci, cf, cf, cf, cf, cf, ci, ci,
-                                 i32p, f32p, i32p, i32p, f32p, f32p, i32p, f32p, i32p, f32p, i32p]
+        _declare_cf(L)
         _lib = L
     return _lib
 
@@ -216,7 +243,8 @@ def cf_field(pif_k, stride, pif_thr):
     return out
 
 
-def cf_decode(pif, paf, limb_a, limb_b, stride, pif_thr, paf_thr, seed_thr, grow_thr, rev_tol, min_parts, pcap=64):
+def cf_decode(pif, paf, limb_a, limb_b, stride, pif_thr, paf_thr, seed_thr, grow_thr, rev_tol, min_parts, pcap=64,
+              libm_exp=False):
     """Composite-field decoding of a batch (C1-C8): pif [N, K, 5, Fh, Fw], paf [N, L, 7, Fh, Fw].
     Returns {"pif": [n][k] -> (cell, value), "paf": [n][l] -> (cell, F1, F2), "poses": [n] -> (xyv [m, K, 3], nparts,
     score), "overflow": [n]}."""
@@ -226,6 +254,7 @@ def cf_decode(pif, paf, limb_a, limb_b, stride, pif_thr, paf_thr, seed_thr, grow
     la, lb = np.ascontiguousarray(limb_a, np.int32), np.ascontiguousarray(limb_b, np.int32)
     cells = Fh * Fw
     out = {"pif": [], "paf": [], "poses": [], "overflow": []}
+    dec = (lib_cf_libm() if libm_exp else lib()).hpc_decode      # libm_exp: the test-only build, see build_cf_libm
 
     def one(n):
         pc, pv, pn = np.zeros((K, cells), np.int32), np.zeros((K, cells), np.float32), np.zeros(K, np.int32)
@@ -234,7 +263,7 @@ def cf_decode(pif, paf, limb_a, limb_b, stride, pif_thr, paf_thr, seed_thr, grow
         xyv, npt, sc = np.zeros((pcap, K, 3), np.float32), np.zeros(pcap, np.int32), np.zeros(pcap, np.float32)
         ovf = np.zeros(1, np.int32)
         a, b = np.ascontiguousarray(pif[n]), np.ascontiguousarray(paf[n])
-        m = lib().hpc_decode(_f32(a), _f32(b), K, L, _i32(la), _i32(lb), Fh, Fw, int(stride), float(pif_thr),
+        m = dec(_f32(a), _f32(b), K, L, _i32(la), _i32(lb), Fh, Fw, int(stride), float(pif_thr),
                              float(paf_thr), float(seed_thr), float(grow_thr), float(rev_tol), int(min_parts), int(pcap),
                              _i32(pc), _f32(pv), _i32(pn), _i32(ac), _f32(f1), _f32(f2), _i32(an), _f32(xyv), _i32(npt),
                              _f32(sc), _i32(ovf))

@@ -73,6 +73,16 @@
 #include <string.h>
 
 /* C0 */
+#ifdef HPC_LIBM_EXP
+/* Test-only build (tests/test_oracle_cf.py): the C library's exponential in place of the fixed
+ * arithmetic of C0, everything else unchanged.  Decoding with it must find the same cells, seeds
+ * and persons: which routine evaluates the exponential may move values in the last digits and
+ * nothing else. */
+float hpc_expneg(float t)
+{
+    return expf(-fmaxf(fminf(t, 80.0f), 0.0f));
+}
+#else
 float hpc_expneg(float t)
 {
     const float tc = fmaxf(fminf(t, 80.0f), 0.0f);
@@ -88,6 +98,7 @@ float hpc_expneg(float t)
     p = fmaf(p, z, 1.0f);
     return ldexpf(p, -(int)n);
 }
+#endif
 
 static int hpc_on_map(float X, float Y, int H, int W)
 {
