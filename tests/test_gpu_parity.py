@@ -94,11 +94,25 @@ def check_all(buf, ora):
     assert_poses_equal(buf.host_poses()[0], ora["poses"])
 
 
-@pytest.mark.parametrize("cfg", SMALL + [CONFIGS[0], CONFIGS[1]], ids=lambda c: f"syn{c.index}")
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"syn{c.index}")
 def test_staged_calls_match_oracle(cfg):
     b = generate(cfg)
     ora = run_oracle(b, DEFAULT_PARAMS)
     buf, st = run_staged(b, ora)
+    assert st == [0, 0, 0]
+    check_all(buf, ora)
+
+
+@pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
+def test_staged_calls_full_configs(ci):
+    """hp_resize -> hp_find_peaks -> hp_score_limbs -> hp_assemble on the five workloads at full size, with the
+    capacities the benchmark times: the strip peak search on the materialised maps, the general scorer gathering from
+    them, both matching kernels (lists of workloads 3 and 4 sort outside LDS) and the assembly, every list against the
+    oracle."""
+    print(f"staged route, config {ci}", flush=True)
+    b = generate(CONFIGS[ci])
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    buf, st = run_staged(b, ora, caps=BENCH_CAPS[ci])
     assert st == [0, 0, 0]
     check_all(buf, ora)
 
@@ -309,10 +323,15 @@ PARAM_CASES = [
     dict(n_samples=10, min_valid_ratio=0.8, min_parts=1),
     dict(n_samples=10, min_valid_ratio=0.8, min_parts=19),
 ]
+# with a validity threshold of -0.5 nearly every pair of positive mean is a candidate (6 000 per limb here): more than
+# the one-launch limb kernel is built for (1024), so that corner runs through the general kernels only
+PARAM_LEGS = [(kw, large) for kw in PARAM_CASES for large in (False, True)
+              if large or kw.get("paf_thr", 0.05) >= 0.0]
 
 
-@pytest.mark.parametrize("large_caps", [False, True], ids=["one_launch", "general"])
-@pytest.mark.parametrize("kw", PARAM_CASES, ids=lambda k: "-".join(f"{a}{b}" for a, b in k.items()))
+@pytest.mark.parametrize("kw,large_caps", PARAM_LEGS,
+                         ids=lambda v: ("general" if v else "one_launch") if isinstance(v, bool)
+                         else "-".join(f"{a}{b}" for a, b in v.items()))
 def test_postprocess_parameter_corners(kw, large_caps):
     """Sample counts and validity ratios at their corners, through the one-launch limb kernel (small
     capacities) and through the general scorer with its screen (large capacities)."""
@@ -327,8 +346,7 @@ def test_postprocess_parameter_corners(kw, large_caps):
     pp = max(len(x[1]) for x in ora["poses"])
     m = hp()
     caps = (512, max(4096, cc + 8), max(64, pp + 8)) if large_caps else (max(16, pk + 8), cc + 8, max(16, pp + 8))
-    if not large_caps and (caps[0] > 256 or caps[1] > 1024):
-        pytest.skip("lists too long for the one-launch kernel")
+    assert large_caps or (caps[0] <= 256 and caps[1] <= 1024), "this leg is meant for the one-launch limb kernel"
     buf = m.Buffers(cfg.batch, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, *caps, DEV)
     prm = m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8)
     m.hp_postprocess(to_dev(b.cm), to_dev(b.paf), skel_of(sk), prm, buf)
