@@ -19,7 +19,8 @@ STATUS_PEAK_OVERFLOW, STATUS_CAND_OVERFLOW, STATUS_POSE_OVERFLOW = 1, 2, 4
 EXPORTS = ("hp_workspace_bytes", "hp_workspace_init", "hp_resize", "hp_find_peaks", "hp_score_limbs", "hp_assemble",
            "hp_postprocess", "hp_postprocess_static", "hp_preprocess", "hp_smooth", "hp_refine_peaks", "hp_pp_decode", "hp_cf_decode", "hp_cf_field", "hp_cf_workspace_bytes", "hp_draw_poses", "hp_draw_workspace_bytes", "hp_profile_begin", "hp_profile_end", "hp_kernel_name", "hp_strerror", "hp_version",
            "hp_batcher_create", "hp_batcher_destroy", "hp_batcher_acquire", "hp_batcher_commit", "hp_batcher_submit",
-           "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive")
+           "hp_batcher_flush", "hp_batcher_next", "hp_batcher_release", "hp_batch_simulate", "hp_batcher_drive",
+           "hp_bench_copy")
 HP_ERR_BUSY, HP_ERR_TIMEOUT, HP_ERR_STATE = -6, -7, -8
 HP_K_COUNT = 22
 
@@ -176,6 +177,8 @@ def lib():
         L.hp_batcher_drive.restype = c_int
         L.hp_batcher_drive.argtypes = [c_void_p, c_int, c_int64, c_int, c_void_p, c_void_p, c_int,
                                        POINTER(c_int64), POINTER(c_int32), POINTER(c_int64)]
+        L.hp_bench_copy.restype = c_int
+        L.hp_bench_copy.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
         L.hp_profile_begin.restype = c_int
         L.hp_profile_begin.argtypes = [c_int]
         L.hp_profile_end.restype = c_int
@@ -196,6 +199,14 @@ def hp_strerror(code):
 
 def hp_version():
     return int(lib().hp_version())
+
+
+def hp_bench_copy(dst, src):
+    """Plain copy of one GPU tensor into another of the same size by a kernel of the library (counter calibration)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("sizes differ")
+    _check(lib().hp_bench_copy(_dev(dst), _dev(src), c_size_t(nbytes), _stream()), "hp_bench_copy")
 
 
 def hp_profile_begin(max_launches):

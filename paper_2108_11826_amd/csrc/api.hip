@@ -156,6 +156,14 @@ struct ProfScope {
         if ((expr) != hipSuccess) return HP_ERR_HIP; \
     } while (0)
 
+// The reference copy of hp_bench_copy: 16 bytes per thread and step, every byte read and written once.
+__global__ void k_copy16(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
 }  // namespace hp
 
 using namespace hp;
@@ -202,8 +210,7 @@ int hp_find_peaks(const float *cm_hi, int N, int C_cm, int K, int H, int W, floa
     ws.peak_ctr = (int32_t *)workspace;
     ws.peak_stage = (uint64_t *)((char *)workspace + ctr_bytes);
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_INIT, launch_init(ws.peak_ctr, N * K * kCtrStride, nullptr, 0, status, s));
-    HP_LAUNCH(HP_K_NMS_HI, launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, s));
+    HP_LAUNCH(HP_K_NMS_HI, launch_nms_hi(cm_hi, N, C_cm, K, H, W, thr, ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, status, s));
     HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, N * K, W, *peaks, status, s));
     return HP_OK;
 }
@@ -225,9 +232,8 @@ int hp_score_limbs(const float *paf_hi, int N, int H, int W, const hp_skeleton *
     HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
     const int K = skel->n_parts, L = skel->n_limbs;
-    HP_LAUNCH(HP_K_INIT, launch_init(ws.cand_ctr, N * L * kCtrStride, nullptr, 0, status, s));
     HP_LAUNCH(HP_K_SCORE_HI, launch_score(paf_hi, nullptr, HP_F32, N, H / HP_SCALE, W / HP_SCALE, tab, K, L, *prm, need, *peaks,
-                           ws.cand_ctr, ws.cand_stage, cands->cap, ws.ccap2, s));
+                           ws.cand_ctr, ws.cand_stage, cands->cap, ws.ccap2, status, s));
     HP_LAUNCH(HP_K_MATCH, launch_match(0, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *cands, status, s));
     return HP_OK;
 }
@@ -250,9 +256,8 @@ int hp_assemble(const hp_skeleton *skel, const hp_params *prm, int N, const hp_p
     HP_TRY(check_ws(workspace, ws_bytes, N, skel->n_parts, skel->n_limbs, peaks->cap, cands->cap, ws));
     hipStream_t s = (hipStream_t)stream;
     const int K = skel->n_parts, L = skel->n_limbs;
-    HP_LAUNCH(HP_K_INIT, launch_init(nullptr, 0, nullptr, 0, status, s));
     HP_LAUNCH(HP_K_MATCH, launch_match(2, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
-    HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
+    HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, cands, *conns, ws, *poses, status, s));
     return HP_OK;
 }
 
@@ -366,10 +371,10 @@ int hp::postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, i
     } else {
         HP_LAUNCH(HP_K_SORT_PEAKS, launch_sort_peaks(ws.peak_ctr, ws.peak_stage, peaks->cap, ws.cap2, N * K, HP_SCALE * w, *peaks, status, s));
         HP_LAUNCH(HP_K_SCORE_LO, launch_score(nullptr, paf_lo, dt, N, h, w, tab, K, L, *prm, need, *peaks, ws.cand_ctr,
-                                              ws.cand_stage, cands->cap, ws.ccap2, s));
+                                              ws.cand_stage, cands->cap, ws.ccap2, nullptr, s));
         HP_LAUNCH(HP_K_MATCH, launch_match(1, tab, N, K, L, *peaks, ws.cand_ctr, ws.cand_stage, ws.ccap2, *cands, *conns, status, s));
     }
-    HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, *conns, ws, *poses, status, s));
+    HP_LAUNCH(HP_K_ASSEMBLE, launch_assemble(tab, N, K, L, prm->min_parts, *peaks, nullptr, *conns, ws, *poses, status, s));
     return HP_OK;
 }
 
@@ -614,6 +619,20 @@ const char *hp_kernel_name(int id)
     case HP_K_CF_FIELD: return "cf_field";
     default: return "unknown";
     }
+}
+
+int hp_bench_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || bytes == 0) return HP_ERR_INVALID_ARG;
+    if ((bytes & 15) != 0 || (((uintptr_t)dst | (uintptr_t)src) & 15) != 0) return HP_ERR_INVALID_ARG;
+    const uintptr_t a = (uintptr_t)src, b = (uintptr_t)dst;
+    if (a < b + bytes && b < a + bytes) return HP_ERR_INVALID_ARG;
+    const size_t n = bytes / 16;
+    size_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(hp::k_copy16, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, (uint4 *)dst,
+                       (const uint4 *)src, n);
+    return hipGetLastError() == hipSuccess ? HP_OK : HP_ERR_HIP;
 }
 
 int hp_workspace_init(void *workspace, size_t ws_bytes, void *stream)

@@ -159,7 +159,8 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
                                                     float *wscore_all, int wcap,
                                                     int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
                                                     int32_t *pose_counts, int pcap, int32_t *status,
-                                                    int32_t *peak_ctr, int32_t *cand_ctr)
+                                                    int32_t *peak_ctr, int32_t *cand_ctr,
+                                                    const int32_t *__restrict__ ccounts, int ccap)
 {
     __shared__ int16_t pool[kPool16];
     __shared__ __align__(16) uint32_t pool32[kPool32];
@@ -170,6 +171,8 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
     // clearing them here leaves the workspace ready for the next call
     if (peak_ctr && lane < K) peak_ctr[(n * K + lane) * kCtrStride] = 0;
     if (cand_ctr && lane < L) cand_ctr[(n * L + lane) * kCtrStride] = 0;
+    // hp_assemble: the candidate lists came from an earlier call; one that needed more than its capacity is reported
+    if (ccounts && lane < L && ccounts[n * L + lane] > ccap) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
     const float *psc = pscore + (size_t)n * K * cap;
     const unsigned long long lt = (1ull << lane) - 1ull;
 
@@ -421,21 +424,23 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
 }
 
 hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,
-                           const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
-                           int32_t *status, hipStream_t s)
+                           const hp_pairs *cands, const hp_pairs &conns, const Workspace &ws,
+                           const hp_poses &poses, int32_t *status, hipStream_t s)
 {
+    const int32_t *ccounts = cands ? cands->count : nullptr;
+    const int ccap = cands ? cands->cap : 0;
     // few peaks per part: the tables of an image almost surely fit the small pools (if they do
     // not, the fold runs on the workspace tables, slower but the same)
     if (pk.cap <= 256)
         HP_KERNEL((k_assemble<kPool16Small, kPool32Small>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
                            pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
                            ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
-                           poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr);
+                           poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr, ccounts, ccap);
     else
         HP_KERNEL((k_assemble<kPool16Large, kPool32Large>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
                            pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
                            ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
-                           poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr);
+                           poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr, ccounts, ccap);
     return hipGetLastError();
 }
 

@@ -7,7 +7,7 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
-#include "hp.h"
+#include "hp_bench.h"
 
 namespace hp {
 
@@ -161,22 +161,26 @@ hipError_t launch_resize_nms(const void *lo, hp_dtype dt, int N, int K, int C_me
 
 hipError_t launch_zero(void *p, size_t bytes, hipStream_t s);
 
+// A non-null `status` is cleared by this launch.
 hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
-                         int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s);
+                         int32_t *counts, uint64_t *stage, int cap, int cap2, int32_t *status, hipStream_t s);
 
 // `ctr` are the strided append counters; the dense counts go to pk.count.
 hipError_t launch_sort_peaks(int32_t *ctr, uint64_t *stage, int cap, int cap2, int planes, int W,
                              const hp_peaks &pk, int32_t *status, hipStream_t s);
 
 // PAF sampled either from hi-res fp32 maps (paf_hi != nullptr) or recomputed from lo-res.
+// A non-null `status` is cleared by this launch.
 hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
                         const LimbTable &T, int K, int L, const hp_params &prm, int need,
                         const hp_peaks &pk, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
-                        hipStream_t s);
+                        int32_t *status, hipStream_t s);
 
 // mode 0: staged candidates -> ordered candidate lists; 1: the same, then matching;
 // 2: ordered candidate lists in -> matching.  `cctr` are the strided append counters of the
-// staged candidates (modes 0 and 1 copy them to cands.count).
+// staged candidates (modes 0 and 1 copy them to cands.count).  Modes 0 and 1 set the candidate
+// overflow bit of `status`; mode 2 is the first kernel of hp_assemble: it clears the status word
+// and leaves the overflow bit to launch_assemble (which is given the candidate counts).
 hipError_t launch_match(int mode, const LimbTable &T, int N, int K, int L, const hp_peaks &pk,
                         int32_t *cctr, uint64_t *cstage, int ccap2, const hp_pairs &cands,
                         const hp_pairs &conns, int32_t *status, hipStream_t s);
@@ -189,9 +193,10 @@ hipError_t launch_limb_small(const void *paf_lo, hp_dtype dt, int N, int h, int 
                              int32_t *status, hipStream_t s);
 
 // Also clears the image's append counters, which leaves the workspace ready for the next call.
+// With `cands` given, lists longer than cands->cap set the candidate overflow bit of `status`.
 hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_parts, const hp_peaks &pk,
-                           const hp_pairs &conns, const Workspace &ws, const hp_poses &poses,
-                           int32_t *status, hipStream_t s);
+                           const hp_pairs *cands, const hp_pairs &conns, const Workspace &ws,
+                           const hp_poses &poses, int32_t *status, hipStream_t s);
 
 // Pre-processing: uint8 [N][Hs][Ws][C] -> `out_dt` [N][C][Hd][Wd]; alpha / beta are host arrays of C.
 hipError_t launch_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out_dt, void *dst, int Hd, int Wd,

@@ -190,13 +190,16 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
                                                   float paf_thr, int need, int tiles_j, int sub_tiles,
                                                   const int32_t *__restrict__ pcounts,
                                                   const int32_t *__restrict__ px, const int32_t *__restrict__ py,
-                                                  int cap, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2)
+                                                  int cap, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
+                                                  int32_t *status)
 {
     __shared__ int4 sA[kTileI];                 // x, y, PAF x bits, PAF y bits at the peak
     __shared__ int2 sB[kTileJ];                 // x, y
     __shared__ uint32_t queues[kBlock / kWave][kQueue];   // i << 16 | j_local of pairs that passed the screen
     const int tid = threadIdx.x;
     const int nl = blockIdx.y;
+    // first kernel of hp_score_limbs: it clears the status word (the ordering kernel that follows sets bits)
+    if (status && (blockIdx.x | blockIdx.y) == 0 && tid == 0) *status = 0;
     const int n = nl / L, l = nl - n * L;
     const int a = tab.a[l], b = tab.b[l];
     const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
@@ -336,7 +339,7 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
 hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
                         const LimbTable &T, int K, int L, const hp_params &prm, int need,
                         const hp_peaks &pk, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
-                        hipStream_t s)
+                        int32_t *status, hipStream_t s)
 {
     // tiles of kTileJ peaks of part b x (sub_tiles * kTileI) peaks of part a cover cap x cap pairs;
     // workgroups whose tile lies beyond the actual counts leave at once, so their number is kept
@@ -352,15 +355,15 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
     if (paf_hi)
         HP_KERNEL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
                            prm.n_samples, prm.paf_thr, need, tiles_j, sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts,
-                           cstage, ccap, ccap2);
+                           cstage, ccap, ccap2, status);
     else if (dt == HP_F16)
         HP_KERNEL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
                            (const __half *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
-                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
+                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2, status);
     else
         HP_KERNEL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
                            (const float *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
-                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2);
+                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2, status);
     return hipGetLastError();
 }
 
@@ -435,7 +438,11 @@ __global__ __launch_bounds__(kBlock) void k_match(LimbTable tab, int K, int L,
             cctr[nl * kCtrStride] = 0;        // sole reader of this list: leave it ready for the next call
         }
     }
-    if (cnt > ccap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
+    if (MODE != 2) {
+        if (cnt > ccap && threadIdx.x == 0) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
+    } else if (nl == 0 && threadIdx.x == 0) {
+        *status = 0;      // first kernel of hp_assemble; the assembly kernel reports lists beyond their capacity
+    }
     uint64_t *g = cstage + (size_t)nl * ccap2;
     const size_t co = (size_t)nl * ccap;
     const int a = tab.a[l], b = tab.b[l];

@@ -378,9 +378,12 @@ hipError_t launch_zero(void *p, size_t bytes, hipStream_t s)
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_nms_hi(const float *__restrict__ cm, int total, int C_cm, int K,
                                                    int H, int W, int tiles_x, int tiles_y, float thr,
-                                                   int32_t *counts, uint64_t *stage, int cap, int cap2)
+                                                   int32_t *counts, uint64_t *stage, int cap, int cap2,
+                                                   int32_t *status)
 {
     int g = blockIdx.x * kBlock + threadIdx.x;
+    // first kernel of hp_find_peaks: it clears the status word (the ordering kernel that follows sets bits)
+    if (status && g == 0) *status = 0;
     if (g >= total) return;
     int q = g;
     int tx = q % tiles_x; q /= tiles_x;
@@ -512,10 +515,12 @@ template <int R>
 __global__ __launch_bounds__(kWave *kStripsPerBlock) void k_nms_hi_strip(const float *__restrict__ cm, int plane0,
                                                                          int C_cm, int K, int H, int W, int W4,
                                                                          float thr, int32_t *counts, uint64_t *stage,
-                                                                         int cap, int cap2)
+                                                                         int cap, int cap2, int32_t *status)
 {
     const int lane = threadIdx.x;
     const int sx = blockIdx.x;
+    // first kernel of hp_find_peaks: it clears the status word (the ordering kernel that follows sets bits)
+    if (status && (blockIdx.x | blockIdx.y | blockIdx.z | threadIdx.y) == 0 && lane == 0) *status = 0;
     const int sy = blockIdx.y * kStripsPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.y);
     const int Y0 = sy * R;
     if (Y0 >= H) return;
@@ -530,7 +535,7 @@ __global__ __launch_bounds__(kWave *kStripsPerBlock) void k_nms_hi_strip(const f
 }
 
 hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int W, float thr,
-                         int32_t *counts, uint64_t *stage, int cap, int cap2, hipStream_t s)
+                         int32_t *counts, uint64_t *stage, int cap, int cap2, int32_t *status, hipStream_t s)
 {
     if (W % 4 == 0 && ((uintptr_t)cm_hi % 16) == 0) {
         constexpr int R = kStripRows;
@@ -543,7 +548,8 @@ hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int 
         for (long long p0 = 0; p0 < planes; p0 += 65535) {
             const long long np = planes - p0 < 65535 ? planes - p0 : 65535;
             HP_KERNEL((k_nms_hi_strip<R>), dim3(strips_x, groups_y, (unsigned)np), dim3(kWave, kStripsPerBlock), 0,
-                               s, cm_hi, (int)p0, C_cm, K, H, W, W4, thr, counts, stage, cap, cap2);
+                               s, cm_hi, (int)p0, C_cm, K, H, W, W4, thr, counts, stage, cap, cap2,
+                               p0 == 0 ? status : (int32_t *)nullptr);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
@@ -555,7 +561,7 @@ hipError_t launch_nms_hi(const float *cm_hi, int N, int C_cm, int K, int H, int 
     int total = (int)total64;
     dim3 grid((total + kBlock - 1) / kBlock), block(kBlock);
     HP_KERNEL((k_nms_hi<false>), grid, block, 0, s, cm_hi, total, C_cm, K, H, W, tiles_x, tiles_y, thr,
-                       counts, stage, cap, cap2);
+                       counts, stage, cap, cap2, status);
     return hipGetLastError();
 }
 

@@ -194,6 +194,87 @@ def test_overflow_is_reported_not_hidden():
     assert_lists_equal("connections", buf.host_conns()[0], ora["conns"])
 
 
+def is_ordered_sublist(got, want):
+    """got / want: (a, b, score) lists; every entry of got occurs in want, in want's order, at most once."""
+    rows = {(int(a), int(b), np.float32(s).view(np.uint32).item()): k for k, (a, b, s) in enumerate(zip(*want))}
+    pos = [rows.get((int(a), int(b), np.float32(s).view(np.uint32).item()), -1) for a, b, s in zip(*got)]
+    return all(p >= 0 for p in pos) and all(p < q for p, q in zip(pos, pos[1:]))
+
+
+@pytest.mark.parametrize("general", [False, True], ids=["one_launch", "general"])
+def test_what_an_overflowed_list_holds(general):
+    """A list that needed more than its capacity: the count is the requirement, the status bit is set, and the
+    `cap` entries that are stored are entries of the true list in canonical order (which ones is not specified).
+    Through the one-launch limb kernel and through the general kernels (candidate capacity beyond 1024 / peak
+    capacity beyond 256 select those)."""
+    m = hp()
+    b = generate(CONFIGS[1])
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    # peaks: capacity 8 where the workload has about 20 per part
+    cap = 8
+    buf, _, _ = run_fused(b, ora, False, caps=(cap, 2048 if general else 1024, 64))
+    assert buf.host_status() & m.STATUS_PEAK_OVERFLOW
+    lists, counts = buf.host_peaks()
+    over = 0
+    for c, want in enumerate(ora["peaks"][0]):
+        assert counts[0, c] == len(want[0])
+        assert len(lists[0][c][0]) == min(cap, len(want[0]))
+        assert is_ordered_sublist(lists[0][c], want), f"part {c}"
+        over += len(want[0]) > cap
+    assert over > 0
+    # candidates: the peaks fit, candidate capacity 2 where limbs have up to ten
+    ccap = 2
+    buf, _, _ = run_fused(b, ora, False, caps=(300 if general else 64, ccap, 64))
+    assert buf.host_status() == m.STATUS_CAND_OVERFLOW
+    assert_lists_equal("peaks", buf.host_peaks()[0], ora["peaks"])
+    lists, counts = buf.host_cands()
+    over = 0
+    for l, want in enumerate(ora["candidates"][0]):
+        assert counts[0, l] == len(want[0])
+        assert len(lists[0][l][0]) == min(ccap, len(want[0]))
+        assert is_ordered_sublist(lists[0][l], want), f"limb {l}"
+        over += len(want[0]) > ccap
+    assert over > 0
+
+
+def test_staged_calls_report_overflow_too():
+    """hp_find_peaks, hp_score_limbs and hp_assemble each overwrite the status word in their first kernel and
+    report lists beyond their capacity; hp_assemble repeats the candidate overflow it is handed."""
+    m = hp()
+    b = generate(CONFIGS[1])
+    cfg = b.config
+    sk = cfg.skeleton
+    ora = run_oracle(b, DEFAULT_PARAMS)
+    skel, prm = skel_of(sk), prm_of()
+    cm_hi, paf_hi = m.hp_resize(to_dev(b.cm)), m.hp_resize(to_dev(b.paf))
+    # peaks do not fit
+    buf = m.Buffers(1, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, 8, 256, 64, DEV)
+    buf.status.fill_(0x70)
+    m.hp_find_peaks(cm_hi, sk.n_parts, DEFAULT_PARAMS.peak_thr, buf)
+    assert buf.host_status() == m.STATUS_PEAK_OVERFLOW
+    assert np.array_equal(buf.host_peaks()[1], np.array([[len(p[0]) for p in im] for im in ora["peaks"]]))
+    # peaks fit, candidates do not
+    buf = m.Buffers(1, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, 64, 2, 64, DEV)
+    buf.status.fill_(0x70)
+    m.hp_find_peaks(cm_hi, sk.n_parts, DEFAULT_PARAMS.peak_thr, buf)
+    assert buf.host_status() == 0
+    buf.status.fill_(0x70)
+    m.hp_score_limbs(paf_hi, skel, prm, buf)
+    assert buf.host_status() == m.STATUS_CAND_OVERFLOW
+    assert np.array_equal(buf.host_cands()[1], np.array([[len(c[0]) for c in im] for im in ora["candidates"]]))
+    buf.status.fill_(0x70)
+    m.hp_assemble(skel, prm, buf)
+    assert buf.host_status() & m.STATUS_CAND_OVERFLOW and not buf.host_status() & 0x70
+    # everything fits, persons do not
+    buf = m.Buffers(1, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, 64, 256, 2, DEV)
+    m.hp_find_peaks(cm_hi, sk.n_parts, DEFAULT_PARAMS.peak_thr, buf)
+    m.hp_score_limbs(paf_hi, skel, prm, buf)
+    buf.status.fill_(0x70)
+    m.hp_assemble(skel, prm, buf)
+    assert buf.host_status() == m.STATUS_POSE_OVERFLOW
+    assert buf.host_poses()[1][0] == len(ora["poses"][0][1])
+
+
 def test_large_lists_sort_outside_lds():
     """More peaks / candidates than the in-LDS sort holds: pure noise with a permissive PAF rule."""
     from synth import Params
