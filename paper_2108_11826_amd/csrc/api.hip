@@ -97,6 +97,8 @@ static int check_dims(int N, int C, int h, int w)
     if (N <= 0 || C <= 0 || h <= 0 || w <= 0) return HP_ERR_INVALID_ARG;
     // hi-res plane keys (Y * W + X) and thread indices must fit 31 bits
     if ((long long)h * w * 64 >= (1LL << 31)) return HP_ERR_UNSUPPORTED;
+    // row offsets in the kernels are 24-bit products (row index x row length), hi-res rows included
+    if (h >= (1 << 21) || w >= (1 << 21)) return HP_ERR_UNSUPPORTED;
     if (2LL * N * C * h * w >= (1LL << 31) - 4096) return HP_ERR_UNSUPPORTED;
     return HP_OK;
 }
@@ -353,7 +355,21 @@ int hp::postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, i
     HP_TRY(check_ws(workspace, ws_bytes, N_layout, K, L, peaks->cap, cands->cap, ws));
     if (check_only) return HP_OK;
     hipStream_t s = (hipStream_t)stream;
+    const int rc = enqueue_postprocess(cm_lo, paf_lo, dt, N, h, w, tab, K, L, prm, need, cm_hi, paf_hi, peaks, cands, conns,
+                                       poses, ws, status, s);
+    // a launch that failed half way leaves append counters that the kernels after it would have reset: clear them
+    // (best effort) so that the workspace is usable again without hp_workspace_init
+    if (rc == HP_ERR_HIP)
+        (void)launch_init(ws.peak_ctr, N_layout * K * kCtrStride, ws.cand_ctr, N_layout * L * kCtrStride, nullptr, s);
+    return rc;
+}
 
+// The launches of hp_postprocess, in order, on stream s.
+int hp::enqueue_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w, const LimbTable &tab,
+                            int K, int L, const hp_params *prm, int need, float *cm_hi, float *paf_hi,
+                            const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
+                            const Workspace &ws, int32_t *status, hipStream_t s)
+{
     if (cm_hi) {
         // materialising form: every CM and PAF channel is written once, in one launch
         HP_LAUNCH(HP_K_RESIZE_W, launch_resize_write(cm_lo, paf_lo, dt, cm_hi, paf_hi, N, K + 1, K + 1, 2 * L, h, w, s));

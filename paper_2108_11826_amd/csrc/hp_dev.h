@@ -251,4 +251,9 @@ int postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int N
                 const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
                 void *workspace, size_t ws_bytes, int32_t *status, void *stream, bool check_only);
 
+int enqueue_postprocess(const void *cm_lo, const void *paf_lo, hp_dtype dt, int N, int h, int w, const LimbTable &tab,
+                        int K, int L, const hp_params *prm, int need, float *cm_hi, float *paf_hi,
+                        const hp_peaks *peaks, const hp_pairs *cands, const hp_pairs *conns, const hp_poses *poses,
+                        const Workspace &ws, int32_t *status, hipStream_t s);
+
 }  // namespace hp

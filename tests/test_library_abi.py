@@ -123,6 +123,11 @@ def test_postprocess_rejects_bad_calls(L):
     assert L.hp_postprocess(*args(cn=small)) == -1
     huge = B._Peaks(FAKE, FAKE, FAKE, FAKE, 1 << 20)
     assert L.hp_postprocess(*args(pk=huge)) == -5
+    # a one-row map 2^21 nodes wide: few enough elements, but hi-res row offsets would not fit the kernels' 24-bit products
+    wide = args()
+    wide[4], wide[5] = 1, 1 << 21
+    wide[15] = 1 << 40
+    assert L.hp_postprocess(*wide) == -5
 
 
 def test_postprocess_static_rejects_on_the_host(L):
