@@ -336,11 +336,132 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
     }
 }
 
+// Scorer for short lists (capacity up to kFlatPeaks peaks per part): one workgroup per (image, limb), one lane per
+// pair, all pairs of the limb spread over the workgroup's threads.  With a few hundred pairs per limb a launch is
+// a chain of dependent memory round trips, and the tiled scorer above spends a dozen of them (screen sample, then a
+// survivor's samples one or two at a time).  Here the chain is: the peak lists; the PAF at every peak (samples 0 and
+// S-1 of all pairs that start or end there, fetched once per peak); per pair, with the exact unit vector, the
+// validity of the two end samples and of samples 1 and 2 fetched together, where nearly all unrelated pairs are
+// rejected; the remaining samples of the few pairs still alive, eight at a time; and the score proper, in sample
+// order, for the pairs that pass.  Rejection does not depend on the order in which samples are looked at, and a
+// rejected pair emits nothing: same candidates as the oracle's loop, bit for bit.
+constexpr int kFlatPeaks = 256;
+constexpr int kFlatBlock = 1024;
+
+template <typename T, bool FROM_HI>
+__global__ __launch_bounds__(kFlatBlock) void k_score_flat(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
+                                                           int h, int w, LimbTable tab, SampleT st, int K, int L, int S,
+                                                           float paf_thr, int need, const int32_t *__restrict__ pcounts,
+                                                           const int32_t *__restrict__ px, const int32_t *__restrict__ py,
+                                                           int cap, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
+                                                           int32_t *status)
+{
+    __shared__ int lxy[4][kFlatPeaks];          // xA, yA, xB, yB
+    __shared__ float lpaf[4][kFlatPeaks];       // PAF x, y at the peaks of A; x, y at the peaks of B
+    const int tid = threadIdx.x;
+    const int nl = blockIdx.x;
+    if (status && nl == 0 && tid == 0) *status = 0;
+    const int n = nl / L, l = nl - n * L;
+    const int a = tab.a[l], b = tab.b[l];
+    const int nA = max(min(pcounts[n * K + a], cap), 0), nB = max(min(pcounts[n * K + b], cap), 0);
+    const int H = 8 * h, W = 8 * w;
+    const float *hx = FROM_HI ? paf_hi + ((size_t)n * 2 * L + 2 * l) * (size_t)H * W : nullptr;
+    const float *hy = FROM_HI ? hx + (size_t)H * W : nullptr;
+    const T *lx = FROM_HI ? nullptr : paf_lo + ((size_t)n * 2 * L + 2 * l) * (size_t)h * w;
+    const T *ly = FROM_HI ? nullptr : lx + (size_t)h * w;
+    {
+        // threads [0, 256) bring in list A, [256, 512) list B, each peak with the PAF at its pixel
+        const int half = tid >> 8, t = tid & (kFlatPeaks - 1);
+        if (half < 2 && t < (half == 0 ? nA : nB)) {
+            const size_t o = (size_t)(n * K + (half == 0 ? a : b)) * cap + t;
+            const int x = px[o], y = py[o];
+            lxy[2 * half][t] = x;
+            lxy[2 * half + 1][t] = y;
+            float vx, vy;
+            paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, min(max(y, 0), H - 1), min(max(x, 0), W - 1), vx, vy);
+            lpaf[2 * half][t] = vx;
+            lpaf[2 * half + 1][t] = vy;
+        }
+    }
+    __syncthreads();
+    const int P = nA * nB, max_bad = S - need;
+    for (int p = tid; p < P; p += kFlatBlock) {
+        const int i = p / nB, j = p - i * nB;
+        const int xA = lxy[0][i], yA = lxy[1][i], xB = lxy[2][j], yB = lxy[3][j];
+        const int dx = xB - xA, dy = yB - yA;
+        if (dx == 0 && dy == 0) continue;
+        const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)xA, fy0 = (float)yA;
+        const float norm = sqrtf((float)(dx * dx + dy * dy));
+        const float ux = fdx / norm, uy = fdy / norm;
+        // samples 0 and S-1 lie on the two peaks (t = 0 and t = 1 round to them exactly)
+        const float d_first = __fmaf_rn(lpaf[1][i], uy, lpaf[0][i] * ux), d_last = __fmaf_rn(lpaf[3][j], uy, lpaf[2][j] * ux);
+        int bad = (d_first > paf_thr ? 0 : 1) + (d_last > paf_thr ? 0 : 1);
+        auto project = [&](int k) {
+            // the clamp only guards against peak lists that were not produced by this library
+            const float t = st.t[k];
+            const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
+            const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
+            float vx, vy;
+            paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, vx, vy);
+            return __fmaf_rn(vy, uy, vx * ux);
+        };
+        // A pair that is still alive at the end has had every sample looked at, so its sum can be formed on the
+        // way, in sample order: d_0, then the interior samples ascending, d_{S-1} last.
+        float acc = 0.0f + d_first;
+        if (bad <= max_bad && S > 2) {
+            const float d1 = project(1), d2 = S > 3 ? project(2) : 0.0f;      // fetched together
+            bad += d1 > paf_thr ? 0 : 1;
+            acc = acc + d1;
+            if (S > 3) {
+                bad += d2 > paf_thr ? 0 : 1;
+                acc = acc + d2;
+            }
+        }
+        for (int k0 = 3; k0 < S - 1 && bad <= max_bad; k0 += 8) {
+            float d[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) d[q] = project(min(k0 + q, S - 2));
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (k0 + q < S - 1) {
+                    bad += d[q] > paf_thr ? 0 : 1;
+                    acc = acc + d[q];
+                }
+            }
+        }
+        if (bad > max_bad) continue;
+        acc = acc + d_last;
+        const float score = acc / (float)S;
+        if (score > 0.0f) {
+            const int slot = atomicAdd(&ccounts[nl * kCtrStride], 1);
+            if (slot < ccap)
+                cstage[(size_t)nl * ccap2 + slot] =
+                    ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+        }
+    }
+}
+
 hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, int N, int h, int w,
                         const LimbTable &T, int K, int L, const hp_params &prm, int need,
                         const hp_peaks &pk, int32_t *ccounts, uint64_t *cstage, int ccap, int ccap2,
                         int32_t *status, hipStream_t s)
 {
+    SampleT st;
+    for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
+    if (pk.cap <= kFlatPeaks) {
+        auto go = [&](auto kernel, const float *hi, auto lo) {
+            HP_KERNEL(kernel, dim3(N * L), dim3(kFlatBlock), 0, s, hi, lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr,
+                      need, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2, status);
+        };
+        const float *none = nullptr;
+        if (paf_hi)
+            go(k_score_flat<float, true>, paf_hi, none);
+        else if (dt == HP_F16)
+            go(k_score_flat<__half, false>, none, (const __half *)paf_lo);
+        else
+            go(k_score_flat<float, false>, none, (const float *)paf_lo);
+        return hipGetLastError();
+    }
     // tiles of kTileJ peaks of part b x (sub_tiles * kTileI) peaks of part a cover cap x cap pairs;
     // workgroups whose tile lies beyond the actual counts leave at once, so their number is kept
     // moderate by letting a workgroup walk over several tiles of part a
@@ -350,8 +471,6 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
     if (sub_tiles < 1) sub_tiles = 1;
     const int tiles = ((tiles_i + sub_tiles - 1) / sub_tiles) * tiles_j;
     dim3 grid(tiles, N * L), block(kBlock);
-    SampleT st;
-    for (int k = 0; k < HP_MAX_SAMPLES; ++k) st.t[k] = (float)k / (float)(prm.n_samples - 1);
     if (paf_hi)
         HP_KERNEL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
                            prm.n_samples, prm.paf_thr, need, tiles_j, sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts,

@@ -406,16 +406,16 @@ PARAM_CASES = [
 ]
 # with a validity threshold of -0.5 nearly every pair of positive mean is a candidate (6 000 per limb here): more than
 # the one-launch limb kernel is built for (1024), so that corner runs through the general kernels only
-PARAM_LEGS = [(kw, large) for kw in PARAM_CASES for large in (False, True)
-              if large or kw.get("paf_thr", 0.05) >= 0.0]
+PARAM_LEGS = [(kw, path) for kw in PARAM_CASES for path in ("one_launch", "short_lists", "general")
+              if path != "one_launch" or kw.get("paf_thr", 0.05) >= 0.0]
 
 
-@pytest.mark.parametrize("kw,large_caps", PARAM_LEGS,
-                         ids=lambda v: ("general" if v else "one_launch") if isinstance(v, bool)
-                         else "-".join(f"{a}{b}" for a, b in v.items()))
-def test_postprocess_parameter_corners(kw, large_caps):
-    """Sample counts and validity ratios at their corners, through the one-launch limb kernel (small
-    capacities) and through the general scorer with its screen (large capacities)."""
+@pytest.mark.parametrize("kw,path", PARAM_LEGS,
+                         ids=lambda v: v if isinstance(v, str) else "-".join(f"{a}{b}" for a, b in v.items()))
+def test_postprocess_parameter_corners(kw, path):
+    """Sample counts and validity ratios at their corners, through the one-launch limb kernel (small capacities),
+    through the scorer for short lists (few peaks, many candidates allowed) and through the tiled scorer with its
+    screen (large capacities)."""
     from synth import Params
     cfg = SynthConfig(30, COCO18, 2, 24, 31, 5, noise_sd=0.03, dropout=0.1, n_spurious=6)
     b = generate(cfg)
@@ -426,8 +426,11 @@ def test_postprocess_parameter_corners(kw, large_caps):
     cc = max(len(x[0]) for im in ora["candidates"] for x in im)
     pp = max(len(x[1]) for x in ora["poses"])
     m = hp()
-    caps = (512, max(4096, cc + 8), max(64, pp + 8)) if large_caps else (max(16, pk + 8), cc + 8, max(16, pp + 8))
-    assert large_caps or (caps[0] <= 256 and caps[1] <= 1024), "this leg is meant for the one-launch limb kernel"
+    caps = {"general": (512, max(4096, cc + 8), max(64, pp + 8)),
+            "short_lists": (max(16, pk + 8), max(2048, cc + 8), max(16, pp + 8)),
+            "one_launch": (max(16, pk + 8), cc + 8, max(16, pp + 8))}[path]
+    assert path == "general" or caps[0] <= 256
+    assert path != "one_launch" or caps[1] <= 1024, "this leg is meant for the one-launch limb kernel"
     buf = m.Buffers(cfg.batch, sk.n_parts, sk.n_limbs, cfg.h, cfg.w, *caps, DEV)
     prm = m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8)
     m.hp_postprocess(to_dev(b.cm), to_dev(b.paf), skel_of(sk), prm, buf)
