@@ -6,12 +6,8 @@
 
 namespace hp {
 
-// How many PAF samples a full score fetches together (first, then `rest` at a time); a pair
-// dies at its (S - need + 1)-th bad sample, three with the usual parameters, and a wavefront
-// keeps going while any lane lives.  Few pairs, one launch (latency matters): 4 samples, then
-// the rest 8 at a time.  Survivors of the general scorer's screen: two at a time, which keeps
-// the register count low enough for eight wavefronts per SIMD.
-struct ChunksLatency { static constexpr int first = 4, singles = 0, rest = 8; };
+// How many PAF samples a full score of the tiled scorer fetches together (first, then `rest` at a time) for a
+// survivor of its screen: two at a time, which keeps the register count low enough for eight wavefronts per SIMD.
 struct ChunksSurvivor { static constexpr int first = 2, singles = 0, rest = 2; };
 constexpr int kRankSort = 256; // lists up to this length are ordered by counting ranks through LDS
 
@@ -184,6 +180,62 @@ __device__ __forceinline__ void paf_at(const float *hx, const float *hy, const T
     }
 }
 
+// Scores the candidate from peak A to peak B when the PAF at the two peaks is already known (pA, pB: samples 0 and
+// S-1 lie on the peaks, since t = 0 and t = 1 round to them exactly, so they are fetched once per peak and limb, not
+// once per pair).  Validity is taken in the order 0, S-1, then samples 1 and 2 fetched together, then the rest eight
+// at a time; the pair leaves as soon as it has more than max_bad invalid samples.  Rejection does not depend on
+// that order, and a pair that is still alive at the end has had every sample looked at, so its sum is formed on the
+// way in sample order: d_0, the interior samples ascending, d_{S-1} last.  Returns whether the pair is accepted.
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ bool score_pair_ends(int xA, int yA, int xB, int yB, float pAx, float pAy, float pBx, float pBy,
+                                                int S, const SampleT &st, float paf_thr, int max_bad, int H, int W, int h,
+                                                int w, const float *hx, const float *hy, const T *lx, const T *ly,
+                                                float &score)
+{
+    const int dx = xB - xA, dy = yB - yA;
+    if (dx == 0 && dy == 0) return false;
+    const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)xA, fy0 = (float)yA;
+    const float norm = sqrtf((float)(dx * dx + dy * dy));
+    const float ux = fdx / norm, uy = fdy / norm;
+    const float d_first = __fmaf_rn(pAy, uy, pAx * ux), d_last = __fmaf_rn(pBy, uy, pBx * ux);
+    int bad = (d_first > paf_thr ? 0 : 1) + (d_last > paf_thr ? 0 : 1);
+    auto project = [&](int k) {
+        // the clamp only guards against peak lists that were not produced by this library
+        const float t = st.t[k];
+        const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
+        const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
+        float vx, vy;
+        paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, vx, vy);
+        return __fmaf_rn(vy, uy, vx * ux);
+    };
+    float acc = 0.0f + d_first;
+    if (bad <= max_bad && S > 2) {
+        const float d1 = project(1), d2 = S > 3 ? project(2) : 0.0f;      // fetched together
+        bad += d1 > paf_thr ? 0 : 1;
+        acc = acc + d1;
+        if (S > 3) {
+            bad += d2 > paf_thr ? 0 : 1;
+            acc = acc + d2;
+        }
+    }
+    for (int k0 = 3; k0 < S - 1 && bad <= max_bad; k0 += 8) {
+        float d[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) d[q] = project(min(k0 + q, S - 2));
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (k0 + q < S - 1) {
+                bad += d[q] > paf_thr ? 0 : 1;
+                acc = acc + d[q];
+            }
+        }
+    }
+    if (bad > max_bad) return false;
+    acc = acc + d_last;
+    score = acc / (float)S;
+    return score > 0.0f;
+}
+
 template <typename T, bool FROM_HI>
 __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
                                                   int h, int w, LimbTable tab, SampleT st, int K, int L, int S,
@@ -339,12 +391,8 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
 // Scorer for short lists (capacity up to kFlatPeaks peaks per part): one workgroup per (image, limb), one lane per
 // pair, all pairs of the limb spread over the workgroup's threads.  With a few hundred pairs per limb a launch is
 // a chain of dependent memory round trips, and the tiled scorer above spends a dozen of them (screen sample, then a
-// survivor's samples one or two at a time).  Here the chain is: the peak lists; the PAF at every peak (samples 0 and
-// S-1 of all pairs that start or end there, fetched once per peak); per pair, with the exact unit vector, the
-// validity of the two end samples and of samples 1 and 2 fetched together, where nearly all unrelated pairs are
-// rejected; the remaining samples of the few pairs still alive, eight at a time; and the score proper, in sample
-// order, for the pairs that pass.  Rejection does not depend on the order in which samples are looked at, and a
-// rejected pair emits nothing: same candidates as the oracle's loop, bit for bit.
+// survivor's samples one or two at a time).  Here the chain is: the peak lists; the PAF at every peak; the pairs
+// through score_pair_ends (two fetch rounds for nearly all of them).  Same candidates as the oracle's loop, bit for bit.
 constexpr int kFlatPeaks = 256;
 constexpr int kFlatBlock = 1024;
 
@@ -387,52 +435,9 @@ __global__ __launch_bounds__(kFlatBlock) void k_score_flat(const float *__restri
     const int P = nA * nB, max_bad = S - need;
     for (int p = tid; p < P; p += kFlatBlock) {
         const int i = p / nB, j = p - i * nB;
-        const int xA = lxy[0][i], yA = lxy[1][i], xB = lxy[2][j], yB = lxy[3][j];
-        const int dx = xB - xA, dy = yB - yA;
-        if (dx == 0 && dy == 0) continue;
-        const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)xA, fy0 = (float)yA;
-        const float norm = sqrtf((float)(dx * dx + dy * dy));
-        const float ux = fdx / norm, uy = fdy / norm;
-        // samples 0 and S-1 lie on the two peaks (t = 0 and t = 1 round to them exactly)
-        const float d_first = __fmaf_rn(lpaf[1][i], uy, lpaf[0][i] * ux), d_last = __fmaf_rn(lpaf[3][j], uy, lpaf[2][j] * ux);
-        int bad = (d_first > paf_thr ? 0 : 1) + (d_last > paf_thr ? 0 : 1);
-        auto project = [&](int k) {
-            // the clamp only guards against peak lists that were not produced by this library
-            const float t = st.t[k];
-            const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
-            const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
-            float vx, vy;
-            paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, vx, vy);
-            return __fmaf_rn(vy, uy, vx * ux);
-        };
-        // A pair that is still alive at the end has had every sample looked at, so its sum can be formed on the
-        // way, in sample order: d_0, then the interior samples ascending, d_{S-1} last.
-        float acc = 0.0f + d_first;
-        if (bad <= max_bad && S > 2) {
-            const float d1 = project(1), d2 = S > 3 ? project(2) : 0.0f;      // fetched together
-            bad += d1 > paf_thr ? 0 : 1;
-            acc = acc + d1;
-            if (S > 3) {
-                bad += d2 > paf_thr ? 0 : 1;
-                acc = acc + d2;
-            }
-        }
-        for (int k0 = 3; k0 < S - 1 && bad <= max_bad; k0 += 8) {
-            float d[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) d[q] = project(min(k0 + q, S - 2));
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (k0 + q < S - 1) {
-                    bad += d[q] > paf_thr ? 0 : 1;
-                    acc = acc + d[q];
-                }
-            }
-        }
-        if (bad > max_bad) continue;
-        acc = acc + d_last;
-        const float score = acc / (float)S;
-        if (score > 0.0f) {
+        float score;
+        if (score_pair_ends<T, FROM_HI>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], lpaf[0][i], lpaf[1][i], lpaf[2][j],
+                                        lpaf[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly, score)) {
             const int slot = atomicAdd(&ccounts[nl * kCtrStride], 1);
             if (slot < ccap)
                 cstage[(size_t)nl * ccap2 + slot] =
@@ -671,6 +676,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
 {
     __shared__ uint64_t sk[kSmallCands];
     __shared__ int lxy[4][kSmallPeaks];          // xA, yA, xB, yB in rank order
+    __shared__ float lpaf[4][kSmallPeaks];       // PAF x, y at the peaks of A; x, y at the peaks of B
     __shared__ int lds_cnt;
     __shared__ uint32_t usedA[kSmallPeaks / 32], usedB[kSmallPeaks / 32];
     extern __shared__ uint32_t lds_paf[];        // the limb's two lo-res PAF planes, when they fit
@@ -764,14 +770,22 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
         const float inv_nB = 1.0f / (float)nB;
         auto score_all = [&](const T *lx, const T *ly) {
             const float *hx = nullptr, *hy = nullptr;          // the PAFs are recomputed from the lo-res planes
+            // the PAF at every peak of the two lists: samples 0 and S-1 of all pairs that start or end there
+            {
+                const int half = tid >> 8, t = tid & (kSmallPeaks - 1);
+                if (half < 2 && t < (half == 0 ? nA : nB))
+                    paf_from_lo(lx, ly, h, w, min(max(lxy[2 * half + 1][t], 0), H - 1), min(max(lxy[2 * half][t], 0), W - 1),
+                                lpaf[2 * half][t], lpaf[2 * half + 1][t]);
+            }
+            __syncthreads();
             for (int p = tid; p < P; p += kSmallBlock) {
                 int i = (int)((float)p * inv_nB);
                 int j = p - i * nB;
                 while (j < 0) { --i; j += nB; }
                 while (j >= nB) { ++i; j -= nB; }
                 float score;
-                if (score_pair<T, false, ChunksLatency>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], S, st, paf_thr, max_bad, H, W, h,
-                                                        w, hx, hy, lx, ly, score)) {
+                if (score_pair_ends<T, false>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], lpaf[0][i], lpaf[1][i], lpaf[2][j],
+                                              lpaf[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly, score)) {
                     const int slot = atomicAdd(&lds_cnt, 1);
                     if (slot < kSmallCands)
                         sk[slot] = ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
