@@ -12,10 +12,14 @@
 // connection reads is written by another one.  New persons are numbered by a prefix count in
 // connection order, as the sequential fold would.
 //
-// One wavefront works on one image.  When the image's tables fit the LDS pools (always, for
-// the workloads of interest) everything after the first gather runs out of LDS: a limb step is
-// a few dependent LDS accesses, not global-memory round trips.  Otherwise the same steps run
-// on tables in the caller's workspace.
+// One workgroup of sixteen wavefronts works on one image.  The fold itself is a chain, one step
+// per limb, and belongs to one wavefront; a single wavefront issues an instruction every four to
+// five cycles at best, so whatever does not have to sit on that chain is spread over the other
+// wavefronts: they fetch every connection with the scores of its two peaks into LDS before the
+// fold (two memory round trips, each wavefront a few limbs), and write the persons afterwards.
+// When the image's tables fit the LDS pools (always, for the workloads of interest) a limb step
+// is a few dependent LDS accesses and about a hundred instructions.  Otherwise the same steps
+// run, on one wavefront, on tables in the caller's workspace.
 #include "hp_dev.h"
 
 namespace hp {
@@ -147,52 +151,67 @@ __device__ __forceinline__ void emit_persons(const Tab &t, int n, int np, int K,
     }
 }
 
+// Orders one wavefront's memory accesses (LDS or global) across its lanes: what some lanes wrote before it, all
+// lanes see after it.  For code that a single wavefront of a workgroup runs while the others have left.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+constexpr int kAsmBlock = 1024, kAsmWaves = kAsmBlock / kWave;
+constexpr int kAsmLimbsPerWave = HP_MAX_LIMBS / kAsmWaves;      // limbs wv, wv + 16, ... of wavefront wv
+
 template <int kPool16, int kPool32>
-__global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L, int min_parts,
-                                                    const int32_t *__restrict__ pcounts,
-                                                    const float *__restrict__ pscore, int cap,
-                                                    const int32_t *__restrict__ mcounts,
-                                                    const int32_t *__restrict__ mi,
-                                                    const int32_t *__restrict__ mj,
-                                                    const float *__restrict__ ms, int mcap,
-                                                    int32_t *owner_all, int32_t *wslots_all, int32_t *wmask_all,
-                                                    float *wscore_all, int wcap,
-                                                    int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
-                                                    int32_t *pose_counts, int pcap, int32_t *status,
-                                                    int32_t *peak_ctr, int32_t *cand_ctr,
-                                                    const int32_t *__restrict__ ccounts, int ccap)
+__global__ __launch_bounds__(kAsmBlock) void k_assemble(LimbTable tab, int K, int L, int min_parts,
+                                                        const int32_t *__restrict__ pcounts,
+                                                        const float *__restrict__ pscore, int cap,
+                                                        const int32_t *__restrict__ mcounts,
+                                                        const int32_t *__restrict__ mi,
+                                                        const int32_t *__restrict__ mj,
+                                                        const float *__restrict__ ms, int mcap,
+                                                        int32_t *owner_all, int32_t *wslots_all, int32_t *wmask_all,
+                                                        float *wscore_all, int wcap,
+                                                        int32_t *pose_slots, int32_t *pose_nparts, float *pose_score,
+                                                        int32_t *pose_counts, int pcap, int32_t *status,
+                                                        int32_t *peak_ctr, int32_t *cand_ctr,
+                                                        const int32_t *__restrict__ ccounts, int ccap)
 {
     __shared__ int16_t pool[kPool16];
     __shared__ __align__(16) uint32_t pool32[kPool32];
     __shared__ int moff[HP_MAX_LIMBS + 1];
+    __shared__ int persons_made;
     const int n = blockIdx.x;
-    const int lane = threadIdx.x;
-    // last kernel of a call: every append counter of this image has been consumed by now;
-    // clearing them here leaves the workspace ready for the next call
-    if (peak_ctr && lane < K) peak_ctr[(n * K + lane) * kCtrStride] = 0;
-    if (cand_ctr && lane < L) cand_ctr[(n * L + lane) * kCtrStride] = 0;
-    // hp_assemble: the candidate lists came from an earlier call; one that needed more than its capacity is reported
-    if (ccounts && lane < L && ccounts[n * L + lane] > ccap) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (wv == 0) {
+        // last kernel of a call: every append counter of this image has been consumed by now;
+        // clearing them here leaves the workspace ready for the next call
+        if (peak_ctr && lane < K) peak_ctr[(n * K + lane) * kCtrStride] = 0;
+        if (cand_ctr && lane < L) cand_ctr[(n * L + lane) * kCtrStride] = 0;
+        // hp_assemble: the candidate lists came from an earlier call; one that needed more than its capacity is reported
+        if (ccounts && lane < L && ccounts[n * L + lane] > ccap) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
+    }
     const float *psc = pscore + (size_t)n * K * cap;
     const unsigned long long lt = (1ull << lane) - 1ull;
 
-    // The first limbs' connections are fetched before their counts are known (lane k reads entry k of each list, which
-    // exists whatever the count; entries beyond the count are never used): one memory round trip less before the fold.
-    constexpr int kGroup = 8;
-    int i0[kGroup], j0[kGroup];
-    float s0[kGroup];
+    // Round trip 1: the counts, and with them (before the counts are known) connection `lane` of each of this
+    // wavefront's limbs: entry k of a list exists whatever the count, and entries beyond the count are never used.
+    int c_i[kAsmLimbsPerWave], c_j[kAsmLimbsPerWave];
+    float c_s[kAsmLimbsPerWave];
 #pragma unroll
-    for (int u = 0; u < kGroup; ++u) {
-        i0[u] = j0[u] = 0;
-        s0[u] = 0.0f;
-        if (u < L && lane < mcap) {
-            const size_t idx = (size_t)(n * L + u) * mcap + lane;
-            i0[u] = mi[idx];
-            j0[u] = mj[idx];
-            s0[u] = ms[idx];
+    for (int q = 0; q < kAsmLimbsPerWave; ++q) {
+        const int l = wv + kAsmWaves * q;
+        c_i[q] = c_j[q] = 0;
+        c_s[q] = 0.0f;
+        if (l < L && lane < mcap) {
+            const size_t idx = (size_t)(n * L + l) * mcap + lane;
+            c_i[q] = mi[idx];
+            c_j[q] = mj[idx];
+            c_s[q] = ms[idx];
         }
     }
-    // connection counts -> offsets of each limb in the image's flat connection list
+    // connection counts -> offsets of each limb in the image's flat connection list (every wavefront for itself)
     const int mc = (lane < L) ? max(min(mcounts[n * L + lane], mcap), 0) : 0;
     int incl = mc;
     for (int d = 1; d < kWave; d <<= 1) {
@@ -200,187 +219,174 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
         if (lane >= d) incl += v;
     }
     const int tot = __shfl(incl, kWave - 1);
-    if (lane < L) moff[lane] = incl - mc;
-    if (lane == 0) moff[L] = tot;
+    const int excl = incl - mc;
     int cmax = (lane < K) ? max(min(pcounts[n * K + lane], cap), 0) : 0;
     for (int d = kWave / 2; d > 0; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d));
-    __syncthreads();
+    const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
 
     // persons never outnumber connections; one spare person, owner entry and slot row absorb the
     // stores of lanes that have nothing to write, so the fold runs without branches
     const int tot2 = (tot + 2) & ~1;              // persons incl. the spare, kept even for 8-byte alignment
-    const bool fits = (long long)K * cmax + 1 + (long long)tot2 * K <= kPool16 && 2LL * tot2 <= kPool32 &&
+    const bool fits = (long long)K * cmax + 1 + (long long)tot2 * (K + 1) <= kPool16 && 2LL * tot2 + 4LL * tot <= kPool32 &&
                       (long long)K * cmax < 65535 && tot < 32766;
     if (fits) {
-        // LDS tables: owner of each peak, person slots, person state.  What a connection brings
-        // along (its two peak ranks, its score, the scores of its two peaks) does not depend on
-        // the fold's state, so it is fetched ahead of the fold, a group of kGroup limbs at a
-        // time: lane k holds connection k of each limb of the group in registers (a limb with
-        // more than 64 connections fetches the rest when its turn comes).  The loads of the next
-        // group are issued while the current one is folded, the dependent ones (peak scores,
-        // which need the ranks) half a group later, so the fold seldom waits for memory.
-        uint2 *pst = (uint2 *)pool32;                        // [tot + 1] person: filled-part mask (0 = merged away), score
+        uint2 *pst = (uint2 *)pool32;                        // [tot2] person: filled-part mask (0 = merged away), score
+        uint32_t *rec_o = pool32 + 2 * tot2;                 // [tot] owner-table entries of the two peaks, oa << 16 | ob
+        float *rec_s = (float *)(rec_o + tot);               // [tot] connection score
+        float *rec_sa = rec_s + tot, *rec_sb = rec_sa + tot; // [tot] scores of the two peaks
         int16_t *owner = pool;                               // [K * cmax + 1] person owning each peak, -1 = none
-        int16_t *slots = owner + K * cmax + 1;               // [tot + 1][K] valid where the person's mask says so
+        int16_t *slots = owner + K * cmax + 1;               // [tot2][K] valid where the person's mask says so
+        int16_t *prank = slots + tot2 * K;                   // [tot2] place of a person in the output, -1 = dropped
         const int spare_p = tot, spare_o = K * cmax;
 
-        for (int idx = lane; idx < K * cmax; idx += kWave) owner[idx] = -1;
-        const int my_a = lane < L ? tab.a[lane] : 0, my_b = lane < L ? tab.b[lane] : 0;
-        struct Group {
-            int i[kGroup], j[kGroup];
-            float s[kGroup], sa[kGroup], sb[kGroup];
-        };
-        // ranks and score of connection `lane` of the limbs of group g
-        auto fetch_conn = [&](int g, Group &q) {
+        for (int idx = tid; idx <= K * cmax; idx += kAsmBlock) owner[idx] = -1;      // the spare entry too: it stays -1
+        // Round trip 2: the scores of the two peaks of every connection fetched above; then the records go to LDS.
+        {
+            float c_sa[kAsmLimbsPerWave], c_sb[kAsmLimbsPerWave];
 #pragma unroll
-            for (int u = 0; u < kGroup; ++u) {
-                const int l = g * kGroup + u;
-                const int cnt = l < L ? __builtin_amdgcn_readlane(mc, min(l, kWave - 1)) : 0;
-                q.i[u] = q.j[u] = 0;
-                q.s[u] = 0.0f;
-                if (lane < cnt) {
-                    const size_t idx = (size_t)(n * L + l) * mcap + lane;
-                    q.i[u] = mi[idx];
-                    q.j[u] = mj[idx];
-                    q.s[u] = ms[idx];
-                }
-            }
-        };
-        // scores of its two peaks
-        auto fetch_peak = [&](int g, Group &q) {
-#pragma unroll
-            for (int u = 0; u < kGroup; ++u) {
-                const int l = g * kGroup + u;
-                const int cnt = l < L ? __builtin_amdgcn_readlane(mc, min(l, kWave - 1)) : 0;
-                const int a = __builtin_amdgcn_readlane(my_a, min(l, kWave - 1)), b = __builtin_amdgcn_readlane(my_b, min(l, kWave - 1));
-                q.sa[u] = q.sb[u] = 0.0f;
-                if (lane < cnt) {
-                    q.sa[u] = psc[a * cap + q.i[u]];
-                    q.sb[u] = psc[b * cap + q.j[u]];
-                }
-            }
-        };
-
-        int np = 0;
-        // one connection per lane: applies connection (i, j, s) of limb (a, b) where `act`
-        auto fold = [&](bool act, int a, int b, int i, int j, float s, float sa, float sb) {
-            const uint32_t bit_a = 1u << a, bit_b = 1u << b;
-            const int oa = act ? a * cmax + i : spare_o, ob = act ? b * cmax + j : spare_o;
-            const int pa = act ? (int)owner[oa] : -1, pb = act ? (int)owner[ob] : -1;
-            const bool has_a = pa >= 0, has_b = pb >= 0;
-            const uint2 sta = pst[max(pa, 0)], stb = pst[max(pb, 0)];
-            const uint32_t ma = has_a ? sta.x : 0u, mb = has_b ? stb.x : 0u;
-            const float sca = __uint_as_float(sta.y), scb = __uint_as_float(stb.y);
-
-            const bool fresh = act && !has_a && !has_b;
-            const unsigned long long fm = __ballot(fresh);
-            const bool ext_a = has_a && !has_b && !(ma & bit_b);      // the a-side owner gains part b
-            const bool ext_b = !has_a && has_b && !(mb & bit_a);      // the b-side owner gains part a
-            const bool cyc = has_a && pa == pb;
-            const bool mrg = has_a && has_b && pa != pb && (ma & mb) == 0u;
-            const bool upd = fresh || ext_a || ext_b || cyc;
-            const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
-            const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
-            const float s0 = fresh ? sa : has_a ? sca : scb;          // running score, then the new
-            const float s1 = (fresh || ext_a) ? sb : sa;              // peak's score (if any), then s
-            const float sc = cyc ? s0 : s0 + s1;
-            const bool wa = fresh || ext_b, wb = fresh || ext_a;
-            pst[upd ? p : spare_p] = make_uint2(mk, __float_as_uint(sc + s));
-            slots[(wa ? p : spare_p) * K + a] = (int16_t)i;
-            owner[wa ? oa : spare_o] = (int16_t)p;
-            slots[(wb ? p : spare_p) * K + b] = (int16_t)j;
-            owner[wb ? ob : spare_o] = (int16_t)p;
-            if (__any(mrg)) {
-                if (mrg) {
-                    const int lo = min(pa, pb), hi = max(pa, pb);
-                    const uint32_t mhi = pa < pb ? mb : ma;
-                    for (int c = 0; c < K; ++c) {
-                        if (mhi & (1u << c)) {
-                            const int16_t rr = slots[hi * K + c];
-                            slots[lo * K + c] = rr;
-                            owner[c * cmax + rr] = (int16_t)lo;
-                        }
+            for (int q = 0; q < kAsmLimbsPerWave; ++q) {
+                const int l = wv + kAsmWaves * q;
+                c_sa[q] = c_sb[q] = 0.0f;
+                if (l < L) {
+                    const int cnt = __builtin_amdgcn_readlane(mc, l);
+                    const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
+                    if (lane < cnt) {
+                        c_sa[q] = psc[a * cap + c_i[q]];
+                        c_sb[q] = psc[b * cap + c_j[q]];
                     }
-                    const float scm = (pa < pb) ? sca + scb : scb + sca;
-                    pst[lo] = make_uint2(ma | mb, __float_as_uint(scm + s));
-                    pst[hi] = make_uint2(kDead, 0u);
                 }
             }
-            np += __popcll(fm);
-            __syncthreads();
-        };
-        // folds the limbs of group g from `cur`; issues the loads of group g + 1 into `nxt`
-        auto run_group = [&](int g, const Group &cur, Group &nxt) {
-            const bool more = (g + 1) * kGroup < L;
-            if (more) fetch_conn(g + 1, nxt);
 #pragma unroll
-            for (int u = 0; u < kGroup; ++u) {
-                const int l = g * kGroup + u;
-                if (u == kGroup / 2 && more) fetch_peak(g + 1, nxt);
+            for (int q = 0; q < kAsmLimbsPerWave; ++q) {
+                const int l = wv + kAsmWaves * q;
+                if (l < L) {
+                    const int cnt = __builtin_amdgcn_readlane(mc, l), base = __builtin_amdgcn_readlane(excl, l);
+                    const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
+                    if (lane < cnt) {
+                        rec_o[base + lane] = ((uint32_t)(a * cmax + c_i[q]) << 16) | (uint32_t)(b * cmax + c_j[q]);
+                        rec_s[base + lane] = c_s[q];
+                        rec_sa[base + lane] = c_sa[q];
+                        rec_sb[base + lane] = c_sb[q];
+                    }
+                }
+            }
+            // limbs with more than 64 connections: the rest, fetched now
+#pragma unroll
+            for (int q = 0; q < kAsmLimbsPerWave; ++q) {
+                const int l = wv + kAsmWaves * q;
                 if (l >= L) continue;
+                const int cnt = __builtin_amdgcn_readlane(mc, l), base = __builtin_amdgcn_readlane(excl, l);
+                const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
+                for (int k = kWave + lane; k < cnt; k += kWave) {
+                    const size_t idx = (size_t)(n * L + l) * mcap + k;
+                    const int i = mi[idx], j = mj[idx];
+                    rec_o[base + k] = ((uint32_t)(a * cmax + i) << 16) | (uint32_t)(b * cmax + j);
+                    rec_s[base + k] = ms[idx];
+                    rec_sa[base + k] = psc[a * cap + i];
+                    rec_sb[base + k] = psc[b * cap + j];
+                }
+            }
+        }
+        __syncthreads();                          // owner table and records are in place
+
+        if (wv == 0) {
+            int np = 0;
+            for (int l = 0; l < L; ++l) {
                 // lane l holds limb l's description; read it with uniform lane reads
                 const int a = __builtin_amdgcn_readlane(my_a, l), b = __builtin_amdgcn_readlane(my_b, l);
-                const int cnt = __builtin_amdgcn_readlane(mc, l);
-                fold(lane < cnt, a, b, cur.i[u], cur.j[u], cur.s[u], cur.sa[u], cur.sb[u]);
-                for (int k0 = kWave; k0 < cnt; k0 += kWave) {
-                    // a long limb: the rest of its connections, fetched now
-                    const int k = k0 + lane;
-                    const bool act = k < cnt;
-                    int i = 0, j = 0;
-                    float s = 0.0f, sa = 0.0f, sb = 0.0f;
-                    if (act) {
-                        const size_t idx = (size_t)(n * L + l) * mcap + k;
-                        i = mi[idx];
-                        j = mj[idx];
-                        s = ms[idx];
-                        sa = psc[a * cap + i];
-                        sb = psc[b * cap + j];
+                const int cnt = __builtin_amdgcn_readlane(mc, l), base = __builtin_amdgcn_readlane(excl, l);
+                const uint32_t bit_a = 1u << a, bit_b = 1u << b;
+                const int row_a = a * cmax, row_b = b * cmax;
+                for (int k0 = 0; k0 < cnt; k0 += kWave) {
+                    // one connection per lane, all connections of the limb at once
+                    const bool act = k0 + lane < cnt;
+                    const int o = base + (act ? k0 + lane : 0);
+                    const uint32_t oab = rec_o[o];
+                    const float s = rec_s[o], sa = rec_sa[o], sb = rec_sb[o];
+                    const int oa = act ? (int)(oab >> 16) : spare_o, ob = act ? (int)(oab & 0xffffu) : spare_o;
+                    const int pa = owner[oa], pb = owner[ob];         // the spare entry reads as -1
+                    const bool has_a = pa >= 0, has_b = pb >= 0;
+                    const uint2 sta = pst[max(pa, 0)], stb = pst[max(pb, 0)];
+                    const uint32_t ma = has_a ? sta.x : 0u, mb = has_b ? stb.x : 0u;
+                    const float sca = __uint_as_float(sta.y), scb = __uint_as_float(stb.y);
+
+                    const bool fresh = act && !has_a && !has_b;
+                    const unsigned long long fm = __ballot(fresh);
+                    const bool ext_a = has_a && !has_b && !(ma & bit_b);      // the a-side owner gains part b
+                    const bool ext_b = !has_a && has_b && !(mb & bit_a);      // the b-side owner gains part a
+                    const bool cyc = has_a && pa == pb;
+                    const bool mrg = has_a && has_b && pa != pb && (ma & mb) == 0u;
+                    const bool upd = fresh || ext_a || ext_b || cyc;
+                    const int p = fresh ? np + __popcll(fm & lt) : (has_a ? pa : pb);
+                    const uint32_t mk = fresh ? (bit_a | bit_b) : ext_a ? (ma | bit_b) : ext_b ? (mb | bit_a) : ma;
+                    const float s0 = fresh ? sa : has_a ? sca : scb;          // running score, then the new
+                    const float s1 = (fresh || ext_a) ? sb : sa;              // peak's score (if any), then s
+                    const float sc = cyc ? s0 : s0 + s1;
+                    const bool wa = fresh || ext_b, wb = fresh || ext_a;
+                    pst[upd ? p : spare_p] = make_uint2(mk, __float_as_uint(sc + s));
+                    slots[(wa ? p : spare_p) * K + a] = (int16_t)(oa - row_a);
+                    owner[wa ? oa : spare_o] = (int16_t)(wa ? p : -1);
+                    slots[(wb ? p : spare_p) * K + b] = (int16_t)(ob - row_b);
+                    owner[wb ? ob : spare_o] = (int16_t)(wb ? p : -1);
+                    if (__any(mrg)) {
+                        if (mrg) {
+                            const int lo = min(pa, pb), hi = max(pa, pb);
+                            const uint32_t mhi = pa < pb ? mb : ma;
+                            for (int c = 0; c < K; ++c) {
+                                if (mhi & (1u << c)) {
+                                    const int16_t rr = slots[hi * K + c];
+                                    slots[lo * K + c] = rr;
+                                    owner[c * cmax + rr] = (int16_t)lo;
+                                }
+                            }
+                            const float scm = (pa < pb) ? sca + scb : scb + sca;
+                            pst[lo] = make_uint2(ma | mb, __float_as_uint(scm + s));
+                            pst[hi] = make_uint2(kDead, 0u);
+                        }
                     }
-                    fold(act, a, b, i, j, s, sa, sb);
+                    np += __popcll(fm);
+                    wave_sync();                  // LDS written by some lanes is read by others in the next step
                 }
             }
-        };
-        __syncthreads();                          // owner table initialised
-        Group ga, gb;
-#pragma unroll
-        for (int u = 0; u < kGroup; ++u) {
-            const int cnt = u < L ? __builtin_amdgcn_readlane(mc, u) : 0;
-            ga.i[u] = lane < cnt ? i0[u] : 0;
-            ga.j[u] = lane < cnt ? j0[u] : 0;
-            ga.s[u] = lane < cnt ? s0[u] : 0.0f;
-        }
-        fetch_peak(0, ga);
-        for (int g = 0; g * kGroup < L; g += 2) {
-            run_group(g, ga, gb);
-            if ((g + 1) * kGroup >= L) break;
-            run_group(g + 1, gb, ga);
-        }
-
-        // alive persons with enough parts, in creation order
-        np = min(np, tot);
-        int out = 0;
-        for (int base = 0; base < np; base += kWave) {
-            const int p = base + lane;
-            const uint2 st = pst[min(p, tot)];
-            const uint32_t mk = p < np ? st.x : kDead;
-            const int parts = __popc(mk);
-            const bool keep = mk != kDead && parts >= min_parts;
-            const unsigned long long m = __ballot(keep);
-            const int rank = out + __popcll(m & lt);
-            if (keep && rank < pcap) {
-                const size_t o = (size_t)n * pcap + rank;
-                for (int c = 0; c < K; ++c) pose_slots[o * K + c] = (mk >> c) & 1u ? (int)slots[p * K + c] : -1;
-                pose_nparts[o] = parts;
-                pose_score[o] = __uint_as_float(st.y);
+            // alive persons with enough parts keep their creation order: their places in the output
+            np = min(np, tot);
+            int out = 0;
+            for (int base = 0; base < np; base += kWave) {
+                const int p = base + lane;
+                const uint32_t mk = p < np ? pst[p].x : kDead;
+                const bool keep = mk != kDead && __popc(mk) >= min_parts;
+                const unsigned long long m = __ballot(keep);
+                if (p < np) prank[p] = (int16_t)(keep && out + __popcll(m & lt) < pcap ? out + __popcll(m & lt) : -1);
+                out += __popcll(m);
             }
-            out += __popcll(m);
+            if (lane == 0) {
+                persons_made = np;
+                pose_counts[n] = out;
+                if (out > pcap) atomicOr(status, (int)HP_STATUS_POSE_OVERFLOW);
+            }
         }
-        if (lane == 0) {
-            pose_counts[n] = out;
-            if (out > pcap) atomicOr(status, (int)HP_STATUS_POSE_OVERFLOW);
+        __syncthreads();
+        // the persons written by all wavefronts: a thread per (person, part)
+        const int np = persons_made;
+        for (int idx = tid; idx < np * K; idx += kAsmBlock) {
+            const int p = idx / K, c = idx - p * K;
+            const int r = prank[p];
+            if (r >= 0) pose_slots[((size_t)n * pcap + r) * K + c] = (pst[p].x >> c) & 1u ? (int)slots[idx] : -1;
+        }
+        for (int p = tid; p < np; p += kAsmBlock) {
+            const int r = prank[p];
+            if (r >= 0) {
+                const uint2 st = pst[p];
+                pose_nparts[(size_t)n * pcap + r] = __popc(st.x);
+                pose_score[(size_t)n * pcap + r] = __uint_as_float(st.y);
+            }
         }
         return;
     }
+    if (wv != 0) return;                          // the fallback is one wavefront's work
+    if (lane < L) moff[lane] = excl;
+    if (lane == 0) moff[L] = tot;
+    wave_sync();
 
     // tables too large for LDS: the same fold on the workspace tables
     GlobalTables t;
@@ -394,7 +400,7 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
         const int cnt = max(min(pcounts[n * K + c], cap), 0);
         for (int r = lane; r < cnt; r += kWave) t.owner[(size_t)c * cap + r] = -1;
     }
-    __syncthreads();
+    wave_sync();
     int np = 0;
     for (int l = 0; l < L; ++l) {
         const int a = tab.a[l], b = tab.b[l];
@@ -417,7 +423,7 @@ __global__ __launch_bounds__(kWave) void k_assemble(LimbTable tab, int K, int L,
             const unsigned long long fm = __ballot(act && pa < 0 && pb < 0);
             if (act) apply_connection(t, K, a, b, i, j, s, sa, sb, pa, pb, np + __popcll(fm & lt), wcap);
             np += __popcll(fm);
-            __syncthreads();
+            wave_sync();
         }
     }
     emit_persons(t, n, min(np, wcap), K, min_parts, pose_slots, pose_nparts, pose_score, pose_counts, pcap, status);
@@ -432,12 +438,12 @@ hipError_t launch_assemble(const LimbTable &T, int N, int K, int L, int min_part
     // few peaks per part: the tables of an image almost surely fit the small pools (if they do
     // not, the fold runs on the workspace tables, slower but the same)
     if (pk.cap <= 256)
-        HP_KERNEL((k_assemble<kPool16Small, kPool32Small>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
+        HP_KERNEL((k_assemble<kPool16Small, kPool32Small>), dim3(N), dim3(kAsmBlock), 0, s, T, K, L, min_parts,
                            pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
                            ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
                            poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr, ccounts, ccap);
     else
-        HP_KERNEL((k_assemble<kPool16Large, kPool32Large>), dim3(N), dim3(kWave), 0, s, T, K, L, min_parts,
+        HP_KERNEL((k_assemble<kPool16Large, kPool32Large>), dim3(N), dim3(kAsmBlock), 0, s, T, K, L, min_parts,
                            pk.count, pk.score, pk.cap, conns.count, conns.i, conns.j, conns.score, conns.cap, ws.owner,
                            ws.wslots, ws.wmask, ws.wscore, ws.wcap, poses.slots, poses.nparts, poses.score,
                            poses.count, poses.cap, status, ws.peak_ctr, ws.cand_ctr, ccounts, ccap);
