@@ -33,6 +33,22 @@ __device__ __forceinline__ void ld_pair(const __half *p, float &a, float &b)
     b = __half2float(v.b);
 }
 
+// Number of keys in a[0 .. n) that are smaller than `key`, for a list padded with ~0 up to a multiple of eight
+// entries (16-byte aligned, in LDS).  All lanes read the same addresses; eight keys are fetched per step so that a
+// list of a few dozen keys costs a few LDS round trips, not one per key.
+__device__ __forceinline__ int rank_below(const uint64_t *a, int n, uint64_t key)
+{
+    int r = 0;
+    for (int u = 0; u < n; u += 8) {
+        uint64_t k[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) k[q] = a[u + q];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r += k[q] < key;
+    }
+    return r;
+}
+
 // The two PAF components of limb l at hi-res pixel (sy, sx), recomputed from the lo-res planes
 // with the upsampling arithmetic (horizontal pass on the two source rows, then vertical); the
 // node indices and weights are shared by the two components.  The two nodes of a row are
@@ -674,7 +690,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
     int32_t *ccounts, int32_t *ci, int32_t *cj, float *cs, int ccap, int32_t *mcounts, int32_t *mi, int32_t *mj,
     float *ms, int mcap, int32_t *status, int planes_in_lds)
 {
-    __shared__ uint64_t sk[kSmallCands];
+    __shared__ __align__(16) uint64_t sk[kSmallCands];
     __shared__ int lxy[4][kSmallPeaks];          // xA, yA, xB, yB in rank order
     __shared__ float lpaf[4][kSmallPeaks];       // PAF x, y at the peaks of A; x, y at the peaks of B
     __shared__ int lds_cnt;
@@ -719,9 +735,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
         }
         __syncthreads();
         if (mine) {
-            const uint64_t *skh = sk + half * kSmallPeaks;
-            int r = 0;
-            for (int u = 0; u < cnt; ++u) r += skh[u] < e;
+            const int r = rank_below(sk + half * kSmallPeaks, cnt, e);      // entries beyond the list hold ~0
             const int key = (int)(e >> 32);
             const int y = key / W, x = key - y * W;
             lxy[2 * half][r] = x;
@@ -751,8 +765,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
             }
             __syncthreads();
             if (tid < cnt) {
-                int r = 0;
-                for (int u = 0; u < cnt; ++u) r += sk[u] < e;
+                const int r = rank_below(sk, cnt, e);
                 const int key = (int)(e >> 32);
                 const int y = key / W;
                 const size_t o = (size_t)plane * cap + r;
@@ -805,12 +818,14 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
         ccounts[nl] = cnt;
         if (cnt > ccap) atomicOr(status, (int)HP_STATUS_CAND_OVERFLOW);
     }
-    // candidates in (i, j) order
+    // candidates in (i, j) order; the list is padded with ~0 for the rank counts (one entry per thread)
     const uint64_t e = tid < c ? sk[tid] : ~0ull;
+    __syncthreads();
+    sk[tid] = e;
+    __syncthreads();
     const size_t co = (size_t)nl * ccap;
     if (tid < c) {
-        int r = 0;
-        for (int u = 0; u < c; ++u) r += sk[u] < e;
+        const int r = rank_below(sk, c, e);
         ci[co + r] = (int32_t)(e >> 48);
         cj[co + r] = (int32_t)((e >> 32) & 0xffffu);
         cs[co + r] = __uint_as_float((uint32_t)e);
@@ -818,12 +833,10 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
     __syncthreads();
     // matching order: (~score bits) << 32 | (i << 16 | j), ascending
     const uint64_t key = tid < c ? ((uint64_t)(~(uint32_t)e) << 32) | (e >> 32) : ~0ull;
-    if (tid < c) sk[tid] = key;
+    sk[tid] = key;
     if (tid < kSmallPeaks / 32) usedA[tid] = usedB[tid] = 0;
     __syncthreads();
-    int r2 = 0;
-    if (tid < c)
-        for (int u = 0; u < c; ++u) r2 += sk[u] < key;
+    const int r2 = tid < c ? rank_below(sk, c, key) : 0;
     __syncthreads();
     if (tid < c) sk[r2] = key;
     __syncthreads();
