@@ -196,37 +196,57 @@ __device__ __forceinline__ void paf_at(const float *hx, const float *hy, const T
     }
 }
 
-// Scores the candidate from peak A to peak B when the PAF at the two peaks is already known (pA, pB: samples 0 and
-// S-1 lie on the peaks, since t = 0 and t = 1 round to them exactly, so they are fetched once per peak and limb, not
-// once per pair).  Validity is taken in the order 0, S-1, then samples 1 and 2 fetched together, then the rest eight
-// at a time; the pair leaves as soon as it has more than max_bad invalid samples.  Rejection does not depend on
-// that order, and a pair that is still alive at the end has had every sample looked at, so its sum is formed on the
-// way in sample order: d_0, the interior samples ascending, d_{S-1} last.  Returns whether the pair is accepted.
-template <typename T, bool FROM_HI>
-__device__ __forceinline__ bool score_pair_ends(int xA, int yA, int xB, int yB, float pAx, float pAy, float pBx, float pBy,
-                                                int S, const SampleT &st, float paf_thr, int max_bad, int H, int W, int h,
-                                                int w, const float *hx, const float *hy, const T *lx, const T *ly,
-                                                float &score)
+// Scoring of the candidate from peak A to peak B when the PAF at the two peaks is already known (samples 0 and S-1
+// lie on the peaks, since t = 0 and t = 1 round to them exactly, so they are fetched once per peak and limb, not
+// once per pair), in two stages.  Stage 1: the two end samples and samples 1 and 2 (fetched together); nearly all
+// unrelated pairs have more than max_bad invalid samples by then and leave.  Stage 2: the remaining samples eight
+// at a time, leaving as soon as the pair is beyond max_bad.  Rejection does not depend on the order in which samples
+// are looked at, and a pair that is still alive at the end has had every sample looked at, so its sum is formed on
+// the way in sample order: d_0, the interior samples ascending, d_{S-1} last.
+struct PairGeom {
+    float fdx, fdy, fx0, fy0, ux, uy;
+};
+
+// false for a pair on one pixel (never a candidate)
+__device__ __forceinline__ bool pair_geometry(int xA, int yA, int xB, int yB, PairGeom &g)
 {
     const int dx = xB - xA, dy = yB - yA;
     if (dx == 0 && dy == 0) return false;
-    const float fdx = (float)dx, fdy = (float)dy, fx0 = (float)xA, fy0 = (float)yA;
+    g.fdx = (float)dx;
+    g.fdy = (float)dy;
+    g.fx0 = (float)xA;
+    g.fy0 = (float)yA;
     const float norm = sqrtf((float)(dx * dx + dy * dy));
-    const float ux = fdx / norm, uy = fdy / norm;
-    const float d_first = __fmaf_rn(pAy, uy, pAx * ux), d_last = __fmaf_rn(pBy, uy, pBx * ux);
-    int bad = (d_first > paf_thr ? 0 : 1) + (d_last > paf_thr ? 0 : 1);
-    auto project = [&](int k) {
-        // the clamp only guards against peak lists that were not produced by this library
-        const float t = st.t[k];
-        const int sx = min(max((int)floorf(__fmaf_rn(t, fdx, fx0) + 0.5f), 0), W - 1);
-        const int sy = min(max((int)floorf(__fmaf_rn(t, fdy, fy0) + 0.5f), 0), H - 1);
-        float vx, vy;
-        paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, vx, vy);
-        return __fmaf_rn(vy, uy, vx * ux);
-    };
-    float acc = 0.0f + d_first;
+    g.ux = g.fdx / norm;
+    g.uy = g.fdy / norm;
+    return true;
+}
+
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ float pair_project(const PairGeom &g, float t, int H, int W, int h, int w, const float *hx,
+                                              const float *hy, const T *lx, const T *ly)
+{
+    // the clamp only guards against peak lists that were not produced by this library
+    const int sx = min(max((int)floorf(__fmaf_rn(t, g.fdx, g.fx0) + 0.5f), 0), W - 1);
+    const int sy = min(max((int)floorf(__fmaf_rn(t, g.fdy, g.fy0) + 0.5f), 0), H - 1);
+    float vx, vy;
+    paf_at<T, FROM_HI>(hx, hy, lx, ly, h, w, W, sy, sx, vx, vy);
+    return __fmaf_rn(vy, g.uy, vx * g.ux);
+}
+
+// Returns whether the pair is still alive; bad = invalid samples so far, acc = d_0 + d_1 + d_2.
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ bool pair_stage1(const PairGeom &g, float pAx, float pAy, float pBx, float pBy, int S,
+                                            const SampleT &st, float paf_thr, int max_bad, int H, int W, int h, int w,
+                                            const float *hx, const float *hy, const T *lx, const T *ly, int &bad,
+                                            float &acc)
+{
+    const float d_first = __fmaf_rn(pAy, g.uy, pAx * g.ux), d_last = __fmaf_rn(pBy, g.uy, pBx * g.ux);
+    bad = (d_first > paf_thr ? 0 : 1) + (d_last > paf_thr ? 0 : 1);
+    acc = 0.0f + d_first;
     if (bad <= max_bad && S > 2) {
-        const float d1 = project(1), d2 = S > 3 ? project(2) : 0.0f;      // fetched together
+        const float d1 = pair_project<T, FROM_HI>(g, st.t[1], H, W, h, w, hx, hy, lx, ly);
+        const float d2 = S > 3 ? pair_project<T, FROM_HI>(g, st.t[2], H, W, h, w, hx, hy, lx, ly) : 0.0f;
         bad += d1 > paf_thr ? 0 : 1;
         acc = acc + d1;
         if (S > 3) {
@@ -234,10 +254,19 @@ __device__ __forceinline__ bool score_pair_ends(int xA, int yA, int xB, int yB, 
             acc = acc + d2;
         }
     }
+    return bad <= max_bad;
+}
+
+// Returns whether the pair is accepted, with its score.
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ bool pair_stage2(const PairGeom &g, float pBx, float pBy, int bad, float acc, int S,
+                                            const SampleT &st, float paf_thr, int max_bad, int H, int W, int h, int w,
+                                            const float *hx, const float *hy, const T *lx, const T *ly, float &score)
+{
     for (int k0 = 3; k0 < S - 1 && bad <= max_bad; k0 += 8) {
         float d[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) d[q] = project(min(k0 + q, S - 2));
+        for (int q = 0; q < 8; ++q) d[q] = pair_project<T, FROM_HI>(g, st.t[min(k0 + q, S - 2)], H, W, h, w, hx, hy, lx, ly);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             if (k0 + q < S - 1) {
@@ -247,9 +276,24 @@ __device__ __forceinline__ bool score_pair_ends(int xA, int yA, int xB, int yB, 
         }
     }
     if (bad > max_bad) return false;
-    acc = acc + d_last;
+    acc = acc + __fmaf_rn(pBy, g.uy, pBx * g.ux);
     score = acc / (float)S;
     return score > 0.0f;
+}
+
+// Both stages in one go.
+template <typename T, bool FROM_HI>
+__device__ __forceinline__ bool score_pair_ends(int xA, int yA, int xB, int yB, float pAx, float pAy, float pBx, float pBy,
+                                                int S, const SampleT &st, float paf_thr, int max_bad, int H, int W, int h,
+                                                int w, const float *hx, const float *hy, const T *lx, const T *ly,
+                                                float &score)
+{
+    PairGeom g;
+    int bad;
+    float acc;
+    if (!pair_geometry(xA, yA, xB, yB, g)) return false;
+    if (!pair_stage1<T, FROM_HI>(g, pAx, pAy, pBx, pBy, S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly, bad, acc)) return false;
+    return pair_stage2<T, FROM_HI>(g, pBx, pBy, bad, acc, S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly, score);
 }
 
 template <typename T, bool FROM_HI>
@@ -693,7 +737,9 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
     __shared__ __align__(16) uint64_t sk[kSmallCands];
     __shared__ int lxy[4][kSmallPeaks];          // xA, yA, xB, yB in rank order
     __shared__ float lpaf[4][kSmallPeaks];       // PAF x, y at the peaks of A; x, y at the peaks of B
-    __shared__ int lds_cnt;
+    __shared__ int lds_cnt, lds_alive;
+    __shared__ uint32_t alive_id[kSmallCands];   // pairs alive after stage 1: invalid samples << 16 | i << 8 | j
+    __shared__ float alive_acc[kSmallCands];     // and their running sums
     __shared__ uint32_t usedA[kSmallPeaks / 32], usedB[kSmallPeaks / 32];
     extern __shared__ uint32_t lds_paf[];        // the limb's two lo-res PAF planes, when they fit
     const int tid = threadIdx.x;
@@ -727,7 +773,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
         const bool publish = half < 2 && tab.writer[half == 0 ? a : b] == l;
         const uint64_t e = mine ? peak_stage[(size_t)plane * cap2 + t] : ~0ull;
         if (half < 2) sk[tid] = e;
-        if (tid == 0) lds_cnt = 0;
+        if (tid == 0) lds_cnt = lds_alive = 0;
         if (publish && t == 0) {
             const int raw = peak_ctr[plane * kCtrStride];
             pcounts[plane] = raw;
@@ -791,18 +837,48 @@ __global__ __launch_bounds__(kSmallBlock) void k_limb_small(
                                 lpaf[2 * half][t], lpaf[2 * half + 1][t]);
             }
             __syncthreads();
+            auto accept = [&](int i, int j, float score) {
+                const int slot = atomicAdd(&lds_cnt, 1);
+                if (slot < kSmallCands)
+                    sk[slot] = ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+            };
+            // stage 1 for every pair; the few that are still alive are listed, so that stage 2 (most of a pair's
+            // samples) is run by as many lanes as there are such pairs instead of by every wavefront for a few lanes
             for (int p = tid; p < P; p += kSmallBlock) {
                 int i = (int)((float)p * inv_nB);
                 int j = p - i * nB;
                 while (j < 0) { --i; j += nB; }
                 while (j >= nB) { ++i; j -= nB; }
-                float score;
-                if (score_pair_ends<T, false>(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], lpaf[0][i], lpaf[1][i], lpaf[2][j],
-                                              lpaf[3][j], S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly, score)) {
-                    const int slot = atomicAdd(&lds_cnt, 1);
-                    if (slot < kSmallCands)
-                        sk[slot] = ((uint64_t)(((uint32_t)i << 16) | (uint32_t)j) << 32) | (uint64_t)__float_as_uint(score);
+                PairGeom g;
+                int bad;
+                float acc;
+                if (!pair_geometry(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], g)) continue;
+                if (!pair_stage1<T, false>(g, lpaf[0][i], lpaf[1][i], lpaf[2][j], lpaf[3][j], S, st, paf_thr, max_bad, H, W, h, w,
+                                           hx, hy, lx, ly, bad, acc))
+                    continue;
+                const int slot = atomicAdd(&lds_alive, 1);
+                if (slot < kSmallCands) {
+                    alive_id[slot] = ((uint32_t)bad << 16) | ((uint32_t)i << 8) | (uint32_t)j;
+                    alive_acc[slot] = acc;
+                } else {
+                    // the list is full: finished on the spot
+                    float score;
+                    if (pair_stage2<T, false>(g, lpaf[2][j], lpaf[3][j], bad, acc, S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx,
+                                              ly, score))
+                        accept(i, j, score);
                 }
+            }
+            __syncthreads();
+            const int n_alive = min(lds_alive, kSmallCands);
+            for (int q = tid; q < n_alive; q += kSmallBlock) {
+                const uint32_t id = alive_id[q];
+                const int i = (int)((id >> 8) & 0xffu), j = (int)(id & 0xffu);
+                PairGeom g;
+                pair_geometry(lxy[0][i], lxy[1][i], lxy[2][j], lxy[3][j], g);
+                float score;
+                if (pair_stage2<T, false>(g, lpaf[2][j], lpaf[3][j], (int)(id >> 16), alive_acc[q], S, st, paf_thr, max_bad, H, W, h,
+                                          w, hx, hy, lx, ly, score))
+                    accept(i, j, score);
             }
         };
         if (planes_in_lds)
@@ -860,7 +936,8 @@ hipError_t launch_limb_small(const void *paf_lo, hp_dtype dt, int N, int h, int 
     // the two PAF planes of a limb go to LDS when they fit beside the kernel's own tables (and can
     // be copied as whole 32-bit words)
     const size_t plane_bytes = (size_t)2 * h * w * (dt == HP_F16 ? 2 : 4);
-    const int in_lds = plane_bytes <= 48 * 1024 && plane_bytes % 4 == 0 && ((uintptr_t)paf_lo & 3) == 0;
+    // (the kernel's own tables take 24 KB of the 64 KB a workgroup gets without asking for more)
+    const int in_lds = plane_bytes <= 39 * 1024 && plane_bytes % 4 == 0 && ((uintptr_t)paf_lo & 3) == 0;
     const size_t lds = in_lds ? plane_bytes : 0;
 #define HP_LIMB_SMALL_ARGS(LO)                                                                                        \
     LO, h, w, T, st, K, L, N *L, prm.n_samples, prm.paf_thr, need, peak_ctr, peak_stage, pk.cap, cap2, pk.count, pk.x, \
