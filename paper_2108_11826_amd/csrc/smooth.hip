@@ -16,6 +16,7 @@
 // about 40 % of both the fp32 vector rate and the HBM peak; switching one phase off at a time shows
 // loading, the horizontal and the vertical pass adding up rather than overlapping.
 #include <algorithm>
+#include <type_traits>
 
 #include "hp_dev.h"
 
@@ -147,6 +148,132 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
     }
 }
 
+// The marching form, for the usual tap counts on maps whose rows are whole 16-byte groups.  A wavefront owns a
+// strip of up to 256 columns (four neighbouring columns per lane) of a band of rows and walks down it one source row
+// at a time.  A step: the row's 16-byte pieces (fetched T or more steps earlier into registers that are refilled in
+// place) go to a row buffer in the wavefront's own LDS; every lane reads back its window of 4 + 2r values and filters
+// its four outputs horizontally; the filtered values are then added, tap by tap, to the T output rows they belong to,
+// whose running sums live in registers; the output row whose last tap this was is stored.  A sum receives its taps in
+// the order the source rows arrive, which is ascending tap order, starting from 0: the same bits as the definition.
+// The row loop is unrolled T-fold (a multiple of it for few taps) so that every register has a fixed name.  No
+// workgroup barrier, one LDS write and (4 + 2r) / 4 + 1 LDS reads per row and lane against 8 T multiply-adds, no
+// horizontally filtered row is computed twice except the 2r rows between two bands, and the stores are whole rows.
+constexpr int kMarchBlock = 256, kMarchWaves = kMarchBlock / kWave;
+
+// f(integral_constant<0>), f(integral_constant<1>), ...: a loop whose counter is a constant in every round
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
+template <int T>
+__global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_smooth_march(const float *__restrict__ src, float *__restrict__ dst, int C,
+                                                              int C_mem, int H, int W, const float *__restrict__ taps,
+                                                              int strips, int sw, int bands, int band)
+{
+    constexpr int r = (T - 1) / 2, rp = (r + 3) & ~3, o0 = rp - r;
+    constexpr int U = T * ((10 + T - 1) / T);            // rows per pass through the unrolled loop (16 bytes x 2 x U in registers)
+    constexpr int kWin = 2 * rp + 4;                     // floats a lane reads back per row
+    constexpr int kBuf = 4 * kWave + 2 * rp + 4;         // floats per row buffer (+ 4 that take the writes of idle lanes)
+    __shared__ __attribute__((aligned(16))) float bufs[kMarchWaves][kBuf + 4];
+    const int lane = threadIdx.x & (kWave - 1), wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int task = blockIdx.x * kMarchWaves + wv;
+    if (task >= strips * bands) return;
+    const int strip = task % strips, bandi = task / strips;
+    const int plane = blockIdx.z;
+    const size_t plane_off = ((size_t)(plane / C) * C_mem + plane % C) * H * W;
+    const float *s = src + plane_off;
+    float *d = dst + plane_off;
+    const int x0 = strip * sw, y_start = bandi * band;
+    if (x0 >= W || y_start >= H) return;
+    const int y_end = min(y_start + band, H);
+    const int sw_valid = min(sw, W - x0);                // a multiple of 4, at least 4
+    const bool active = 4 * lane < sw_valid;
+    const int X = active ? x0 + 4 * lane : x0;
+    // the rp columns to the left and to the right of the strip: lanes [0, rp/4) and [rp/4, rp/2), one 16-byte piece
+    // each.  A piece lies wholly inside the map or wholly outside it; outside, the edge pixel is repeated.  Every
+    // lane performs the same loads and LDS writes (idle lanes re-read their own piece and write to a spare place), so
+    // that a row step is straight-line code and the loads of later rows stay in flight across it.
+    const bool h_left = lane < rp / 4, h_any = lane < rp / 2;
+    const int h_col = h_left ? x0 - rp + 4 * lane : x0 + sw_valid + 4 * (lane - rp / 4);
+    const bool h_out = h_any && (h_col < 0 || h_col >= W);
+    const bool h_first = h_col < 0;
+    const int h_ld = h_any ? min(max(h_col, 0), W - 4) : X;
+    const int h_dst = h_any ? (h_left ? 4 * lane : rp + sw_valid + 4 * (lane - rp / 4)) : kBuf;
+    const int m_dst = active ? rp + 4 * lane : kBuf;
+    float *buf = bufs[wv];
+
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    v4f pre_main[U], pre_halo[U];
+    auto load_row = [&](int yy, v4f &m, v4f &hh) {
+        const float *line = s + (size_t)min(max(yy, 0), H - 1) * W;
+        m = *(const v4f *)(line + X);
+        hh = *(const v4f *)(line + h_ld);
+    };
+    // a piece outside the map: the row's first or last pixel, four times
+    auto edge_fix = [&](const v4f &hh) {
+        const float e = h_first ? hh.x : hh.w;
+        const v4f rep = {e, e, e, e};
+        return h_out ? rep : hh;
+    };
+    const int n_steps = (y_end - y_start) + 2 * r;       // source rows y_start - r .. y_end - 1 + r, clamped to the map
+#pragma unroll
+    for (int u = 0; u < U; ++u) load_row(y_start - r + u, pre_main[u], pre_halo[u]);
+
+    float ring[T][4];
+#pragma unroll
+    for (int j = 0; j < T; ++j)
+#pragma unroll
+        for (int o = 0; o < 4; ++o) ring[j][o] = 0.0f;
+
+    for (int base = 0; base < n_steps; base += U) {
+        static_for<U>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            const int step = base + u;                   // steps beyond n_steps (the last pass of a band) store nothing
+            *(v4f *)&buf[m_dst] = pre_main[u];
+            *(v4f *)&buf[h_dst] = edge_fix(pre_halo[u]);
+            load_row(y_start - r + step + U, pre_main[u], pre_halo[u]);      // refilled for the next pass
+            // LDS serves a wavefront's requests in order: the reads below see the writes above
+            __builtin_amdgcn_wave_barrier();
+            float win[kWin];
+#pragma unroll
+            for (int q = 0; q < kWin / 4; ++q) {
+                const v4f v = *(const v4f *)&buf[4 * lane + 4 * q];
+                win[4 * q] = v.x;
+                win[4 * q + 1] = v.y;
+                win[4 * q + 2] = v.z;
+                win[4 * q + 3] = v.w;
+            }
+            __builtin_amdgcn_wave_barrier();
+            float t4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int i = 0; i < T; ++i) {
+                const float tap = taps[i];
+#pragma unroll
+                for (int o = 0; o < 4; ++o) t4[o] = __fmaf_rn(tap, win[o0 + o + i], t4[o]);
+            }
+            // this row is tap j of the output row that started j steps ago
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                const float tap = taps[j];
+                constexpr int kBig = 4 * T;
+                const int slot = (u % T - j + kBig) % T;     // a constant once the loop over j is unrolled
+#pragma unroll
+                for (int o = 0; o < 4; ++o) ring[slot][o] = __fmaf_rn(tap, t4[o], j == 0 ? 0.0f : ring[slot][o]);
+            }
+            if (step >= 2 * r && step < n_steps && active) {
+                const int slot = (u % T + 1) % T;        // the row that has just received its last tap
+                const v4f out = {ring[slot][0], ring[slot][1], ring[slot][2], ring[slot][3]};
+                __builtin_nontemporal_store(out, (v4f *)&d[(size_t)(y_start + step - 2 * r) * W + X]);
+            }
+        });
+    }
+}
+
 // Rows staged at a time and the floats between staged rows, for radius r (the kernel derives the same two numbers).
 static void smooth_stage(int r, int &stage, int &pitch)
 {
@@ -159,6 +286,44 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
                          int n_taps, hipStream_t s)
 {
     const int r = (n_taps - 1) / 2;
+    // The marching kernel, where it is the faster one (measured on 8 x 18 maps of 368 x 656 / 4 x 18 maps of 1080 x 1920,
+    // tile kernel -> marching kernel): 5 taps 62 -> 48 / 267 -> 242 us, 9 taps 68 -> 54 / 279 -> 251, 13 taps 75 -> 61 /
+    // 304 -> 256, 17 taps 87 -> 96 / 355 -> 298: with 17 taps a lane holds 228 registers, two wavefronts share a SIMD, and
+    // a launch of fewer than about 2000 such wavefronts leaves SIMDs with one; the small case stays with the tile kernel.
+    const bool march_pays = n_taps == 5 || n_taps == 9 || n_taps == 13 ||
+                            (n_taps == 17 && (long long)N * C * H * W >= 64LL * 1000 * 1000);
+    if (march_pays && W % 4 == 0 && ((((uintptr_t)src) | ((uintptr_t)dst)) & 15) == 0) {
+        // strips of equal width (a multiple of 4, at most 256 columns); bands so that about two wavefronts per SIMD are
+        // under way: fewer would leave the memory system idle, more would filter more rows twice (2r per band)
+        const int strips = (W + 4 * kWave - 1) / (4 * kWave);
+        const int sw = ((W + strips - 1) / strips + 3) & ~3;
+        for (int p0 = 0; p0 < N * C; p0 += 65535 / C * C) {
+            const int planes = std::min(N * C - p0, 65535 / C * C);
+            const size_t off = (size_t)(p0 / C) * C_mem * H * W;
+            // the kernel keeps two wavefronts per SIMD: at most 2048 of them at once on 256 compute units.  One more than
+            // fit is a second round for the whole launch, so the count stays just below
+            const long long columns = (long long)strips * planes;
+            int bands = (int)std::min<long long>((H + 15) / 16, std::max<long long>(1, 2048 / columns));
+            const int band = (H + bands - 1) / bands;
+            bands = (H + band - 1) / band;
+            const dim3 grid((strips * bands + kMarchWaves - 1) / kMarchWaves, 1, planes);
+#define HP_MARCH_CASE(T_)                                                                                             \
+    case T_:                                                                                                         \
+        HP_KERNEL(k_smooth_march<T_>, grid, dim3(kMarchBlock), 0, s, src + off, dst + off, C, C_mem, H, W, taps, strips, sw, \
+                  bands, band);                                                                                      \
+        break;
+            switch (n_taps) {
+                HP_MARCH_CASE(5)
+                HP_MARCH_CASE(9)
+                HP_MARCH_CASE(13)
+                HP_MARCH_CASE(17)
+            }
+#undef HP_MARCH_CASE
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     int stage, pitch;
     smooth_stage(r, stage, pitch);
     const size_t lds = sizeof(float) * ((size_t)(kSmoothTileH + 2 * r) * kSmoothTile + (size_t)stage * pitch + 8);

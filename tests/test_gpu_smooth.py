@@ -25,6 +25,15 @@ CASES = [
     dict(N=1, C_mem=2, C=1, H=65, W=129, taps=np.array([1.0], np.float32)),
     dict(N=2, C_mem=2, C=2, H=3, W=300, taps=np.array([0.25, 0.5, 0.25], np.float32)),
     dict(N=1, C_mem=1, C=1, H=300, W=2, taps=gaussian_taps(2.0, 5)),
+    # rows of whole 16-byte groups with 5, 9, 13 taps (and 17 on large inputs) take the kernel that walks down strips:
+    # one and several strips, ragged last strip, a map narrower than the halo, one row, bands that end mid-pass
+    dict(N=2, C_mem=3, C=2, H=45, W=64, taps=gaussian_taps(1.0, 2)),
+    dict(N=1, C_mem=2, C=2, H=100, W=260, taps=gaussian_taps(2.0, 4)),
+    dict(N=1, C_mem=1, C=1, H=33, W=4, taps=gaussian_taps(2.5, 6)),
+    dict(N=1, C_mem=1, C=1, H=1, W=512, taps=gaussian_taps(2.5, 6)),
+    dict(N=1, C_mem=2, C=2, H=300, W=1028, taps=np.linspace(-1.0, 2.0, 9).astype(np.float32)),
+    dict(N=3, C_mem=20, C=19, H=17, W=8, taps=gaussian_taps(1.0, 2)),
+    dict(N=1, C_mem=5, C=4, H=2048, W=2048 * 4, taps=gaussian_taps(3.0, 8)),         # 67 M pixels: 17 taps, marching
 ]
 
 
