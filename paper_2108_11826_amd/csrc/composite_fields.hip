@@ -19,7 +19,7 @@
 //              repeated only against each newly finished person; a person grows in rounds, a wavefront per
 //              frontier limb (the search, 64 associations at a time, over records held in LDS);
 //   k_cf_field one wavefront per strip of 64 x 8 pixels: the part's listed cells whose window meets the strip, then
-//              the sum per pixel.
+//              the sum per pixel, eight 8 x 8 groups of pixels a lane.
 #include <limits.h>
 #include <string.h>
 
@@ -31,7 +31,8 @@ namespace hp {
 
 constexpr int kCfBlock = 256;       // k_cf_pif, k_cf_paf, k_cf_field
 constexpr int kCfGrowBlock = 256;   // k_cf_grow: four wavefronts, one per frontier limb of a round
-constexpr int kCfTileW = 64, kCfTileH = 32;
+// hp_cf_field: a wavefront fills a strip of kCfTileW x kCfStripH pixels, a workgroup four strips one above the other
+constexpr int kCfTileW = 64, kCfStripH = 8, kCfTileH = kCfStripH * (kCfBlock / 64);
 
 struct CFParams {
     float pif_thr, paf_thr, seed_thr, grow_thr, rev_tol;
@@ -756,22 +757,66 @@ __global__ __launch_bounds__(kCfGrowBlock) void k_cf_grow(CFParams P, CFWork ws,
 }
 
 // ---- C2 as an array ----------------------------------------------------------------------------------------------
+// The Gaussian of C2 for a pixel inside a cell's window.  There t = d2 / (2 sg^2) with |dx|, |dy| <= w + 1/2,
+// w = ceil(3 sg) and sg >= 1, so 0 <= t <= (3 + 3/(2 sg))^2 <= 20.25: the clamps of cf_expneg never act and are left
+// out, and the sign moves into the constants (y, n and y - n change sign together and exactly, the products and the
+// polynomial keep their bits), which saves the negation before the scaling.
+__device__ __forceinline__ float cf_expneg_window(float t)
+{
+    const float y = t * -0x1.715476p+0f;
+    const float n = rintf(y);
+    const float z = (y - n) * 0x1.62e430p-1f;
+    float p = 0x1.6c16c2p-10f;
+    p = __fmaf_rn(p, z, 0x1.111112p-7f);
+    p = __fmaf_rn(p, z, 0x1.555556p-5f);
+    p = __fmaf_rn(p, z, 0x1.555556p-3f);
+    p = __fmaf_rn(p, z, 0.5f);
+    p = __fmaf_rn(p, z, 1.0f);
+    p = __fmaf_rn(p, z, 1.0f);
+    return ldexpf(p, (int)n);
+}
+
 // A wavefront fills a strip of 64 x 8 pixels on its own (four strips a workgroup, no barrier): it picks, in list order,
-// the part's listed cells whose window meets the strip (most strips meet none and are plain zero stores), then sums
-// per pixel.  The first 64 records are fetched together with the list's length, so that one memory round trip
-// separates a strip's start from its first store.
-constexpr int kCfStripH = 8;
+// the part's listed cells whose window meets the strip, then sums per pixel.  Most strips meet none and are plain zero
+// stores (ordinary stores: an all-zero map then takes as long as a fill, 18 us for the benchmark's 125 MB, where
+// non-temporal ones took 25).  The first 64 records are fetched together with the list's length, so that one memory
+// round trip separates a strip's start from its first store.
+// The sums are what the kernel's time goes to (windows are some 40 pixels wide: with a lane per column of the strip,
+// most lanes idled and the arithmetic alone took 20 us).  So the strip is summed as eight groups of 8 x 8 pixels, a
+// lane holding one pixel of each: a cell's record sits in scalar registers (it is the same for all lanes), a group
+// whose pixels all lie outside the window is skipped after two instructions, and in the others the pixels outside are
+// masked off.  Scalar tests of which groups a window meets cost more than they saved: the scalar unit was the
+// bottleneck then (35 against 29 us), and so did a jump to the first such group (32 us).  A pixel still adds its
+// cells in list order.  The sums then pass through LDS to leave as whole rows.
+constexpr int kCfGroups = kCfTileW / 8, kCfTilePitch = kCfTileW + 8;
+__host__ __device__ constexpr int cf_field_wave_f4(int cap)
+{
+    return 2 * cap > kCfStripH * kCfTilePitch / 4 ? 2 * cap : kCfStripH * kCfTilePitch / 4;
+}
+
 __global__ __launch_bounds__(kCfBlock) void k_cf_field(CFParams P, CFWork ws, const int32_t *__restrict__ pif_count,
                                                        float *__restrict__ out)
 {
     extern __shared__ float4 s_dyn4[];
-    const int plane = blockIdx.z, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-    float4 *s_a = s_dyn4 + (size_t)wv * 2 * P.cap;   // [cap] this wavefront's cells, in list order
+    const int plane = blockIdx.z, tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float4 *s_a = s_dyn4 + (size_t)wv * cf_field_wave_f4(P.cap);   // [cap] this wavefront's cells, in list order
     int4 *s_b = (int4 *)(s_a + P.cap);
+    float *tile = (float *)s_a;                                    // [8][72] the strip's sums, once the cells are done
 
     const int H = P.Fh * P.stride, W = P.Fw * P.stride;
-    const int x0 = blockIdx.x * kCfTileW, y0 = blockIdx.y * kCfTileH + wv * kCfStripH;
+    const int strip_row = blockIdx.y * (kCfBlock / kWave) + wv;
+    const int x0 = blockIdx.x * kCfTileW, y0 = strip_row * kCfStripH;
     if (y0 >= H) return;
+    const int px = x0 + lane;
+    float *const o = out + ((size_t)plane * H + y0) * W + px;
+    auto zeros = [&]() {
+        if (px < W) {
+#pragma unroll
+            for (int r = 0; r < kCfStripH; ++r)
+                if (y0 + r < H) o[(size_t)r * W] = 0.0f;
+        }
+    };
     const size_t list = (size_t)plane * P.cap;
     // records beyond the list's end are never used: the first fetch only may not wait for the length
     int4 b = lane < P.cap ? ws.pif_b[list + lane] : make_int4(0, 0, 0, 0);
@@ -794,33 +839,63 @@ __global__ __launch_bounds__(kCfBlock) void k_cf_field(CFParams P, CFWork ws, co
         }
         cnt += __popcll(mask);
     }
+    if (cnt == 0) {
+        zeros();
+        return;
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the records above are read by the other lanes below
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const int px = x0 + lane;
-    if (px >= W) return;
-    // the cells outermost, the strip's rows innermost: a pixel still adds its cells in list order
-    float f[kCfStripH];
+
+    const int lx = lane & 7, ly = lane >> 3;
+    const int gx = x0 + lx, py = y0 + ly;     // this lane's pixel of group g is (gx + 8 g, py)
+    const float pyf = (float)py;
+    float pxf[kCfGroups], f[kCfGroups];
 #pragma unroll
-    for (int r = 0; r < kCfStripH; ++r) f[r] = 0.0f;
+    for (int g = 0; g < kCfGroups; ++g) {
+        pxf[g] = (float)(gx + 8 * g);
+        f[g] = 0.0f;
+    }
+    int4 bn = s_b[0];
+    float4 an = s_a[0];
     for (int j = 0; j < cnt; ++j) {
-        const int4 bj = s_b[j];
-        if (abs(px - bj.x) > bj.w) continue;
-        const float4 aj = s_a[j];
-        const float dx = (float)px - aj.x;
-        const float dx2 = dx * dx;
+        // one record for all lanes: kept in scalar registers, the next one is on its way meanwhile
+        const int bx = __builtin_amdgcn_readfirstlane(bn.x), by = __builtin_amdgcn_readfirstlane(bn.y);
+        const int bw = __builtin_amdgcn_readfirstlane(bn.w);
+        const float aX = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(an.x)));
+        const float aY = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(an.y)));
+        const float az = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(an.z)));
+        const float ac = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(an.w)));
+        const int jn = min(j + 1, cnt - 1);
+        bn = s_b[jn];
+        an = s_a[jn];
+        const int xlo = bx - bw;
+        const unsigned span = 2u * (unsigned)bw;
+        const bool in_y = (unsigned)(py - (by - bw)) <= span;           // |py - yr| <= w
+        const float dy = pyf - aY;
+        const float dy2 = dy * dy;
 #pragma unroll
-        for (int r = 0; r < kCfStripH; ++r) {
-            const int py = y0 + r;
-            if (abs(py - bj.y) > bj.w) continue;              // the same for the whole wavefront
-            const float dy = (float)py - aj.y;
-            const float d2 = dx2 + dy * dy;
-            f[r] = f[r] + aj.w * cf_expneg(d2 * aj.z);
+        for (int g = 0; g < kCfGroups; ++g) {
+            if (in_y && (unsigned)(gx + 8 * g - xlo) <= span) {         // |px - xr| <= w; often for no lane at all
+                const float dx = pxf[g] - aX;
+                const float dx2 = dx * dx;
+                const float d2 = dx2 + dy2;
+                f[g] = f[g] + ac * cf_expneg_window(d2 * az);
+            }
         }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the records have been read: their place takes the sums
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int r = 0; r < kCfStripH; ++r)
-        if (y0 + r < H) __builtin_nontemporal_store(f[r], &out[((size_t)plane * H + y0 + r) * W + px]);
+    for (int g = 0; g < kCfGroups; ++g) tile[ly * kCfTilePitch + 8 * g + lx] = f[g];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (px < W) {
+#pragma unroll
+        for (int r = 0; r < kCfStripH; ++r)
+            if (y0 + r < H) o[(size_t)r * W] = tile[r * kCfTilePitch + lane];
+    }
 }
 
 // ---- host side ---------------------------------------------------------------------------------------------------
@@ -928,7 +1003,7 @@ hipError_t launch_cf_field(int N, int Fh, int Fw, int K, const hp_cf_params &prm
     const CFWork ws = cf_layout(workspace, N, K, 0, cap, 0);
     const int H = Fh * prm.stride, W = Fw * prm.stride;
     const dim3 grid((W + kCfTileW - 1) / kCfTileW, (H + kCfTileH - 1) / kCfTileH, N * K);
-    const size_t lds = sizeof(float4) * 2 * (size_t)cap * (kCfBlock / kWave);
+    const size_t lds = sizeof(float4) * (size_t)cf_field_wave_f4(cap) * (kCfBlock / kWave);
     if (hipError_t e = allow_lds(k_cf_field, lds)) return e;
     HP_KERNEL(k_cf_field, grid, dim3(kCfBlock), lds, s, P, ws, count, out);
     return hipGetLastError();
