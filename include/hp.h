@@ -279,7 +279,9 @@ int hp_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, hp_dtype out
  * returns.  Frame and map sides up to 16384, N up to 65535, thickness and radius 0..1024.
  * workspace: device memory of hp_draw_workspace_bytes(N, n_parts, n_limbs, poses->cap, Hf, Wf)
  * bytes, 256-byte aligned, no need to clear it (it receives the images' primitives in painter's
- * order and one bit per frame tile); two calls running concurrently must not share it.
+ * order and, per frame tile of 64 x 16 pixels, up to 64 of those that can touch it: about one byte
+ * per frame pixel); two calls running concurrently must not share it.  poses->cap x (n_parts +
+ * n_limbs) may not exceed 2^24.
  * Allocates nothing; enqueues two kernels on `stream`. */
 size_t hp_draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf);
 int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,

@@ -562,12 +562,14 @@ int hp_draw_poses(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C
         if (a < b + bytes && b < a + bytes) return HP_ERR_INVALID_ARG;
     }
     const int K = skel->n_parts, L = skel->n_limbs;
+    if ((long long)poses->cap * (K + L) > (1 << 24)) return HP_ERR_UNSUPPORTED;   // a primitive's rank takes 24 bits
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || ws_bytes < draw_workspace_bytes(N, K, L, poses->cap, Hf, Wf))
         return HP_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    HP_LAUNCH(HP_K_DRAW_LIST, launch_draw_list(N, Hf, Wf, H, W, tab, K, L, *peaks, *poses, thickness, radius, workspace, s));
-    HP_LAUNCH(HP_K_DRAW, launch_draw_tiles(src, dst, N, Hf, Wf, C, H, W, tab, K, L, *peaks, *poses, limb_rgb, part_rgb,
-                                           thickness, radius, workspace, s));
+    HP_LAUNCH(HP_K_DRAW_LIST, launch_draw_list(N, Hf, Wf, H, W, tab, K, L, *peaks, *poses, limb_rgb, part_rgb, thickness, radius,
+                                               workspace, s));
+    HP_LAUNCH(HP_K_DRAW, launch_draw_tiles(src, dst, N, Hf, Wf, C, H, W, tab, K, L, *peaks, *poses, thickness, radius,
+                                           workspace, s));
     return HP_OK;
 }
 

@@ -7,27 +7,40 @@
 //
 // Two launches.  k_draw_list, one workgroup per image, walks the person table once and writes the
 // image's primitives, in painter's order, as 16-byte records (end points in frame coordinates, id,
-// and the largest cross product a covered pixel can have) into the workspace, plus one bit per
-// frame tile that says whether any primitive can touch it.  k_draw_tiles, one workgroup per tile
-// of 64 x 16 pixels, copies untouched tiles and rasterises the others primitive by primitive
-// instead of testing every pixel against every primitive: the records are read 512 at a time
-// (coalesced), those whose bounding box and line can meet the tile are kept in LDS, and each
-// thread then takes (record, row) pairs: the covered pixels of a row are an interval (a capsule
-// is convex) whose ends follow exactly from two integer square roots and four exact integer
-// divisions, and the thread raises the owner word of each pixel in it to (rank of the record,
-// colour id) with an LDS atomic max, which is the painter's order.  A thread finally owns four
-// neighbouring pixels, looks up their owners and writes them once.  Testing the pixels of a strip
-// against every record that touches it (the first version of this kernel) cost 200 instructions
-// per (strip, record) pair for the sixteen or so pixels a thin limb covers there, and that
-// arithmetic, not memory, set the kernel's duration.
+// and the largest cross product a covered pixel can have) into the workspace; it also hands each
+// record, with its rank in that order, to every frame tile its capsule can touch (a count and up
+// to kTileCap records per tile).  k_draw_tiles, one workgroup per tile of 128 x 16 pixels, copies
+// tiles nothing was handed to and rasterises the others primitive by primitive instead of testing
+// every pixel against every primitive: each thread takes (record, row) pairs: the covered pixels
+// of a row are an interval (a capsule is convex) whose ends follow exactly from two integer square
+// roots and four exact integer divisions, and the thread raises the owner word of each pixel in it
+// to (rank of the record, colour id) with an LDS atomic max, which is the painter's order.  A
+// thread finally looks up the owners of its own pixels and writes them once.  A
+// tile that was handed more records than it can hold goes through the image's whole list instead,
+// 512 records at a time, keeping those whose bounding box and line can meet it (every touched tile
+// did that at first: with a thousand records an image the tests were 10 us of arithmetic, and the
+// list cost a tile a second memory round trip).  Testing the pixels of a strip against every
+// record that touches it (the first version of this kernel) cost 200 instructions per (strip,
+// record) pair for the sixteen or so pixels a thin limb covers there.
 #include <string.h>
 
 #include "hp_dev.h"
 
 namespace hp {
 
-constexpr int kTileW = 64, kTileH = 16;   // pixels a workgroup paints; a thread owns four neighbouring pixels of a row
-static_assert(kTileW * kTileH == 4 * kBlock, "four pixels per thread");
+// Frames are read and written with ordinary loads and stores: non-temporal ones took a sixth longer (17.9 against
+// 15.1 us for the benchmark's 64 frames with nothing to draw).
+#define DRAW_ST(v, p) (*(p) = (v))
+#define DRAW_LD(p) (*(p))
+
+// Pixels a workgroup paints.  A thread owns kTileGroups groups of four neighbouring pixels, 64 pixels apart in a
+// row and 16 rows apart: sixteen threads fetch 64 neighbouring pixels of a row at a time.  (The kernel waits for its
+// pixels once per workgroup: a tile of 64 x 16 took the benchmark's frames 25 us, one of 128 x 16 21 us.)
+constexpr int kTileW = 128, kTileH = 16, kTileGroupsX = kTileW / 64, kTileGroups = kTileGroupsX * (kTileH / 16);
+static_assert(kTileW * kTileH == 4 * kTileGroups * kBlock, "kTileGroups groups of four pixels a thread");
+constexpr int kTileCap = 64;              // records a tile can be handed; with more it reads the image's list itself
+constexpr int kListBinTiles = 8192;       // k_draw_list counts a frame's tiles in LDS up to this many, else in the workspace
+static_assert(kTileCap <= kBlock && HP_MAX_LIMBS + HP_MAX_PARTS <= kBlock, "a thread fetches one of its tile's records and one colour");
 
 // Per-primitive tables, indexed by id = limb index, or n_limbs + part index.  Passed by value and copied to LDS
 // through constant indices: a kernel argument indexed per lane would be unpacked by long select chains.
@@ -42,13 +55,13 @@ struct DrawParams {
     int th2_quarter;   // floor(thickness^2 / 4): 4 |u|^2 <= thickness^2 for integer |u|^2
     int reach;         // pixels a limb can extend beyond its end points
     int list_cap;      // records per image in the workspace
-    int tiles_x, tiles_y, mask_words;   // tiles of a frame and the 32-bit words of its tile mask
+    int tiles_x, tiles_y, tiles;        // tiles of a frame
 };
 
 // A primitive as the tile kernel reads it.
 struct DrawRecord {
     int a, b;     // end points, x | y << 16 in frame pixels (equal for a part)
-    int id;       // limb index, or n_limbs + part index
+    int id;       // limb index, or n_limbs + part index; in a tile's records: id | rank in painter's order << 7
     int cmax;     // limbs: floor(sqrt(thickness^2 |B - A|^2 / 4)), the largest |(P - A) x (B - A)| of a covered pixel
 };
 
@@ -92,11 +105,12 @@ __global__ __launch_bounds__(kListBlock) void k_draw_list(const int32_t *__restr
                                                       const int32_t *__restrict__ slots,
                                                       const int32_t *__restrict__ pose_count, DrawTables tab, DrawParams P,
                                                       DrawRecord *__restrict__ records, int32_t *__restrict__ record_count,
-                                                      uint32_t *__restrict__ tile_mask)
+                                                      int32_t *__restrict__ tile_count, DrawRecord *__restrict__ tile_records,
+                                                      uint32_t *__restrict__ rgb_table)
 {
     __shared__ uint8_t s_part_a[HP_MAX_LIMBS], s_part_b[HP_MAX_LIMBS];
     __shared__ int s_scan[kListBlock / kWave + 1];
-    extern __shared__ uint32_t s_mask[];   // one bit per tile: can any primitive touch it?
+    extern __shared__ int s_tiles[];   // records handed to each tile so far (frames of up to kListBinTiles tiles)
     const int n = blockIdx.x, tid = threadIdx.x;
     if (tid == 0) {
 #pragma unroll
@@ -104,8 +118,17 @@ __global__ __launch_bounds__(kListBlock) void k_draw_list(const int32_t *__restr
             s_part_a[i] = tab.a[i];
             s_part_b[i] = tab.b[i];
         }
+        if (n == 0) {
+            // the colours by id, where every tile can fetch them with its first loads
+#pragma unroll
+            for (int i = 0; i < HP_MAX_LIMBS + HP_MAX_PARTS; ++i) rgb_table[i] = tab.rgb[i];
+        }
     }
-    for (int i = tid; i < P.mask_words; i += kListBlock) s_mask[i] = 0;
+    int32_t *const tile_count_n = tile_count + (size_t)n * P.tiles;
+    const bool in_lds = P.tiles <= kListBinTiles;
+    int *const handed = in_lds ? s_tiles : tile_count_n;
+    for (int i = tid; i < P.tiles; i += kListBlock) handed[i] = 0;
+    if (!in_lds) __threadfence();   // the zeros are in place before another thread's atomic finds the word
     __syncthreads();
     const int per_person = P.L + P.K;
     const int items = min(pose_count[n], P.pcap) * per_person;
@@ -115,6 +138,7 @@ __global__ __launch_bounds__(kListBlock) void k_draw_list(const int32_t *__restr
         const int q = base + tid;
         bool keep = false;
         DrawRecord rec = {0, 0, 0, 0};
+        int ax = 0, ay = 0, bx = 0, by = 0;
         if (q < items) {
             const int p = q / per_person;
             rec.id = q - p * per_person;
@@ -126,8 +150,8 @@ __global__ __launch_bounds__(kListBlock) void k_draw_list(const int32_t *__restr
             if (ia >= 0 && ib >= 0 && ia < P.cap && ib < P.cap) {
                 keep = true;
                 const size_t oa = ((size_t)n * P.K + a) * P.cap + ia, ob = ((size_t)n * P.K + b) * P.cap + ib;
-                const int ax = to_frame(peak_x[oa], P.W, P.Wf), ay = to_frame(peak_y[oa], P.H, P.Hf);
-                const int bx = to_frame(peak_x[ob], P.W, P.Wf), by = to_frame(peak_y[ob], P.H, P.Hf);
+                ax = to_frame(peak_x[oa], P.W, P.Wf), ay = to_frame(peak_y[oa], P.H, P.Hf);
+                bx = to_frame(peak_x[ob], P.W, P.Wf), by = to_frame(peak_y[ob], P.H, P.Hf);
                 rec.a = pack_xy(ax, ay);
                 rec.b = pack_xy(bx, by);
                 if (limb) {
@@ -139,31 +163,41 @@ __global__ __launch_bounds__(kListBlock) void k_draw_list(const int32_t *__restr
                     while ((r + 1) * (r + 1) <= v) ++r;
                     rec.cmax = (int)r;
                 }
-                const int reach = limb ? P.reach : P.radius;
-                const int tx0 = max(min(ax, bx) - reach, 0) / kTileW, tx1 = min((max(ax, bx) + reach) / kTileW, P.tiles_x - 1);
-                const int ty0 = max(min(ay, by) - reach, 0) / kTileH, ty1 = min((max(ay, by) + reach) / kTileH, P.tiles_y - 1);
-                for (int ty = ty0; ty <= ty1; ++ty)
-                    for (int tx = tx0; tx <= tx1; ++tx) {
-                        if (limb && far_from_line(rec.a, rec.b, rec.cmax, 2 * tx * kTileW + kTileW - 1,
-                                                  2 * ty * kTileH + kTileH - 1, kTileW - 1, kTileH - 1))
-                            continue;
-                        const int t = ty * P.tiles_x + tx;
-                        atomicOr(&s_mask[t >> 5], 1u << (t & 31));
-                    }
             }
         }
         int kept;
         const int pos = total + block_flag_scan(keep, s_scan, kept);
-        if (keep) out[pos] = rec;
         total += kept;
+        if (keep) {
+            out[pos] = rec;
+            // the tiles its bounding box meets, less those its line stays clear of, get it with its rank
+            const bool limb = rec.id < P.L;
+            DrawRecord ranked = rec;
+            ranked.id = rec.id | (pos << 7);
+            const int reach = limb ? P.reach : P.radius;
+            const int tx0 = max(min(ax, bx) - reach, 0) / kTileW, tx1 = min((max(ax, bx) + reach) / kTileW, P.tiles_x - 1);
+            const int ty0 = max(min(ay, by) - reach, 0) / kTileH, ty1 = min((max(ay, by) + reach) / kTileH, P.tiles_y - 1);
+            for (int ty = ty0; ty <= ty1; ++ty)
+                for (int tx = tx0; tx <= tx1; ++tx) {
+                    if (limb && far_from_line(rec.a, rec.b, rec.cmax, 2 * tx * kTileW + kTileW - 1,
+                                              2 * ty * kTileH + kTileH - 1, kTileW - 1, kTileH - 1))
+                        continue;
+                    const int t = ty * P.tiles_x + tx;
+                    const int at = atomicAdd(&handed[t], 1);
+                    if (at < kTileCap) tile_records[((size_t)n * P.tiles + t) * kTileCap + at] = ranked;
+                }
+        }
     }
     if (tid == 0) record_count[n] = total;
-    __syncthreads();
-    for (int i = tid; i < P.mask_words; i += kListBlock) tile_mask[(size_t)n * P.mask_words + i] = s_mask[i];
+    if (in_lds) {
+        __syncthreads();
+        for (int i = tid; i < P.tiles; i += kListBlock) tile_count_n[i] = s_tiles[i];
+    }
 }
 
 // floor(n / d) for d > 0, exact: the quotient of two 32-bit integers is either an integer (then the double
-// division is exact) or at least 1 / d away from one, far more than a double's rounding error.
+// division is exact) or at least 1 / d away from one, far more than a double's rounding error.  (A single-precision
+// estimate put right by the remainder was no faster: the kernel does not wait for this arithmetic.)
 __device__ __forceinline__ int floor_div(int n, int d) { return (int)floor((double)n / (double)d); }
 
 // Largest h >= 0 with h * h <= v (v >= 0, below 2^31).
@@ -233,10 +267,11 @@ template <int C, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_draw_tiles(const uint8_t *src, uint8_t *dst,   // may be the same buffer
                                                        const DrawRecord *__restrict__ records,
                                                        const int32_t *__restrict__ record_count,
-                                                       const uint32_t *__restrict__ tile_mask, DrawTables tab,
-                                                       DrawParams P)
+                                                       const int32_t *__restrict__ tile_count,
+                                                       const DrawRecord *__restrict__ tile_records,
+                                                       const uint32_t *__restrict__ rgb_table, DrawParams P)
 {
-    constexpr int kRound = 2 * kBlock;   // records looked at per round: two per thread, one memory round trip
+    constexpr int kRound = 2 * kBlock;   // records of the image's list looked at per round: two per thread
     __shared__ uint32_t s_rgb[HP_MAX_LIMBS + HP_MAX_PARTS];
     __shared__ DrawRecord s_rec[kRound];            // records that can meet the tile
     __shared__ int s_rank[kRound];                  // their ranks in painter's order
@@ -246,143 +281,188 @@ __global__ __launch_bounds__(kBlock) void k_draw_tiles(const uint8_t *src, uint8
     const int n = blockIdx.z;
     const int tid = threadIdx.x;
     const int tile_x0 = blockIdx.x * kTileW, tile_y0 = blockIdx.y * kTileH;
-    const int x0 = tile_x0 + 4 * (tid & 15), y = tile_y0 + (tid >> 4);   // this thread's four pixels
-    const bool inside = y < P.Hf && x0 < P.Wf;
+    // this thread's pixels: group g is (gx(g) + 0..3, gy(g))
+    auto gx = [&](int g) { return tile_x0 + 4 * (tid & 15) + 64 * (g % kTileGroupsX); };
+    auto gy = [&](int g) { return tile_y0 + (tid >> 4) + 16 * (g / kTileGroupsX); };
+    auto grow = [&](int g) { return ((size_t)n * P.Hf + gy(g)) * P.Wf + gx(g); };   // pixel index of the group's first
     const int r2 = P.radius * P.radius;
-    // tiles no primitive can touch (most of them) skip the records altogether
-    const int tile = blockIdx.y * P.tiles_x + blockIdx.x;
-    const int listed = record_count[n];   // read whether needed or not: one memory round trip for both words
-    const bool touched = (tile_mask[(size_t)n * P.mask_words + (tile >> 5)] >> (tile & 31)) & 1u;
-    const int count = touched ? min(listed, P.list_cap) : 0;
-    const DrawRecord *list = records + (size_t)n * P.list_cap;
+    // what the tile was handed: the count, and one record a thread, fetched whether it exists or not (the slot does),
+    // so that one memory round trip brings the count, the records and the pixels
+    const size_t tile = (size_t)n * P.tiles + blockIdx.y * P.tiles_x + blockIdx.x;
+    const int handed = tile_count[tile];
+    DrawRecord mine = {0, 0, 0, 0};
+    if (tid < kTileCap) mine = tile_records[tile * kTileCap + tid];
+    const uint32_t colour = tid < HP_MAX_LIMBS + HP_MAX_PARTS ? rgb_table[tid] : 0u;   // r | g << 8 | b << 16 of id `tid`
 
-    // this thread's pixels are on their way while the records are looked at
-    const size_t row = ((size_t)n * P.Hf + y) * P.Wf;
+    // this thread's pixels are on their way meanwhile
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (VEC && inside) {
-        if (C == 3) {
-            const uint32_t *s = (const uint32_t *)(src + (row + x0) * 3);
-            w[0] = __builtin_nontemporal_load(s);
-            w[1] = __builtin_nontemporal_load(s + 1);
-            w[2] = __builtin_nontemporal_load(s + 2);
-        } else {
-            const v4u v = __builtin_nontemporal_load((const v4u *)(src + (row + x0) * 4));
-            w[0] = v[0];
-            w[1] = v[1];
-            w[2] = v[2];
-            w[3] = v[3];
+    uint32_t w[kTileGroups][4];
+#pragma unroll
+    for (int g = 0; g < kTileGroups; ++g) {
+        w[g][0] = w[g][1] = w[g][2] = w[g][3] = 0;
+        if (VEC && gy(g) < P.Hf && gx(g) < P.Wf) {
+            if (C == 3) {
+                const uint32_t *s = (const uint32_t *)(src + grow(g) * 3);
+                w[g][0] = DRAW_LD(s);
+                w[g][1] = DRAW_LD(s + 1);
+                w[g][2] = DRAW_LD(s + 2);
+            } else {
+                const v4u v = DRAW_LD((const v4u *)(src + grow(g) * 4));
+                w[g][0] = v[0];
+                w[g][1] = v[1];
+                w[g][2] = v[2];
+                w[g][3] = v[3];
+            }
         }
     }
 
-    if (count > 0) {   // the same for every thread
-        if (tid == 0) {
-            // colours by id; tab is a kernel argument, so the copy goes through constant indices
-#pragma unroll
-            for (int i = 0; i < HP_MAX_LIMBS + HP_MAX_PARTS; ++i) s_rgb[i] = tab.rgb[i];
+    // (record, row) pairs of the first `kept` records in LDS: the covered interval of the row, clipped to the tile,
+    // raises the owners
+    auto paint = [&](int kept) {
+        const int pairs = kept * kTileH;
+        for (int task = tid; task < pairs; task += kBlock) {
+            const int k = task / kTileH, r = task - k * kTileH;
+            const DrawRecord rec = s_rec[k];
+            int xl, xr;
+            row_interval(rec, rec.id < P.L, tile_y0 + r, P.th2_quarter, r2, xl, xr);
+            xl = max(xl, tile_x0);
+            xr = min(xr, tile_x0 + kTileW - 1);
+            const int value = ((s_rank[k] + 1) << 7) | rec.id;
+            for (int x = xl; x <= xr; ++x) atomicMax(&s_owner[r * kTileW + x - tile_x0], value);
         }
+    };
+
+    if (handed > 0) {   // the same for every thread
+        if (tid < HP_MAX_LIMBS + HP_MAX_PARTS) s_rgb[tid] = colour;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s_owner[4 * tid + j] = 0;
-        for (int base = 0; base < count; base += kRound) {
-            if (tid == 0) s_kept = 0;
+        for (int j = 0; j < 4 * kTileGroups; ++j) s_owner[j * kBlock + tid] = 0;
+        if (handed <= kTileCap) {
+            if (tid < handed) {
+                s_rank[tid] = mine.id >> 7;
+                mine.id &= 127;
+                s_rec[tid] = mine;
+            }
             __syncthreads();
+            paint(handed);
+            __syncthreads();
+        } else {
+            // more than the tile could hold: the image's whole list, a round at a time
+            const int count = min(record_count[n], P.list_cap);
+            const DrawRecord *list = records + (size_t)n * P.list_cap;
+            for (int base = 0; base < count; base += kRound) {
+                if (tid == 0) s_kept = 0;
+                __syncthreads();
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const int q = base + half * kBlock + tid;
-                if (q < count) {
-                    const DrawRecord rec = list[q];
-                    const bool limb = rec.id < P.L;
-                    if (box_meets(rec.a, rec.b, limb ? P.reach : P.radius, tile_x0, tile_y0, kTileW, kTileH) &&
-                        !(limb && far_from_line(rec.a, rec.b, rec.cmax, 2 * tile_x0 + kTileW - 1,
-                                                2 * tile_y0 + kTileH - 1, kTileW - 1, kTileH - 1))) {
-                        const int pos = atomicAdd(&s_kept, 1);
-                        s_rec[pos] = rec;
-                        s_rank[pos] = q;
+                for (int half = 0; half < 2; ++half) {
+                    const int q = base + half * kBlock + tid;
+                    if (q < count) {
+                        const DrawRecord rec = list[q];
+                        const bool limb = rec.id < P.L;
+                        if (box_meets(rec.a, rec.b, limb ? P.reach : P.radius, tile_x0, tile_y0, kTileW, kTileH) &&
+                            !(limb && far_from_line(rec.a, rec.b, rec.cmax, 2 * tile_x0 + kTileW - 1,
+                                                    2 * tile_y0 + kTileH - 1, kTileW - 1, kTileH - 1))) {
+                            const int pos = atomicAdd(&s_kept, 1);
+                            s_rec[pos] = rec;
+                            s_rank[pos] = q;
+                        }
                     }
                 }
+                __syncthreads();
+                paint(s_kept);
+                __syncthreads();
             }
-            __syncthreads();
-            // (record, row) pairs: the covered interval of the row, clipped to the tile, raises the owners
-            const int pairs = s_kept * kTileH;
-            for (int task = tid; task < pairs; task += kBlock) {
-                const int k = task / kTileH, r = task - k * kTileH;
-                const DrawRecord rec = s_rec[k];
-                int xl, xr;
-                row_interval(rec, rec.id < P.L, tile_y0 + r, P.th2_quarter, r2, xl, xr);
-                xl = max(xl, tile_x0);
-                xr = min(xr, tile_x0 + kTileW - 1);
-                const int value = ((s_rank[k] + 1) << 7) | rec.id;
-                for (int x = xl; x <= xr; ++x) atomicMax(&s_owner[r * kTileW + x - tile_x0], value);
-            }
-            __syncthreads();
         }
     }
 
-    if (!inside) return;
-    int best[4] = {-1, -1, -1, -1};   // colour id per pixel
-    if (count > 0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int o = s_owner[4 * tid + j];
-            best[j] = o ? (o & 127) : -1;
-        }
-    }
-    if (VEC) {
-        // four whole pixels: 12 or 16 bytes at a 4-byte (C = 3) or 16-byte (C = 4) aligned address
-        if (C == 3) {
+    for (int g = 0; g < kTileGroups; ++g) {
+        const int xg = gx(g);
+        if (xg >= P.Wf || gy(g) >= P.Hf) continue;
+        const size_t row = grow(g) - xg;
+        int best[4] = {-1, -1, -1, -1};   // colour id per pixel
+        if (handed > 0) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (best[j] < 0) continue;
-                const uint32_t rgb = s_rgb[best[j]];
-#pragma unroll
-                for (int ch = 0; ch < 3; ++ch) {
-                    const int byte = 3 * j + ch;
-                    w[byte >> 2] = (w[byte >> 2] & ~(0xFFu << (8 * (byte & 3)))) |
-                                   (((rgb >> (8 * ch)) & 0xFFu) << (8 * (byte & 3)));
-                }
+                const int o = s_owner[(gy(g) - tile_y0) * kTileW + xg - tile_x0 + j];
+                best[j] = o ? (o & 127) : -1;
             }
-            uint32_t *d = (uint32_t *)(dst + (row + x0) * 3);
-            __builtin_nontemporal_store(w[0], d);
-            __builtin_nontemporal_store(w[1], d + 1);
-            __builtin_nontemporal_store(w[2], d + 2);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (best[j] >= 0) w[j] = (w[j] & 0xFF000000u) | s_rgb[best[j]];
-            v4u v = {w[0], w[1], w[2], w[3]};
-            __builtin_nontemporal_store(v, (v4u *)(dst + (row + x0) * 4));
         }
-    } else {
-        for (int j = 0; j < 4 && x0 + j < P.Wf; ++j) {
-            const uint8_t *s = src + (row + x0 + j) * C;
-            uint8_t *d = dst + (row + x0 + j) * C;
-            uint8_t v[C];
+        if (VEC) {
+            // four whole pixels: 12 or 16 bytes at a 4-byte (C = 3) or 16-byte (C = 4) aligned address
+            if (C == 3) {
 #pragma unroll
-            for (int ch = 0; ch < C; ++ch) v[ch] = s[ch];
-            if (best[j] >= 0) {
-                const uint32_t rgb = s_rgb[best[j]];
+                for (int j = 0; j < 4; ++j) {
+                    if (best[j] < 0) continue;
+                    const uint32_t rgb = s_rgb[best[j]];
 #pragma unroll
-                for (int ch = 0; ch < 3; ++ch) v[ch] = (uint8_t)(rgb >> (8 * ch));
+                    for (int ch = 0; ch < 3; ++ch) {
+                        const int byte = 3 * j + ch;
+                        w[g][byte >> 2] = (w[g][byte >> 2] & ~(0xFFu << (8 * (byte & 3)))) |
+                                          (((rgb >> (8 * ch)) & 0xFFu) << (8 * (byte & 3)));
+                    }
+                }
+                uint32_t *d = (uint32_t *)(dst + (row + xg) * 3);
+                DRAW_ST(w[g][0], d);
+                DRAW_ST(w[g][1], d + 1);
+                DRAW_ST(w[g][2], d + 2);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (best[j] >= 0) w[g][j] = (w[g][j] & 0xFF000000u) | s_rgb[best[j]];
+                v4u v = {w[g][0], w[g][1], w[g][2], w[g][3]};
+                DRAW_ST(v, (v4u *)(dst + (row + xg) * 4));
             }
+        } else {
+            for (int j = 0; j < 4 && xg + j < P.Wf; ++j) {
+                const uint8_t *s = src + (row + xg + j) * C;
+                uint8_t *d = dst + (row + xg + j) * C;
+                uint8_t v[C];
 #pragma unroll
-            for (int ch = 0; ch < C; ++ch) d[ch] = v[ch];
+                for (int ch = 0; ch < C; ++ch) v[ch] = s[ch];
+                if (best[j] >= 0) {
+                    const uint32_t rgb = s_rgb[best[j]];
+#pragma unroll
+                    for (int ch = 0; ch < 3; ++ch) v[ch] = (uint8_t)(rgb >> (8 * ch));
+                }
+#pragma unroll
+                for (int ch = 0; ch < C; ++ch) d[ch] = v[ch];
+            }
         }
     }
 }
 
-// Workspace: [N record counts][N tile masks][N x list_cap records], each part on a 256-byte boundary.
+// Workspace: [colours by id][N record counts][N x tiles tile counts][N x list_cap records][N x tiles x kTileCap tile records], each
+// part on a 256-byte boundary.
 static size_t pad256(size_t v) { return (v + 255) / 256 * 256; }
-static uint32_t *mask_of(void *workspace, int N) { return (uint32_t *)((char *)workspace + pad256((size_t)N * sizeof(int32_t))); }
-static DrawRecord *records_of(void *workspace, int N, int mask_words)
+static size_t frame_tiles(int Hf, int Wf) { return (size_t)((Wf + kTileW - 1) / kTileW) * ((Hf + kTileH - 1) / kTileH); }
+struct DrawWork {
+    uint32_t *rgb_table;
+    int32_t *record_count, *tile_count;
+    DrawRecord *records, *tile_records;
+    size_t bytes;
+};
+static DrawWork draw_layout(void *workspace, int N, int list_cap, size_t tiles)
 {
-    return (DrawRecord *)((char *)mask_of(workspace, N) + pad256((size_t)N * mask_words * sizeof(uint32_t)));
+    DrawWork w;
+    char *p = (char *)workspace;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *q = p ? p + off : nullptr;
+        off += pad256(bytes);
+        return q;
+    };
+    w.rgb_table = (uint32_t *)take((HP_MAX_LIMBS + HP_MAX_PARTS) * sizeof(uint32_t));
+    w.record_count = (int32_t *)take((size_t)N * sizeof(int32_t));
+    w.tile_count = (int32_t *)take((size_t)N * tiles * sizeof(int32_t));
+    w.records = (DrawRecord *)take((size_t)N * list_cap * sizeof(DrawRecord));
+    w.tile_records = (DrawRecord *)take((size_t)N * tiles * kTileCap * sizeof(DrawRecord));
+    w.bytes = off;
+    return w;
 }
 
 size_t draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf)
 {
-    const size_t tiles = (size_t)((Wf + kTileW - 1) / kTileW) * ((Hf + kTileH - 1) / kTileH);
-    return pad256((size_t)N * sizeof(int32_t)) + pad256((size_t)N * ((tiles + 31) / 32) * sizeof(uint32_t)) +
-           (size_t)N * pcap * (K + L) * sizeof(DrawRecord);
+    return draw_layout(nullptr, N, pcap * (K + L), frame_tiles(Hf, Wf)).bytes;
 }
 
 static void draw_setup(int Hf, int Wf, int H, int W, const LimbTable &T, int K, int L, const hp_peaks &pk,
@@ -411,45 +491,49 @@ static void draw_setup(int Hf, int Wf, int H, int W, const LimbTable &T, int K, 
     P.list_cap = poses.cap * (K + L);
     P.tiles_x = (Wf + kTileW - 1) / kTileW;
     P.tiles_y = (Hf + kTileH - 1) / kTileH;
-    P.mask_words = (P.tiles_x * P.tiles_y + 31) / 32;
+    P.tiles = P.tiles_x * P.tiles_y;
 }
 
 hipError_t launch_draw_list(int N, int Hf, int Wf, int H, int W, const LimbTable &T, int K, int L, const hp_peaks &pk,
-                            const hp_poses &poses, int thickness, int radius, void *workspace, hipStream_t s)
-{
-    DrawTables tab;
-    DrawParams P;
-    const uint8_t none[3 * (HP_MAX_LIMBS + HP_MAX_PARTS)] = {0};   // the list holds no colours
-    draw_setup(Hf, Wf, H, W, T, K, L, pk, poses, none, none, thickness, radius, tab, P);
-    HP_KERNEL(k_draw_list, dim3(N), dim3(kListBlock), P.mask_words * sizeof(uint32_t), s, pk.x, pk.y, poses.slots, poses.count, tab, P,
-              records_of(workspace, N, P.mask_words), (int32_t *)workspace, mask_of(workspace, N));
-    return hipGetLastError();
-}
-
-hipError_t launch_draw_tiles(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
-                             const LimbTable &T, int K, int L, const hp_peaks &pk, const hp_poses &poses,
-                             const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
-                             const void *workspace, hipStream_t s)
+                            const hp_poses &poses, const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness,
+                            int radius, void *workspace, hipStream_t s)
 {
     DrawTables tab;
     DrawParams P;
     draw_setup(Hf, Wf, H, W, T, K, L, pk, poses, limb_rgb, part_rgb, thickness, radius, tab, P);
-    const DrawRecord *records = records_of((void *)workspace, N, P.mask_words);
-    const int32_t *record_count = (const int32_t *)workspace;
-    const uint32_t *tile_mask = mask_of((void *)workspace, N);
+    const DrawWork ws = draw_layout(workspace, N, P.list_cap, (size_t)P.tiles);
+    const size_t lds = P.tiles <= kListBinTiles ? (size_t)P.tiles * sizeof(int) : 0;
+    HP_KERNEL(k_draw_list, dim3(N), dim3(kListBlock), lds, s, pk.x, pk.y, poses.slots, poses.count, tab, P, ws.records,
+              ws.record_count, ws.tile_count, ws.tile_records, ws.rgb_table);
+    return hipGetLastError();
+}
+
+hipError_t launch_draw_tiles(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
+                             const LimbTable &T, int K, int L, const hp_peaks &pk, const hp_poses &poses, int thickness,
+                             int radius, const void *workspace, hipStream_t s)
+{
+    DrawTables tab;   // the colours are in the workspace by now
+    DrawParams P;
+    const uint8_t none[3 * (HP_MAX_LIMBS + HP_MAX_PARTS)] = {0};
+    draw_setup(Hf, Wf, H, W, T, K, L, pk, poses, none, none, thickness, radius, tab, P);
+    const DrawWork ws = draw_layout((void *)workspace, N, P.list_cap, (size_t)P.tiles);
     const dim3 grid((Wf + kTileW - 1) / kTileW, (Hf + kTileH - 1) / kTileH, N);
     const uintptr_t bits = (uintptr_t)src | (uintptr_t)dst;
     const bool vec = (Wf % 4) == 0 && (bits & (C == 4 ? 15 : 3)) == 0;
     if (C == 3) {
         if (vec)
-            HP_KERNEL((k_draw_tiles<3, true>), grid, dim3(kBlock), 0, s, src, dst, records, record_count, tile_mask, tab, P);
+            HP_KERNEL((k_draw_tiles<3, true>), grid, dim3(kBlock), 0, s, src, dst, ws.records, ws.record_count, ws.tile_count,
+                      ws.tile_records, ws.rgb_table, P);
         else
-            HP_KERNEL((k_draw_tiles<3, false>), grid, dim3(kBlock), 0, s, src, dst, records, record_count, tile_mask, tab, P);
+            HP_KERNEL((k_draw_tiles<3, false>), grid, dim3(kBlock), 0, s, src, dst, ws.records, ws.record_count, ws.tile_count,
+                      ws.tile_records, ws.rgb_table, P);
     } else {
         if (vec)
-            HP_KERNEL((k_draw_tiles<4, true>), grid, dim3(kBlock), 0, s, src, dst, records, record_count, tile_mask, tab, P);
+            HP_KERNEL((k_draw_tiles<4, true>), grid, dim3(kBlock), 0, s, src, dst, ws.records, ws.record_count, ws.tile_count,
+                      ws.tile_records, ws.rgb_table, P);
         else
-            HP_KERNEL((k_draw_tiles<4, false>), grid, dim3(kBlock), 0, s, src, dst, records, record_count, tile_mask, tab, P);
+            HP_KERNEL((k_draw_tiles<4, false>), grid, dim3(kBlock), 0, s, src, dst, ws.records, ws.record_count, ws.tile_count,
+                      ws.tile_records, ws.rgb_table, P);
     }
     return hipGetLastError();
 }

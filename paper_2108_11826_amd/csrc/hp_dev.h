@@ -207,11 +207,11 @@ hipError_t launch_preprocess(const uint8_t *src, int N, int Hs, int Ws, int C, h
 // limb_rgb / part_rgb are host arrays of L x 3 and K x 3 bytes.
 size_t draw_workspace_bytes(int N, int K, int L, int pcap, int Hf, int Wf);
 hipError_t launch_draw_list(int N, int Hf, int Wf, int H, int W, const LimbTable &T, int K, int L, const hp_peaks &pk,
-                            const hp_poses &poses, int thickness, int radius, void *workspace, hipStream_t s);
+                            const hp_poses &poses, const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness,
+                            int radius, void *workspace, hipStream_t s);
 hipError_t launch_draw_tiles(const uint8_t *src, uint8_t *dst, int N, int Hf, int Wf, int C, int H, int W,
-                             const LimbTable &T, int K, int L, const hp_peaks &pk, const hp_poses &poses,
-                             const uint8_t *limb_rgb, const uint8_t *part_rgb, int thickness, int radius,
-                             const void *workspace, hipStream_t s);
+                             const LimbTable &T, int K, int L, const hp_peaks &pk, const hp_poses &poses, int thickness,
+                             int radius, const void *workspace, hipStream_t s);
 
 // Separable smoothing of channels [0, C) of fp32 maps [N][C_mem][H][W]; taps is a device array of n_taps (odd) floats.
 hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, int H, int W, const float *taps,

@@ -452,7 +452,8 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
 // pair, all pairs of the limb spread over the workgroup's threads.  With a few hundred pairs per limb a launch is
 // a chain of dependent memory round trips, and the tiled scorer above spends a dozen of them (screen sample, then a
 // survivor's samples one or two at a time).  Here the chain is: the peak lists; the PAF at every peak; the pairs
-// through score_pair_ends (two fetch rounds for nearly all of them).  Same candidates as the oracle's loop, bit for bit.
+// through score_pair_ends (two fetch rounds for nearly all of them).  Same candidates as the definition's
+// sample-by-sample loop, bit for bit.
 constexpr int kFlatPeaks = 256;
 constexpr int kFlatBlock = 1024;
 

@@ -86,6 +86,7 @@ def scene(rng, N, K, L, cap, pcap, H, W, persons, missing):
     (3, COCO18, 8, [3], (1, 1), 3, 1, 0),
     (4, BODY25, 64, [64, 64], (200, 300), 4, 40, 25),          # primitives larger than tiles
     (5, COCO18, 32, [9, 32, 0, 5], (48, 64), 3, 0, 0),
+    (6, COCO18, 8, [8], (2304, 4096), 3, 6, 5),                # more tiles than the list kernel counts in LDS
 ])
 def test_random_scenes(seed, sk, pcap, persons, frame, C, thickness, radius):
     m = hp()
