@@ -194,15 +194,16 @@ def main():
         warm = max(args.warmup, 2 * len(calls)) if warm is None else warm
         for i in range(warm):
             calls[i % len(calls)]()
-        main = torch.cuda.current_stream()
+        # the window opens on the first of the streams and the others wait for that event: the default stream stays
+        # out of it (a process has four hardware queues here; a fifth stream would share one with a lane)
+        first = streams[0]
         per_call = []
         for _ in range(windows):
             torch.cuda.synchronize()
             start = torch.cuda.Event(enable_timing=True)
-            start.record(main)
-            for st in streams:
-                if st is not main:
-                    st.wait_event(start)
+            start.record(first)
+            for st in streams[1:]:
+                st.wait_event(start)
             for i in range(calls_per_window):
                 calls[i % len(calls)]()
             ends = []
