@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--streams", type=int, default=3, help="HIP streams the timed steps are spread over")
     ap.add_argument("--no-streaming", action="store_true", help="skip the streaming-front measurement")
     ap.add_argument("--no-traffic", action="store_true", help="skip the rocprofv3 child runs that count HBM bytes")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other workloads (a kernel profile of one workload wants them out)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the operators around the hot path (pre-processing, smoothing, drawing, the other two "
                          "algorithm classes, the streaming front) and the other workloads")
@@ -424,7 +426,7 @@ def main():
 
     # ---- the other four workloads: fused form, same streams and window scheme (shorter), parity with the oracle ----
     other_configs = None
-    if not args.no_extras:
+    if not args.no_extras and not args.no_other_configs:
         other_configs = {}
         for ci in range(len(CONFIGS)):
             if ci == args.config:
