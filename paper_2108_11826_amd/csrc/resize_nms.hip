@@ -42,17 +42,16 @@ __device__ __forceinline__ void emit_peak(int32_t *counts, uint64_t *stage, int 
 // nodes (m, m+1) with weight (2t-7)/16 for t >= 4; left of node 0 the weight is 0 and right
 // of node w-1 the upper node is clamped.  Rows alike.
 
+// The nine nodes around node (j, m) = node t of a plane (t = j w + m): offsets from the plane's first node, no multiply.
 template <typename T>
-__device__ __forceinline__ void load_nodes(const T *pl, int h, int w, int j, int m, float (&lo9)[3][3])
+__device__ __forceinline__ void load_nodes(const T *pl, int h, int w, int j, int m, int t, float (&lo9)[3][3])
 {
-    const int jr[3] = {max(j - 1, 0), j, min(j + 1, h - 1)};
+    const int row[3] = {j > 0 ? t - m - w : t - m, t - m, j < h - 1 ? t - m + w : t - m};
     const int mc[3] = {max(m - 1, 0), m, min(m + 1, w - 1)};
 #pragma unroll
-    for (int r = 0; r < 3; ++r) {
-        const T *row = pl + (size_t)jr[r] * w;
+    for (int r = 0; r < 3; ++r)
 #pragma unroll
-        for (int k = 0; k < 3; ++k) lo9[r][k] = ld(row + mc[k]);
-    }
+        for (int k = 0; k < 3; ++k) lo9[r][k] = ld(pl + (unsigned)(row[r] + mc[k]));
 }
 
 // Every value of a tile and its halo is a convex combination of its nine nodes, formed with
@@ -70,21 +69,25 @@ __device__ __forceinline__ bool tile_may_peak(const float (&lo9)[3][3], float th
 }
 
 // Upsamples one tile (with halo) from its nine nodes into v[10][6]: v[r+1][k] is row 8j+r,
-// column 8m+4hf-1+k.
+// column 8m+4hf-1+k.  Column k = 0 always reads nodes (m-1, m), column 5 always (m, m+1); columns 1..4 read
+// (m-1, m) in the left half tile (hf = 0) and (m, m+1) in the right one, so the half decides a pair of nodes per
+// source row and six weights once, instead of every column choosing its nodes for itself.
 __device__ __forceinline__ void upsample_tile(const float (&lo9)[3][3], int j, int m, int hf, float (&v)[10][6])
 {
+    const bool right = hf != 0, edge = m == 0;     // left of node 0 the weight is 0
+    float fx[6];
+    fx[0] = edge ? 0.0f : (right ? 15.0f : 7.0f) * 0.0625f;
+#pragma unroll
+    for (int k = 1; k <= 4; ++k) fx[k] = right ? (float)(2 * k - 1) * 0.0625f : (edge ? 0.0f : (float)(2 * k + 7) * 0.0625f);
+    fx[5] = right ? 9.0f * 0.0625f : 0.0625f;
     float hr[3][6];
 #pragma unroll
-    for (int k = 0; k < 6; ++k) {
-        const int t = 4 * hf - 1 + k;
-        const bool lft = t <= 3;
-        const float fx = lft ? (m == 0 ? 0.0f : (float)(2 * t + 9) * 0.0625f) : (float)(2 * t - 7) * 0.0625f;
+    for (int r = 0; r < 3; ++r) {
+        const float p = right ? lo9[r][1] : lo9[r][0], q = right ? lo9[r][2] : lo9[r][1];
+        hr[r][0] = __fmaf_rn(fx[0], lo9[r][1], (1.0f - fx[0]) * lo9[r][0]);
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-            const float a = lft ? lo9[r][0] : lo9[r][1];
-            const float b = lft ? lo9[r][1] : lo9[r][2];
-            hr[r][k] = __fmaf_rn(fx, b, (1.0f - fx) * a);
-        }
+        for (int k = 1; k <= 4; ++k) hr[r][k] = __fmaf_rn(fx[k], q, (1.0f - fx[k]) * p);
+        hr[r][5] = __fmaf_rn(fx[5], lo9[r][2], (1.0f - fx[5]) * lo9[r][1]);
     }
 #pragma unroll
     for (int r = -1; r <= 8; ++r) {
@@ -253,60 +256,83 @@ __global__ __launch_bounds__(1024) void k_resize_write(const T *__restrict__ lo_
 }
 
 // Fused form: nothing is written but peaks.  Every wavefront works by itself on NP * 64 consecutive lo-res nodes
-// of the K searched channels (no workgroup barrier).  Phase 1, NP nodes per lane, their loads in flight together:
-// can the node's two tiles hold a peak at all?  The nodes that can are compacted, with their nine values, into a
-// list in the wavefront's own piece of LDS (places from ballots); phase 2 spreads the list's tiles densely over the
-// lanes, so the upsampling and the 3x3 test are only paid where the map rises to the threshold, and a wavefront
-// whose nodes are all below it leaves after one round of loads.
+// of one searched plane (no workgroup barrier; the plane comes from the block index, channel and image).  Phase 1,
+// NP nodes per lane, their loads in flight together: can the node's two tiles hold a peak at all?  The nodes that can
+// are compacted, with their nine values, into a list in the wavefront's own piece of LDS (places from ballots);
+// phase 2 spreads the list's tiles densely over the lanes, so the upsampling and the 3x3 test are only paid where the
+// map rises to the threshold, and a wavefront whose nodes are all below it leaves after one round of loads.
+// The kernel issues 4 M vector instructions a launch at the benchmark's size and is bound by that more than by
+// anything else, so the index arithmetic is kept small: a node's row and column come from one single-precision
+// quotient put right by its remainder (three integer divisions a node, for column, row and plane, were a third of
+// phase 1), and its neighbours' offsets from additions.
 // (Six wavefronts per SIMD: the 80 registers that leaves still hold a tile without spilling.)
 constexpr int kNmsWaves = kBlock / kWave;
-constexpr int kEntWords = 13;        // 9 values + row, column, plane; odd stride: no LDS bank conflicts
+constexpr int kEntWords = 11;        // 9 values + row, column; odd stride: no LDS bank conflicts
 
 template <typename T, int NP>
-__global__ __launch_bounds__(kBlock, 6) void k_resize_nms(const T *__restrict__ lo, int total_nodes, int K,
-                                                       int C_mem, int h, int w, float thr, int32_t *counts,
-                                                       uint64_t *stage, int cap, int cap2, int32_t *status)
+__global__ __launch_bounds__(kBlock, 6) void k_resize_nms(const T *__restrict__ lo, int K, int C_mem, int h, int w,
+                                                       float thr, int32_t *counts, uint64_t *stage, int cap,
+                                                       int cap2, int32_t *status)
 {
     __shared__ uint32_t ent_all[kNmsWaves][NP * kWave][kEntWords];
     // first kernel of hp_postprocess: it clears the status word (no kernel of this launch sets bits)
-    if (status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
-    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+    if (status && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *status = 0;
+    const int lane = threadIdx.x & (kWave - 1), wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t(*ent)[kEntWords] = ent_all[wv];
-    const int node0 = (blockIdx.x * kNmsWaves + wv) * (NP * kWave);
-    if (node0 >= total_nodes) return;
+    const int hw = h * w;
+    const int t0 = (blockIdx.x * kNmsWaves + wv) * (NP * kWave);          // first node of this wavefront in its plane
+    if (t0 >= hw) return;
+    const int c = blockIdx.y, n = blockIdx.z, plane = n * K + c;
+    const T *pl = lo + ((size_t)n * C_mem + c) * (size_t)hw;
     const unsigned long long below = (1ull << lane) - 1ull;
+    const float inv_w = 1.0f / (float)w;
+    const bool exact_in_float = hw <= (1 << 24);                          // every node index is a float then
 
     // two nodes per lane at a time: their loads are in flight together and the registers still hold a tile later
     constexpr int kPer = NP < 2 ? NP : 2;
     int n_ent = 0;
     for (int u0 = 0; u0 < NP; u0 += kPer) {
         float lo9[kPer][3][3];
-        int jj[kPer], mm[kPer], pl[kPer];
+        int jj[kPer], mm[kPer];
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
-            // nodes beyond the end repeat the last one (their verdict is dropped)
-            int q = min(node0 + (u0 + u) * kWave + lane, total_nodes - 1);
-            mm[u] = q % w; q /= w;
-            jj[u] = q % h; q /= h;
-            pl[u] = q;                                   // n * K + c
-            const int c = q % K, n = q / K;
-            load_nodes(lo + ((size_t)n * C_mem + c) * (size_t)h * w, h, w, jj[u], mm[u], lo9[u]);
+            // nodes beyond the plane's end repeat its last one (their verdict is dropped)
+            const int t = min(t0 + (u0 + u) * kWave + lane, hw - 1);
+            int j, m;
+            if (exact_in_float) {
+                // t / w to within one unit; the remainder says which way
+                j = (int)((float)t * inv_w);
+                m = t - __mul24(j, w);
+                if (m < 0) {
+                    --j;
+                    m += w;
+                }
+                if (m >= w) {
+                    ++j;
+                    m -= w;
+                }
+            } else {
+                j = t / w;
+                m = t - j * w;
+            }
+            jj[u] = j;
+            mm[u] = m;
+            load_nodes(pl, h, w, j, m, t, lo9[u]);
         }
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
-            const bool act = node0 + (u0 + u) * kWave + lane < total_nodes && tile_may_peak(lo9[u], thr);
-            const unsigned long long m = __ballot(act);
+            const bool act = t0 + (u0 + u) * kWave + lane < hw && tile_may_peak(lo9[u], thr);
+            const unsigned long long mk = __ballot(act);
             if (act) {
-                uint32_t *e = ent[n_ent + __popcll(m & below)];
+                uint32_t *e = ent[n_ent + __popcll(mk & below)];
 #pragma unroll
                 for (int r = 0; r < 3; ++r)
 #pragma unroll
                     for (int k = 0; k < 3; ++k) e[3 * r + k] = __float_as_uint(lo9[u][r][k]);
                 e[9] = (uint32_t)jj[u];
                 e[10] = (uint32_t)mm[u];
-                e[11] = (uint32_t)pl[u];
             }
-            n_ent += __popcll(m);
+            n_ent += __popcll(mk);
         }
     }
     if (n_ent == 0) return;
@@ -324,7 +350,7 @@ __global__ __launch_bounds__(kBlock, 6) void k_resize_nms(const T *__restrict__ 
         for (int r = 0; r < 3; ++r)
 #pragma unroll
             for (int k = 0; k < 3; ++k) v9[r][k] = __uint_as_float(e[3 * r + k]);
-        const int j = (int)e[9], m = (int)e[10], plane = (int)e[11];
+        const int j = (int)e[9], m = (int)e[10];
         float v[10][6];
         upsample_tile(v9, j, m, hf, v);
         tile_peaks(v, j, h, 8 * m + 4 * hf, 8 * j, W, thr, counts, stage, plane, cap, cap2);
@@ -383,15 +409,16 @@ template <typename T>
 static hipError_t launch_resize_nms_t(const T *lo, int N, int K, int C_mem, int h, int w, float thr, int32_t *counts,
                                       uint64_t *stage, int cap, int cap2, int32_t *status, hipStream_t s)
 {
-    long long nodes64 = (long long)N * K * h * w;
-    if (nodes64 <= 0 || nodes64 >= (1LL << 31) - kBlock) return hipErrorInvalidValue;
-    int nodes = (int)nodes64;
+    const long long hw = (long long)h * w;
+    if (hw <= 0 || hw >= (1LL << 31) - 4 * kBlock || h >= (1 << 24) || w >= (1 << 24) || K <= 0 || K > 65535 || N <= 0 ||
+        N > 65535)
+        return hipErrorInvalidValue;
     // two nodes per lane: measured against one, four and eight on the five workloads (equal on the small ones, 13-19 %
     // faster on the large ones, where the tiles of a wavefront's survivors fill its lanes better)
     constexpr int NP = 2;
     constexpr int per_block = kBlock * NP;
-    HP_KERNEL((k_resize_nms<T, NP>), dim3((nodes + per_block - 1) / per_block), dim3(kBlock), 0, s, lo, nodes, K, C_mem,
-                       h, w, thr, counts, stage, cap, cap2, status);
+    HP_KERNEL((k_resize_nms<T, NP>), dim3((unsigned)((hw + per_block - 1) / per_block), K, N), dim3(kBlock), 0, s, lo, K, C_mem,
+              h, w, thr, counts, stage, cap, cap2, status);
     return hipGetLastError();
 }
 
