@@ -572,22 +572,28 @@ __device__ __forceinline__ int wave_greedy_match(const uint64_t *keys, int c, in
         // indices beyond the peak lists are only possible for candidate lists this library did not write
         bool ok = have && i < (uint32_t)nA && j < (uint32_t)nB;
         if (ok && more_chunks) ok = !((usedA[i >> 5] >> (i & 31)) & 1u) && !((usedB[j >> 5] >> (j & 31)) & 1u);
-        unsigned long long alive = __ballot(ok);
-        while (alive && m < limit) {
+        unsigned long long alive = __ballot(ok), accepted = 0ull;
+        int taken = 0;
+        // the chain itself is scalar work and two lane reads a connection; what the accepted lanes have to store waits
+        // until the chunk is through (stores inside the loop put a dozen more instructions on every step of the chain)
+        while (alive && m + taken < limit) {
             const int r = __ffsll((long long)alive) - 1;
             const uint32_t ir = __builtin_amdgcn_readlane(i, r), jr = __builtin_amdgcn_readlane(j, r);
-            if (lane == r) {
-                mi[m] = (int32_t)i;
-                mj[m] = (int32_t)j;
-                ms[m] = __uint_as_float(~(uint32_t)(e >> 32));
-                if (more_chunks) {
-                    usedA[i >> 5] |= 1u << (i & 31);
-                    usedB[j >> 5] |= 1u << (j & 31);
-                }
-            }
-            ++m;
+            accepted |= 1ull << r;
+            ++taken;
             alive &= ~__ballot(i == ir || j == jr);
         }
+        if ((accepted >> lane) & 1ull) {
+            const int at = m + __popcll(accepted & ((1ull << lane) - 1ull));     // acceptance order = lane order
+            mi[at] = (int32_t)i;
+            mj[at] = (int32_t)j;
+            ms[at] = __uint_as_float(~(uint32_t)(e >> 32));
+            if (more_chunks) {
+                atomicOr(&usedA[i >> 5], 1u << (i & 31));
+                atomicOr(&usedB[j >> 5], 1u << (j & 31));
+            }
+        }
+        m += taken;
         // the bit maps are written and read by this wavefront only
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
