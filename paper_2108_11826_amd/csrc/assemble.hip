@@ -328,20 +328,27 @@ __global__ __launch_bounds__(kAsmBlock) void k_assemble(LimbTable tab, int K, in
                     owner[wa ? oa : spare_o] = (int16_t)(wa ? p : -1);
                     slots[(wb ? p : spare_p) * K + b] = (int16_t)(ob - row_b);
                     owner[wb ? ob : spare_o] = (int16_t)(wb ? p : -1);
-                    if (__any(mrg)) {
+                    unsigned long long merging = __ballot(mrg);
+                    if (merging) {
+                        // the survivor is the earlier person; it takes the other's parts, one merge at a time with a
+                        // lane a part (the merges of one limb concern different persons, so their order is free; a
+                        // merging lane walking its person's parts by itself took a microsecond a limb)
+                        const int lo = min(pa, pb), hi = max(pa, pb);
+                        const uint32_t mhi = pa < pb ? mb : ma;
                         if (mrg) {
-                            const int lo = min(pa, pb), hi = max(pa, pb);
-                            const uint32_t mhi = pa < pb ? mb : ma;
-                            for (int c = 0; c < K; ++c) {
-                                if (mhi & (1u << c)) {
-                                    const int16_t rr = slots[hi * K + c];
-                                    slots[lo * K + c] = rr;
-                                    owner[c * cmax + rr] = (int16_t)lo;
-                                }
-                            }
                             const float scm = (pa < pb) ? sca + scb : scb + sca;
                             pst[lo] = make_uint2(ma | mb, __float_as_uint(scm + s));
                             pst[hi] = make_uint2(kDead, 0u);
+                        }
+                        for (; merging; merging &= merging - 1ull) {
+                            const int r = __ffsll((long long)merging) - 1;
+                            const int lo_r = __builtin_amdgcn_readlane(lo, r), hi_r = __builtin_amdgcn_readlane(hi, r);
+                            const uint32_t parts = (uint32_t)__builtin_amdgcn_readlane((int)mhi, r);
+                            if (lane < K && ((parts >> lane) & 1u)) {
+                                const int16_t rr = slots[hi_r * K + lane];
+                                slots[lo_r * K + lane] = rr;
+                                owner[lane * cmax + rr] = (int16_t)lo_r;
+                            }
                         }
                     }
                     np += __popcll(fm);
