@@ -149,15 +149,21 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
 }
 
 // The marching form, for the usual tap counts on maps whose rows are whole 16-byte groups.  A wavefront owns a
-// strip of up to 256 columns (four neighbouring columns per lane) of a band of rows and walks down it one source row
-// at a time.  A step: the row's 16-byte pieces (fetched T or more steps earlier into registers that are refilled in
-// place) go to a row buffer in the wavefront's own LDS; every lane reads back its window of 4 + 2r values and filters
-// its four outputs horizontally; the filtered values are then added, tap by tap, to the T output rows they belong to,
-// whose running sums live in registers; the output row whose last tap this was is stored.  A sum receives its taps in
-// the order the source rows arrive, which is ascending tap order, starting from 0: the same bits as the definition.
-// The row loop is unrolled T-fold (a multiple of it for few taps) so that every register has a fixed name.  No
-// workgroup barrier, one LDS write and (4 + 2r) / 4 + 1 LDS reads per row and lane against 8 T multiply-adds, no
-// horizontally filtered row is computed twice except the 2r rows between two bands, and the stores are whole rows.
+// strip of a band of rows and walks down it one source row at a time; its 64 lanes hold 256 neighbouring columns, four
+// a lane, of which the outer rp on either side (r rounded up to whole 16-byte pieces) are only read: neighbouring
+// strips overlap by that much, so a lane never fetches anything but its own piece.  A step: the row's 16-byte pieces
+// (fetched T or more steps earlier into registers that are refilled in place) go to a row buffer in the wavefront's
+// own LDS; every lane reads back its window of 4 + 2 rp values and filters its four outputs horizontally; the
+// filtered values are then added, tap by tap, to the T output rows they belong to, whose running sums live in
+// registers; the output row whose last tap this was is stored.  A sum receives its taps in the order the source rows
+// arrive, which is ascending tap order, starting from 0: the same bits as the definition.
+// The row loop is unrolled T-fold (a multiple of it for few taps) so that every register has a fixed name, and a
+// step is straight-line code, the same for every lane (columns outside the map read the clamped piece and repeat its
+// edge pixel), so that the loads of later rows stay in flight across it.  No workgroup barrier, one LDS write and
+// (4 + 2 rp) / 4 LDS reads per row and lane against 8 T multiply-adds, no horizontally filtered row is computed twice
+// except the 2r rows between two bands, and the stores are whole rows.
+// (With separate loads for the pieces left and right of a strip, kept in registers like the others, the 17-tap kernel
+// needed 276 registers: one wavefront a SIMD, 95 us for the benchmark's maps.)
 constexpr int kMarchBlock = 256, kMarchWaves = kMarchBlock / kWave;
 
 // f(integral_constant<0>), f(integral_constant<1>), ...: a loop whose counter is a constant in every round
@@ -176,10 +182,10 @@ __global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 
                                                               int strips, int sw, int bands, int band)
 {
     constexpr int r = (T - 1) / 2, rp = (r + 3) & ~3, o0 = rp - r;
-    constexpr int U = T * ((10 + T - 1) / T);            // rows per pass through the unrolled loop (16 bytes x 2 x U in registers)
+    constexpr int U = T * ((10 + T - 1) / T);            // rows per pass through the unrolled loop (16 bytes x U in registers)
     constexpr int kWin = 2 * rp + 4;                     // floats a lane reads back per row
-    constexpr int kBuf = 4 * kWave + 2 * rp + 4;         // floats per row buffer (+ 4 that take the writes of idle lanes)
-    __shared__ __attribute__((aligned(16))) float bufs[kMarchWaves][kBuf + 4];
+    constexpr int kBuf = 4 * kWave + 2 * rp;             // floats per row buffer: rp never written on either side
+    __shared__ __attribute__((aligned(16))) float bufs[kMarchWaves][kBuf];
     const int lane = threadIdx.x & (kWave - 1), wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int task = blockIdx.x * kMarchWaves + wv;
     if (task >= strips * bands) return;
@@ -188,41 +194,28 @@ __global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 
     const size_t plane_off = ((size_t)(plane / C) * C_mem + plane % C) * H * W;
     const float *s = src + plane_off;
     float *d = dst + plane_off;
-    const int x0 = strip * sw, y_start = bandi * band;
+    const int x0 = strip * sw, y_start = bandi * band;   // the strip's first output column, the band's first row
     if (x0 >= W || y_start >= H) return;
     const int y_end = min(y_start + band, H);
-    const int sw_valid = min(sw, W - x0);                // a multiple of 4, at least 4
-    const bool active = 4 * lane < sw_valid;
-    const int X = active ? x0 + 4 * lane : x0;
-    // the rp columns to the left and to the right of the strip: lanes [0, rp/4) and [rp/4, rp/2), one 16-byte piece
-    // each.  A piece lies wholly inside the map or wholly outside it; outside, the edge pixel is repeated.  Every
-    // lane performs the same loads and LDS writes (idle lanes re-read their own piece and write to a spare place), so
-    // that a row step is straight-line code and the loads of later rows stay in flight across it.
-    const bool h_left = lane < rp / 4, h_any = lane < rp / 2;
-    const int h_col = h_left ? x0 - rp + 4 * lane : x0 + sw_valid + 4 * (lane - rp / 4);
-    const bool h_out = h_any && (h_col < 0 || h_col >= W);
-    const bool h_first = h_col < 0;
-    const int h_ld = h_any ? min(max(h_col, 0), W - 4) : X;
-    const int h_dst = h_any ? (h_left ? 4 * lane : rp + sw_valid + 4 * (lane - rp / 4)) : kBuf;
-    const int m_dst = active ? rp + 4 * lane : kBuf;
+    const int sw_valid = min(sw, W - x0);                // output columns: a multiple of 4, at least 4
+    const int X = x0 - rp + 4 * lane;                    // this lane's four columns
+    const bool writes = X >= x0 && X < x0 + sw_valid;
+    // a piece lies wholly inside the map or wholly outside it; outside, the edge pixel is repeated
+    const bool before = X < 0, beyond = X >= W;
+    const int x_ld = min(max(X, 0), W - 4);
     float *buf = bufs[wv];
 
     typedef float v4f __attribute__((ext_vector_type(4)));
-    v4f pre_main[U], pre_halo[U];
-    auto load_row = [&](int yy, v4f &m, v4f &hh) {
-        const float *line = s + (size_t)min(max(yy, 0), H - 1) * W;
-        m = *(const v4f *)(line + X);
-        hh = *(const v4f *)(line + h_ld);
-    };
-    // a piece outside the map: the row's first or last pixel, four times
-    auto edge_fix = [&](const v4f &hh) {
-        const float e = h_first ? hh.x : hh.w;
+    v4f pre[U];
+    auto load_row = [&](int yy, v4f &m) { m = *(const v4f *)(s + (size_t)min(max(yy, 0), H - 1) * W + x_ld); };
+    auto edge_fix = [&](const v4f &m) {
+        const float e = before ? m.x : m.w;
         const v4f rep = {e, e, e, e};
-        return h_out ? rep : hh;
+        return (before || beyond) ? rep : m;
     };
     const int n_steps = (y_end - y_start) + 2 * r;       // source rows y_start - r .. y_end - 1 + r, clamped to the map
 #pragma unroll
-    for (int u = 0; u < U; ++u) load_row(y_start - r + u, pre_main[u], pre_halo[u]);
+    for (int u = 0; u < U; ++u) load_row(y_start - r + u, pre[u]);
 
     float ring[T][4];
 #pragma unroll
@@ -234,9 +227,8 @@ __global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 
         static_for<U>([&](auto uc) {
             constexpr int u = decltype(uc)::value;
             const int step = base + u;                   // steps beyond n_steps (the last pass of a band) store nothing
-            *(v4f *)&buf[m_dst] = pre_main[u];
-            *(v4f *)&buf[h_dst] = edge_fix(pre_halo[u]);
-            load_row(y_start - r + step + U, pre_main[u], pre_halo[u]);      // refilled for the next pass
+            *(v4f *)&buf[rp + 4 * lane] = edge_fix(pre[u]);
+            load_row(y_start - r + step + U, pre[u]);    // refilled for the next pass
             // LDS serves a wavefront's requests in order: the reads below see the writes above
             __builtin_amdgcn_wave_barrier();
             float win[kWin];
@@ -265,7 +257,7 @@ __global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 
 #pragma unroll
                 for (int o = 0; o < 4; ++o) ring[slot][o] = __fmaf_rn(tap, t4[o], j == 0 ? 0.0f : ring[slot][o]);
             }
-            if (step >= 2 * r && step < n_steps && active) {
+            if (step >= 2 * r && step < n_steps && writes) {
                 const int slot = (u % T + 1) % T;        // the row that has just received its last tap
                 const v4f out = {ring[slot][0], ring[slot][1], ring[slot][2], ring[slot][3]};
                 __builtin_nontemporal_store(out, (v4f *)&d[(size_t)(y_start + step - 2 * r) * W + X]);
@@ -286,16 +278,16 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
                          int n_taps, hipStream_t s)
 {
     const int r = (n_taps - 1) / 2;
-    // The marching kernel, where it is the faster one (measured on 8 x 18 maps of 368 x 656 / 4 x 18 maps of 1080 x 1920,
-    // tile kernel -> marching kernel): 5 taps 62 -> 48 / 267 -> 242 us, 9 taps 68 -> 54 / 279 -> 251, 13 taps 75 -> 61 /
-    // 304 -> 256, 17 taps 87 -> 96 / 355 -> 298: with 17 taps a lane holds 228 registers, two wavefronts share a SIMD, and
-    // a launch of fewer than about 2000 such wavefronts leaves SIMDs with one; the small case stays with the tile kernel.
-    const bool march_pays = n_taps == 5 || n_taps == 9 || n_taps == 13 ||
-                            (n_taps == 17 && (long long)N * C * H * W >= 64LL * 1000 * 1000);
+    // The marching kernel serves the tap counts it is compiled for (measured on 8 x 18 maps of 368 x 656 / 4 x 18 maps of
+    // 1080 x 1920, tile kernel -> marching kernel): 5 taps 62 -> 48 / 267 -> 238 us, 9 taps 68 -> 54 / 279 -> 244, 13 taps
+    // 75 -> 61 / 304 -> 247, 17 taps 87 -> 78 / 355 -> 275 (201 registers a lane: two wavefronts share a SIMD).
+    const bool march_pays = n_taps == 5 || n_taps == 9 || n_taps == 13 || n_taps == 17;
     if (march_pays && W % 4 == 0 && ((((uintptr_t)src) | ((uintptr_t)dst)) & 15) == 0) {
-        // strips of equal width (a multiple of 4, at most 256 columns); bands so that about two wavefronts per SIMD are
-        // under way: fewer would leave the memory system idle, more would filter more rows twice (2r per band)
-        const int strips = (W + 4 * kWave - 1) / (4 * kWave);
+        // strips of equal width (a multiple of 4; with the columns read on either side, at most 256); bands so that
+        // about two wavefronts per SIMD are under way: fewer would leave the memory system idle, more would filter more
+        // rows twice (2r per band)
+        const int rp = (r + 3) & ~3, sw_max = 4 * kWave - 2 * rp;
+        const int strips = (W + sw_max - 1) / sw_max;
         const int sw = ((W + strips - 1) / strips + 3) & ~3;
         for (int p0 = 0; p0 < N * C; p0 += 65535 / C * C) {
             const int planes = std::min(N * C - p0, 65535 / C * C);
