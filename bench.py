@@ -577,7 +577,7 @@ def widened_operators(hp, oracle, np, torch, dev, cfg, batch, cm, paf, cm_hi, sk
                                 oracle.smooth(oracle.resize(batch.cm[N - 1, K - 1], 8), taps_np)))
     parity = parity and sm_ok
     sm_fma = sm_px * len(taps_np) * 2
-    smooth = {"kernel": "k_smooth (hp_smooth: separable %d-tap smoothing of the %d part maps per image, %dx%d)" % (len(taps_np), K, cfg.W, cfg.H),
+    smooth = {"kernel": "k_smooth_march (hp_smooth: separable %d-tap smoothing of the %d part maps per image, %dx%d)" % (len(taps_np), K, cfg.W, cfg.H),
               "us_per_launch": round(sm_us, 2),
               "roofline": {"bound": "hbm", "achieved": round(8 * sm_px / (sm_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": round(8 * sm_px / (sm_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "bytes_per_launch": 8 * sm_px},
