@@ -25,7 +25,7 @@ CASES = [
     dict(N=1, C_mem=2, C=1, H=65, W=129, taps=np.array([1.0], np.float32)),
     dict(N=2, C_mem=2, C=2, H=3, W=300, taps=np.array([0.25, 0.5, 0.25], np.float32)),
     dict(N=1, C_mem=1, C=1, H=300, W=2, taps=gaussian_taps(2.0, 5)),
-    # rows of whole 16-byte groups with 5, 9, 13 taps (and 17 on large inputs) take the kernel that walks down strips:
+    # rows of whole 16-byte groups with 5, 9, 13 or 17 taps take the kernel that walks down strips:
     # one and several strips, ragged last strip, a map narrower than the halo, one row, bands that end mid-pass
     dict(N=2, C_mem=3, C=2, H=45, W=64, taps=gaussian_taps(1.0, 2)),
     dict(N=1, C_mem=2, C=2, H=100, W=260, taps=gaussian_taps(2.0, 4)),
@@ -34,6 +34,16 @@ CASES = [
     dict(N=1, C_mem=2, C=2, H=300, W=1028, taps=np.linspace(-1.0, 2.0, 9).astype(np.float32)),
     dict(N=3, C_mem=20, C=19, H=17, W=8, taps=gaussian_taps(1.0, 2)),
     dict(N=1, C_mem=5, C=4, H=2048, W=2048 * 4, taps=gaussian_taps(3.0, 8)),         # 67 M pixels: 17 taps, marching
+    # strips overlap by the taps' reach rounded up to 16-byte pieces: widths on both sides of one strip's and two
+    # strips' output columns, for every tap count the kernel is built for (17 taps: 240 columns a strip; 5: 248)
+    dict(N=1, C_mem=1, C=1, H=40, W=240, taps=gaussian_taps(3.0, 8)),
+    dict(N=1, C_mem=1, C=1, H=40, W=244, taps=gaussian_taps(3.0, 8)),
+    dict(N=1, C_mem=2, C=2, H=23, W=484, taps=gaussian_taps(3.0, 8)),
+    dict(N=2, C_mem=2, C=2, H=19, W=656, taps=gaussian_taps(3.0, 8)),
+    dict(N=1, C_mem=1, C=1, H=18, W=248, taps=gaussian_taps(1.0, 2)),
+    dict(N=1, C_mem=1, C=1, H=18, W=252, taps=gaussian_taps(1.0, 2)),
+    dict(N=1, C_mem=1, C=1, H=50, W=500, taps=gaussian_taps(2.5, 6)),
+    dict(N=1, C_mem=1, C=1, H=9, W=12, taps=np.linspace(0.5, -0.25, 17).astype(np.float32)),
 ]
 
 
