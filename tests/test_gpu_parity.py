@@ -296,6 +296,28 @@ def test_large_lists_sort_outside_lds():
     check_all(buf, ora)
 
 
+@pytest.mark.parametrize("w", [1, 2, 3])
+def test_narrow_maps(w):
+    """Lo-res maps one, two and three columns wide (8, 16, 24 hi-res columns): the bilinear gather of the scorers has a
+    form of its own for a single column, and the last column is the one place where its paired loads are shifted.
+    Both capacities: the one-launch limb kernel and the general scorer."""
+    from synth import Params
+    rng = np.random.default_rng(700 + w)
+    K, L, h = 3, 2, 40
+    cm = (0.2 * rng.random((2, K + 1, h, w))).astype(np.float32)      # the last channel is background
+    paf = rng.normal(0.0, 0.5, (2, 2 * L, h, w)).astype(np.float32)
+    la, lb = [0, 1], [1, 2]
+    p = Params(peak_thr=0.05, paf_thr=-0.5, n_samples=7, min_valid_ratio=0.6, min_parts=2)
+    ora = oracle.postprocess(cm, paf, la, lb, p, threads=4)
+    assert min(len(x[0]) for im in ora["candidates"] for x in im) > 20
+    m = hp()
+    for caps in ((256, 1 << 14, 256), (512, 1 << 15, 512)):
+        buf = m.Buffers(2, K, L, h, w, *caps, DEV)
+        m.hp_postprocess(to_dev(cm), to_dev(paf), m.Skeleton(K, la, lb),
+                         m.Params(p.peak_thr, p.paf_thr, p.n_samples, p.min_valid_ratio, p.min_parts, 8), buf)
+        check_all(buf, ora)
+
+
 def test_assembly_with_tables_beyond_lds():
     """An image with more connections than the in-LDS person tables hold: the fold runs on the
     workspace tables instead and must give the same persons."""
