@@ -296,7 +296,10 @@ __device__ __forceinline__ bool score_pair_ends(int xA, int yA, int xB, int yB, 
     return pair_stage2<T, FROM_HI>(g, pBx, pBy, bad, acc, S, st, paf_thr, max_bad, H, W, h, w, hx, hy, lx, ly, score);
 }
 
-template <typename T, bool FROM_HI>
+// WIDE: the lo-res map has at least two columns (the launcher's choice).  Stating it to the compiler removes the
+// one-column form of the bilinear gather, whose merged results would otherwise make every gather wait for the
+// one before it.
+template <typename T, bool FROM_HI, bool WIDE>
 __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_hi, const T *__restrict__ paf_lo,
                                                   int h, int w, LimbTable tab, SampleT st, int K, int L, int S,
                                                   float paf_thr, int need, int tiles_j, int sub_tiles,
@@ -308,6 +311,7 @@ __global__ __launch_bounds__(kBlock) void k_score(const float *__restrict__ paf_
     __shared__ int4 sA[kTileI];                 // x, y, PAF x bits, PAF y bits at the peak
     __shared__ int2 sB[kTileJ];                 // x, y
     __shared__ uint32_t queues[kBlock / kWave][kQueue];   // i << 16 | j_local of pairs that passed the screen
+    if (WIDE) __builtin_assume(w >= 2);
     const int tid = threadIdx.x;
     const int nl = blockIdx.y;
     // first kernel of hp_score_limbs: it clears the status word (the ordering kernel that follows sets bits)
@@ -537,18 +541,20 @@ hipError_t launch_score(const float *paf_hi, const void *paf_lo, hp_dtype dt, in
     if (sub_tiles < 1) sub_tiles = 1;
     const int tiles = ((tiles_i + sub_tiles - 1) / sub_tiles) * tiles_j;
     dim3 grid(tiles, N * L), block(kBlock);
+    auto go = [&](auto kernel, const float *hi, auto lo) {
+        HP_KERNEL(kernel, grid, block, 0, s, hi, lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
+                  sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2, status);
+    };
+    const float *none = nullptr;
+    const bool wide = w >= 2;
     if (paf_hi)
-        HP_KERNEL((k_score<float, true>), grid, block, 0, s, paf_hi, (const float *)nullptr, h, w, T, st, K, L,
-                           prm.n_samples, prm.paf_thr, need, tiles_j, sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts,
-                           cstage, ccap, ccap2, status);
+        go(k_score<float, true, false>, paf_hi, none);
     else if (dt == HP_F16)
-        HP_KERNEL((k_score<__half, false>), grid, block, 0, s, (const float *)nullptr,
-                           (const __half *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
-                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2, status);
+        wide ? go(k_score<__half, false, true>, none, (const __half *)paf_lo)
+             : go(k_score<__half, false, false>, none, (const __half *)paf_lo);
     else
-        HP_KERNEL((k_score<float, false>), grid, block, 0, s, (const float *)nullptr,
-                           (const float *)paf_lo, h, w, T, st, K, L, prm.n_samples, prm.paf_thr, need, tiles_j,
-                           sub_tiles, pk.count, pk.x, pk.y, pk.cap, ccounts, cstage, ccap, ccap2, status);
+        wide ? go(k_score<float, false, true>, none, (const float *)paf_lo)
+             : go(k_score<float, false, false>, none, (const float *)paf_lo);
     return hipGetLastError();
 }
 
