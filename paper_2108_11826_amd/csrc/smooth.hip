@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kSmoothBlock) void k_smooth(const float *__restrict
 // strip of a band of rows and walks down it one source row at a time; its 64 lanes hold 256 neighbouring columns, four
 // a lane, of which the outer rp on either side (r rounded up to whole 16-byte pieces) are only read: neighbouring
 // strips overlap by that much, so a lane never fetches anything but its own piece.  A step: the row's 16-byte pieces
-// (fetched T or more steps earlier into registers that are refilled in place) go to a row buffer in the wavefront's
+// (fetched kMarchAhead steps earlier into registers) go to a row buffer in the wavefront's
 // own LDS; every lane reads back its window of 4 + 2 rp values and filters its four outputs horizontally; the
 // filtered values are then added, tap by tap, to the T output rows they belong to, whose running sums live in
 // registers; the output row whose last tap this was is stored.  A sum receives its taps in the order the source rows
@@ -176,8 +176,9 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+constexpr int kMarchAhead = 6;        // rows a wavefront has under way: a row is fetched this many steps before its turn
 template <int T>
-__global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 2))) void k_smooth_march(const float *__restrict__ src, float *__restrict__ dst, int C,
+__global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 3))) void k_smooth_march(const float *__restrict__ src, float *__restrict__ dst, int C,
                                                               int C_mem, int H, int W, const float *__restrict__ taps,
                                                               int strips, int sw, int bands, int band)
 {
@@ -214,8 +215,10 @@ __global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 
         return (before || beyond) ? rep : m;
     };
     const int n_steps = (y_end - y_start) + 2 * r;       // source rows y_start - r .. y_end - 1 + r, clamped to the map
+    constexpr int P = kMarchAhead;
+    static_assert(P <= U, "a slot is refilled after its turn");
 #pragma unroll
-    for (int u = 0; u < U; ++u) load_row(y_start - r + u, pre[u]);
+    for (int u = 0; u < P; ++u) load_row(y_start - r + u, pre[u]);
 
     float ring[T][4];
 #pragma unroll
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(kMarchBlock) __attribute__((amdgpu_waves_per_eu(1, 
             constexpr int u = decltype(uc)::value;
             const int step = base + u;                   // steps beyond n_steps (the last pass of a band) store nothing
             *(v4f *)&buf[rp + 4 * lane] = edge_fix(pre[u]);
-            load_row(y_start - r + step + U, pre[u]);    // refilled for the next pass
+            load_row(y_start - r + step + P, pre[(u + P) % U]);
             // LDS serves a wavefront's requests in order: the reads below see the writes above
             __builtin_amdgcn_wave_barrier();
             float win[kWin];
@@ -279,8 +282,8 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
 {
     const int r = (n_taps - 1) / 2;
     // The marching kernel serves the tap counts it is compiled for (measured on 8 x 18 maps of 368 x 656 / 4 x 18 maps of
-    // 1080 x 1920, tile kernel -> marching kernel): 5 taps 62 -> 48 / 267 -> 238 us, 9 taps 68 -> 54 / 279 -> 244, 13 taps
-    // 75 -> 61 / 304 -> 247, 17 taps 87 -> 78 / 355 -> 275 (201 registers a lane: two wavefronts share a SIMD).
+    // 1080 x 1920, tile kernel -> marching kernel): 5 taps 62 -> 46 / 267 -> 238 us, 9 taps 68 -> 52 / 279 -> 244, 13 taps
+    // 75 -> 58 / 304 -> 247, 17 taps 87 -> 74 / 355 -> 270 (161 registers a lane).
     const bool march_pays = n_taps == 5 || n_taps == 9 || n_taps == 13 || n_taps == 17;
     if (march_pays && W % 4 == 0 && ((((uintptr_t)src) | ((uintptr_t)dst)) & 15) == 0) {
         // strips of equal width (a multiple of 4; with the columns read on either side, at most 256); bands so that
@@ -292,8 +295,9 @@ hipError_t launch_smooth(const float *src, float *dst, int N, int C, int C_mem, 
         for (int p0 = 0; p0 < N * C; p0 += 65535 / C * C) {
             const int planes = std::min(N * C - p0, 65535 / C * C);
             const size_t off = (size_t)(p0 / C) * C_mem * H * W;
-            // the kernel keeps two wavefronts per SIMD: at most 2048 of them at once on 256 compute units.  One more than
-            // fit is a second round for the whole launch, so the count stays just below
+            // two wavefronts per SIMD, 2048 on 256 compute units, measured best although three fit at 17 taps and more
+            // at fewer: 5, 6 and 7 bands on the first of the shapes above (2160, 2592, 3024 wavefronts) took 88, 75 and
+            // 93 us against 74 with 4 bands (1728)
             const long long columns = (long long)strips * planes;
             int bands = (int)std::min<long long>((H + 15) / 16, std::max<long long>(1, 2048 / columns));
             const int band = (H + bands - 1) / bands;
