@@ -296,16 +296,17 @@ def test_large_lists_sort_outside_lds():
     check_all(buf, ora)
 
 
+@pytest.mark.parametrize("dtype", ["float32", "float16"])
 @pytest.mark.parametrize("w", [1, 2, 3])
-def test_narrow_maps(w):
+def test_narrow_maps(w, dtype):
     """Lo-res maps one, two and three columns wide (8, 16, 24 hi-res columns): the bilinear gather of the scorers has a
     form of its own for a single column, and the last column is the one place where its paired loads are shifted.
     Both capacities: the one-launch limb kernel and the general scorer."""
     from synth import Params
     rng = np.random.default_rng(700 + w)
     K, L, h = 3, 2, 40
-    cm = (0.2 * rng.random((2, K + 1, h, w))).astype(np.float32)      # the last channel is background
-    paf = rng.normal(0.0, 0.5, (2, 2 * L, h, w)).astype(np.float32)
+    cm = (0.2 * rng.random((2, K + 1, h, w))).astype(dtype)           # the last channel is background
+    paf = rng.normal(0.0, 0.5, (2, 2 * L, h, w)).astype(dtype)
     la, lb = [0, 1], [1, 2]
     p = Params(peak_thr=0.05, paf_thr=-0.5, n_samples=7, min_valid_ratio=0.6, min_parts=2)
     ora = oracle.postprocess(cm, paf, la, lb, p, threads=4)
